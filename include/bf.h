@@ -1,0 +1,193 @@
+/*
+ * bf.h -- C ABI of libbf: decentralized neighbor averaging for n simulated agents on one MI355X.
+ *
+ * The n agents of the paper's problem statement (eq. dist-opt: min (1/n) sum_i f_i(x)) live on one
+ * GPU.  Agent i's vector x_i is row i of an agent-major matrix X (n x d) in device memory, and the
+ * paper's "communication" -- partial averaging over a topology with weight matrix W -- becomes a
+ * sparse gather-reduce over the rows of X.
+ *
+ * Conventions shared by every entry point
+ *   - w_ij scales the copy of x_j that flows from agent j to agent i (eq. wij).  A topology stores,
+ *     per round, the in-neighbor lists N(i) united with {i} as a receiver-major CSR: row i of the
+ *     CSR lists (j, w_ij) with j ascending.
+ *   - Matrices are agent-major.  Row i starts at base + i*ld*s bytes, s = 4 (BF_F32) or 2 (BF_BF16);
+ *     ld >= d is the leading dimension in elements.  base and ld*s must be multiples of 16 bytes.
+ *     Columns d..ld-1 of a row are never read or written.
+ *   - Pointers named X*, G, M, Y, A, b, C, E, w_in/w_out and stats are DEVICE pointers owned by the
+ *     caller; the library never allocates, frees or resizes them.  Pointers inside
+ *     bf_topo_params_t and the export arrays are HOST pointers.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the null stream).  Compute calls enqueue
+ *     on it and return at once: they are the paper's nonblocking primitive, and waiting on the
+ *     stream is its wait(handle).  No call synchronizes the device or reads results back.
+ *   - X_out may be exactly X_in (in place) or must not overlap it at all; any partial overlap, or an
+ *     output overlapping another operand, is BF_ERR_ALIAS.  Two calls that touch the same buffers
+ *     on different streams race; ordering them is the caller's job.
+ *   - `round` selects the weight matrix W^(round mod rounds) of a time-varying topology (the paper
+ *     passes per-iteration weights to neighbor_allreduce); static topologies have rounds == 1.
+ *   - Every function returns BF_OK (0) or a negative bf_status_t.  All argument checks happen on the
+ *     host before anything is launched, so no error path touches the device.  Nothing throws or
+ *     aborts across this boundary.
+ */
+#ifndef BF_H_
+#define BF_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BF_OK = 0,
+  BF_ERR_NULL = -1,            /* a required pointer is NULL                                   */
+  BF_ERR_SIZE = -2,            /* n, d, ld, m, out_degree or rounds out of range               */
+  BF_ERR_ALIGN = -3,           /* base pointer or row pitch not a multiple of 16 bytes         */
+  BF_ERR_ALIAS = -4,           /* operands overlap in a way other than exact in-place          */
+  BF_ERR_KIND = -5,            /* unknown topology kind / dtype / mode                         */
+  BF_ERR_ROUND = -6,           /* negative round index                                         */
+  BF_ERR_NOT_STOCHASTIC = -7,  /* required row / column sums differ from 1 by more than 1e-6   */
+  BF_ERR_NOT_CONNECTED = -8,   /* no strongly connected draw found / user graph not connected  */
+  BF_ERR_CSR = -9,             /* malformed CSR: bad rowptr, column out of range, unsorted or
+                                  duplicate columns, missing diagonal, non-finite weight       */
+  BF_ERR_TOPO_MISMATCH = -10,  /* a sender's dst list and a receiver's src list disagree       */
+  BF_ERR_UNSUPPORTED = -11,    /* valid request this build has no kernel for (says which)      */
+  BF_ERR_HIP = -12,            /* a HIP runtime call failed; bf_last_hip_error() has the code  */
+  BF_ERR_NOMEM = -13           /* host allocation failed                                       */
+} bf_status_t;
+
+typedef enum {
+  BF_RING = 0,             /* self and both ring neighbors, equal weights (1/3 for n >= 3)       */
+  BF_EXP_STATIC = 1,       /* neighbors i +/- 2^k mod n for every 2^k < n, as a set; equal weights
+                              over the set plus self (1/12 at n = 64, 1/10 at n = 32)            */
+  BF_EXP2_ONE_PEER = 2,    /* round r: x_i <- x_i/2 + x_((i + 2^(r mod R)) mod n)/2,
+                              R = number of powers of two below n (log2 n for n = 2^p)           */
+  BF_RANDOM_DIRECTED = 3,  /* push graph: each sender draws out_degree distinct targets != self;
+                              column j holds 1/(out_degree+1) on targets and diagonal            */
+  BF_CSR_USER = 4,         /* caller supplies receiver-major CSR slices, one per round           */
+  BF_DENSE_USER = 5        /* caller supplies dense row-major n x n matrices, one per round      */
+} bf_topo_kind_t;
+
+typedef enum { BF_F32 = 0, BF_BF16 = 1 } bf_dtype_t;
+typedef enum { BF_ATC = 0, BF_AWC = 1 } bf_mode_t;
+
+/* Classes of weight matrix (section "Weight matrix"): pull = rows sum to 1, push = columns sum to
+ * 1, standard = both.  Bit mask: bit 0 = pull, bit 1 = push. */
+typedef enum { BF_W_ANY = 0, BF_W_PULL = 1, BF_W_PUSH = 2, BF_W_STANDARD = 3 } bf_wclass_t;
+
+typedef struct {
+  /* BF_RANDOM_DIRECTED */
+  int32_t  out_degree;                  /* 0 <= out_degree <= n-1                                */
+  int32_t  require_strongly_connected;  /* nonzero: try seed, seed+1, ... until strongly connected
+                                           (at most 10000 tries, else BF_ERR_NOT_CONNECTED)      */
+  uint64_t seed;
+  /* BF_CSR_USER / BF_DENSE_USER */
+  int32_t  rounds;                      /* number of slices, >= 1 (0 is read as 1)               */
+  int32_t  require_class;               /* bf_wclass_t every slice must satisfy (the paper's
+                                           topology check, done once at create time)             */
+  const int64_t* rowptr;                /* rounds*(n+1) entries; slice r uses rowptr[r*(n+1)..],
+                                           offsets are absolute positions in col/wgt             */
+  const int32_t* col;                   /* ascending and unique within a row; diagonal present   */
+  const float*   wgt;
+  const float*   dense_w;               /* rounds*n*n, entry [r][i][j] = w_ij of round r         */
+} bf_topo_params_t;
+
+typedef struct bf_topology bf_topology_t;   /* opaque; immutable after creation; may be shared by
+                                               streams and threads                               */
+
+/* Build a topology and its weights (the paper's set_topology(graph), sections "Network topology",
+ * "Weight matrix" and "Static topology").  `p` may be NULL for the first three kinds.  The random
+ * directed draw is specified as: splitmix64 seeded with the attempt's seed; for sender j = 0..n-1,
+ * list the other agents ascending and run out_degree Fisher-Yates steps, step t swapping slot t
+ * with slot t + (next() mod (n-1-t)); the first out_degree slots are M(j).
+ * On success *out owns host memory (and, lazily, a few KB of device memory per device used). */
+int bf_topology_create(bf_topology_t** out, bf_topo_kind_t kind, int32_t n, const bf_topo_params_t* p);
+
+/* Build a one-round topology from each agent's local view (section "Push- and pull-style
+ * communication over time-varying topology", eqs. dyn-push-comm / dyn-pull-comm): agent i passes
+ * self_weight[i] = w_ii, its source list (j, r_ij) over N(i) and its destination list (i', s_i'i)
+ * over M(i), both as CSR with ascending ranks.  A NULL src_weight means r = 1, a NULL dst_weight
+ * means s = 1 (pure push / pure pull).  The resulting weight is w_ij = r_ij * s_ij.  The lists are
+ * cross-checked: edge (j -> i) must appear in i's sources and in j's destinations, else
+ * BF_ERR_TOPO_MISMATCH (the paper's automatic topology check, which exists so that an unmatched
+ * send/receive pair is reported instead of hanging). */
+int bf_topology_create_push_pull(bf_topology_t** out, int32_t n, const float* self_weight,
+                                 const int64_t* src_rowptr, const int32_t* src_rank, const float* src_weight,
+                                 const int64_t* dst_rowptr, const int32_t* dst_rank, const float* dst_weight);
+
+int     bf_topology_destroy(bf_topology_t* t);          /* NULL is accepted                      */
+int32_t bf_topology_n(const bf_topology_t* t);          /* number of agents, or negative status  */
+int32_t bf_topology_rounds(const bf_topology_t* t);     /* 1 for static graphs                   */
+int64_t bf_topology_nnz(const bf_topology_t* t, int32_t round);       /* self loops included     */
+int32_t bf_topology_max_degree(const bf_topology_t* t, int32_t round);/* longest CSR row         */
+int32_t bf_topology_class(const bf_topology_t* t, int32_t round);     /* bf_wclass_t bit mask,
+                                                            sums tested to 1e-6 in fp64          */
+/* Copy round's CSR to caller-sized host arrays: rowptr[n+1] (starting at 0), col[nnz], wgt[nnz].
+ * Any output pointer may be NULL.  accepted_seed receives the seed a random draw settled on
+ * (the params seed for other kinds).  The fp32 weights exported here are the exact values the
+ * kernels multiply by. */
+int bf_topology_export_csr(const bf_topology_t* t, int32_t round, int64_t* rowptr, int32_t* col,
+                           float* wgt, uint64_t* accepted_seed);
+
+/* Partial averaging (eq. dsgd-2, eq. dgd-2; the neighbor_allreduce primitive):
+ *   X_out[i,:] = sum_{(j,w) in row i of W^(round)} w * X_in[j,:].
+ * Accumulation is fp32 in CSR order; BF_BF16 rounds the result to nearest-even on store. */
+int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                          int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+
+/* Same product through the dense n x n form of W^(round) on the fp32 matrix cores (BF_F32 only;
+ * n <= 256).  Intended for dense / fully connected W (periodic global averaging is W = 11^T/n) and
+ * as an independent cross-check of the sparse kernels. */
+int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                 int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+
+/* One synchronous push-sum round (section "Asynchronous push-style partial averaging" with unit
+ * delays; the u, v, x lines of push-sum gradient tracking): X_out = W X_in, w_out = W w_in and, if
+ * Y is not NULL, Y[i,:] = X_out[i,:] / w_out[i].  W should be column stochastic and w start at 1;
+ * this is not enforced.  w_in, w_out: n fp32 values (the paper's scalar p_i; kept apart from X so
+ * rows stay 16-byte aligned).  w_out may equal w_in; Y has the layout of X_out and may not alias
+ * anything. */
+int bf_pushsum_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                    const float* w_in, float* w_out, void* Y, int64_t d, int64_t ld,
+                    bf_dtype_t dt, void* hip_stream);
+
+/* Local update fused with partial averaging (eqs. eq.atc / eq.awc; dsgd-1 + dsgd-2):
+ *   M == NULL, BF_ATC:  X_out[i,:] = sum_j w_ij (X_in[j,:] - alpha G[j,:])
+ *   M == NULL, BF_AWC:  X_out[i,:] = sum_j w_ij X_in[j,:] - alpha G[i,:]
+ *   M != NULL (heavy-ball momentum, fp32, n x d with leading dimension ld, updated in place):
+ *       M[j,:] <- beta M[j,:] + G[j,:], then the formulas above with M in the place of G.
+ * G has the dtype and leading dimension of X.  beta is ignored when M is NULL. */
+int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld,
+                bf_dtype_t dt, void* hip_stream);
+
+/* Local least-squares gradients of decentralized linear regression (eq. dgd-1):
+ *   G[i,:] = A_i^T (A_i x_i - b_i),  A: n x m x d row-major fp32, b: n x m fp32.
+ * 1 <= m <= 64, d a multiple of 4.  G must not alias X. */
+int bf_grad_least_squares(int32_t n, int32_t m, int64_t d, const float* A, const float* b,
+                          const float* X, int64_t ldx, float* G, int64_t ldg, void* hip_stream);
+
+/* Synthetic stochastic gradient of f_i(x) = lam/2 |x - c_i|^2: G = lam (X - C) + sigma E, all
+ * n x d with leading dimension ld and dtype dt; computed in fp32.  Used to drive the momentum
+ * benchmark; not part of the timed path. */
+int bf_grad_quadratic(int32_t n, int64_t d, int64_t ld, const void* X, const void* C, const void* E,
+                      float lam, float sigma, void* G, bf_dtype_t dt, void* hip_stream);
+
+/* Diagnostics (average consensus problem, section "Asynchronous push-style partial averaging"):
+ * with y_i = x_i (p == NULL) or x_i / p[i], and ybar the column mean of the y_i, writes to the
+ * device array stats[3] (fp64): sum_ic (y_ic - ybar_c)^2, max_ic |y_ic - ybar_c|, max_ic |y_ic|.
+ * If mean_out is not NULL it receives ybar as d fp32 values.  Accumulation is fp64. */
+int bf_consensus_stats(int32_t n, int64_t d, int64_t ld, const void* X, const float* p, bf_dtype_t dt,
+                       double* stats, float* mean_out, void* hip_stream);
+
+const char* bf_strerror(int code);
+int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on this thread        */
+
+/* Launch-shape override for experiments and sweeps: 0 restores the built-in heuristic.
+ * knob 0 = column-tile width in elements, knob 1 = workgroups per compute unit.
+ * Values the kernels cannot honour give BF_ERR_UNSUPPORTED at the next compute call. */
+int bf_set_tuning(int32_t knob, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BF_H_ */

@@ -1,0 +1,172 @@
+"""Oracle iterations in fp64 numpy.  TEST INFRASTRUCTURE ONLY.
+
+State layout: ``X`` is an (n, d) array whose row i is agent i's vector x_i.
+``W`` is a dictionary of in-neighbor lists (see ``oracle.topology``).
+Every function returns new arrays and leaves its arguments untouched.
+Each function is the definition it cites written out row by row; there is no
+blocking, fusion or reordering.
+"""
+
+import numpy as np
+
+
+def _f64(a):
+    return np.asarray(a, dtype=np.float64)
+
+
+def mix(X, W):
+    """Partial averaging (eq. dsgd-2, eq. dgd-2):
+    x_i <- w_ii x_i + sum_{j in N(i)} w_ij x_j, for every agent i."""
+    X = _f64(X)
+    out = np.zeros_like(X)
+    for i in range(X.shape[0]):
+        for j, w in W[i]:
+            out[i, :] += w * X[j, :]
+    return out
+
+
+def mix_push_pull(X, self_w, r, s):
+    """Time-varying partial averaging with sender-side scaling s_ij and
+    receiver-side scaling r_ij (eqs. 2bzbz09, dyn-push-comm, dyn-pull-comm):
+    y_ij = s_ij x_j ;  x_i <- w_ii x_i + sum_j r_ij y_ij.
+    ``r`` and ``s`` are dictionaries i -> [(j, weight)] over N(i); ``self_w[i]``
+    is w_ii."""
+    X = _f64(X)
+    out = np.zeros_like(X)
+    for i in range(X.shape[0]):
+        out[i, :] += self_w[i] * X[i, :]
+        sj = dict(s[i])
+        for j, rij in r[i]:
+            y_ij = sj[j] * X[j, :]
+            out[i, :] += rij * y_ij
+    return out
+
+
+def pushsum_step(X, p, W):
+    """One synchronous push-sum round (push-sum recursion with all delays equal
+    to one; identical to the u, v, x lines of push-sum gradient tracking with a
+    zero step): x <- W x, p <- W p, y_i = x_i / p_i.  W is column stochastic
+    and p starts at one.  Returns (X', p', Y)."""
+    X = _f64(X)
+    p = _f64(p)
+    Xn = mix(X, W)
+    pn = np.zeros_like(p)
+    for i in range(p.shape[0]):
+        for j, w in W[i]:
+            pn[i] += w * p[j]
+    Y = Xn / pn[:, None]
+    return Xn, pn, Y
+
+
+def atc_step(X, G, W, alpha):
+    """Adapt-then-combine (eq. eq.atc; eqs. dsgd-1/dsgd-2; dgd-1/dgd-2):
+    x_i <- sum_{j in N(i) or j=i} w_ij (x_j - alpha g_j), g_j the gradient of
+    agent j at its own previous iterate."""
+    X = _f64(X)
+    G = _f64(G)
+    half = X - alpha * G
+    return mix(half, W)
+
+
+def awc_step(X, G, W, alpha):
+    """Adapt-while-communicate (eq. eq.awc):
+    x_i <- sum_{j in N(i) or j=i} w_ij x_j - alpha g_i."""
+    X = _f64(X)
+    G = _f64(G)
+    return mix(X, W) - alpha * G
+
+
+def dmsgd_atc_step(X, M, G, W, alpha, beta):
+    """Heavy-ball decentralized momentum SGD in adapt-then-combine order.
+    The paper names decentralized momentum SGD in its accuracy tables but gives
+    no recursion; this is the plain form: m_i <- beta m_i + g_i, then eq.atc
+    with m_i in the place of the gradient.  Returns (X', M')."""
+    X = _f64(X)
+    M = _f64(M)
+    G = _f64(G)
+    Mn = beta * M + G
+    return mix(X - alpha * Mn, W), Mn
+
+
+def ls_grad(A, b, X):
+    """Local least-squares gradients used by decentralized gradient descent
+    (eq. dgd-1): g_i = A_i^T (A_i x_i - b_i).  A is (n, m, d), b is (n, m)."""
+    A = _f64(A)
+    b = _f64(b)
+    X = _f64(X)
+    G = np.zeros_like(X)
+    for i in range(X.shape[0]):
+        resid = A[i] @ X[i] - b[i]
+        G[i, :] = A[i].T @ resid
+    return G
+
+
+def quadratic_noise_grad(X, C, E, lam, sigma):
+    """Synthetic local gradient of f_i(x) = lam/2 |x - c_i|^2 plus additive
+    noise: g_i = lam (x_i - c_i) + sigma e_i (the benchmark's stand-in for a
+    network's stochastic gradient)."""
+    return lam * (_f64(X) - _f64(C)) + sigma * _f64(E)
+
+
+def exact_diffusion_step(X, psi_prev, G, W, alpha):
+    """Exact-Diffusion (eqs. ed-1, ed-2, ed-3): psi = x - alpha g;
+    phi = psi + x - psi_prev; x <- W phi.  Returns (X', psi)."""
+    X = _f64(X)
+    psi = X - alpha * _f64(G)
+    phi = psi + X - _f64(psi_prev)
+    return mix(phi, W), psi
+
+
+def column_mean(X):
+    return _f64(X).mean(axis=0)
+
+
+def consensus_error(X):
+    """Frobenius distance of X from the consensus matrix 1 xbar^T."""
+    X = _f64(X)
+    return float(np.linalg.norm(X - X.mean(axis=0, keepdims=True)))
+
+
+def round_to_bf16(x32):
+    """Round fp32 values to the nearest bfloat16 (ties to even), returned as
+    fp32.  bfloat16 is the top 16 bits of the IEEE-754 binary32 pattern; NaNs
+    are kept quiet."""
+    a = np.ascontiguousarray(x32, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    r = ((u + 0x7FFF + lsb) >> 16) << 16
+    nan = np.isnan(a)
+    r = np.where(nan, (u | 0x00400000) & 0xFFFF0000, r)
+    return (r & 0xFFFFFFFF).astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def dmsgd_atc_step_bf16_storage(X_bf, M32, G_bf, W, alpha, beta):
+    """Diagnostic twin of ``dmsgd_atc_step`` for the bf16-storage layout: X and
+    G hold bf16 values, M holds fp32 values; arithmetic is exact fp64 and each
+    result is rounded once to its storage type (M to fp32, X to fp32 then
+    bf16).  Returns (X' as fp32 holding bf16 values, M' as fp32)."""
+    Mn = (beta * _f64(M32) + _f64(G_bf)).astype(np.float32)
+    Xn = mix(_f64(X_bf) - alpha * _f64(Mn), W)
+    return round_to_bf16(Xn.astype(np.float32)), Mn
+
+
+def mix_fp32_chain(X32, W):
+    """fp32 emulation of a fused-multiply-add chain over each in-neighbor list
+    in list order: acc = fl(w_0 x_0); acc = fl(w_p x_p + acc).  Each product is
+    exact in fp64 (24+24 bits); the fp64 sum is then rounded to fp32.  This is
+    bit-identical to a hardware FMA chain whenever w_p x_p + acc is exact in
+    fp64 before the final rounding, in particular for power-of-two weights
+    (the one-peer exponential graph, where each round is one correctly rounded
+    fp32 addition of two exactly halved values)."""
+    X32 = np.asarray(X32, dtype=np.float32)
+    out = np.zeros_like(X32)
+    for i in range(X32.shape[0]):
+        acc = None
+        for j, w in W[i]:
+            prod = np.float64(np.float32(w)) * X32[j, :].astype(np.float64)
+            if acc is None:
+                acc = prod.astype(np.float32)
+            else:
+                acc = (prod + acc.astype(np.float64)).astype(np.float32)
+        out[i, :] = acc
+    return out

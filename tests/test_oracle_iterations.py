@@ -1,0 +1,367 @@
+"""Pins for the oracle's iterations against library routines, closed forms,
+invariants and limiting cases.  A transposed operand, a dropped term, a wrong
+sign or a wrong index in ``oracle.iterations`` fails at least one test here."""
+
+import math
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import torch
+
+from oracle import iterations as O
+from oracle import topology as T
+
+
+def _rand_W(n, rng, density=0.4):
+    """A random non-symmetric, non-stochastic weight matrix with a full diagonal."""
+    D = rng.normal(size=(n, n)) * (rng.random((n, n)) < density)
+    D[np.arange(n), np.arange(n)] = rng.normal(size=n) + 2.0
+    return D
+
+
+# ---------------------------------------------------------------- mix
+def test_mix_equals_dense_and_scipy_spmm():
+    rng = np.random.default_rng(1)
+    n, d = 7, 13
+    D = _rand_W(n, rng)
+    assert abs(D - D.T).max() > 0.5                      # asymmetric: catches a transposed W
+    X = rng.normal(size=(n, d))
+    got = O.mix(X, T.from_dense(D))
+    np.testing.assert_allclose(got, D @ X, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(got, sp.csr_matrix(D) @ X, rtol=0, atol=1e-13)
+
+
+def test_mix_brute_force_scalar_loops():
+    rng = np.random.default_rng(2)
+    n, d = 5, 3
+    D = _rand_W(n, rng)
+    X = rng.normal(size=(n, d))
+    got = O.mix(X, T.from_dense(D))
+    for i in range(n):
+        for c in range(d):
+            s = 0.0
+            for j in range(n):
+                s += D[i, j] * X[j, c]       # w_ij scales x_j (eq. wij)
+            assert abs(got[i, c] - s) < 1e-13
+
+
+def test_mix_mean_preserved_iff_columns_sum_to_one():
+    rng = np.random.default_rng(3)
+    X = rng.normal(size=(64, 50))
+    W = T.static_exponential(64)
+    Xn = O.mix(X, W)
+    np.testing.assert_allclose(Xn.sum(0), X.sum(0), atol=64 * 1e-15 * 10)
+    # a pull-only (row-stochastic) matrix fixes consensus but does not preserve the mean
+    inn = {i: [(i + 1) % 5] if i else [1, 2, 3, 4] for i in range(5)}
+    Wp = T.uniform_from_neighbor_sets(inn)
+    Xc = np.tile(rng.normal(size=(1, 6)), (5, 1))
+    np.testing.assert_allclose(O.mix(Xc, Wp), Xc, atol=1e-15)
+    X5 = rng.normal(size=(5, 6))
+    assert abs(O.mix(X5, Wp).sum(0) - X5.sum(0)).max() > 1e-3
+
+
+def test_mix_does_not_modify_input_and_empty_width():
+    X = np.ones((4, 3))
+    X0 = X.copy()
+    O.mix(X, T.ring(4))
+    assert np.array_equal(X, X0)
+    assert O.mix(np.zeros((4, 0)), T.ring(4)).shape == (4, 0)
+
+
+def test_consensus_contracts_at_lambda2_ring_and_static_exp():
+    rng = np.random.default_rng(4)
+    for W, lam2 in ((T.ring(16), 0.9492530216741911), (T.static_exponential(64), 2 / 3)):
+        n = len(W)
+        X = rng.uniform(-1, 1, size=(n, 40))
+        e_prev = O.consensus_error(X)
+        ratios = []
+        for k in range(50):
+            X = O.mix(X, W)
+            e = O.consensus_error(X)
+            assert e <= lam2 * e_prev * (1 + 1e-12)       # hard bound every round
+            ratios.append(e / e_prev)
+            e_prev = e
+        assert ratios[-1] <= lam2 + 1e-12
+        assert ratios[-1] > 0.9 * lam2                     # and approaches it from below
+    # static exp: error after 50 rounds is below (2/3)^50 of the start
+    assert (2 / 3) ** 50 < 1.6e-9
+
+
+def test_consensus_error_definition():
+    X = np.array([[1.0, 2.0], [3.0, 6.0]])
+    # means (2,4): deviations (+-1, +-2) -> sqrt(1+1+4+4)
+    assert abs(O.consensus_error(X) - math.sqrt(10)) < 1e-15
+    np.testing.assert_allclose(O.column_mean(X), [2.0, 4.0])
+
+
+def test_one_peer_eight_rounds_give_exact_mean():
+    rng = np.random.default_rng(5)
+    n = 256
+    X = rng.normal(size=(n, 17))
+    mean = X.mean(0)
+    Y = X
+    for r in range(8):
+        Y = O.mix(Y, T.one_peer_exponential(n, r))
+        if r < 7:
+            assert abs(Y - mean).max() > 1e-3
+    np.testing.assert_allclose(Y, np.tile(mean, (n, 1)), atol=4e-16 * 8)
+
+
+def test_static_is_special_case_of_push_pull_split():
+    # eq. 2bzbz09 with r*s = w reduces to eq. dsgd-2; pure push (r=1,s=w) == pure pull (r=w,s=1).
+    rng = np.random.default_rng(6)
+    n = 9
+    D = _rand_W(n, rng)
+    W = T.from_dense(D)
+    X = rng.normal(size=(n, 5))
+    selfw = {i: D[i, i] for i in range(n)}
+    nb = {i: [(j, w) for j, w in W[i] if j != i] for i in range(n)}
+    ones = {i: [(j, 1.0) for j, _ in nb[i]] for i in range(n)}
+    pull = O.mix_push_pull(X, selfw, nb, ones)
+    push = O.mix_push_pull(X, selfw, ones, nb)
+    np.testing.assert_allclose(pull, D @ X, atol=1e-13)
+    np.testing.assert_allclose(push, D @ X, atol=1e-13)
+    half = {i: [(j, math.sqrt(abs(w))) for j, w in nb[i]] for i in range(n)}
+    halfs = {i: [(j, math.copysign(math.sqrt(abs(w)), w)) for j, w in nb[i]] for i in range(n)}
+    np.testing.assert_allclose(O.mix_push_pull(X, selfw, half, halfs), D @ X, atol=1e-13)
+
+
+# ---------------------------------------------------------------- push-sum
+def test_pushsum_invariants_and_limit():
+    rng = np.random.default_rng(7)
+    n = 128
+    W, _ = T.random_directed_push(n, 4, 401)
+    X = rng.normal(5, 2, size=(n, 11))
+    xbar = X.mean(0)
+    p = np.ones(n)
+    s0 = X.sum(0)
+    for k in range(100):
+        X, p, Y = O.pushsum_step(X, p, W)
+        np.testing.assert_allclose(X.sum(0), s0, rtol=1e-13)      # 1^T W = 1^T
+        assert abs(p.sum() - n) < 1e-11                           # sum of p stays n
+        if k == 0:
+            assert abs(Y - xbar).max() > 0.1
+    np.testing.assert_allclose(Y, np.tile(xbar, (n, 1)), atol=1e-12)
+    assert abs(X / p[:, None] - Y).max() == 0.0
+    assert abs(p - 1).max() > 0.05                                 # the correction is not trivial
+
+
+def test_pushsum_weights_converge_to_perron_vector_tiny():
+    # brute force at n=6: p_k = W^k 1 -> n * pi, pi the right Perron vector of column-stochastic W
+    W, _ = T.random_directed_push(6, 2, 7)
+    D = T.to_dense(W)
+    ev, V = np.linalg.eig(D)
+    k = int(np.argmax(ev.real))
+    pi = np.real(V[:, k])
+    pi = pi / pi.sum()
+    X = np.arange(12.0).reshape(6, 2)
+    p = np.ones(6)
+    for _ in range(200):
+        X, p, Y = O.pushsum_step(X, p, W)
+    np.testing.assert_allclose(p, 6 * pi, atol=1e-12)
+    np.testing.assert_allclose(p, np.linalg.matrix_power(D, 200) @ np.ones(6), atol=1e-12)
+    np.testing.assert_allclose(Y, np.tile(np.arange(12.0).reshape(6, 2).mean(0), (6, 1)), atol=1e-11)
+
+
+def test_pushsum_without_correction_is_biased():
+    # the plain iterate x (no division by p) does not reach the mean on a push-only graph
+    W, _ = T.random_directed_push(16, 3, 11)
+    rng = np.random.default_rng(8)
+    X = rng.normal(size=(16, 4))
+    xbar = X.mean(0)
+    p = np.ones(16)
+    for _ in range(300):
+        X, p, Y = O.pushsum_step(X, p, W)
+    assert abs(Y - xbar).max() < 1e-12
+    assert abs(X - xbar).max() > 1e-2
+
+
+# ---------------------------------------------------------------- least-squares gradient
+def test_ls_grad_is_gradient_of_half_squared_residual():
+    rng = np.random.default_rng(9)
+    n, m, d = 3, 4, 6
+    A = rng.normal(size=(n, m, d))
+    b = rng.normal(size=(n, m))
+    X = rng.normal(size=(n, d))
+    G = O.ls_grad(A, b, X)
+    f = lambda i, x: 0.5 * np.sum((A[i] @ x - b[i]) ** 2)
+    h = 1e-6
+    for i in range(n):
+        for c in range(d):
+            e = np.zeros(d)
+            e[c] = h
+            fd = (f(i, X[i] + e) - f(i, X[i] - e)) / (2 * h)
+            assert abs(G[i, c] - fd) < 1e-6
+    At = torch.tensor(A)
+    xt = torch.tensor(X, requires_grad=True)
+    loss = 0.5 * ((torch.einsum("imd,id->im", At, xt) - torch.tensor(b)) ** 2).sum()
+    loss.backward()
+    np.testing.assert_allclose(G, xt.grad.numpy(), atol=1e-12)
+
+
+# ---------------------------------------------------------------- ATC / AWC
+def test_atc_single_agent_is_gradient_descent_closed_form():
+    # n=1, W=[1]: x_k = (I - alpha A^T A)^k x_0 + ... ; closed form through the SVD of A.
+    rng = np.random.default_rng(10)
+    m, d, alpha, K = 4, 7, 0.05, 60
+    A = rng.normal(size=(1, m, d))
+    b = rng.normal(size=(1, m))
+    W = {0: [(0, 1.0)]}
+    X = np.zeros((1, d))
+    for _ in range(K):
+        X = O.atc_step(X, O.ls_grad(A, b, X), W, alpha)
+    U, s, Vt = np.linalg.svd(A[0], full_matrices=False)
+    coef = (1 - (1 - alpha * s ** 2) ** K) / s * (U.T @ b[0])
+    np.testing.assert_allclose(X[0], Vt.T @ coef, atol=1e-12)
+    # and the limit is the pseudo-inverse solution
+    for _ in range(5000):
+        X = O.atc_step(X, O.ls_grad(A, b, X), W, alpha)
+    np.testing.assert_allclose(X[0], np.linalg.pinv(A[0]) @ b[0], atol=1e-9)
+
+
+def test_atc_with_global_averaging_is_centralized_gd():
+    # W = 11^T/n and equal starts: x <- x - (alpha/n) sum_i g_i  (eq. sgd-2)
+    rng = np.random.default_rng(11)
+    n, m, d, alpha = 4, 3, 5, 0.02
+    A = rng.normal(size=(n, m, d))
+    b = rng.normal(size=(n, m))
+    W = T.from_dense(np.full((n, n), 1.0 / n))
+    x = rng.normal(size=d)
+    X = np.tile(x, (n, 1))
+    for _ in range(7):
+        g = sum(A[i].T @ (A[i] @ x - b[i]) for i in range(n))
+        x = x - alpha / n * g
+        X = O.atc_step(X, O.ls_grad(A, b, X), W, alpha)
+    np.testing.assert_allclose(X, np.tile(x, (n, 1)), atol=1e-13)
+
+
+def test_atc_and_awc_against_dense_formulas():
+    rng = np.random.default_rng(12)
+    n, d, alpha = 6, 4, 0.3
+    D = _rand_W(n, rng)
+    W = T.from_dense(D)
+    X = rng.normal(size=(n, d))
+    G = rng.normal(size=(n, d))
+    np.testing.assert_allclose(O.atc_step(X, G, W, alpha), D @ (X - alpha * G), atol=1e-13)
+    np.testing.assert_allclose(O.awc_step(X, G, W, alpha), D @ X - alpha * G, atol=1e-13)
+    assert abs(O.atc_step(X, G, W, alpha) - O.awc_step(X, G, W, alpha)).max() > 1e-2
+    Z = np.zeros_like(G)
+    np.testing.assert_allclose(O.atc_step(X, Z, W, alpha), O.awc_step(X, Z, W, alpha), atol=0)
+    np.testing.assert_allclose(O.atc_step(X, G, W, 0.0), O.mix(X, W), atol=0)
+    np.testing.assert_allclose(O.awc_step(X, G, W, 0.0), O.mix(X, W), atol=0)
+
+
+def test_dgd_on_ring_converges_near_least_squares_solution():
+    # DGD (eqs. dgd-1, dgd-2) with a small step lands in a neighbourhood of x*; all agents agree
+    rng = np.random.default_rng(13)
+    n, m, d, alpha = 8, 6, 5, 0.01
+    A = rng.normal(size=(n, m, d))
+    xs = rng.normal(size=d)
+    b = np.einsum("imd,d->im", A, xs)            # consistent system: x* is every agent's minimiser
+    W = T.ring(n)
+    X = np.zeros((n, d))
+    for _ in range(4000):
+        X = O.atc_step(X, O.ls_grad(A, b, X), W, alpha)
+    np.testing.assert_allclose(X, np.tile(xs, (n, 1)), atol=1e-8)
+
+
+# ---------------------------------------------------------------- momentum
+def test_dmsgd_beta_zero_is_atc():
+    rng = np.random.default_rng(14)
+    W = T.static_exponential(8)
+    X, M, G = (rng.normal(size=(8, 5)) for _ in range(3))
+    Xn, Mn = O.dmsgd_atc_step(X, M, G, W, 0.1, 0.0)
+    np.testing.assert_allclose(Xn, O.atc_step(X, G, W, 0.1), atol=0)
+    np.testing.assert_allclose(Mn, G, atol=0)
+
+
+def test_dmsgd_single_agent_matches_torch_sgd_momentum():
+    rng = np.random.default_rng(15)
+    d, alpha, beta, lam = 6, 0.1, 0.9, 1.0
+    c = rng.normal(size=d)
+    noise = rng.normal(size=(12, d))
+    p = torch.zeros(d, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=alpha, momentum=beta, dampening=0, nesterov=False)
+    X = np.zeros((1, d))
+    M = np.zeros((1, d))
+    W = {0: [(0, 1.0)]}
+    for k in range(12):
+        G = O.quadratic_noise_grad(X, c[None], noise[k][None], lam, 0.1)
+        X, M = O.dmsgd_atc_step(X, M, G, W, alpha, beta)
+        opt.zero_grad()
+        p.grad = lam * (p.detach() - torch.tensor(c)) + 0.1 * torch.tensor(noise[k])
+        opt.step()
+        np.testing.assert_allclose(X[0], p.detach().numpy(), atol=1e-13)
+
+
+def test_dmsgd_noise_free_two_by_two_recurrence():
+    # per coordinate, W = I: [x;m]' = [[1-a l, -a b],[l, b]] [x;m] + [a l c; -l c]; fixed point x=c, m=0
+    alpha, beta, lam, c = 0.1, 0.9, 1.0, 0.7
+    Amat = np.array([[1 - alpha * lam, -alpha * beta], [lam, beta]])
+    off = np.array([alpha * lam * c, -lam * c])
+    ev, V = np.linalg.eig(Amat)
+    z0 = np.array([0.0, 0.0]) - np.array([c, 0.0])
+    X = np.zeros((1, 1))
+    M = np.zeros((1, 1))
+    W = {0: [(0, 1.0)]}
+    for k in range(1, 30):
+        G = O.quadratic_noise_grad(X, np.array([[c]]), np.zeros((1, 1)), lam, 0.1)
+        X, M = O.dmsgd_atc_step(X, M, G, W, alpha, beta)
+        zk = np.real(V @ (ev ** k * np.linalg.solve(V, z0.astype(complex)))) + np.array([c, 0.0])
+        assert abs(X[0, 0] - zk[0]) < 1e-12 and abs(M[0, 0] - zk[1]) < 1e-12
+    assert np.allclose(Amat @ np.array([c, 0.0]) + off, [c, 0.0])
+
+
+def test_dmsgd_column_sums():
+    rng = np.random.default_rng(16)
+    W = T.static_exponential(32)
+    X, M, G = (rng.normal(size=(32, 9)) for _ in range(3))
+    Xn, Mn = O.dmsgd_atc_step(X, M, G, W, 0.1, 0.9)
+    np.testing.assert_allclose(Xn.sum(0), (X - 0.1 * Mn).sum(0), atol=1e-12)
+    np.testing.assert_allclose(Mn, 0.9 * M + G, atol=0)
+
+
+# ---------------------------------------------------------------- Exact-Diffusion (next row)
+def test_exact_diffusion_fixed_point_is_least_squares_solution():
+    rng = np.random.default_rng(17)
+    n, m, d, alpha = 8, 4, 6, 0.02          # n*m >= d: the stacked system has full column rank
+    A = rng.normal(size=(n, m, d))
+    b = rng.normal(size=(n, m))
+    W = T.ring(n)
+    X = np.zeros((n, d))
+    psi_prev = X.copy()                     # psi^{(-1)} = x^{(0)}
+    for _ in range(20000):
+        X, psi_prev = O.exact_diffusion_step(X, psi_prev, O.ls_grad(A, b, X), W, alpha)
+    xs = np.linalg.lstsq(A.reshape(n * m, d), b.reshape(n * m), rcond=None)[0]
+    np.testing.assert_allclose(X, np.tile(xs, (n, 1)), atol=1e-8)
+
+
+# ---------------------------------------------------------------- bf16 rounding and fp32 chain
+def test_round_to_bf16_matches_torch():
+    rng = np.random.default_rng(18)
+    vals = np.concatenate([
+        rng.normal(size=4000).astype(np.float32),
+        (rng.normal(size=2000) * 1e-40).astype(np.float32),            # subnormals
+        np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1.0, 1.00390625, 1.01171875,
+                  3.3895314e38, -3.3895314e38, 3.4028235e38], dtype=np.float32),
+        # exact ties: bf16 has 8 significant bits; 1 + (2k+1) 2^-8 lies halfway
+        np.array([1 + (2 * k + 1) * 2.0 ** -8 for k in range(64)], dtype=np.float32),
+    ])
+    got = O.round_to_bf16(vals)
+    ref = torch.from_numpy(vals).to(torch.bfloat16).to(torch.float32).numpy()
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), ref[~nan].view(np.uint32))
+
+
+def test_mix_fp32_chain_one_peer_is_single_rounded_add():
+    rng = np.random.default_rng(19)
+    X = rng.normal(size=(8, 33)).astype(np.float32)
+    W = T.one_peer_exponential(8, 1)
+    got = O.mix_fp32_chain(X, W)
+    ref = np.empty_like(X)
+    for i in range(8):
+        ref[i] = (X[i] + X[(i + 2) % 8]) / np.float32(2)   # one rounded add, exact halving
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    np.testing.assert_allclose(got, O.mix(X, W), rtol=1e-7, atol=1e-7)
