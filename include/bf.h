@@ -183,7 +183,8 @@ const char* bf_strerror(int code);
 int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on this thread        */
 
 /* Launch-shape override for experiments and sweeps: 0 restores the built-in heuristic.
- * knob 0 = column-tile width in elements, knob 1 = workgroups per compute unit.
+ * knob 0 = column-tile width in elements (64..1024, power of two), knob 1 = workgroups per
+ * compute unit, knob 2 = 1 forces the cache-reliant row-gather fallback (out of place only).
  * Values the kernels cannot honour give BF_ERR_UNSUPPORTED at the next compute call. */
 int bf_set_tuning(int32_t knob, int32_t value);
 

@@ -1,0 +1,299 @@
+"""ctypes binding of libbf: argument marshalling only.
+
+Every function here has the name of the C entry point it forwards to (see
+``include/bf.h``) and does nothing but turn torch tensors into device pointers,
+sizes and the current HIP stream.  All arithmetic happens in the library's
+kernels.  If ``libbf.so`` has not been built the import fails; there is no
+fallback path.
+"""
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbf.so")
+
+BF_OK = 0
+(BF_ERR_NULL, BF_ERR_SIZE, BF_ERR_ALIGN, BF_ERR_ALIAS, BF_ERR_KIND, BF_ERR_ROUND,
+ BF_ERR_NOT_STOCHASTIC, BF_ERR_NOT_CONNECTED, BF_ERR_CSR, BF_ERR_TOPO_MISMATCH,
+ BF_ERR_UNSUPPORTED, BF_ERR_HIP, BF_ERR_NOMEM) = range(-1, -14, -1)
+
+BF_RING, BF_EXP_STATIC, BF_EXP2_ONE_PEER, BF_RANDOM_DIRECTED, BF_CSR_USER, BF_DENSE_USER = range(6)
+BF_F32, BF_BF16 = 0, 1
+BF_ATC, BF_AWC = 0, 1
+BF_W_ANY, BF_W_PULL, BF_W_PUSH, BF_W_STANDARD = 0, 1, 2, 3
+
+EXPORTS = [
+    "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
+    "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
+    "bf_topology_export_csr", "bf_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step",
+    "bf_atc_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
+    "bf_strerror", "bf_last_hip_error", "bf_set_tuning",
+]
+
+
+class bf_topo_params_t(C.Structure):
+    _fields_ = [
+        ("out_degree", C.c_int32),
+        ("require_strongly_connected", C.c_int32),
+        ("seed", C.c_uint64),
+        ("rounds", C.c_int32),
+        ("require_class", C.c_int32),
+        ("rowptr", C.POINTER(C.c_int64)),
+        ("col", C.POINTER(C.c_int32)),
+        ("wgt", C.POINTER(C.c_float)),
+        ("dense_w", C.POINTER(C.c_float)),
+    ]
+
+
+class BfError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        msg = lib.bf_strerror(code).decode()
+        if code == BF_ERR_HIP:
+            msg += " (hipError %d)" % lib.bf_last_hip_error()
+        super().__init__("%s: %s [%d]" % (where, msg, code))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libbf.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "from the repository root (needs hipcc). There is no CPU fallback.")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    L.bf_topology_create.argtypes = [C.POINTER(vp), C.c_int, i32, C.POINTER(bf_topo_params_t)]
+    L.bf_topology_create_push_pull.argtypes = [C.POINTER(vp), i32, vp, vp, vp, vp, vp, vp, vp]
+    L.bf_topology_destroy.argtypes = [vp]
+    L.bf_topology_n.argtypes = [vp]
+    L.bf_topology_rounds.argtypes = [vp]
+    L.bf_topology_nnz.argtypes = [vp, i32]
+    L.bf_topology_nnz.restype = i64
+    L.bf_topology_max_degree.argtypes = [vp, i32]
+    L.bf_topology_class.argtypes = [vp, i32]
+    L.bf_topology_export_csr.argtypes = [vp, i32, vp, vp, vp, C.POINTER(C.c_uint64)]
+    L.bf_neighbor_allreduce.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_dense_mix.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_pushsum_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_atc_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, f32, C.c_int, i64, i64, C.c_int, vp]
+    L.bf_grad_least_squares.argtypes = [i32, i32, i64, vp, vp, vp, i64, vp, i64, vp]
+    L.bf_grad_quadratic.argtypes = [i32, i64, i64, vp, vp, vp, f32, f32, vp, C.c_int, vp]
+    L.bf_consensus_stats.argtypes = [i32, i64, i64, vp, vp, C.c_int, vp, vp, vp]
+    L.bf_strerror.argtypes = [C.c_int]
+    L.bf_strerror.restype = C.c_char_p
+    L.bf_last_hip_error.argtypes = []
+    L.bf_set_tuning.argtypes = [i32, i32]
+    for name in EXPORTS:
+        getattr(L, name)          # raises AttributeError if a declared symbol is missing
+    return L
+
+
+lib = _load()
+
+
+def _check(code, where):
+    if code != BF_OK:
+        raise BfError(code, where)
+
+
+def _np_ptr(a, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+class Topology:
+    """Owner of a ``bf_topology_t*``."""
+
+    def __init__(self, handle):
+        self.handle = handle
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h:
+            lib.bf_topology_destroy(h)
+
+    @property
+    def n(self):
+        return lib.bf_topology_n(self.handle)
+
+    @property
+    def rounds(self):
+        return lib.bf_topology_rounds(self.handle)
+
+
+def bf_topology_create(kind, n, out_degree=0, seed=0, require_strongly_connected=True,
+                       rounds=1, require_class=BF_W_ANY, rowptr=None, col=None, wgt=None, dense_w=None):
+    p = bf_topo_params_t()
+    p.out_degree = out_degree
+    p.seed = seed
+    p.require_strongly_connected = int(bool(require_strongly_connected))
+    p.rounds = rounds
+    p.require_class = require_class
+    keep = []
+    if rowptr is not None:
+        a = np.ascontiguousarray(rowptr, dtype=np.int64); keep.append(a); p.rowptr = _np_ptr(a, C.c_int64)
+    if col is not None:
+        a = np.ascontiguousarray(col, dtype=np.int32); keep.append(a); p.col = _np_ptr(a, C.c_int32)
+    if wgt is not None:
+        a = np.ascontiguousarray(wgt, dtype=np.float32); keep.append(a); p.wgt = _np_ptr(a, C.c_float)
+    if dense_w is not None:
+        a = np.ascontiguousarray(dense_w, dtype=np.float32); keep.append(a); p.dense_w = _np_ptr(a, C.c_float)
+    h = C.c_void_p()
+    _check(lib.bf_topology_create(C.byref(h), kind, n, C.byref(p)), "bf_topology_create")
+    return Topology(h)
+
+
+def bf_topology_create_push_pull(n, self_weight, src_rowptr, src_rank, src_weight, dst_rowptr, dst_rank, dst_weight):
+    def arr(a, dt):
+        return None if a is None else np.ascontiguousarray(a, dtype=dt)
+    sw = arr(self_weight, np.float32)
+    srp, srk, swt = arr(src_rowptr, np.int64), arr(src_rank, np.int32), arr(src_weight, np.float32)
+    drp, drk, dwt = arr(dst_rowptr, np.int64), arr(dst_rank, np.int32), arr(dst_weight, np.float32)
+    ptr = lambda a: None if a is None else a.ctypes.data
+    h = C.c_void_p()
+    _check(lib.bf_topology_create_push_pull(C.byref(h), n, ptr(sw), ptr(srp), ptr(srk), ptr(swt),
+                                            ptr(drp), ptr(drk), ptr(dwt)), "bf_topology_create_push_pull")
+    return Topology(h)
+
+
+def bf_topology_rounds(t):
+    return lib.bf_topology_rounds(t.handle)
+
+
+def bf_topology_nnz(t, rnd=0):
+    return lib.bf_topology_nnz(t.handle, rnd)
+
+
+def bf_topology_max_degree(t, rnd=0):
+    return lib.bf_topology_max_degree(t.handle, rnd)
+
+
+def bf_topology_class(t, rnd=0):
+    return lib.bf_topology_class(t.handle, rnd)
+
+
+def bf_topology_export_csr(t, rnd=0):
+    """Returns (rowptr int64[n+1], col int32[nnz], wgt float32[nnz], accepted_seed)."""
+    n = lib.bf_topology_n(t.handle)
+    nnz = lib.bf_topology_nnz(t.handle, rnd)
+    if nnz < 0:
+        raise BfError(int(nnz), "bf_topology_nnz")
+    rowptr = np.empty(n + 1, dtype=np.int64)
+    col = np.empty(nnz, dtype=np.int32)
+    wgt = np.empty(nnz, dtype=np.float32)
+    seed = C.c_uint64(0)
+    _check(lib.bf_topology_export_csr(t.handle, rnd, rowptr.ctypes.data, col.ctypes.data, wgt.ctypes.data,
+                                      C.byref(seed)), "bf_topology_export_csr")
+    return rowptr, col, wgt, seed.value
+
+
+# ---- tensor marshalling ----------------------------------------------------------------------
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return BF_F32
+    if t.dtype == torch.bfloat16:
+        return BF_BF16
+    raise TypeError("libbf handles float32 and bfloat16 matrices, got %s" % t.dtype)
+
+
+def _mat(t, name):
+    """(ptr, n, d, ld) of an agent-major 2-D tensor with unit column stride."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("%s must be 2-D with contiguous rows" % name)
+    n, d = t.shape
+    ld = t.stride(0) if n > 1 else max(d, 1)
+    if n == 1:
+        per16 = 16 // t.element_size()
+        ld = (ld + per16 - 1) // per16 * per16 if ld % per16 else ld
+    return t.data_ptr(), n, d, ld
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _same_layout(ref, other, name):
+    if other.shape != ref.shape or (ref.shape[0] > 1 and other.stride(0) != ref.stride(0)) or other.dtype != ref.dtype:
+        raise ValueError("%s must match the shape, row stride and dtype of X_in" % name)
+
+
+def bf_neighbor_allreduce(t, rnd, X_in, X_out, stream=None):
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _same_layout(X_in, X_out, "X_out")
+    _check(lib.bf_neighbor_allreduce(t.handle, rnd, ptr, X_out.data_ptr(), d, ld, _dtype_code(X_in),
+                                     _stream(stream)), "bf_neighbor_allreduce")
+    return X_out
+
+
+def bf_dense_mix(t, rnd, X_in, X_out, stream=None):
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _same_layout(X_in, X_out, "X_out")
+    _check(lib.bf_dense_mix(t.handle, rnd, ptr, X_out.data_ptr(), d, ld, _dtype_code(X_in), _stream(stream)),
+           "bf_dense_mix")
+    return X_out
+
+
+def bf_pushsum_step(t, rnd, X_in, X_out, w_in, w_out, Y=None, stream=None):
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _same_layout(X_in, X_out, "X_out")
+    if Y is not None:
+        _same_layout(X_in, Y, "Y")
+    _check(lib.bf_pushsum_step(t.handle, rnd, ptr, X_out.data_ptr(), w_in.data_ptr(), w_out.data_ptr(),
+                               None if Y is None else Y.data_ptr(), d, ld, _dtype_code(X_in), _stream(stream)),
+           "bf_pushsum_step")
+    return X_out, w_out, Y
+
+
+def bf_atc_step(t, rnd, X_in, X_out, G, M=None, alpha=0.0, beta=0.0, mode=BF_ATC, stream=None):
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _same_layout(X_in, X_out, "X_out")
+    _same_layout(X_in, G, "G")
+    if M is not None:
+        import torch
+        if M.dtype != torch.float32 or M.shape != X_in.shape or (n > 1 and M.stride(0) != ld):
+            raise ValueError("M must be float32 with the shape and row stride of X_in")
+    _check(lib.bf_atc_step(t.handle, rnd, ptr, X_out.data_ptr(), G.data_ptr(),
+                           None if M is None else M.data_ptr(), alpha, beta, mode, d, ld,
+                           _dtype_code(X_in), _stream(stream)), "bf_atc_step")
+    return X_out
+
+
+def bf_grad_least_squares(A, b, X, G, stream=None):
+    n, m, d = A.shape
+    xp, xn, xd, ldx = _mat(X, "X")
+    gp, gn, gd, ldg = _mat(G, "G")
+    if not A.is_contiguous() or not b.is_contiguous() or (xn, xd) != (n, d) or (gn, gd) != (n, d) or tuple(b.shape) != (n, m):
+        raise ValueError("shapes: A (n,m,d) contiguous, b (n,m) contiguous, X and G (n,d)")
+    _check(lib.bf_grad_least_squares(n, m, d, A.data_ptr(), b.data_ptr(), xp, ldx, gp, ldg, _stream(stream)),
+           "bf_grad_least_squares")
+    return G
+
+
+def bf_grad_quadratic(X, Cc, E, lam, sigma, G, stream=None):
+    ptr, n, d, ld = _mat(X, "X")
+    for nm, o in (("C", Cc), ("E", E), ("G", G)):
+        _same_layout(X, o, nm)
+    _check(lib.bf_grad_quadratic(n, d, ld, ptr, Cc.data_ptr(), E.data_ptr(), lam, sigma, G.data_ptr(),
+                                 _dtype_code(X), _stream(stream)), "bf_grad_quadratic")
+    return G
+
+
+def bf_consensus_stats(X, p=None, stats=None, mean_out=None, stream=None):
+    """stats: float64 device tensor of 3 (sum of squared deviations, max deviation, max |y|)."""
+    import torch
+    ptr, n, d, ld = _mat(X, "X")
+    if stats is None:
+        stats = torch.empty(3, dtype=torch.float64, device=X.device)
+    _check(lib.bf_consensus_stats(n, d, ld, ptr, None if p is None else p.data_ptr(), _dtype_code(X),
+                                  stats.data_ptr(), None if mean_out is None else mean_out.data_ptr(),
+                                  _stream(stream)), "bf_consensus_stats")
+    return stats
+
+
+def bf_set_tuning(knob, value):
+    _check(lib.bf_set_tuning(knob, value), "bf_set_tuning")

@@ -1,0 +1,52 @@
+// Private to libbf: host-side representation of a topology and the launch interface between the
+// C-ABI layer (argument checks, dispatch) and the HIP kernels.
+#ifndef BF_INTERNAL_H_
+#define BF_INTERNAL_H_
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "bf.h"
+
+namespace bf {
+
+// One weight matrix W^(r) as receiver-major CSR: row i lists (j, w_ij), j ascending.
+struct Round {
+  std::vector<int64_t> rowptr;   // n+1
+  std::vector<int32_t> col;      // nnz
+  std::vector<float>   wgt;      // nnz
+  int32_t max_degree = 0;
+  int32_t wclass = 0;            // bf_wclass_t bit mask
+};
+
+// Device-resident copy of all rounds, built on first use on a device.
+struct DeviceCopy {
+  int      device = -1;
+  char*    blob = nullptr;               // [round]: int32 rowptr[n+1] (padded to 8 B) | {int32 col, f32 w}[nnz]
+  std::vector<size_t> rowptr_off;        // byte offsets into blob, per round
+  std::vector<size_t> entry_off;
+  float*   dense_t = nullptr;            // [round][k][i] = w_ik, n_pad x n_pad, lazily built
+  int32_t  n_pad = 0;
+};
+
+}  // namespace bf
+
+struct bf_topology {
+  int32_t  n = 0;
+  int32_t  kind = 0;
+  uint64_t accepted_seed = 0;
+  std::vector<bf::Round> rounds;
+  std::mutex mu;                          // guards dev
+  std::vector<bf::DeviceCopy> dev;
+};
+
+namespace bf {
+
+// Host-only helpers implemented in bf_topology.cpp.
+int  finalize_round(Round& r, int32_t n);           // sort check, class, max degree; returns status
+void dense_transposed(const Round& r, int32_t n, int32_t n_pad, float* out);  // out[k*n_pad+i] = w_ik
+
+}  // namespace bf
+
+#endif  // BF_INTERNAL_H_

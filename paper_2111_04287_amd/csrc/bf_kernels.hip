@@ -1,0 +1,1065 @@
+// HIP kernels of libbf for gfx950 (MI355X) and their C-ABI entry points.
+//
+// Core idea.  Partial averaging X_out = W X_in (eq. dsgd-2) is column separable: column c of the
+// result depends on column c of the input only.  A workgroup therefore owns a tile of C columns for
+// ALL n agents: it streams the n x C tile from HBM once (16-byte loads, long coalesced row
+// segments), forms the local update x_j - alpha g_j (eq. dsgd-1 / eq. eq.atc) while staging the
+// tile into LDS, then produces every output row of the tile from LDS -- one wave per (row, 64-lane
+// span), the row's in-neighbor list read through the scalar cache, accumulation in registers --
+// and writes each output element once.  HBM traffic is the compulsory read-once / write-once; the
+// (nnz) x d gather traffic stays inside LDS.  Because no other workgroup touches those columns the
+// update may be in place.
+//
+// Workgroups are persistent: tile t+1's global loads are issued into registers before tile t is
+// reduced, so HBM requests are in flight during the LDS phase.
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+
+#include "bf_internal.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+thread_local int g_last_hip_error = 0;
+
+#define BF_HIP_TRY(expr)                                  \
+  do {                                                    \
+    hipError_t e_ = (expr);                               \
+    if (e_ != hipSuccess) {                               \
+      g_last_hip_error = static_cast<int>(e_);            \
+      return BF_ERR_HIP;                                  \
+    }                                                     \
+  } while (0)
+
+// ---------------------------------------------------------------------------------------------
+// bf16 <-> fp32 (bfloat16 = upper half of binary32; round to nearest, ties to even)
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xFFFF0000u); }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;   // quiet NaN
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// Scalar-cache view of the topology: uniform addresses into these become s_load instructions.
+typedef const int32_t __attribute__((address_space(4)))* csr_i32_ptr;
+typedef const u32x2 __attribute__((address_space(4)))* csr_ent_ptr;
+
+enum { OP_MIX = 0, OP_ATC = 1, OP_AWC = 2, OP_MOM_ATC = 3, OP_MOM_AWC = 4 };
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+struct TileParams {
+  const char* x_in;      // n x ld, dtype DT
+  char*       x_out;
+  const char* g;         // gradient, dtype DT (ATC/AWC/momentum)
+  float*      m;         // momentum, fp32 (momentum ops)
+  char*       y;         // push-sum ratio output, dtype DT (optional)
+  const float* p_out;    // push-sum weights after this round (for y)
+  const int32_t* rowptr; // device CSR of the round
+  const u32x2*   ent;    // {col, weight bits}
+  int64_t d, ld;
+  int64_t ntiles;
+  int32_t n;
+  int32_t log_c;         // tile width C = 1 << log_c elements
+  float alpha, beta;
+};
+
+template <int DT> struct Elem { static constexpr int bytes = DT == DT_F32 ? 4 : 2; static constexpr int per16 = 16 / bytes; };
+
+// Load 16 bytes of X/G and widen to fp32.
+template <int DT>
+__device__ __forceinline__ void widen(const u32x4& raw, float* out) {
+  if constexpr (DT == DT_F32) {
+    out[0] = __uint_as_float(raw.x); out[1] = __uint_as_float(raw.y);
+    out[2] = __uint_as_float(raw.z); out[3] = __uint_as_float(raw.w);
+  } else {
+    out[0] = bf16_lo(raw.x); out[1] = bf16_hi(raw.x); out[2] = bf16_lo(raw.y); out[3] = bf16_hi(raw.y);
+    out[4] = bf16_lo(raw.z); out[5] = bf16_hi(raw.z); out[6] = bf16_lo(raw.w); out[7] = bf16_hi(raw.w);
+  }
+}
+
+// Store LW consecutive results of dtype DT at element offset `off` of row base `base`;
+// `valid` = how many of them lie below d.
+template <int DT, int LW>
+__device__ __forceinline__ void store_out(char* base, int64_t off, const float* v, int valid) {
+  if constexpr (DT == DT_F32) {
+    float* ptr = reinterpret_cast<float*>(base) + off;
+    if (valid >= LW) {
+      if constexpr (LW == 4) { f32x4 t = {v[0], v[1], v[2], v[3]}; *reinterpret_cast<f32x4*>(ptr) = t; }
+      else if constexpr (LW == 2) { f32x2 t = {v[0], v[1]}; *reinterpret_cast<f32x2*>(ptr) = t; }
+      else { ptr[0] = v[0]; }
+    } else {
+      for (int k = 0; k < LW; ++k) if (k < valid) ptr[k] = v[k];
+    }
+  } else {
+    uint16_t* ptr = reinterpret_cast<uint16_t*>(base) + off;
+    if (valid >= LW) {
+      if constexpr (LW == 4) { u32x2 t = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; *reinterpret_cast<u32x2*>(ptr) = t; }
+      else if constexpr (LW == 2) { *reinterpret_cast<uint32_t*>(ptr) = pack_bf16x2(v[0], v[1]); }
+      else { ptr[0] = static_cast<uint16_t>(f32_to_bf16_bits(v[0])); }
+    } else {
+      for (int k = 0; k < LW; ++k) if (k < valid) ptr[k] = static_cast<uint16_t>(f32_to_bf16_bits(v[k]));
+    }
+  }
+}
+
+// Load LW consecutive values of dtype DT (all below ld, so in bounds) and widen.
+template <int DT, int LW>
+__device__ __forceinline__ void load_in(const char* base, int64_t off, float* v) {
+  if constexpr (DT == DT_F32) {
+    const float* ptr = reinterpret_cast<const float*>(base) + off;
+    if constexpr (LW == 4) { f32x4 t = *reinterpret_cast<const f32x4*>(ptr); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
+    else if constexpr (LW == 2) { f32x2 t = *reinterpret_cast<const f32x2*>(ptr); v[0] = t.x; v[1] = t.y; }
+    else { v[0] = ptr[0]; }
+  } else {
+    const uint16_t* ptr = reinterpret_cast<const uint16_t*>(base) + off;
+    if constexpr (LW == 4) { u32x2 t = *reinterpret_cast<const u32x2*>(ptr); v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y); }
+    else if constexpr (LW == 2) { uint32_t t = *reinterpret_cast<const uint32_t*>(ptr); v[0] = bf16_lo(t); v[1] = bf16_hi(t); }
+    else { v[0] = __uint_as_float(static_cast<uint32_t>(ptr[0]) << 16); }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The tile kernel.  DT: storage type of X/G/Y.  OP: what is staged and what is subtracted.
+// WITH_Y: also write the push-sum ratio.  LW: columns per lane in the reduce phase (a wave spans
+// 64*LW columns of one output row).  MAXPF: staging units (16-byte vectors of X) per thread.
+template <int DT, int OP, bool WITH_Y, int LW, int THREADS, int MAXPF>
+__global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
+  extern __shared__ f32x4 lds_raw[];
+  float* lds = reinterpret_cast<float*>(lds_raw);
+
+  constexpr int EB = Elem<DT>::bytes;
+  constexpr int UC = Elem<DT>::per16;               // columns per staging unit
+  constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
+  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC);
+  constexpr bool STAGE_M = (OP == OP_MOM_ATC);
+  constexpr int MV = UC / 4;                        // 16-byte vectors of M per unit
+
+  const int tid = threadIdx.x;
+  const int log_c = p.log_c;
+  const int upr_log = log_c - UC_LOG;               // staging units per tile row (log2)
+  const int upr_mask = (1 << upr_log) - 1;
+  const int nunits = p.n << upr_log;
+  const int64_t d = p.d, ld = p.ld;
+
+  u32x4 xr[MAXPF];
+  u32x4 gr[STAGE_G ? MAXPF : 1];
+  f32x4 mr[STAGE_M ? MAXPF * MV : 1];
+
+  // Loads are unconditional (uniform control flow keeps all of a tile's loads in flight at
+  // once): a unit past the tile's end re-reads the last unit, a column at or past d re-reads the
+  // row's last in-range vector.  Only the LDS write and the M store are predicated.
+  const int64_t last_vec = d > 0 ? ((d - 1) >> UC_LOG) << UC_LOG : 0;
+  auto issue_loads = [&](int64_t tile) {
+    const int64_t c0 = tile << log_c;
+#pragma unroll
+    for (int k = 0; k < MAXPF; ++k) {
+      const int u = min(tid + k * THREADS, nunits - 1);
+      const int row = u >> upr_log;
+      const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
+      const int64_t off = static_cast<int64_t>(row) * ld + col;
+      xr[k] = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
+      if constexpr (STAGE_G) gr[k] = *reinterpret_cast<const u32x4*>(p.g + off * EB);
+      if constexpr (STAGE_M) {
+#pragma unroll
+        for (int q = 0; q < MV; ++q) mr[k * MV + q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+      }
+    }
+  };
+
+  // Transform one staging unit (local update, momentum) and put it into the LDS tile.
+  auto stage_unit = [&](int u, int64_t c0, const u32x4& xraw, const u32x4& graw, const f32x4* mraw) {
+    const int row = u >> upr_log;
+    const int cit = (u & upr_mask) << UC_LOG;       // column inside the tile
+    const int64_t col = c0 + cit;
+    const bool live = u < nunits && col < d;
+    float xv[UC];
+    widen<DT>(xraw, xv);
+    if constexpr (STAGE_G) {
+      float gv[UC];
+      widen<DT>(graw, gv);
+      if constexpr (STAGE_M) {
+        const int64_t off = static_cast<int64_t>(row) * ld + col;
+#pragma unroll
+        for (int q = 0; q < MV; ++q) {
+          f32x4 mv = mraw[q];
+          mv.x = fmaf(p.beta, mv.x, gv[4 * q + 0]);
+          mv.y = fmaf(p.beta, mv.y, gv[4 * q + 1]);
+          mv.z = fmaf(p.beta, mv.z, gv[4 * q + 2]);
+          mv.w = fmaf(p.beta, mv.w, gv[4 * q + 3]);
+          gv[4 * q + 0] = mv.x; gv[4 * q + 1] = mv.y; gv[4 * q + 2] = mv.z; gv[4 * q + 3] = mv.w;
+          if (live) {
+            const int64_t rem = d - (col + 4 * q);
+            if (rem >= 4) *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = mv;
+            else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = gv[4 * q + e];
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
+    }
+    if (live) {
+      float* dst = lds + (row << log_c) + cit;
+#pragma unroll
+      for (int q = 0; q < MV; ++q) {
+        f32x4 t = {xv[4 * q], xv[4 * q + 1], xv[4 * q + 2], xv[4 * q + 3]};
+        *reinterpret_cast<f32x4*>(dst + 4 * q) = t;
+      }
+    }
+  };
+
+  auto stage = [&](int64_t tile) {
+    const int64_t c0 = tile << log_c;
+#pragma unroll
+    for (int k = 0; k < MAXPF; ++k)
+      stage_unit(tid + k * THREADS, c0, xr[k], gr[STAGE_G ? k : 0], &mr[STAGE_M ? k * MV : 0]);
+    // Tiles taller than THREADS*MAXPF units (many agents): the rest is loaded here, unprefetched.
+    for (int u = tid + MAXPF * THREADS; u < nunits; u += THREADS) {
+      const int row = u >> upr_log;
+      const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
+      const int64_t off = static_cast<int64_t>(row) * ld + col;
+      const u32x4 xraw = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
+      u32x4 graw = {0, 0, 0, 0};
+      f32x4 mraw[MV];
+      if constexpr (STAGE_G) graw = *reinterpret_cast<const u32x4*>(p.g + off * EB);
+      if constexpr (STAGE_M) {
+#pragma unroll
+        for (int q = 0; q < MV; ++q) mraw[q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+      }
+      stage_unit(u, c0, xraw, graw, mraw);
+    }
+  };
+
+  const csr_i32_ptr rowptr = (csr_i32_ptr)(uintptr_t)p.rowptr;
+  const csr_ent_ptr ent = (csr_ent_ptr)(uintptr_t)p.ent;
+
+  auto reduce_and_store = [&](int64_t tile) {
+    constexpr int NW = THREADS / 64;
+    constexpr int SPAN_LOG = (LW == 4 ? 8 : (LW == 2 ? 7 : 6));      // log2(64*LW)
+    const int64_t c0 = tile << log_c;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int spans_log = log_c - SPAN_LOG;
+    const int nops = p.n << spans_log;
+    for (int op = wave; op < nops; op += NW) {
+      const int i = op >> spans_log;
+      const int cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
+      const int64_t col = c0 + cit;
+      const int beg = rowptr[i], end = rowptr[i + 1];
+      float acc[LW];
+#pragma unroll
+      for (int e = 0; e < LW; ++e) acc[e] = 0.0f;
+      const float* src = lds + cit;
+#pragma unroll 4
+      for (int q = beg; q < end; ++q) {
+        const u32x2 en = ent[q];
+        const float w = __uint_as_float(en.y);
+        const float* s = src + (static_cast<int>(en.x) << log_c);
+        if constexpr (LW == 4) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(s);
+          acc[0] = fmaf(w, v.x, acc[0]); acc[1] = fmaf(w, v.y, acc[1]);
+          acc[2] = fmaf(w, v.z, acc[2]); acc[3] = fmaf(w, v.w, acc[3]);
+        } else if constexpr (LW == 2) {
+          const f32x2 v = *reinterpret_cast<const f32x2*>(s);
+          acc[0] = fmaf(w, v.x, acc[0]); acc[1] = fmaf(w, v.y, acc[1]);
+        } else {
+          acc[0] = fmaf(w, s[0], acc[0]);
+        }
+      }
+      if (col < d) {
+        const int64_t rem = d - col;
+        const int valid = rem >= LW ? LW : static_cast<int>(rem);
+        const int64_t off = static_cast<int64_t>(i) * ld + col;
+        if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
+          // Adapt-while-communicate: the receiver's own gradient is subtracted after the mix.
+          float gv[LW];
+          load_in<DT, LW>(p.g, off, gv);
+          if constexpr (OP == OP_MOM_AWC) {
+            float mv[LW];
+            load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), off, mv);
+#pragma unroll
+            for (int e = 0; e < LW; ++e) gv[e] = fmaf(p.beta, mv[e], gv[e]);
+            store_out<DT_F32, LW>(reinterpret_cast<char*>(p.m), off, gv, valid);
+          }
+#pragma unroll
+          for (int e = 0; e < LW; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);
+        }
+        store_out<DT, LW>(p.x_out, off, acc, valid);
+        if constexpr (WITH_Y) {
+          const float rcp = 1.0f / p.p_out[i];
+          float yv[LW];
+#pragma unroll
+          for (int e = 0; e < LW; ++e) yv[e] = acc[e] * rcp;
+          store_out<DT, LW>(p.y, off, yv, valid);
+        }
+      }
+    }
+  };
+
+  int64_t tile = blockIdx.x;
+  if (tile < p.ntiles) issue_loads(tile);
+  while (tile < p.ntiles) {
+    stage(tile);
+    __syncthreads();
+    const int64_t next = tile + gridDim.x;
+    if (next < p.ntiles) issue_loads(next);
+    reduce_and_store(tile);
+    __syncthreads();
+    tile = next;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fallback for agent counts whose n x 64 tile does not fit LDS: a plain row gather.  Each thread
+// owns one 16-byte vector of one output row and walks the row's in-neighbor list, reading neighbor
+// vectors from global memory (re-reads are served by L2 / Infinity Cache as far as they fit).
+// Out of place only.  For the momentum ops M has already been advanced by bf_momentum_kernel and
+// stands in for the gradient.
+template <int DT, int OP, bool WITH_Y>
+__global__ __launch_bounds__(256) void bf_gather_kernel(const TileParams p) {
+  constexpr int EB = Elem<DT>::bytes;
+  constexpr int UC = Elem<DT>::per16;
+  constexpr bool MOM = (OP == OP_MOM_ATC || OP == OP_MOM_AWC);
+  constexpr bool G_IN_SUM = (OP == OP_ATC || OP == OP_MOM_ATC);
+  constexpr bool G_AFTER = (OP == OP_AWC || OP == OP_MOM_AWC);
+  const int64_t d = p.d, ld = p.ld;
+  const int64_t upr = (d + UC - 1) / UC;
+  const int64_t total = upr * p.n;
+  auto load_g = [&](int64_t off, float* gv) {
+    if constexpr (MOM) {
+#pragma unroll
+      for (int q = 0; q < UC / 4; ++q) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+        gv[4 * q] = t.x; gv[4 * q + 1] = t.y; gv[4 * q + 2] = t.z; gv[4 * q + 3] = t.w;
+      }
+    } else {
+      widen<DT>(*reinterpret_cast<const u32x4*>(p.g + off * EB), gv);
+    }
+  };
+  for (int64_t u = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; u < total;
+       u += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    const int i = static_cast<int>(u / upr);
+    const int64_t col = (u % upr) * UC;
+    float acc[UC];
+#pragma unroll
+    for (int e = 0; e < UC; ++e) acc[e] = 0.0f;
+    for (int q = p.rowptr[i]; q < p.rowptr[i + 1]; ++q) {
+      const u32x2 en = p.ent[q];
+      const float w = __uint_as_float(en.y);
+      const int64_t off = static_cast<int64_t>(en.x) * ld + col;
+      float xv[UC];
+      widen<DT>(*reinterpret_cast<const u32x4*>(p.x_in + off * EB), xv);
+      if constexpr (G_IN_SUM) {
+        float gv[UC];
+        load_g(off, gv);
+#pragma unroll
+        for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
+      }
+#pragma unroll
+      for (int e = 0; e < UC; ++e) acc[e] = fmaf(w, xv[e], acc[e]);
+    }
+    const int64_t off = static_cast<int64_t>(i) * ld + col;
+    if constexpr (G_AFTER) {
+      float gv[UC];
+      load_g(off, gv);
+#pragma unroll
+      for (int e = 0; e < UC; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);
+    }
+    const int64_t rem = d - col;
+#pragma unroll
+    for (int h = 0; h < UC / 4; ++h) {
+      const int valid = rem - 4 * h >= 4 ? 4 : (rem - 4 * h > 0 ? static_cast<int>(rem - 4 * h) : 0);
+      if (valid > 0) {
+        store_out<DT, 4>(p.x_out, off + 4 * h, acc + 4 * h, valid);
+        if constexpr (WITH_Y) {
+          const float rcp = 1.0f / p.p_out[i];
+          float yv[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) yv[e] = acc[4 * h + e] * rcp;
+          store_out<DT, 4>(p.y, off + 4 * h, yv, valid);
+        }
+      }
+    }
+  }
+}
+
+// M <- beta M + G, elementwise (pre-pass of the gather fallback's momentum ops).
+template <int DT>
+__global__ __launch_bounds__(256) void bf_momentum_kernel(float* M, const char* G, int n, int64_t d, int64_t ld, float beta) {
+  constexpr int EB = Elem<DT>::bytes;
+  const int64_t upr = (d + 3) / 4;
+  const int64_t total = upr * n;
+  for (int64_t u = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; u < total;
+       u += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    const int64_t off = (u / upr) * ld + (u % upr) * 4;
+    const int64_t rem = d - (u % upr) * 4;
+    float gv[4], mv[4];
+    load_in<DT, 4>(G, off, gv);
+    load_in<DT_F32, 4>(reinterpret_cast<const char*>(M), off, mv);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) mv[e] = fmaf(beta, mv[e], gv[e]);
+    store_out<DT_F32, 4>(reinterpret_cast<char*>(M), off, mv, rem >= 4 ? 4 : static_cast<int>(rem));
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Push-sum weights: w_out = W w_in for n scalars (the p_i of the push-sum recursion).  One
+// workgroup; w_in is copied to LDS first so that w_out may be w_in.
+__global__ __launch_bounds__(1024) void bf_pushsum_w_kernel(const int32_t* rowptr, const u32x2* ent,
+                                                           const float* w_in, float* w_out, int n) {
+  extern __shared__ f32x4 lds_raw[];
+  float* wl = reinterpret_cast<float*>(lds_raw);
+  for (int i = threadIdx.x; i < n; i += blockDim.x) wl[i] = w_in[i];
+  __syncthreads();
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    float acc = 0.0f;
+    for (int q = rowptr[i]; q < rowptr[i + 1]; ++q) {
+      const u32x2 en = ent[q];
+      acc = fmaf(__uint_as_float(en.y), wl[en.x], acc);
+    }
+    w_out[i] = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dense W on the fp32 matrix cores: X_out tile (n_pad x 64) = W (n_pad x n_pad) * X tile.
+// v_mfma_f32_32x32x2_f32 operand layout (wave64): A lane l holds A[l%32][l/32], B lane l holds
+// B[l/32][l%32], D register v of lane l holds D[8*(v/4) + 4*(l/32) + v%4][l%32].
+// wt is W transposed and zero padded (wt[k*n_pad + i] = w_ik) so A operands load coalesced.
+__global__ __launch_bounds__(256) void bf_dense_kernel(const float* x_in, float* x_out, const float* wt,
+                                                      int n, int n_pad, int64_t d, int64_t ld,
+                                                      int64_t ntiles) {
+  extern __shared__ f32x4 lds_raw[];
+  float* lds = reinterpret_cast<float*>(lds_raw);       // n_pad x 64
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, lh = lane >> 5;
+  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int64_t c0 = tile * 64;
+    // stage: 16 float4 per row
+    for (int u = tid; u < n_pad * 16; u += 256) {
+      const int row = u >> 4, cit = (u & 15) * 4;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (row < n && c0 + cit < d) v = *reinterpret_cast<const f32x4*>(x_in + static_cast<int64_t>(row) * ld + c0 + cit);
+      *reinterpret_cast<f32x4*>(lds + row * 64 + cit) = v;
+    }
+    __syncthreads();
+    for (int ib = wave; ib < n_pad / 32; ib += 4) {
+      f32x16 acc0 = {0}, acc1 = {0};
+      const float* wa = wt + ib * 32 + l32;
+      for (int k = 0; k < n_pad; k += 2) {
+        const float a = wa[static_cast<size_t>(k + lh) * n_pad];
+        const float b0 = lds[(k + lh) * 64 + l32];
+        const float b1 = lds[(k + lh) * 64 + 32 + l32];
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = ib * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+        if (row < n) {
+          float* o = x_out + static_cast<int64_t>(row) * ld + c0;
+          if (c0 + l32 < d) o[l32] = acc0[v];
+          if (c0 + 32 + l32 < d) o[32 + l32] = acc1[v];
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Least-squares gradient g_i = A_i^T (A_i x_i - b_i) (eq. dgd-1).  One workgroup per agent.
+// Phase 1: one wave per row of A_i forms the residual (fp32 products, per-lane partial sums, wave
+// tree).  Phase 2: each thread owns 4 columns and accumulates A_i^T r over the m rows.
+__global__ __launch_bounds__(1024) void bf_ls_grad_kernel(const float* A, const float* b, const float* X,
+                                                         float* G, int m, int64_t d, int64_t ldx, int64_t ldg) {
+  __shared__ float resid[64];
+  const int i = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+  const float* Ai = A + static_cast<int64_t>(i) * m * d;
+  const float* xi = X + static_cast<int64_t>(i) * ldx;
+  for (int k = wave; k < m; k += nw) {
+    const float* row = Ai + static_cast<int64_t>(k) * d;
+    float s = 0.0f;
+    for (int64_t c = lane * 4; c < d; c += 256) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(row + c);
+      const f32x4 x = *reinterpret_cast<const f32x4*>(xi + c);
+      s = fmaf(a.x, x.x, s); s = fmaf(a.y, x.y, s); s = fmaf(a.z, x.z, s); s = fmaf(a.w, x.w, s);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) resid[k] = s - b[static_cast<int64_t>(i) * m + k];
+  }
+  __syncthreads();
+  float* gi = G + static_cast<int64_t>(i) * ldg;
+  for (int64_t c = static_cast<int64_t>(tid) * 4; c < d; c += static_cast<int64_t>(blockDim.x) * 4) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < m; ++k) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(Ai + static_cast<int64_t>(k) * d + c);
+      const float r = resid[k];
+      acc.x = fmaf(a.x, r, acc.x); acc.y = fmaf(a.y, r, acc.y);
+      acc.z = fmaf(a.z, r, acc.z); acc.w = fmaf(a.w, r, acc.w);
+    }
+    *reinterpret_cast<f32x4*>(gi + c) = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Synthetic gradient G = lam (X - C) + sigma E, elementwise in fp32.
+template <int DT>
+__global__ __launch_bounds__(256) void bf_grad_quadratic_kernel(const char* X, const char* C, const char* E, char* G,
+                                                               int n, int64_t d, int64_t ld, float lam, float sigma) {
+  constexpr int UC = Elem<DT>::per16;
+  constexpr int EB = Elem<DT>::bytes;
+  const int64_t upr = (d + UC - 1) / UC;
+  const int64_t total = upr * n;
+  for (int64_t u = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; u < total;
+       u += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    const int64_t row = u / upr, col = (u % upr) * UC;
+    const int64_t off = row * ld + col;
+    float xv[UC], cv[UC], ev[UC], gv[UC];
+    widen<DT>(*reinterpret_cast<const u32x4*>(X + off * EB), xv);
+    widen<DT>(*reinterpret_cast<const u32x4*>(C + off * EB), cv);
+    widen<DT>(*reinterpret_cast<const u32x4*>(E + off * EB), ev);
+#pragma unroll
+    for (int e = 0; e < UC; ++e) gv[e] = fmaf(sigma, ev[e], lam * (xv[e] - cv[e]));
+    const int64_t rem = d - col;
+    if (rem >= UC) {
+      u32x4 o;
+      if constexpr (DT == DT_F32) {
+        o.x = __float_as_uint(gv[0]); o.y = __float_as_uint(gv[1]); o.z = __float_as_uint(gv[2]); o.w = __float_as_uint(gv[3]);
+      } else {
+        o.x = pack_bf16x2(gv[0], gv[1]); o.y = pack_bf16x2(gv[2], gv[3]);
+        o.z = pack_bf16x2(gv[4], gv[5]); o.w = pack_bf16x2(gv[6], gv[7]);
+      }
+      *reinterpret_cast<u32x4*>(G + off * EB) = o;
+    } else {
+      for (int e = 0; e < UC; ++e)
+        if (e < rem) {
+          if constexpr (DT == DT_F32) reinterpret_cast<float*>(G)[off + e] = gv[e];
+          else reinterpret_cast<uint16_t*>(G)[off + e] = static_cast<uint16_t>(f32_to_bf16_bits(gv[e]));
+        }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Consensus diagnostics in fp64: one thread per column, two passes over the n rows.
+__global__ void bf_stats_clear_kernel(double* stats) {
+  if (threadIdx.x < 3) stats[threadIdx.x] = 0.0;
+}
+
+__device__ __forceinline__ void atomic_max_nonneg(double* addr, double v) {
+  // non-negative doubles order like their bit patterns
+  atomicMax(reinterpret_cast<unsigned long long*>(addr), static_cast<unsigned long long>(__double_as_longlong(v)));
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void bf_stats_kernel(const char* X, const float* p, int n, int64_t d, int64_t ld,
+                                                      double* stats, float* mean_out) {
+  __shared__ double red[3][4];
+  double ss = 0.0, mdev = 0.0, mabs = 0.0;
+  for (int64_t c = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; c < d;
+       c += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    double sum = 0.0;
+    for (int i = 0; i < n; ++i) {
+      float v;
+      load_in<DT, 1>(X, static_cast<int64_t>(i) * ld + c, &v);
+      sum += p ? static_cast<double>(v) / static_cast<double>(p[i]) : static_cast<double>(v);
+    }
+    const double mean = sum / n;
+    if (mean_out) mean_out[c] = static_cast<float>(mean);
+    for (int i = 0; i < n; ++i) {
+      float v;
+      load_in<DT, 1>(X, static_cast<int64_t>(i) * ld + c, &v);
+      const double y = p ? static_cast<double>(v) / static_cast<double>(p[i]) : static_cast<double>(v);
+      const double dev = fabs(y - mean);
+      ss += dev * dev;
+      mdev = fmax(mdev, dev);
+      mabs = fmax(mabs, fabs(y));
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    ss += __shfl_xor(ss, o, 64);
+    mdev = fmax(mdev, __shfl_xor(mdev, o, 64));
+    mabs = fmax(mabs, __shfl_xor(mabs, o, 64));
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) { red[0][wave] = ss; red[1][wave] = mdev; red[2][wave] = mabs; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) { ss += red[0][w]; mdev = fmax(mdev, red[1][w]); mabs = fmax(mabs, red[2][w]); }
+    atomicAdd(&stats[0], ss);
+    atomic_max_nonneg(&stats[1], mdev);
+    atomic_max_nonneg(&stats[2], mabs);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host side: device copies of a topology, launch-shape heuristic, argument checks.
+
+struct DeviceInfo {
+  int cus = 0;
+  size_t lds_per_cu = 0;
+  size_t lds_per_block_optin = 0;
+};
+
+int device_info(int dev, DeviceInfo* out) {
+  static std::mutex mu;
+  static std::vector<std::pair<int, DeviceInfo>> cache;
+  std::lock_guard<std::mutex> lk(mu);
+  for (auto& c : cache)
+    if (c.first == dev) { *out = c.second; return BF_OK; }
+  hipDeviceProp_t prop;
+  BF_HIP_TRY(hipGetDeviceProperties(&prop, dev));
+  DeviceInfo di;
+  di.cus = prop.multiProcessorCount;
+  di.lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+  di.lds_per_block_optin = prop.sharedMemPerBlock;
+  int v = 0;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeSharedMemPerBlockOptin, dev) == hipSuccess && v > 0)
+    di.lds_per_block_optin = std::max<size_t>(di.lds_per_block_optin, static_cast<size_t>(v));
+  cache.emplace_back(dev, di);
+  *out = di;
+  return BF_OK;
+}
+
+int get_device_copy(bf_topology_t* t, bool need_dense, bf::DeviceCopy** out) {
+  int dev = 0;
+  BF_HIP_TRY(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lk(t->mu);
+  bf::DeviceCopy* dc = nullptr;
+  for (auto& c : t->dev)
+    if (c.device == dev) dc = &c;
+  if (!dc) {
+    bf::DeviceCopy c;
+    c.device = dev;
+    size_t bytes = 0;
+    for (auto& r : t->rounds) {
+      c.rowptr_off.push_back(bytes);
+      bytes += ((static_cast<size_t>(t->n) + 1 + 1) / 2) * 8;
+      c.entry_off.push_back(bytes);
+      bytes += r.col.size() * 8;
+    }
+    std::vector<char> host(bytes, 0);
+    for (size_t k = 0; k < t->rounds.size(); ++k) {
+      auto& r = t->rounds[k];
+      int32_t* rp = reinterpret_cast<int32_t*>(host.data() + c.rowptr_off[k]);
+      for (int32_t i = 0; i <= t->n; ++i) rp[i] = static_cast<int32_t>(r.rowptr[i]);
+      uint32_t* en = reinterpret_cast<uint32_t*>(host.data() + c.entry_off[k]);
+      for (size_t q = 0; q < r.col.size(); ++q) {
+        en[2 * q] = static_cast<uint32_t>(r.col[q]);
+        std::memcpy(&en[2 * q + 1], &r.wgt[q], 4);
+      }
+    }
+    BF_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&c.blob), std::max<size_t>(bytes, 16)));
+    hipError_t e = hipMemcpy(c.blob, host.data(), bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(c.blob); g_last_hip_error = e; return BF_ERR_HIP; }
+    t->dev.push_back(std::move(c));
+    dc = &t->dev.back();
+  }
+  if (need_dense && !dc->dense_t) {
+    const int32_t n_pad = (t->n + 31) / 32 * 32;
+    const size_t per = static_cast<size_t>(n_pad) * n_pad;
+    std::vector<float> host(per * t->rounds.size());
+    for (size_t k = 0; k < t->rounds.size(); ++k) bf::dense_transposed(t->rounds[k], t->n, n_pad, host.data() + per * k);
+    float* dptr = nullptr;
+    BF_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&dptr), host.size() * sizeof(float)));
+    hipError_t e = hipMemcpy(dptr, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(dptr); g_last_hip_error = e; return BF_ERR_HIP; }
+    dc->dense_t = dptr;
+    dc->n_pad = n_pad;
+  }
+  *out = dc;
+  return BF_OK;
+}
+
+int g_tune_tile = 0;      // column-tile width override (elements)
+int g_tune_wgs = 0;       // workgroups per CU override
+int g_tune_gather = 0;    // 1: force the gather fallback
+
+struct Shape { int log_c; int lw; int wgs_per_cu; size_t lds_bytes; };
+
+int ilog2(int64_t v) { int l = 0; while ((int64_t{1} << (l + 1)) <= v) ++l; return l; }
+
+// Choose the tile: the widest power-of-two C in [64, 1024] whose n x C fp32 tile fits the LDS share
+// of one of `wgs` workgroups per CU (two 1024-thread workgroups per CU when possible, so one can
+// stream while the other reduces), narrowed while the launch would leave workgroup slots idle.
+int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s) {
+  const size_t lds_cu = di.lds_per_cu ? di.lds_per_cu : 65536;
+  const size_t lds_blk = di.lds_per_block_optin ? di.lds_per_block_optin : lds_cu;
+  int wgs = g_tune_wgs > 0 ? g_tune_wgs : 2;
+  int log_c = -1;
+  if (g_tune_tile > 0) {
+    const int lc = ilog2(g_tune_tile);
+    if ((1 << lc) != g_tune_tile || lc < 6 || lc > 10) return BF_ERR_UNSUPPORTED;
+    const size_t bytes = static_cast<size_t>(n) * g_tune_tile * 4;
+    if (bytes > lds_blk || bytes > lds_cu) return BF_ERR_UNSUPPORTED;
+    if (g_tune_wgs == 0) wgs = static_cast<int>(std::max<size_t>(1, lds_cu / bytes));
+    if (bytes * wgs > lds_cu) return BF_ERR_UNSUPPORTED;
+    log_c = lc;
+  } else {
+    for (; wgs >= 1 && log_c < 0; --wgs) {
+      const size_t budget = std::min(lds_cu / wgs, lds_blk);
+      for (int lc = 10; lc >= 6; --lc)
+        if (static_cast<size_t>(n) * (size_t{1} << lc) * 4 <= budget) { log_c = lc; break; }
+      if (log_c >= 0) break;
+    }
+    if (log_c < 0) return BF_ERR_UNSUPPORTED;
+    wgs = std::max(wgs, 1);
+    const int64_t slots = static_cast<int64_t>(di.cus) * std::min(wgs, 2);
+    while (log_c > 6 && ((d + (int64_t{1} << log_c) - 1) >> log_c) < slots) --log_c;
+  }
+  s->log_c = log_c;
+  s->lw = log_c >= 8 ? 4 : (log_c == 7 ? 2 : 1);
+  s->wgs_per_cu = std::max(1, std::min(wgs, 2));
+  s->lds_bytes = static_cast<size_t>(n) * (size_t{1} << log_c) * 4;
+  return BF_OK;
+}
+
+template <int DT, int OP, bool WITH_Y, int LW>
+int launch_tile_lw(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
+  constexpr int THREADS = 1024;
+  constexpr int MAXPF = DT == DT_F32 ? 4 : 2;   // a 64 KB tile is 4 (fp32) / 2 (bf16) vectors per thread
+  auto kern = bf_tile_kernel<DT, OP, WITH_Y, LW, THREADS, MAXPF>;
+  if (lds > 48 * 1024) {
+    static thread_local size_t raised = 0;
+    if (raised < lds) {
+      BF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     static_cast<int>(lds)));
+      raised = lds;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds, st, tp);
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+template <int DT, int OP, bool WITH_Y>
+int launch_tile(const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
+  switch (s.lw) {
+    case 4: return launch_tile_lw<DT, OP, WITH_Y, 4>(tp, grid, s.lds_bytes, st);
+    case 2: return launch_tile_lw<DT, OP, WITH_Y, 2>(tp, grid, s.lds_bytes, st);
+    default: return launch_tile_lw<DT, OP, WITH_Y, 1>(tp, grid, s.lds_bytes, st);
+  }
+}
+
+template <int DT>
+int launch_tile_op(int op, bool with_y, const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
+  switch (op) {
+    case OP_MIX: return with_y ? launch_tile<DT, OP_MIX, true>(tp, s, grid, st) : launch_tile<DT, OP_MIX, false>(tp, s, grid, st);
+    case OP_ATC: return launch_tile<DT, OP_ATC, false>(tp, s, grid, st);
+    case OP_AWC: return launch_tile<DT, OP_AWC, false>(tp, s, grid, st);
+    case OP_MOM_ATC: return launch_tile<DT, OP_MOM_ATC, false>(tp, s, grid, st);
+    default: return launch_tile<DT, OP_MOM_AWC, false>(tp, s, grid, st);
+  }
+}
+
+// Overlap test on byte ranges [a, a+na) and [b, b+nb).
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+  return pa < pb + nb && pb < pa + na;
+}
+
+struct MatArgs { int64_t d, ld; int dt; int n; size_t bytes; };
+
+// Common checks of an n x d matrix argument set.  Returns the extent in bytes through ma->bytes.
+int check_matrix_shape(int32_t n, int64_t d, int64_t ld, int dt, MatArgs* ma) {
+  if (dt != BF_F32 && dt != BF_BF16) return BF_ERR_KIND;
+  if (d < 0 || ld < d || ld < 1 || ld > (int64_t{1} << 40)) return BF_ERR_SIZE;
+  const int eb = dt == BF_F32 ? 4 : 2;
+  if ((ld * eb) % 16 != 0) return BF_ERR_ALIGN;
+  ma->d = d; ma->ld = ld; ma->dt = dt; ma->n = n;
+  ma->bytes = static_cast<size_t>(n - 1) * ld * eb + static_cast<size_t>(d) * eb;
+  return BF_OK;
+}
+
+bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+template <int DT>
+int launch_gather(int op, bool with_y, const TileParams& tp, int grid, hipStream_t st) {
+#define BF_GATHER(OPV, YV) hipLaunchKernelGGL((bf_gather_kernel<DT, OPV, YV>), dim3(grid), dim3(256), 0, st, tp)
+  switch (op) {
+    case OP_MIX: if (with_y) BF_GATHER(OP_MIX, true); else BF_GATHER(OP_MIX, false); break;
+    case OP_ATC: BF_GATHER(OP_ATC, false); break;
+    case OP_AWC: BF_GATHER(OP_AWC, false); break;
+    case OP_MOM_ATC: BF_GATHER(OP_MOM_ATC, false); break;
+    default: BF_GATHER(OP_MOM_AWC, false); break;
+  }
+#undef BF_GATHER
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp, int dt, hipStream_t st) {
+  if (tp.d == 0) return BF_OK;
+  bf::DeviceCopy* dc = nullptr;
+  int rc = get_device_copy(t, false, &dc);
+  if (rc != BF_OK) return rc;
+  DeviceInfo di;
+  rc = device_info(dc->device, &di);
+  if (rc != BF_OK) return rc;
+  const size_t k = static_cast<size_t>(round) % t->rounds.size();
+  tp.rowptr = reinterpret_cast<const int32_t*>(dc->blob + dc->rowptr_off[k]);
+  tp.ent = reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[k]);
+  tp.n = t->n;
+  Shape s;
+  rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(t->n, tp.d, di, &s);
+  if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
+    // Too many agents for an LDS tile: row gather through the caches, out of place only.
+    if (tp.x_in == tp.x_out) return BF_ERR_UNSUPPORTED;
+    const int per16 = dt == BF_F32 ? 4 : 8;
+    const int64_t units = (tp.d + per16 - 1) / per16 * t->n;
+    const int grid = static_cast<int>(std::min<int64_t>((units + 255) / 256, static_cast<int64_t>(di.cus) * 32));
+    if (op == OP_MOM_ATC || op == OP_MOM_AWC) {
+      const int64_t u4 = (tp.d + 3) / 4 * t->n;
+      const int g2 = static_cast<int>(std::min<int64_t>((u4 + 255) / 256, static_cast<int64_t>(di.cus) * 32));
+      if (dt == BF_F32) hipLaunchKernelGGL(bf_momentum_kernel<DT_F32>, dim3(g2), dim3(256), 0, st, tp.m, tp.g, t->n, tp.d, tp.ld, tp.beta);
+      else hipLaunchKernelGGL(bf_momentum_kernel<DT_BF16>, dim3(g2), dim3(256), 0, st, tp.m, tp.g, t->n, tp.d, tp.ld, tp.beta);
+      BF_HIP_TRY(hipGetLastError());
+    }
+    return dt == BF_F32 ? launch_gather<DT_F32>(op, with_y, tp, grid, st) : launch_gather<DT_BF16>(op, with_y, tp, grid, st);
+  }
+  if (rc != BF_OK) return rc;
+  tp.log_c = s.log_c;
+  tp.ntiles = (tp.d + (int64_t{1} << s.log_c) - 1) >> s.log_c;
+  const int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus) * s.wgs_per_cu));
+  return dt == BF_F32 ? launch_tile_op<DT_F32>(op, with_y, tp, s, grid, st)
+                      : launch_tile_op<DT_BF16>(op, with_y, tp, s, grid, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int bf_last_hip_error(void) { return g_last_hip_error; }
+
+int bf_set_tuning(int32_t knob, int32_t value) {
+  if (value < 0) return BF_ERR_SIZE;
+  if (knob == 0) g_tune_tile = value;
+  else if (knob == 1) g_tune_wgs = value;
+  else if (knob == 2) g_tune_gather = value;
+  else return BF_ERR_KIND;
+  return BF_OK;
+}
+
+int bf_topology_destroy(bf_topology_t* t) {
+  if (!t) return BF_OK;
+  int rc = BF_OK;
+  for (auto& c : t->dev) {
+    if (c.blob && hipFree(c.blob) != hipSuccess) rc = BF_ERR_HIP;
+    if (c.dense_t && hipFree(c.dense_t) != hipSuccess) rc = BF_ERR_HIP;
+  }
+  delete t;
+  return rc;
+}
+
+int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                          int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  if (!t || !X_in || !X_out) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  MatArgs ma;
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
+  if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (t->kind == BF_DENSE_USER && dt == BF_F32 && t->n <= 256)
+    return bf_dense_mix(t, round, X_in, X_out, d, ld, dt, hip_stream);
+  TileParams tp{};
+  tp.x_in = static_cast<const char*>(X_in);
+  tp.x_out = static_cast<char*>(X_out);
+  tp.d = d; tp.ld = ld;
+  return run_tile(const_cast<bf_topology_t*>(t), round, OP_MIX, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                 int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  if (!t || !X_in || !X_out) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  MatArgs ma;
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (dt != BF_F32 || t->n > 256) return BF_ERR_UNSUPPORTED;
+  if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
+  if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (d == 0) return BF_OK;
+  bf::DeviceCopy* dc = nullptr;
+  rc = get_device_copy(const_cast<bf_topology_t*>(t), true, &dc);
+  if (rc != BF_OK) return rc;
+  DeviceInfo di;
+  rc = device_info(dc->device, &di);
+  if (rc != BF_OK) return rc;
+  const int n_pad = dc->n_pad;
+  const size_t lds = static_cast<size_t>(n_pad) * 64 * 4;
+  const size_t k = static_cast<size_t>(round) % t->rounds.size();
+  const float* wt = dc->dense_t + k * static_cast<size_t>(n_pad) * n_pad;
+  const int64_t ntiles = (d + 63) / 64;
+  if (lds > 48 * 1024) {
+    static thread_local size_t raised = 0;
+    if (raised < lds) {
+      BF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bf_dense_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+      raised = lds;
+    }
+  }
+  const int per_cu = std::max<int>(1, static_cast<int>(std::min<size_t>(8, (di.lds_per_cu ? di.lds_per_cu : 65536) / lds)));
+  const int grid = static_cast<int>(std::min<int64_t>(ntiles, static_cast<int64_t>(di.cus) * per_cu));
+  hipLaunchKernelGGL(bf_dense_kernel, dim3(grid), dim3(256), lds, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const float*>(X_in), static_cast<float*>(X_out), wt, t->n, n_pad, d, ld, ntiles);
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+int bf_pushsum_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                    const float* w_in, float* w_out, void* Y, int64_t d, int64_t ld,
+                    bf_dtype_t dt, void* hip_stream) {
+  if (!t || !X_in || !X_out || !w_in || !w_out) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  MatArgs ma;
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (misaligned16(X_in) || misaligned16(X_out) || (Y && misaligned16(Y))) return BF_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(w_in) & 3u) || (reinterpret_cast<uintptr_t>(w_out) & 3u)) return BF_ERR_ALIGN;
+  const size_t wb = static_cast<size_t>(t->n) * 4;
+  if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (w_in != w_out && overlaps(w_in, wb, w_out, wb)) return BF_ERR_ALIAS;
+  if (overlaps(w_out, wb, X_out, ma.bytes) || overlaps(w_out, wb, X_in, ma.bytes) ||
+      overlaps(w_in, wb, X_out, ma.bytes))
+    return BF_ERR_ALIAS;
+  if (Y && (overlaps(Y, ma.bytes, X_in, ma.bytes) || overlaps(Y, ma.bytes, X_out, ma.bytes) ||
+            overlaps(Y, ma.bytes, w_in, wb) || overlaps(Y, ma.bytes, w_out, wb)))
+    return BF_ERR_ALIAS;
+  if (static_cast<size_t>(t->n) * 4 > 160 * 1024) return BF_ERR_UNSUPPORTED;
+  bf_topology_t* tt = const_cast<bf_topology_t*>(t);
+  bf::DeviceCopy* dc = nullptr;
+  rc = get_device_copy(tt, false, &dc);
+  if (rc != BF_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const size_t k = static_cast<size_t>(round) % t->rounds.size();
+  const size_t wl = std::max<size_t>(wb, 16);
+  if (wl > 48 * 1024) {
+    static thread_local size_t raised = 0;
+    if (raised < wl) {
+      BF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bf_pushsum_w_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(wl)));
+      raised = wl;
+    }
+  }
+  // w first (one small workgroup, in-place safe); the tile kernel then reads w_out for the ratio.
+  hipLaunchKernelGGL(bf_pushsum_w_kernel, dim3(1), dim3(1024), wl, st,
+                     reinterpret_cast<const int32_t*>(dc->blob + dc->rowptr_off[k]),
+                     reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[k]), w_in, w_out, t->n);
+  BF_HIP_TRY(hipGetLastError());
+  TileParams tp{};
+  tp.x_in = static_cast<const char*>(X_in);
+  tp.x_out = static_cast<char*>(X_out);
+  tp.y = static_cast<char*>(Y);
+  tp.p_out = w_out;
+  tp.d = d; tp.ld = ld;
+  return run_tile(tt, round, OP_MIX, Y != nullptr, tp, dt, st);
+}
+
+int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld,
+                bf_dtype_t dt, void* hip_stream) {
+  if (!t || !X_in || !X_out || !G) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  if (mode != BF_ATC && mode != BF_AWC) return BF_ERR_KIND;
+  MatArgs ma;
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if ((ld * 4) % 16 != 0 && M) return BF_ERR_ALIGN;
+  if (misaligned16(X_in) || misaligned16(X_out) || misaligned16(G) || (M && misaligned16(M))) return BF_ERR_ALIGN;
+  const size_t mb = static_cast<size_t>(t->n - 1) * ld * 4 + static_cast<size_t>(d) * 4;
+  if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (overlaps(G, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (M && (overlaps(M, mb, X_out, ma.bytes) || overlaps(M, mb, X_in, ma.bytes) || overlaps(M, mb, G, ma.bytes)))
+    return BF_ERR_ALIAS;
+  TileParams tp{};
+  tp.x_in = static_cast<const char*>(X_in);
+  tp.x_out = static_cast<char*>(X_out);
+  tp.g = static_cast<const char*>(G);
+  tp.m = M;
+  tp.alpha = alpha; tp.beta = beta;
+  tp.d = d; tp.ld = ld;
+  const int op = M ? (mode == BF_ATC ? OP_MOM_ATC : OP_MOM_AWC) : (mode == BF_ATC ? OP_ATC : OP_AWC);
+  return run_tile(const_cast<bf_topology_t*>(t), round, op, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int bf_grad_least_squares(int32_t n, int32_t m, int64_t d, const float* A, const float* b,
+                          const float* X, int64_t ldx, float* G, int64_t ldg, void* hip_stream) {
+  if (!A || !b || !X || !G) return BF_ERR_NULL;
+  if (n < 1 || m < 1 || m > 64 || d < 0 || (d % 4) != 0 || ldx < d || ldg < d) return BF_ERR_SIZE;
+  if ((ldx % 4) != 0 || (ldg % 4) != 0) return BF_ERR_ALIGN;
+  if (misaligned16(A) || misaligned16(X) || misaligned16(G) || (reinterpret_cast<uintptr_t>(b) & 3u)) return BF_ERR_ALIGN;
+  const size_t xb = (static_cast<size_t>(n - 1) * ldx + d) * 4, gb = (static_cast<size_t>(n - 1) * ldg + d) * 4;
+  const size_t ab = static_cast<size_t>(n) * m * d * 4, bb = static_cast<size_t>(n) * m * 4;
+  if (overlaps(G, gb, X, xb) || overlaps(G, gb, A, ab) || overlaps(G, gb, b, bb)) return BF_ERR_ALIAS;
+  if (d == 0) return BF_OK;
+  hipLaunchKernelGGL(bf_ls_grad_kernel, dim3(n), dim3(1024), 0, static_cast<hipStream_t>(hip_stream),
+                     A, b, X, G, m, d, ldx, ldg);
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+int bf_grad_quadratic(int32_t n, int64_t d, int64_t ld, const void* X, const void* C, const void* E,
+                      float lam, float sigma, void* G, bf_dtype_t dt, void* hip_stream) {
+  if (!X || !C || !E || !G) return BF_ERR_NULL;
+  if (n < 1) return BF_ERR_SIZE;
+  MatArgs ma;
+  int rc = check_matrix_shape(n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (misaligned16(X) || misaligned16(C) || misaligned16(E) || misaligned16(G)) return BF_ERR_ALIGN;
+  if (overlaps(G, ma.bytes, X, ma.bytes) || overlaps(G, ma.bytes, C, ma.bytes) || overlaps(G, ma.bytes, E, ma.bytes))
+    return BF_ERR_ALIAS;
+  if (d == 0) return BF_OK;
+  const int per16 = dt == BF_F32 ? 4 : 8;
+  const int64_t units = (d + per16 - 1) / per16 * n;
+  const int grid = static_cast<int>(std::min<int64_t>((units + 255) / 256, 256 * 32));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (dt == BF_F32)
+    hipLaunchKernelGGL(bf_grad_quadratic_kernel<DT_F32>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X),
+                       static_cast<const char*>(C), static_cast<const char*>(E), static_cast<char*>(G), n, d, ld, lam, sigma);
+  else
+    hipLaunchKernelGGL(bf_grad_quadratic_kernel<DT_BF16>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X),
+                       static_cast<const char*>(C), static_cast<const char*>(E), static_cast<char*>(G), n, d, ld, lam, sigma);
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+int bf_consensus_stats(int32_t n, int64_t d, int64_t ld, const void* X, const float* p, bf_dtype_t dt,
+                       double* stats, float* mean_out, void* hip_stream) {
+  if (!X || !stats) return BF_ERR_NULL;
+  if (n < 1) return BF_ERR_SIZE;
+  MatArgs ma;
+  int rc = check_matrix_shape(n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (misaligned16(X) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return BF_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(bf_stats_clear_kernel, dim3(1), dim3(64), 0, st, stats);
+  BF_HIP_TRY(hipGetLastError());
+  if (d == 0) return BF_OK;
+  const int grid = static_cast<int>(std::min<int64_t>((d + 255) / 256, 256 * 16));
+  if (dt == BF_F32)
+    hipLaunchKernelGGL(bf_stats_kernel<DT_F32>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X), p, n, d, ld, stats, mean_out);
+  else
+    hipLaunchKernelGGL(bf_stats_kernel<DT_BF16>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X), p, n, d, ld, stats, mean_out);
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+}  // extern "C"

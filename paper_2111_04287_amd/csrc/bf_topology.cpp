@@ -1,0 +1,456 @@
+// Host side of libbf: topology generators, weight-matrix checks and CSR export.
+// Plain C++17; nothing in this file touches the GPU, so every path here runs on a CPU-only host.
+//
+// Definitions follow the paper's sections "Network topology" (in-coming sets N(i), out-going sets
+// M(j)) and "Weight matrix" (w_ij is nonzero only on an edge j -> i or on the diagonal; pull, push
+// and standard classes).  The named graphs are the ones the benchmark configurations define.
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <utility>
+
+#include "bf_internal.h"
+
+namespace bf {
+
+namespace {
+
+constexpr double kStochasticTol = 1e-6;
+
+// Turn per-receiver neighbor sets (self excluded) into a uniform-weight round:
+// every entry of row i, the diagonal included, gets 1/(|N(i)|+1).
+Round uniform_round(const std::vector<std::vector<int32_t>>& in_nbrs) {
+  const int32_t n = static_cast<int32_t>(in_nbrs.size());
+  Round r;
+  r.rowptr.assign(n + 1, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    std::vector<int32_t> row(in_nbrs[i]);
+    row.push_back(i);
+    std::sort(row.begin(), row.end());
+    row.erase(std::unique(row.begin(), row.end()), row.end());
+    const float w = static_cast<float>(1.0 / static_cast<double>(row.size()));
+    for (int32_t j : row) {
+      r.col.push_back(j);
+      r.wgt.push_back(w);
+    }
+    r.rowptr[i + 1] = static_cast<int64_t>(r.col.size());
+  }
+  return r;
+}
+
+std::vector<int32_t> powers_of_two_below(int32_t n) {
+  std::vector<int32_t> v;
+  for (int64_t p = 1; p < n; p *= 2) v.push_back(static_cast<int32_t>(p));
+  return v;
+}
+
+Round make_ring(int32_t n) {
+  std::vector<std::vector<int32_t>> nb(n);
+  for (int32_t i = 0; i < n; ++i) {
+    nb[i].push_back((i + 1) % n);
+    nb[i].push_back((i + n - 1) % n);
+  }
+  return uniform_round(nb);
+}
+
+Round make_exp_static(int32_t n) {
+  const auto offs = powers_of_two_below(n);
+  std::vector<std::vector<int32_t>> nb(n);
+  for (int32_t i = 0; i < n; ++i)
+    for (int32_t o : offs) {
+      nb[i].push_back(static_cast<int32_t>((static_cast<int64_t>(i) + o) % n));
+      nb[i].push_back(static_cast<int32_t>((static_cast<int64_t>(i) + n - o) % n));
+    }
+  return uniform_round(nb);
+}
+
+// Round r of the one-peer exponential-2 schedule: pull from (i + 2^(r mod R)) mod n, weights 1/2.
+Round make_one_peer(int32_t n, int32_t offset) {
+  Round r;
+  r.rowptr.assign(n + 1, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t j = static_cast<int32_t>((static_cast<int64_t>(i) + offset) % n);
+    if (j == i) {
+      r.col.push_back(i);
+      r.wgt.push_back(1.0f);
+    } else {
+      const int32_t lo = std::min(i, j), hi = std::max(i, j);
+      r.col.push_back(lo);
+      r.wgt.push_back(0.5f);
+      r.col.push_back(hi);
+      r.wgt.push_back(0.5f);
+    }
+    r.rowptr[i + 1] = static_cast<int64_t>(r.col.size());
+  }
+  return r;
+}
+
+struct SplitMix64 {
+  uint64_t s;
+  uint64_t next() {
+    s += 0x9E3779B97F4A7C15ull;
+    uint64_t z = s;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+  }
+};
+
+// out[j] = M(j): out_degree distinct targets other than j, by a Fisher-Yates prefix.
+std::vector<std::vector<int32_t>> draw_targets(int32_t n, int32_t k, uint64_t seed) {
+  SplitMix64 g{seed};
+  std::vector<std::vector<int32_t>> out(n);
+  std::vector<int32_t> cand;
+  cand.reserve(n);
+  for (int32_t j = 0; j < n; ++j) {
+    cand.clear();
+    for (int32_t a = 0; a < n; ++a)
+      if (a != j) cand.push_back(a);
+    for (int32_t t = 0; t < k; ++t) {
+      const uint64_t span = static_cast<uint64_t>(n - 1 - t);
+      const int32_t p = t + static_cast<int32_t>(g.next() % span);
+      std::swap(cand[t], cand[p]);
+    }
+    out[j].assign(cand.begin(), cand.begin() + k);
+  }
+  return out;
+}
+
+bool reaches_all(const std::vector<std::vector<int32_t>>& adj) {
+  const int32_t n = static_cast<int32_t>(adj.size());
+  std::vector<char> seen(n, 0);
+  std::vector<int32_t> stack{0};
+  seen[0] = 1;
+  int32_t count = 1;
+  while (!stack.empty()) {
+    const int32_t u = stack.back();
+    stack.pop_back();
+    for (int32_t v : adj[u])
+      if (!seen[v]) {
+        seen[v] = 1;
+        ++count;
+        stack.push_back(v);
+      }
+  }
+  return count == n;
+}
+
+bool strongly_connected(const std::vector<std::vector<int32_t>>& out) {
+  const int32_t n = static_cast<int32_t>(out.size());
+  if (n == 0) return false;
+  std::vector<std::vector<int32_t>> in(n);
+  for (int32_t j = 0; j < n; ++j)
+    for (int32_t i : out[j]) in[i].push_back(j);
+  return reaches_all(out) && reaches_all(in);
+}
+
+// Column-stochastic W from out-lists: column j holds 1/(k+1) on M(j) and on the diagonal.
+Round push_round_from_targets(const std::vector<std::vector<int32_t>>& out, int32_t k) {
+  const int32_t n = static_cast<int32_t>(out.size());
+  const float w = static_cast<float>(1.0 / (static_cast<double>(k) + 1.0));
+  std::vector<std::vector<int32_t>> rows(n);
+  for (int32_t j = 0; j < n; ++j) {
+    rows[j].push_back(j);
+    for (int32_t i : out[j]) rows[i].push_back(j);
+  }
+  Round r;
+  r.rowptr.assign(n + 1, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    std::sort(rows[i].begin(), rows[i].end());
+    for (int32_t j : rows[i]) {
+      r.col.push_back(j);
+      r.wgt.push_back(w);
+    }
+    r.rowptr[i + 1] = static_cast<int64_t>(r.col.size());
+  }
+  return r;
+}
+
+}  // namespace
+
+int finalize_round(Round& r, int32_t n) {
+  if (static_cast<int32_t>(r.rowptr.size()) != n + 1 || r.rowptr[0] != 0) return BF_ERR_CSR;
+  const int64_t nnz = r.rowptr[n];
+  if (nnz < 0 || nnz != static_cast<int64_t>(r.col.size()) || r.col.size() != r.wgt.size() ||
+      nnz > INT32_MAX)
+    return BF_ERR_CSR;
+  std::vector<double> rs(n, 0.0), cs(n, 0.0);
+  int32_t maxdeg = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const int64_t b = r.rowptr[i], e = r.rowptr[i + 1];
+    if (e < b) return BF_ERR_CSR;
+    maxdeg = std::max<int32_t>(maxdeg, static_cast<int32_t>(e - b));
+    for (int64_t p = b; p < e; ++p) {
+      const int32_t j = r.col[p];
+      if (j < 0 || j >= n) return BF_ERR_CSR;
+      if (p > b && r.col[p - 1] >= j) return BF_ERR_CSR;      // ascending and unique
+      if (!std::isfinite(r.wgt[p])) return BF_ERR_CSR;
+      rs[i] += static_cast<double>(r.wgt[p]);
+      cs[j] += static_cast<double>(r.wgt[p]);
+    }
+  }
+  bool pull = true, push = true;
+  for (int32_t i = 0; i < n; ++i) {
+    if (std::fabs(rs[i] - 1.0) > kStochasticTol) pull = false;
+    if (std::fabs(cs[i] - 1.0) > kStochasticTol) push = false;
+  }
+  r.max_degree = maxdeg;
+  r.wclass = (pull ? BF_W_PULL : 0) | (push ? BF_W_PUSH : 0);
+  return BF_OK;
+}
+
+void dense_transposed(const Round& r, int32_t n, int32_t n_pad, float* out) {
+  std::fill(out, out + static_cast<size_t>(n_pad) * n_pad, 0.0f);
+  for (int32_t i = 0; i < n; ++i)
+    for (int64_t p = r.rowptr[i]; p < r.rowptr[i + 1]; ++p)
+      out[static_cast<size_t>(r.col[p]) * n_pad + i] = r.wgt[p];
+}
+
+}  // namespace bf
+
+using bf::Round;
+
+namespace {
+
+int slice_index(const bf_topology_t* t, int32_t round) {
+  return static_cast<int>(round % static_cast<int32_t>(t->rounds.size()));
+}
+
+int check_class(const Round& r, int32_t required) {
+  if ((required & ~3) != 0) return BF_ERR_KIND;
+  return ((r.wclass & required) == required) ? BF_OK : BF_ERR_NOT_STOCHASTIC;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bf_topology_create(bf_topology_t** out, bf_topo_kind_t kind, int32_t n, const bf_topo_params_t* p) {
+  if (!out) return BF_ERR_NULL;
+  *out = nullptr;
+  if (n < 1 || n > (1 << 20)) return BF_ERR_SIZE;
+  bf_topology_t* t = new (std::nothrow) bf_topology_t();
+  if (!t) return BF_ERR_NOMEM;
+  t->n = n;
+  t->kind = static_cast<int32_t>(kind);
+  t->accepted_seed = p ? p->seed : 0;
+  int st = BF_OK;
+  try {
+    switch (kind) {
+      case BF_RING:
+        t->rounds.push_back(bf::make_ring(n));
+        break;
+      case BF_EXP_STATIC:
+        t->rounds.push_back(bf::make_exp_static(n));
+        break;
+      case BF_EXP2_ONE_PEER: {
+        const auto offs = bf::powers_of_two_below(n);
+        if (offs.empty()) t->rounds.push_back(bf::make_one_peer(n, 0));
+        for (int32_t o : offs) t->rounds.push_back(bf::make_one_peer(n, o));
+        break;
+      }
+      case BF_RANDOM_DIRECTED: {
+        if (!p) { st = BF_ERR_NULL; break; }
+        if (p->out_degree < 0 || p->out_degree > n - 1) { st = BF_ERR_SIZE; break; }
+        const int tries = p->require_strongly_connected ? 10000 : 1;
+        st = BF_ERR_NOT_CONNECTED;
+        for (int a = 0; a < tries; ++a) {
+          const uint64_t s = p->seed + static_cast<uint64_t>(a);
+          auto targets = bf::draw_targets(n, p->out_degree, s);
+          if (!p->require_strongly_connected || bf::strongly_connected(targets)) {
+            t->rounds.push_back(bf::push_round_from_targets(targets, p->out_degree));
+            t->accepted_seed = s;
+            st = BF_OK;
+            break;
+          }
+        }
+        break;
+      }
+      case BF_CSR_USER: {
+        if (!p || !p->rowptr || !p->col || !p->wgt) { st = BF_ERR_NULL; break; }
+        const int32_t R = p->rounds == 0 ? 1 : p->rounds;
+        if (R < 1 || R > 65536) { st = BF_ERR_SIZE; break; }
+        for (int32_t r = 0; r < R && st == BF_OK; ++r) {
+          const int64_t* rp = p->rowptr + static_cast<size_t>(r) * (n + 1);
+          Round rd;
+          rd.rowptr.resize(n + 1);
+          const int64_t base = rp[0];
+          if (base < 0) { st = BF_ERR_CSR; break; }
+          for (int32_t i = 0; i <= n; ++i) {
+            if (rp[i] < base || (i > 0 && rp[i] < rp[i - 1]) || rp[i] - base > INT32_MAX) { st = BF_ERR_CSR; break; }
+            rd.rowptr[i] = rp[i] - base;
+          }
+          if (st != BF_OK) break;
+          rd.col.assign(p->col + base, p->col + rp[n]);
+          rd.wgt.assign(p->wgt + base, p->wgt + rp[n]);
+          t->rounds.push_back(std::move(rd));
+        }
+        break;
+      }
+      case BF_DENSE_USER: {
+        if (!p || !p->dense_w) { st = BF_ERR_NULL; break; }
+        if (n > 4096) { st = BF_ERR_SIZE; break; }
+        const int32_t R = p->rounds == 0 ? 1 : p->rounds;
+        if (R < 1 || R > 65536) { st = BF_ERR_SIZE; break; }
+        for (int32_t r = 0; r < R; ++r) {
+          const float* D = p->dense_w + static_cast<size_t>(r) * n * n;
+          Round rd;
+          rd.rowptr.assign(n + 1, 0);
+          for (int32_t i = 0; i < n; ++i) {
+            for (int32_t j = 0; j < n; ++j) {
+              const float w = D[static_cast<size_t>(i) * n + j];
+              if (w != 0.0f || i == j) {     // w != 0 is also true for NaN: caught by finalize
+                rd.col.push_back(j);
+                rd.wgt.push_back(w);
+              }
+            }
+            rd.rowptr[i + 1] = static_cast<int64_t>(rd.col.size());
+          }
+          t->rounds.push_back(std::move(rd));
+        }
+        break;
+      }
+      default:
+        st = BF_ERR_KIND;
+    }
+    for (auto& r : t->rounds) {
+      if (st != BF_OK) break;
+      st = bf::finalize_round(r, n);
+      if (st == BF_OK && p && (kind == BF_CSR_USER || kind == BF_DENSE_USER))
+        st = check_class(r, p->require_class);
+    }
+  } catch (const std::bad_alloc&) {
+    st = BF_ERR_NOMEM;
+  }
+  if (st != BF_OK) {
+    delete t;
+    return st;
+  }
+  *out = t;
+  return BF_OK;
+}
+
+int bf_topology_create_push_pull(bf_topology_t** out, int32_t n, const float* self_weight,
+                                 const int64_t* src_rowptr, const int32_t* src_rank, const float* src_weight,
+                                 const int64_t* dst_rowptr, const int32_t* dst_rank, const float* dst_weight) {
+  if (!out) return BF_ERR_NULL;
+  *out = nullptr;
+  if (!self_weight || !src_rowptr || !src_rank || !dst_rowptr || !dst_rank) return BF_ERR_NULL;
+  if (n < 1 || n > (1 << 20)) return BF_ERR_SIZE;
+  try {
+    // Structural checks of both views.
+    for (int pass = 0; pass < 2; ++pass) {
+      const int64_t* rp = pass ? dst_rowptr : src_rowptr;
+      const int32_t* rk = pass ? dst_rank : src_rank;
+      if (rp[0] != 0) return BF_ERR_CSR;
+      for (int32_t i = 0; i < n; ++i) {
+        if (rp[i + 1] < rp[i]) return BF_ERR_CSR;
+        for (int64_t q = rp[i]; q < rp[i + 1]; ++q) {
+          if (rk[q] < 0 || rk[q] >= n || rk[q] == i) return BF_ERR_CSR;
+          if (q > rp[i] && rk[q - 1] >= rk[q]) return BF_ERR_CSR;
+        }
+      }
+    }
+    if (src_rowptr[n] != dst_rowptr[n]) return BF_ERR_TOPO_MISMATCH;
+    // The topology check: receiver i lists j as a source  <=>  sender j lists i as a destination.
+    Round rd;
+    rd.rowptr.assign(n + 1, 0);
+    for (int32_t i = 0; i < n; ++i) {
+      bool self_done = false;
+      auto push_self = [&]() {
+        rd.col.push_back(i);
+        rd.wgt.push_back(self_weight[i]);
+        self_done = true;
+      };
+      for (int64_t q = src_rowptr[i]; q < src_rowptr[i + 1]; ++q) {
+        const int32_t j = src_rank[q];
+        const int32_t* b = dst_rank + dst_rowptr[j];
+        const int32_t* e = dst_rank + dst_rowptr[j + 1];
+        const int32_t* hit = std::lower_bound(b, e, i);
+        if (hit == e || *hit != i) return BF_ERR_TOPO_MISMATCH;
+        const float rr = src_weight ? src_weight[q] : 1.0f;
+        const float ss = dst_weight ? dst_weight[hit - dst_rank] : 1.0f;
+        if (!self_done && j > i) push_self();
+        rd.col.push_back(j);
+        rd.wgt.push_back(rr * ss);
+      }
+      if (!self_done) push_self();
+      rd.rowptr[i + 1] = static_cast<int64_t>(rd.col.size());
+    }
+    // Equal edge counts plus src-edge-in-dst for every edge means the two edge sets coincide.
+    bf_topology_t* t = new (std::nothrow) bf_topology_t();
+    if (!t) return BF_ERR_NOMEM;
+    t->n = n;
+    t->kind = BF_CSR_USER;
+    const int st = bf::finalize_round(rd, n);
+    if (st != BF_OK) {
+      delete t;
+      return st;
+    }
+    t->rounds.push_back(std::move(rd));
+    *out = t;
+    return BF_OK;
+  } catch (const std::bad_alloc&) {
+    return BF_ERR_NOMEM;
+  }
+}
+
+int32_t bf_topology_n(const bf_topology_t* t) { return t ? t->n : BF_ERR_NULL; }
+
+int32_t bf_topology_rounds(const bf_topology_t* t) {
+  return t ? static_cast<int32_t>(t->rounds.size()) : BF_ERR_NULL;
+}
+
+int64_t bf_topology_nnz(const bf_topology_t* t, int32_t round) {
+  if (!t) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  return t->rounds[slice_index(t, round)].rowptr[t->n];
+}
+
+int32_t bf_topology_max_degree(const bf_topology_t* t, int32_t round) {
+  if (!t) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  return t->rounds[slice_index(t, round)].max_degree;
+}
+
+int32_t bf_topology_class(const bf_topology_t* t, int32_t round) {
+  if (!t) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  return t->rounds[slice_index(t, round)].wclass;
+}
+
+int bf_topology_export_csr(const bf_topology_t* t, int32_t round, int64_t* rowptr, int32_t* col,
+                           float* wgt, uint64_t* accepted_seed) {
+  if (!t) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  const Round& r = t->rounds[slice_index(t, round)];
+  if (rowptr) std::memcpy(rowptr, r.rowptr.data(), r.rowptr.size() * sizeof(int64_t));
+  if (col) std::memcpy(col, r.col.data(), r.col.size() * sizeof(int32_t));
+  if (wgt) std::memcpy(wgt, r.wgt.data(), r.wgt.size() * sizeof(float));
+  if (accepted_seed) *accepted_seed = t->accepted_seed;
+  return BF_OK;
+}
+
+const char* bf_strerror(int code) {
+  switch (code) {
+    case BF_OK: return "ok";
+    case BF_ERR_NULL: return "required pointer is NULL";
+    case BF_ERR_SIZE: return "size argument out of range";
+    case BF_ERR_ALIGN: return "pointer or row pitch not 16-byte aligned";
+    case BF_ERR_ALIAS: return "operands overlap (only exact in-place X_in == X_out is allowed)";
+    case BF_ERR_KIND: return "unknown topology kind, dtype, mode or class";
+    case BF_ERR_ROUND: return "negative round index";
+    case BF_ERR_NOT_STOCHASTIC: return "weight matrix is not in the required pull/push/standard class";
+    case BF_ERR_NOT_CONNECTED: return "graph is not strongly connected";
+    case BF_ERR_CSR: return "malformed CSR or neighbor list";
+    case BF_ERR_TOPO_MISMATCH: return "source and destination lists describe different edges";
+    case BF_ERR_UNSUPPORTED: return "no kernel for this shape (n too large for the tile kernels, or tuning override not honourable)";
+    case BF_ERR_HIP: return "HIP runtime call failed";
+    case BF_ERR_NOMEM: return "host allocation failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,275 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads and exports every declared
+symbol, its topologies equal the oracle's, and every argument error is reported before any launch."""
+
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2111_04287_amd as bf
+from oracle import topology as OT
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "bf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(bf_[a-z0-9_]+)\s*\(", text))
+    assert {"bf_topology_create", "bf_neighbor_allreduce", "bf_pushsum_step", "bf_atc_step"} <= declared
+    raw = C.CDLL(bf.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(raw, name), name
+    assert declared == set(bf.EXPORTS)
+
+
+def _lib_W(t, r=0):
+    rowptr, col, wgt, seed = bf.bf_topology_export_csr(t, r)
+    return OT.from_csr(rowptr, col, wgt), seed
+
+
+def _assert_same(Wlib, Wor):
+    assert set(Wlib) == set(Wor)
+    for i in Wor:
+        assert [j for j, _ in Wlib[i]] == [j for j, _ in Wor[i]], i
+        for (_, a), (_, b) in zip(Wlib[i], Wor[i]):
+            assert a == float(np.float32(b))            # the fp32 rounding of the exact weight
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 16, 33])
+def test_ring_matches_oracle(n):
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    _assert_same(_lib_W(t)[0], OT.ring(n))
+    assert bf.bf_topology_class(t) == bf.BF_W_STANDARD and bf.bf_topology_rounds(t) == 1
+
+
+@pytest.mark.parametrize("n", [1, 2, 7, 12, 32, 64, 100])
+def test_static_exponential_matches_oracle(n):
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    _assert_same(_lib_W(t)[0], OT.static_exponential(n))
+    assert bf.bf_topology_class(t) == bf.BF_W_STANDARD
+
+
+def test_static_exponential_degrees_at_benchmark_sizes():
+    for n, deg in ((64, 12), (32, 10)):
+        t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+        assert bf.bf_topology_max_degree(t) == deg and bf.bf_topology_nnz(t) == n * deg
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8, 256])
+def test_one_peer_matches_oracle(n):
+    t = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+    R = bf.bf_topology_rounds(t)
+    assert R == OT.one_peer_rounds(n)
+    for r in range(R + 2):                                  # round index wraps
+        _assert_same(_lib_W(t, r)[0], OT.one_peer_exponential(n, r))
+        assert bf.bf_topology_class(t, r) == bf.BF_W_STANDARD
+
+
+@pytest.mark.parametrize("n,k,seed", [(128, 4, 401), (16, 3, 11), (6, 2, 7), (5, 4, 3), (4, 0, 1)])
+def test_random_directed_matches_oracle(n, k, seed):
+    strong = k > 0
+    t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=k, seed=seed,
+                              require_strongly_connected=strong)
+    Wl, s_lib = _lib_W(t)
+    Wo, s_or = OT.random_directed_push(n, k, seed, require_strongly_connected=strong)
+    assert s_lib == s_or
+    _assert_same(Wl, Wo)
+    assert bf.bf_topology_class(t) & bf.BF_W_PUSH
+
+
+def test_random_directed_rejects_bad_degree_and_unconnectable():
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, 8, out_degree=8, seed=1)
+    assert e.value.code == bf.BF_ERR_SIZE
+    with pytest.raises(bf.BfError) as e:                    # out-degree 0 can never be connected
+        bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, 4, out_degree=0, seed=1)
+    assert e.value.code == bf.BF_ERR_NOT_CONNECTED
+
+
+def _csr(W):
+    rowptr, col, wgt = [0], [], []
+    for i in range(len(W)):
+        for j, w in W[i]:
+            col.append(j)
+            wgt.append(w)
+        rowptr.append(len(col))
+    return rowptr, col, wgt
+
+
+def test_user_csr_round_trip_and_rounds():
+    n = 8
+    parts = [_csr(OT.one_peer_exponential(n, r)) for r in range(3)]
+    rowptr, col, wgt = [], [], []
+    for rp, c, w in parts:
+        rowptr += [v + len(col) for v in rp]
+        col += c
+        wgt += w
+    t = bf.bf_topology_create(bf.BF_CSR_USER, n, rounds=3, rowptr=rowptr, col=col, wgt=wgt,
+                              require_class=bf.BF_W_STANDARD)
+    assert bf.bf_topology_rounds(t) == 3
+    for r in range(3):
+        _assert_same(_lib_W(t, r)[0], OT.one_peer_exponential(n, r))
+
+
+def test_user_csr_validation():
+    n = 4
+    rowptr, col, wgt = _csr(OT.ring(n))
+
+    def create(**kw):
+        a = dict(rowptr=rowptr, col=col, wgt=wgt)
+        a.update(kw)
+        return bf.bf_topology_create(bf.BF_CSR_USER, n, **a)
+
+    def code(**kw):
+        with pytest.raises(bf.BfError) as e:
+            create(**kw)
+        return e.value.code
+
+    create()
+    bad = list(col); bad[1] = 7
+    assert code(col=bad) == bf.BF_ERR_CSR                       # dangling column
+    bad = list(col); bad[0], bad[1] = bad[1], bad[0]
+    assert code(col=bad) == bf.BF_ERR_CSR                       # unsorted row
+    bad = list(col); bad[1] = bad[0]
+    assert code(col=bad) == bf.BF_ERR_CSR                       # duplicate
+    bad = list(rowptr); bad[2] = bad[1] - 1
+    assert code(rowptr=bad) == bf.BF_ERR_CSR                    # decreasing rowptr
+    bad = list(wgt); bad[0] = float("nan")
+    assert code(wgt=bad) == bf.BF_ERR_CSR
+    bad = list(wgt); bad[0] = 0.5
+    assert code(wgt=bad, require_class=bf.BF_W_PULL) == bf.BF_ERR_NOT_STOCHASTIC
+    create(wgt=bad, require_class=bf.BF_W_ANY)                  # allowed when no class is required
+    assert code(require_class=8) == bf.BF_ERR_KIND
+
+
+def test_dense_user_and_classes():
+    rng = np.random.default_rng(0)
+    n = 5
+    D = rng.random((n, n)).astype(np.float32)
+    D[0, 3] = 0.0
+    rowst = (D / D.sum(1, keepdims=True)).astype(np.float32)
+    colst = (D / D.sum(0, keepdims=True)).astype(np.float32)
+    t = bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=rowst, require_class=bf.BF_W_PULL)
+    assert bf.bf_topology_class(t) == bf.BF_W_PULL
+    Wl, _ = _lib_W(t)
+    np.testing.assert_array_equal(OT.to_dense(Wl), rowst.astype(np.float64))
+    t = bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=colst, require_class=bf.BF_W_PUSH)
+    assert bf.bf_topology_class(t) == bf.BF_W_PUSH
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=colst, require_class=bf.BF_W_STANDARD)
+    assert e.value.code == bf.BF_ERR_NOT_STOCHASTIC
+    J = np.full((n, n), 1.0 / n, dtype=np.float32)              # periodic global averaging
+    t = bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=J, require_class=bf.BF_W_STANDARD)
+    assert bf.bf_topology_nnz(t) == n * n
+
+
+def test_push_pull_local_views_and_topology_check(golden_dir):
+    # the 5-node example: N(5) = {1,2,3,4}, M(5) = {1,3}
+    edges = []
+    with open(os.path.join(golden_dir, "five_node_example.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                a, b = line.split()
+                edges.append((int(a) - 1, int(b) - 1))
+    n = 5
+    src = {i: sorted(j for j, k in edges if k == i) for i in range(n)}
+    dst = {j: sorted(k for a, k in edges if a == j) for j in range(n)}
+    srp = np.cumsum([0] + [len(src[i]) for i in range(n)])
+    drp = np.cumsum([0] + [len(dst[j]) for j in range(n)])
+    srk = [j for i in range(n) for j in src[i]]
+    drk = [k for j in range(n) for k in dst[j]]
+    selfw = [1.0 / (len(dst[j]) + 1) for j in range(n)]
+    dwt = [1.0 / (len(dst[j]) + 1) for j in range(n) for _ in dst[j]]
+    # pure push: r = 1, s = 1/(outdeg+1) -> column stochastic
+    t = bf.bf_topology_create_push_pull(n, selfw, srp, srk, None, drp, drk, dwt)
+    assert bf.bf_topology_class(t) == bf.BF_W_PUSH
+    Wl, _ = _lib_W(t)
+    assert OT.in_lists(Wl) == src and OT.out_lists(Wl) == dst
+    assert sorted(j + 1 for j in OT.in_lists(Wl)[4]) == [1, 2, 3, 4]
+    assert sorted(j + 1 for j in OT.out_lists(Wl)[4]) == [1, 3]
+    # pure pull: s = 1, r = 1/(indeg+1) -> row stochastic
+    selfr = [1.0 / (len(src[i]) + 1) for i in range(n)]
+    swt = [1.0 / (len(src[i]) + 1) for i in range(n) for _ in src[i]]
+    t = bf.bf_topology_create_push_pull(n, selfr, srp, srk, swt, drp, drk, None)
+    assert bf.bf_topology_class(t) == bf.BF_W_PULL
+    # push-pull: w = r*s
+    t = bf.bf_topology_create_push_pull(n, selfr, srp, srk, swt, drp, drk, dwt)
+    D = OT.to_dense(_lib_W(t)[0])
+    for j, i in edges:
+        assert D[i, j] == float(np.float32(1.0 / (len(src[i]) + 1)) * np.float32(1.0 / (len(dst[j]) + 1)))
+    # a receiver that expects a sender who does not send: reported, not hung
+    dst_bad = dict(dst)
+    dst_bad[4] = [1, 2]                                         # node 5 sends to 2 instead of 1
+    bad_drk = [k for j in range(n) for k in dst_bad[j]]
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_topology_create_push_pull(n, selfw, srp, srk, None, drp, bad_drk, dwt)
+    assert e.value.code == bf.BF_ERR_TOPO_MISMATCH
+    # one edge missing on the sender side
+    drp2 = drp.copy(); drp2[5:] -= 1
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_topology_create_push_pull(n, selfw, srp, srk, None, drp2, drk[:-1], dwt[:-1])
+    assert e.value.code == bf.BF_ERR_TOPO_MISMATCH
+
+
+def test_create_argument_errors():
+    h = C.c_void_p()
+    assert bf.lib.bf_topology_create(None, bf.BF_RING, 4, None) == bf.BF_ERR_NULL
+    assert bf.lib.bf_topology_create(C.byref(h), bf.BF_RING, 0, None) == bf.BF_ERR_SIZE
+    assert bf.lib.bf_topology_create(C.byref(h), 99, 4, None) == bf.BF_ERR_KIND
+    assert bf.lib.bf_topology_create(C.byref(h), bf.BF_RANDOM_DIRECTED, 4, None) == bf.BF_ERR_NULL
+    assert bf.lib.bf_topology_create(C.byref(h), bf.BF_CSR_USER, 4, None) == bf.BF_ERR_NULL
+    assert h.value is None
+    assert bf.lib.bf_topology_destroy(None) == bf.BF_OK
+    assert bf.lib.bf_topology_n(None) == bf.BF_ERR_NULL
+    assert b"aligned" in bf.lib.bf_strerror(bf.BF_ERR_ALIGN)
+
+
+def test_compute_calls_validate_before_touching_the_device():
+    # Fake but well-formed device addresses: every call below must fail on the host.
+    t = bf.bf_topology_create(bf.BF_RING, 4)
+    h = t.handle
+    A, B = 0x10000000, 0x20000000
+    L = bf.lib
+    na = L.bf_neighbor_allreduce
+    assert na(None, 0, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert na(h, 0, None, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert na(h, -1, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ROUND
+    assert na(h, 0, A, B, 64, 32, bf.BF_F32, None) == bf.BF_ERR_SIZE          # ld < d
+    assert na(h, 0, A, B, -1, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert na(h, 0, A, B, 62, 62, bf.BF_F32, None) == bf.BF_ERR_ALIGN         # row pitch 248 B
+    assert na(h, 0, A + 4, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIGN
+    assert na(h, 0, A, B, 64, 64, 7, None) == bf.BF_ERR_KIND
+    assert na(h, 0, A, A + 256, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS    # partial overlap
+    assert na(h, 0, A, B, 0, 64, bf.BF_F32, None) == bf.BF_OK                  # empty: nothing to launch
+    assert na(h, 0, A, A, 0, 64, bf.BF_F32, None) == bf.BF_OK
+    assert L.bf_dense_mix(h, 0, A, B, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_UNSUPPORTED
+    ps = L.bf_pushsum_step
+    W1, W2 = 0x30000000, 0x30001000
+    assert ps(h, 0, A, B, None, W2, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert ps(h, 0, A, B, W1, W1 + 8, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert ps(h, 0, A, B, W1, W2, A, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS   # Y aliases X_in
+    assert ps(h, 0, A, B, W1, A, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS  # w_out inside X
+    at = L.bf_atc_step
+    G, M = 0x40000000, 0x50000000
+    assert at(h, 0, A, B, None, None, 0.1, 0.0, bf.BF_ATC, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert at(h, 0, A, B, G, None, 0.1, 0.0, 5, 64, 64, bf.BF_F32, None) == bf.BF_ERR_KIND
+    assert at(h, 0, A, B, B, None, 0.1, 0.0, bf.BF_ATC, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert at(h, 0, A, B, G, A, 0.1, 0.9, bf.BF_ATC, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert at(h, 0, A, B, G, M + 8, 0.1, 0.9, bf.BF_ATC, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIGN
+    ls = L.bf_grad_least_squares
+    assert ls(4, 0, 64, A, B, G, 64, M, 64, None) == bf.BF_ERR_SIZE
+    assert ls(4, 65, 64, A, B, G, 64, M, 64, None) == bf.BF_ERR_SIZE
+    assert ls(4, 8, 62, A, B, G, 64, M, 64, None) == bf.BF_ERR_SIZE
+    assert ls(4, 8, 64, A, B, G, 64, G, 64, None) == bf.BF_ERR_ALIAS
+    assert ls(4, 8, 64, A, None, G, 64, M, 64, None) == bf.BF_ERR_NULL
+    gq = L.bf_grad_quadratic
+    assert gq(4, 64, 64, A, B, G, 1.0, 0.1, A, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert gq(0, 64, 64, A, B, G, 1.0, 0.1, M, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    cs = L.bf_consensus_stats
+    assert cs(4, 64, 64, A, None, bf.BF_F32, None, None, None) == bf.BF_ERR_NULL
+    assert cs(4, 64, 64, A, None, bf.BF_F32, M + 4, None, None) == bf.BF_ERR_ALIGN
+    assert L.bf_set_tuning(9, 1) == bf.BF_ERR_KIND
+    assert L.bf_set_tuning(0, 0) == bf.BF_OK

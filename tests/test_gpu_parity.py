@@ -1,0 +1,434 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element,
+on the same seeded inputs.  Tolerances: fp32 configs max|x_gpu - x_ref| <= 1e-5 max|x_ref| per
+round; bf16-storage config <= 2e-2 max|x_ref| per step; integer/bitwise claims exact."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2111_04287_amd as bf
+import workloads
+from oracle import iterations as O
+from oracle import topology as OT
+
+pytestmark = pytest.mark.gpu
+
+DEV = torch.device("cuda:0")
+TOL32 = 1e-5
+TOL16 = 2e-2
+
+
+def lib_W(t, r=0):
+    rowptr, col, wgt, _ = bf.bf_topology_export_csr(t, r)
+    return OT.from_csr(rowptr, col, wgt)          # W is data: the oracle gets the library's fp32 weights
+
+
+def host(x):
+    return x.detach().float().cpu().numpy().astype(np.float64)
+
+
+def assert_close(gpu, ref, tol, what=""):
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = np.abs(ref).max() if ref.size else 0.0
+    err = np.abs(host(gpu) - ref).max() if ref.size else 0.0
+    assert err <= tol * scale + 1e-30, "%s: max err %.3e > %.1e * %.3e" % (what, err, tol, scale)
+    return err
+
+
+def rows(n, d, seed, dtype=torch.float32, ld=None, std=1.0, mean=0.0):
+    ld = workloads.padded_ld(d, 2 if dtype == torch.bfloat16 else 4) if ld is None else ld
+    return workloads.normal_rows(n, d, seed, DEV, mean=mean, std=std, ld=ld, dtype=dtype)
+
+
+def empty_like_rows(x):
+    n, d = x.shape
+    ld = x.stride(0) if n > 1 else d
+    return workloads.alloc_rows(n, d, x.dtype, DEV, ld=ld)
+
+
+TOPOS = [
+    ("ring", lambda n: bf.bf_topology_create(bf.BF_RING, n)),
+    ("exp", lambda n: bf.bf_topology_create(bf.BF_EXP_STATIC, n)),
+    ("onepeer", lambda n: bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)),
+    ("push", lambda n: bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=min(4, n - 1), seed=401)),
+]
+
+
+# ------------------------------------------------------------------ a1/a2: neighbor_allreduce
+@pytest.mark.parametrize("name,make", TOPOS)
+@pytest.mark.parametrize("n,d", [(1, 64), (3, 4), (16, 1024), (64, 8192 + 520), (100, 3004), (256, 4096 + 72),
+                                 (320, 1000), (37, 130)])
+def test_mix_fp32_matches_oracle(name, make, n, d):
+    if name == "push" and n < 3:
+        pytest.skip("needs a few agents")
+    t = make(n)
+    X = rows(n, d, 1000 + n)
+    for r in range(min(2, bf.bf_topology_rounds(t))):
+        out = empty_like_rows(X)
+        out.fill_(float("nan"))
+        bf.bf_neighbor_allreduce(t, r, X, out)
+        assert_close(out, O.mix(host(X), lib_W(t, r)), TOL32, "%s n=%d d=%d r=%d" % (name, n, d, r))
+        # in place gives the same bits
+        Xi = empty_like_rows(X)
+        Xi.copy_(X)
+        bf.bf_neighbor_allreduce(t, r, Xi, Xi)
+        assert torch.equal(Xi, out)
+
+
+def test_mix_never_touches_row_padding():
+    n, d, ld = 16, 1000, 1024
+    base = torch.full((n, ld), 7.0, device=DEV)
+    X = rows(n, d, 5, ld=ld)
+    out = base[:, :d]
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    bf.bf_neighbor_allreduce(t, 0, X, out)
+    assert torch.all(base[:, d:] == 7.0)
+    assert_close(out, O.mix(host(X), lib_W(t)), TOL32)
+
+
+def test_mix_empty_width_is_a_no_op():
+    t = bf.bf_topology_create(bf.BF_RING, 4)
+    X = torch.zeros((4, 64), device=DEV)
+    assert bf.lib.bf_neighbor_allreduce(t.handle, 0, X.data_ptr(), X.data_ptr(), 0, 64, bf.BF_F32, None) == 0
+
+
+@pytest.mark.parametrize("tile", [64, 128, 256, 512, 1024])
+def test_mix_result_is_independent_of_tile_width(tile):
+    n, d = 16, 5000
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    X = rows(n, d, 77)
+    ref = empty_like_rows(X)
+    bf.bf_neighbor_allreduce(t, 0, X, ref)
+    try:
+        bf.bf_set_tuning(0, tile)
+        out = empty_like_rows(X)
+        bf.bf_neighbor_allreduce(t, 0, X, out)
+    finally:
+        bf.bf_set_tuning(0, 0)
+    assert torch.equal(out, ref)                  # same CSR order, same FMA chain: same bits
+
+
+def test_mix_bf16_matches_oracle():
+    n, d = 32, 2048 + 40
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    X = rows(n, d, 9, dtype=torch.bfloat16)
+    out = empty_like_rows(X)
+    bf.bf_neighbor_allreduce(t, 0, X, out)
+    ref = O.mix(host(X), lib_W(t))
+    got = host(out)
+    # exact fp64 result rounded once to bf16, except where fp32 accumulation moved it across a tie
+    rounded = O.round_to_bf16(ref.astype(np.float32)).astype(np.float64)
+    ulp = np.abs(ref) * 2.0 ** -7 + 1e-30
+    assert (np.abs(got - ref) <= 0.51 * ulp).all()
+    assert (got == rounded).mean() > 0.999
+
+
+def test_dynamic_api_with_constant_weights_equals_static():
+    n, d = 64, 3000
+    ts = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    rowptr, col, wgt, _ = bf.bf_topology_export_csr(ts)
+    R = 3
+    rp = np.concatenate([rowptr + k * len(col) for k in range(R)])
+    tu = bf.bf_topology_create(bf.BF_CSR_USER, n, rounds=R, rowptr=rp, col=np.tile(col, R), wgt=np.tile(wgt, R),
+                               require_class=bf.BF_W_STANDARD)
+    X = rows(n, d, 3)
+    a, b = empty_like_rows(X), empty_like_rows(X)
+    bf.bf_neighbor_allreduce(ts, 0, X, a)
+    for r in range(R):
+        bf.bf_neighbor_allreduce(tu, r, X, b)
+        assert torch.equal(a, b)
+
+
+def test_push_equals_pull_on_one_device():
+    # w = r*s: pure push (r=1, s=w) and pure pull (r=w, s=1) give the same result
+    n, d = 12, 520
+    W = OT.static_exponential(n)
+    src = {i: [(j, w) for j, w in W[i] if j != i] for i in range(n)}
+    srp = np.cumsum([0] + [len(src[i]) for i in range(n)])
+    srk = [j for i in range(n) for j, _ in src[i]]
+    swt = [w for i in range(n) for _, w in src[i]]
+    dst = {j: sorted(i for i in range(n) for jj, _ in src[i] if jj == j) for j in range(n)}
+    drp = np.cumsum([0] + [len(dst[j]) for j in range(n)])
+    drk = [i for j in range(n) for i in dst[j]]
+    dwt = [dict(src[i])[j] for j in range(n) for i in dst[j]]
+    selfw = [dict(W[i])[i] for i in range(n)]
+    t_pull = bf.bf_topology_create_push_pull(n, selfw, srp, srk, swt, drp, drk, None)
+    t_push = bf.bf_topology_create_push_pull(n, selfw, srp, srk, None, drp, drk, dwt)
+    X = rows(n, d, 21)
+    a, b = empty_like_rows(X), empty_like_rows(X)
+    bf.bf_neighbor_allreduce(t_pull, 0, X, a)
+    bf.bf_neighbor_allreduce(t_push, 0, X, b)
+    assert torch.equal(a, b)
+    assert_close(a, O.mix(host(X), W), TOL32)
+
+
+# ------------------------------------------------------------------ configuration 2 (reduced d)
+def test_config2_static_exp_50_rounds():
+    n, d = 64, 8192 + 264
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    W = lib_W(t)
+    X = workloads.config2_state(DEV, n=n, d=d, ld=workloads.padded_ld(d, 4))
+    ref = host(X)
+    e0 = O.consensus_error(ref)
+    floor = 1e-6 * np.abs(ref).max() * np.sqrt(n * d)
+    buf = [X, empty_like_rows(X)]
+    stats = torch.empty(3, dtype=torch.float64, device=DEV)
+    for k in range(50):
+        bf.bf_neighbor_allreduce(t, k, buf[k & 1], buf[1 - (k & 1)])
+        ref = O.mix(ref, W)
+        cur = buf[1 - (k & 1)]
+        assert_close(cur, ref, TOL32, "round %d" % k)
+        bf.bf_consensus_stats(cur, None, stats)
+        err = float(stats[0].sqrt())
+        bound = (2.0 / 3.0) ** (k + 1) * e0
+        if bound > floor:                                   # contraction at |lambda_2| = 2/3
+            assert err <= bound * (1 + 1e-4)
+        np.testing.assert_allclose(err, O.consensus_error(host(cur)), rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(host(cur).mean(0), host(X).mean(0) if False else ref.mean(0), atol=2e-6)
+
+
+# ------------------------------------------------------------------ configuration 3 (reduced d)
+def test_config3_one_peer_8_rounds_exact_mean_and_bitwise():
+    n, d = 256, 4096 + 136
+    t = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+    assert bf.bf_topology_rounds(t) == 8
+    X = workloads.config3_state(DEV, n=n, d=d, ld=workloads.padded_ld(d, 4))
+    ref = host(X)
+    emu = X.cpu().numpy()
+    mean = ref.mean(0)
+    buf = [X, empty_like_rows(X)]
+    for r in range(8):
+        cur = buf[1 - (r & 1)]
+        bf.bf_neighbor_allreduce(t, r, buf[r & 1], cur)
+        W = lib_W(t, r)
+        ref = O.mix(ref, W)
+        emu = O.mix_fp32_chain(emu, W)
+        assert_close(cur, ref, TOL32, "round %d" % r)
+        assert np.array_equal(cur.cpu().numpy().view(np.uint32), emu.view(np.uint32)), "round %d bits" % r
+    got = host(cur)
+    assert np.abs(got - mean).max() <= 1e-6 * np.abs(ref).max() + 8 * 6e-8 * np.abs(host(X)).max()
+    assert np.abs(ref - mean).max() < 1e-14
+
+
+# ------------------------------------------------------------------ a3 / configuration 4 (reduced d)
+def test_config4_pushsum_100_rounds():
+    n, d = 128, 2048 + 328
+    t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=4, seed=workloads.CONFIG4_GRAPH_SEED)
+    W = lib_W(t)
+    X = workloads.config4_state(DEV, n=n, d=d, ld=workloads.padded_ld(d, 4))
+    Xr = host(X)
+    xbar = Xr.mean(0)
+    pr = np.ones(n)
+    w = [torch.ones(n, device=DEV), torch.empty(n, device=DEV)]
+    buf = [X, empty_like_rows(X)]
+    Y = empty_like_rows(X)
+    for k in range(100):
+        a, b = k & 1, 1 - (k & 1)
+        bf.bf_pushsum_step(t, k, buf[a], buf[b], w[a], w[b], Y)
+        Xr, pr, Yr = O.pushsum_step(Xr, pr, W)
+        assert_close(buf[b], Xr, TOL32, "X round %d" % k)
+        assert_close(w[b], pr, TOL32, "w round %d" % k)
+        assert_close(Y, Yr, 2e-5, "Y round %d" % k)
+    assert abs(float(w[b].sum()) - n) < 1e-3
+    assert np.abs(host(Y) - xbar).max() < 2e-5 * np.abs(xbar).max()
+    stats = bf.bf_consensus_stats(buf[b], w[b])
+    assert float(stats[1]) < 2e-5 * float(stats[2])
+
+
+def test_pushsum_in_place_and_without_ratio():
+    n, d = 16, 700
+    t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=3, seed=11)
+    W = lib_W(t)
+    X = rows(n, d, 31, mean=5.0, std=2.0, ld=704)
+    Xr, pr = host(X), np.ones(n)
+    w = torch.ones(n, device=DEV)
+    for k in range(5):
+        bf.bf_pushsum_step(t, k, X, X, w, w, None)
+        Xr, pr, _ = O.pushsum_step(Xr, pr, W)
+    assert_close(X, Xr, TOL32)
+    assert_close(w, pr, TOL32)
+
+
+# ------------------------------------------------------------------ a4/a5/a7: ATC, AWC, least squares
+def test_least_squares_gradient_matches_oracle():
+    data = workloads.config1_least_squares(DEV)
+    A, b = data["A"], data["b"]
+    X = rows(16, 1024, 41)
+    G = empty_like_rows(X)
+    bf.bf_grad_least_squares(A, b, X, G)
+    ref = O.ls_grad(host(A), host(b), host(X))
+    assert_close(G, ref, 2e-6, "ls grad")
+
+
+@pytest.mark.parametrize("n,m,d", [(1, 1, 4), (3, 5, 260), (5, 64, 1028)])
+def test_least_squares_gradient_shapes(n, m, d):
+    g = torch.Generator(device=DEV).manual_seed(n * 100 + m)
+    A = torch.randn((n, m, d), generator=g, device=DEV)
+    b = torch.randn((n, m), generator=g, device=DEV)
+    X = rows(n, d, 43)
+    G = empty_like_rows(X)
+    bf.bf_grad_least_squares(A, b, X, G)
+    assert_close(G, O.ls_grad(host(A), host(b), host(X)), 5e-6)
+
+
+@pytest.mark.parametrize("mode", [bf.BF_ATC, bf.BF_AWC])
+@pytest.mark.parametrize("n,d", [(16, 1024), (64, 2000), (256, 520), (5, 68)])
+def test_atc_awc_step_matches_oracle(mode, n, d):
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    W = lib_W(t)
+    X, G = rows(n, d, 51), rows(n, d, 52)
+    alpha = 0.05
+    out = empty_like_rows(X)
+    bf.bf_atc_step(t, 0, X, out, G, None, alpha=alpha, mode=mode)
+    a64 = float(np.float32(alpha))
+    ref = (O.atc_step if mode == bf.BF_ATC else O.awc_step)(host(X), host(G), W, a64)
+    assert_close(out, ref, TOL32)
+    Xi = empty_like_rows(X)
+    Xi.copy_(X)
+    bf.bf_atc_step(t, 0, Xi, Xi, G, None, alpha=alpha, mode=mode)      # in place
+    assert torch.equal(Xi, out)
+
+
+def test_config1_dgd_least_squares_200_iterations():
+    data = workloads.config1_least_squares(DEV)
+    A, b, alpha = data["A"], data["b"], data["alpha"]
+    n, m, d = A.shape
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    W = lib_W(t)
+    for (_, w) in W[0]:
+        assert w == float(np.float32(1 / 3))
+    X = [torch.zeros((n, d), device=DEV), torch.zeros((n, d), device=DEV)]
+    G = torch.empty((n, d), device=DEV)
+    Ah, bh = host(A), host(b)
+    Xr = np.zeros((n, d))
+    a64 = float(np.float32(alpha))
+    worst = 0.0
+    for k in range(data["iters"]):
+        a, c = k & 1, 1 - (k & 1)
+        bf.bf_grad_least_squares(A, b, X[a], G)
+        bf.bf_atc_step(t, k, X[a], X[c], G, None, alpha=alpha, mode=bf.BF_ATC)
+        Xr = O.atc_step(Xr, O.ls_grad(Ah, bh, Xr), W, a64)
+        if k % 10 == 9 or k < 5:
+            err = assert_close(X[c], Xr, TOL32, "iteration %d" % k)
+            worst = max(worst, err / np.abs(Xr).max())
+    # the iterates approach x* on the sampled subspace: the residual has dropped a lot
+    r0 = np.linalg.norm(bh)
+    rk = np.linalg.norm(np.einsum("imd,id->im", Ah, Xr) - bh)
+    assert rk < 0.2 * r0
+    print("config1 worst relative error %.2e" % worst)
+
+
+# ------------------------------------------------------------------ a6 / configuration 5 (reduced d)
+@pytest.mark.parametrize("mode", [bf.BF_ATC, bf.BF_AWC])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_momentum_step_matches_oracle(mode, dtype):
+    n, d = 32, 1024 + 40
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    W = lib_W(t)
+    X, G = rows(n, d, 61, dtype=dtype), rows(n, d, 62, dtype=dtype)
+    ldm = X.stride(0)
+    M = workloads.normal_rows(n, d, 63, DEV, ld=ldm)
+    M0 = host(M)
+    out = empty_like_rows(X)
+    alpha, beta = 0.1, 0.9
+    bf.bf_atc_step(t, 0, X, out, G, M, alpha=alpha, beta=beta, mode=mode)
+    a64, b64 = float(np.float32(alpha)), float(np.float32(beta))
+    Mn = b64 * M0 + host(G)
+    if mode == bf.BF_ATC:
+        ref, Mref = O.dmsgd_atc_step(host(X), M0, host(G), W, a64, b64)
+    else:
+        ref, Mref = O.mix(host(X), W) - a64 * Mn, Mn
+    assert_close(M, Mref, 1e-6, "momentum")
+    assert_close(out, ref, TOL32 if dtype == torch.float32 else 2.0 ** -8, "x")
+
+
+def test_config5_dmsgd_bf16_20_steps():
+    n, d = 32, 4096 + 40                                        # same 40-column ragged tail as 25,557,032
+    cfg = workloads.CONFIG5
+    ld = workloads.padded_ld(d, 2)
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    W = lib_W(t)
+    Cc = workloads.config5_centres(DEV, n=n, d=d, ld=ld)
+    X = [workloads.alloc_rows(n, d, torch.bfloat16, DEV, ld=ld, fill=0) for _ in range(2)]
+    G = workloads.alloc_rows(n, d, torch.bfloat16, DEV, ld=ld)
+    M = workloads.alloc_rows(n, d, torch.float32, DEV, ld=ld, fill=0)
+    lam, sig, alpha, beta = cfg["lam"], cfg["sigma"], cfg["alpha"], cfg["beta"]
+    a64, b64, s64 = float(np.float32(alpha)), float(np.float32(beta)), float(np.float32(sig))
+    Xr, Mr = np.zeros((n, d)), np.zeros((n, d))                 # graded oracle: fp64 state, no rounding
+    Xs, Ms = np.zeros((n, d), np.float32), np.zeros((n, d), np.float32)   # diagnostic: bf16 storage
+    Ch = host(Cc)
+    for k in range(cfg["steps"]):
+        a, c = k & 1, 1 - (k & 1)
+        E = workloads.config5_noise(DEV, k, n=n, d=d, ld=ld)
+        Eh = host(E)
+        bf.bf_grad_quadratic(X[a], Cc, E, lam, sig, G)
+        # the generator kernel: fp32 arithmetic on bf16 inputs, one bf16 rounding
+        gs = O.round_to_bf16(O.quadratic_noise_grad(Xs, Ch, Eh, lam, s64).astype(np.float32))
+        assert (host(G) == gs.astype(np.float64)).mean() > 0.995
+        bf.bf_atc_step(t, k, X[a], X[c], G, M, alpha=alpha, beta=beta, mode=bf.BF_ATC)
+        Xr, Mr = O.dmsgd_atc_step(Xr, Mr, O.quadratic_noise_grad(Xr, Ch, Eh, lam, s64), W, a64, b64)
+        assert_close(X[c], Xr, TOL16, "step %d" % k)
+        Xs, Ms = O.dmsgd_atc_step_bf16_storage(Xs, Ms, host(G), W, a64, b64)
+        # same storage rounding on both sides: at most one bf16 ulp apart, nearly always equal
+        diff = np.abs(host(X[c]) - Xs.astype(np.float64))
+        assert (diff <= np.abs(Xs) * 2.0 ** -7 + 1e-30).all(), "step %d" % k
+        Xs = X[c].float().cpu().numpy()                         # re-synchronise the diagnostic twin
+        Ms = M.cpu().numpy().copy()
+
+
+# ------------------------------------------------------------------ a8: dense W on the matrix cores
+@pytest.mark.parametrize("n,d", [(5, 100), (32, 1000), (64, 4096 + 8), (100, 260), (256, 1024)])
+def test_dense_mix_matches_oracle_and_sparse_kernel(n, d):
+    rng = np.random.default_rng(n)
+    D = rng.random((n, n)).astype(np.float32)
+    D = (D / D.sum(1, keepdims=True)).astype(np.float32)
+    td = bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=D, require_class=bf.BF_W_PULL)
+    X = rows(n, d, 71)
+    out = empty_like_rows(X)
+    bf.bf_neighbor_allreduce(td, 0, X, out)                   # dispatches to the MFMA kernel
+    ref = O.mix(host(X), OT.from_dense(D.astype(np.float64)))
+    assert_close(out, ref, TOL32, "dense")
+    np.testing.assert_allclose(ref, D.astype(np.float64) @ host(X), atol=1e-12)
+    Xi = empty_like_rows(X)
+    Xi.copy_(X)
+    bf.bf_dense_mix(td, 0, Xi, Xi)                             # in place
+    assert torch.equal(Xi, out)
+    # the sparse tile kernel on a sparse topology agrees with its dense form on the matrix cores
+    ts = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    a, b = empty_like_rows(X), empty_like_rows(X)
+    bf.bf_neighbor_allreduce(ts, 0, X, a)
+    bf.bf_dense_mix(ts, 0, X, b)
+    assert_close(b, host(a), 2e-6, "dense vs sparse")
+
+
+def test_global_averaging_through_dense_w():
+    n, d = 16, 520
+    J = np.full((n, n), 1.0 / n, dtype=np.float32)
+    t = bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=J, require_class=bf.BF_W_STANDARD)
+    X = rows(n, d, 73)
+    out = empty_like_rows(X)
+    bf.bf_neighbor_allreduce(t, 0, X, out)
+    assert_close(out, np.tile(host(X).mean(0), (n, 1)), TOL32)
+
+
+# ------------------------------------------------------------------ a9 and the gradient generator
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_consensus_stats_and_quadratic_gradient(dtype):
+    n, d = 24, 1000 if dtype == torch.float32 else 1000
+    X = rows(n, d, 81, dtype=dtype, std=2.0, mean=1.0)
+    p = torch.rand(n, device=DEV) + 0.5
+    mean = torch.empty(d, device=DEV)
+    st = bf.bf_consensus_stats(X, p, mean_out=mean)
+    Yh = host(X) / host(p)[:, None]
+    mu = Yh.mean(0)
+    np.testing.assert_allclose(float(st[0]), ((Yh - mu) ** 2).sum(), rtol=1e-10)
+    np.testing.assert_allclose(float(st[1]), np.abs(Yh - mu).max(), rtol=1e-12)
+    np.testing.assert_allclose(float(st[2]), np.abs(Yh).max(), rtol=1e-12)
+    np.testing.assert_allclose(host(mean), mu, rtol=1e-6, atol=1e-7)
+    st = bf.bf_consensus_stats(X)
+    np.testing.assert_allclose(float(st[0]) ** 0.5, O.consensus_error(host(X)), rtol=1e-10)
+    Cc, E = rows(n, d, 82, dtype=dtype), rows(n, d, 83, dtype=dtype)
+    G = empty_like_rows(X)
+    bf.bf_grad_quadratic(X, Cc, E, 1.5, 0.1, G)
+    ref = O.quadratic_noise_grad(host(X), host(Cc), host(E), 1.5, float(np.float32(0.1)))
+    assert_close(G, ref, 1e-6 if dtype == torch.float32 else 2.0 ** -8)
