@@ -184,7 +184,8 @@ int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on t
 
 /* Launch-shape override for experiments and sweeps: 0 restores the built-in heuristic.
  * knob 0 = column-tile width in elements (64..1024, power of two), knob 1 = workgroups per
- * compute unit, knob 2 = 1 forces the cache-reliant row-gather fallback (out of place only).
+ * compute unit, knob 2 = 1 forces the cache-reliant row-gather fallback (out of place only),
+ * knob 3 = upper bound on the number of persistent workgroups.
  * Values the kernels cannot honour give BF_ERR_UNSUPPORTED at the next compute call. */
 int bf_set_tuning(int32_t knob, int32_t value);
 

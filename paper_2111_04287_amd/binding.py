@@ -62,6 +62,13 @@ def _load():
         raise ImportError(
             "libbf.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
             "from the repository root (needs hipcc). There is no CPU fallback.")
+    # One HIP runtime per process: PyTorch ships its own libamdhip64 (same SONAME as the system
+    # one).  Loading torch first makes libbf's dependency resolve to that already-loaded copy, so
+    # device pointers and streams created by torch are valid inside libbf.
+    import torch
+    hip = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    if os.path.exists(hip):
+        C.CDLL(hip, mode=C.RTLD_GLOBAL)
     L = C.CDLL(LIB_PATH)
     vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     L.bf_topology_create.argtypes = [C.POINTER(vp), C.c_int, i32, C.POINTER(bf_topo_params_t)]

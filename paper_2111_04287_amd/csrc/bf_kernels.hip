@@ -54,6 +54,36 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
+// Streaming accesses.  Every element of X, G and M is read once and written once per call.
+// Measured on MI355X: the non-temporal hint on the result stores helps (they are full 128-byte
+// lines per wave instruction and never re-read); on the loads it is neutral to harmful, and on
+// the momentum store, whose two 16-byte halves per lane are written by separate instructions, it
+// turns every line into two partial writes and costs a quarter of the bandwidth.  Hence: stores
+// of X_out / Y stream, everything else uses the default policy.
+#ifndef BF_NT_LOAD
+#define BF_NT_LOAD 0
+#endif
+#ifndef BF_NT_STORE
+#define BF_NT_STORE 1
+#endif
+#ifndef BF_NT_MSTORE
+#define BF_NT_MSTORE 0
+#endif
+template <typename T> __device__ __forceinline__ T ld_stream(const T* ptr) {
+#if BF_NT_LOAD
+  return __builtin_nontemporal_load(ptr);
+#else
+  return *ptr;
+#endif
+}
+template <typename T> __device__ __forceinline__ void st_stream(T* ptr, const T& v) {
+#if BF_NT_STORE
+  __builtin_nontemporal_store(v, ptr);
+#else
+  *ptr = v;
+#endif
+}
+
 // Scalar-cache view of the topology: uniform addresses into these become s_load instructions.
 typedef const int32_t __attribute__((address_space(4)))* csr_i32_ptr;
 typedef const u32x2 __attribute__((address_space(4)))* csr_ent_ptr;
@@ -98,17 +128,17 @@ __device__ __forceinline__ void store_out(char* base, int64_t off, const float* 
   if constexpr (DT == DT_F32) {
     float* ptr = reinterpret_cast<float*>(base) + off;
     if (valid >= LW) {
-      if constexpr (LW == 4) { f32x4 t = {v[0], v[1], v[2], v[3]}; *reinterpret_cast<f32x4*>(ptr) = t; }
-      else if constexpr (LW == 2) { f32x2 t = {v[0], v[1]}; *reinterpret_cast<f32x2*>(ptr) = t; }
-      else { ptr[0] = v[0]; }
+      if constexpr (LW == 4) { f32x4 t = {v[0], v[1], v[2], v[3]}; st_stream(reinterpret_cast<f32x4*>(ptr), t); }
+      else if constexpr (LW == 2) { f32x2 t = {v[0], v[1]}; st_stream(reinterpret_cast<f32x2*>(ptr), t); }
+      else { st_stream(ptr, v[0]); }
     } else {
       for (int k = 0; k < LW; ++k) if (k < valid) ptr[k] = v[k];
     }
   } else {
     uint16_t* ptr = reinterpret_cast<uint16_t*>(base) + off;
     if (valid >= LW) {
-      if constexpr (LW == 4) { u32x2 t = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; *reinterpret_cast<u32x2*>(ptr) = t; }
-      else if constexpr (LW == 2) { *reinterpret_cast<uint32_t*>(ptr) = pack_bf16x2(v[0], v[1]); }
+      if constexpr (LW == 4) { u32x2 t = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; st_stream(reinterpret_cast<u32x2*>(ptr), t); }
+      else if constexpr (LW == 2) { st_stream(reinterpret_cast<uint32_t*>(ptr), pack_bf16x2(v[0], v[1])); }
       else { ptr[0] = static_cast<uint16_t>(f32_to_bf16_bits(v[0])); }
     } else {
       for (int k = 0; k < LW; ++k) if (k < valid) ptr[k] = static_cast<uint16_t>(f32_to_bf16_bits(v[k]));
@@ -171,11 +201,11 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const int row = u >> upr_log;
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
       const int64_t off = static_cast<int64_t>(row) * ld + col;
-      xr[k] = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
-      if constexpr (STAGE_G) gr[k] = *reinterpret_cast<const u32x4*>(p.g + off * EB);
+      xr[k] = ld_stream(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
+      if constexpr (STAGE_G) gr[k] = ld_stream(reinterpret_cast<const u32x4*>(p.g + off * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
-        for (int q = 0; q < MV; ++q) mr[k * MV + q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+        for (int q = 0; q < MV; ++q) mr[k * MV + q] = ld_stream(reinterpret_cast<const f32x4*>(p.m + off + 4 * q));
       }
     }
   };
@@ -203,7 +233,11 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
           gv[4 * q + 0] = mv.x; gv[4 * q + 1] = mv.y; gv[4 * q + 2] = mv.z; gv[4 * q + 3] = mv.w;
           if (live) {
             const int64_t rem = d - (col + 4 * q);
+#if BF_NT_MSTORE
+            if (rem >= 4) st_stream(reinterpret_cast<f32x4*>(p.m + off + 4 * q), mv);
+#else
             if (rem >= 4) *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = mv;
+#endif
             else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = gv[4 * q + e];
           }
         }
@@ -231,13 +265,13 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const int row = u >> upr_log;
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
       const int64_t off = static_cast<int64_t>(row) * ld + col;
-      const u32x4 xraw = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
+      const u32x4 xraw = ld_stream(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
       u32x4 graw = {0, 0, 0, 0};
       f32x4 mraw[MV];
-      if constexpr (STAGE_G) graw = *reinterpret_cast<const u32x4*>(p.g + off * EB);
+      if constexpr (STAGE_G) graw = ld_stream(reinterpret_cast<const u32x4*>(p.g + off * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
-        for (int q = 0; q < MV; ++q) mraw[q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+        for (int q = 0; q < MV; ++q) mraw[q] = ld_stream(reinterpret_cast<const f32x4*>(p.m + off + 4 * q));
       }
       stage_unit(u, c0, xraw, graw, mraw);
     }
@@ -691,6 +725,7 @@ int get_device_copy(bf_topology_t* t, bool need_dense, bf::DeviceCopy** out) {
 int g_tune_tile = 0;      // column-tile width override (elements)
 int g_tune_wgs = 0;       // workgroups per CU override
 int g_tune_gather = 0;    // 1: force the gather fallback
+int g_tune_grid = 0;      // total workgroups override (capped by the resident slots)
 
 struct Shape { int log_c; int lw; int wgs_per_cu; size_t lds_bytes; };
 
@@ -837,7 +872,8 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   if (rc != BF_OK) return rc;
   tp.log_c = s.log_c;
   tp.ntiles = (tp.d + (int64_t{1} << s.log_c) - 1) >> s.log_c;
-  const int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus) * s.wgs_per_cu));
+  int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus) * s.wgs_per_cu));
+  if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
   return dt == BF_F32 ? launch_tile_op<DT_F32>(op, with_y, tp, s, grid, st)
                       : launch_tile_op<DT_BF16>(op, with_y, tp, s, grid, st);
 }
@@ -853,6 +889,7 @@ int bf_set_tuning(int32_t knob, int32_t value) {
   if (knob == 0) g_tune_tile = value;
   else if (knob == 1) g_tune_wgs = value;
   else if (knob == 2) g_tune_gather = value;
+  else if (knob == 3) g_tune_grid = value;
   else return BF_ERR_KIND;
   return BF_OK;
 }

@@ -71,8 +71,51 @@ def test_mix_fp32_matches_oracle(name, make, n, d):
         # in place gives the same bits
         Xi = empty_like_rows(X)
         Xi.copy_(X)
-        bf.bf_neighbor_allreduce(t, r, Xi, Xi)
+        try:
+            bf.bf_neighbor_allreduce(t, r, Xi, Xi)
+        except bf.BfError as e:                   # only legal where the tile does not fit LDS
+            assert e.code == bf.BF_ERR_UNSUPPORTED and n * 64 * 4 > 64 * 1024
+            continue
         assert torch.equal(Xi, out)
+
+
+def test_many_agents_use_the_gather_fallback():
+    # 2048 agents: a 2048 x 64 fp32 tile is 512 KB, beyond LDS; out of place works, in place is refused
+    n, d = 2048, 520
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    W = lib_W(t)
+    X = rows(n, d, 5)
+    out = empty_like_rows(X)
+    bf.bf_neighbor_allreduce(t, 0, X, out)
+    assert_close(out, O.mix(host(X), W), TOL32)
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_neighbor_allreduce(t, 0, X, X)
+    assert e.value.code == bf.BF_ERR_UNSUPPORTED
+    G = rows(n, d, 6)
+    M = workloads.normal_rows(n, d, 7, DEV, ld=X.stride(0))
+    M0 = host(M)
+    for mode in (bf.BF_ATC, bf.BF_AWC):
+        bf.bf_atc_step(t, 0, X, out, G, None, alpha=0.05, mode=mode)
+        ref = (O.atc_step if mode == bf.BF_ATC else O.awc_step)(host(X), host(G), W, float(np.float32(0.05)))
+        assert_close(out, ref, TOL32)
+    bf.bf_atc_step(t, 0, X, out, G, M, alpha=0.05, beta=0.9, mode=bf.BF_ATC)
+    ref, Mref = O.dmsgd_atc_step(host(X), M0, host(G), W, float(np.float32(0.05)), float(np.float32(0.9)))
+    assert_close(out, ref, TOL32)
+    assert_close(M, Mref, 1e-6)
+
+
+def test_forced_gather_path_matches_tile_path():
+    n, d = 64, 3000
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    X = rows(n, d, 8)
+    a, b = empty_like_rows(X), empty_like_rows(X)
+    bf.bf_neighbor_allreduce(t, 0, X, a)
+    try:
+        bf.bf_set_tuning(2, 1)
+        bf.bf_neighbor_allreduce(t, 0, X, b)
+    finally:
+        bf.bf_set_tuning(2, 0)
+    assert torch.equal(a, b)
 
 
 def test_mix_never_touches_row_padding():
@@ -116,11 +159,13 @@ def test_mix_bf16_matches_oracle():
     bf.bf_neighbor_allreduce(t, 0, X, out)
     ref = O.mix(host(X), lib_W(t))
     got = host(out)
-    # exact fp64 result rounded once to bf16, except where fp32 accumulation moved it across a tie
+    # the exact result rounded once to bf16 (half an ulp), plus the fp32 accumulation error, which
+    # matters only where the sum cancels to almost nothing or sits next to a rounding tie
     rounded = O.round_to_bf16(ref.astype(np.float32)).astype(np.float64)
-    ulp = np.abs(ref) * 2.0 ** -7 + 1e-30
-    assert (np.abs(got - ref) <= 0.51 * ulp).all()
-    assert (got == rounded).mean() > 0.999
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-300))) - 7)
+    assert (np.abs(got - ref) <= 0.5 * ulp + 4e-7 * np.abs(host(X)).max()).all()
+    # equal weights put many exact sums next to a rounding tie (0.1f * short sum): most, not all, agree
+    assert (got == rounded).mean() > 0.98
 
 
 def test_dynamic_api_with_constant_weights_equals_static():
@@ -184,7 +229,7 @@ def test_config2_static_exp_50_rounds():
         if bound > floor:                                   # contraction at |lambda_2| = 2/3
             assert err <= bound * (1 + 1e-4)
         np.testing.assert_allclose(err, O.consensus_error(host(cur)), rtol=1e-9, atol=1e-12)
-    np.testing.assert_allclose(host(cur).mean(0), host(X).mean(0) if False else ref.mean(0), atol=2e-6)
+    np.testing.assert_allclose(host(cur).mean(0), ref.mean(0), atol=2e-6)
 
 
 # ------------------------------------------------------------------ configuration 3 (reduced d)
@@ -371,7 +416,9 @@ def test_config5_dmsgd_bf16_20_steps():
         Xs, Ms = O.dmsgd_atc_step_bf16_storage(Xs, Ms, host(G), W, a64, b64)
         # same storage rounding on both sides: at most one bf16 ulp apart, nearly always equal
         diff = np.abs(host(X[c]) - Xs.astype(np.float64))
-        assert (diff <= np.abs(Xs) * 2.0 ** -7 + 1e-30).all(), "step %d" % k
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(Xs.astype(np.float64)), 1e-300))) - 7)
+        assert (diff <= ulp + 1e-6 * np.abs(Xs).max()).all(), "step %d" % k
+        assert (diff == 0).mean() > 0.98
         Xs = X[c].float().cpu().numpy()                         # re-synchronise the diagnostic twin
         Ms = M.cpu().numpy().copy()
 
@@ -414,7 +461,7 @@ def test_global_averaging_through_dense_w():
 # ------------------------------------------------------------------ a9 and the gradient generator
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_consensus_stats_and_quadratic_gradient(dtype):
-    n, d = 24, 1000 if dtype == torch.float32 else 1000
+    n, d = 24, 1000
     X = rows(n, d, 81, dtype=dtype, std=2.0, mean=1.0)
     p = torch.rand(n, device=DEV) + 0.5
     mean = torch.empty(d, device=DEV)
