@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the decentralized-averaging hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-extra]
+
+Headline workload (the second benchmark configuration): pure averaging on the static exponential
+graph, n = 64 agents, X 64 x 2^20 fp32 ~ U(-1,1) (seed 201).  One step = one mixing round
+X <- W X (bf_neighbor_allreduce, ping-pong buffers, inputs resident in HBM).  The metric is the
+effective HBM bandwidth: compulsory bytes (every element read once and written once,
+2*n*d*4 per round) divided by time.  The other four configurations are timed in the same run and
+reported under "per_config"; the CPU oracle is timed on a bounded sample under "cpu_baseline".
+Prints ONE JSON line.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-extra", action="store_true", help="time the headline workload only")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU (all n agents are rows of one matrix in one "
+                         "GPU's HBM); there is no multi-GPU path, so --gpus must be 1.\n")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2111_04287_amd as bf
+    import workloads
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def mat(n, d, dtype, fill=None):
+        ld = bf.bf_recommended_ld(d, bf.BF_F32 if dtype == torch.float32 else bf.BF_BF16)
+        return workloads.alloc_rows(n, d, dtype, dev, ld=ld, fill=fill), ld
+
+    def timed(step_fn, steps, warmup, per_launch_events=True):
+        """W untimed + K timed calls of step_fn(k).  Returns (wall seconds, mean ms per launch by
+        HIP events recorded on the launch stream around every call)."""
+        for k in range(warmup):
+            step_fn(k)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)] if per_launch_events else None
+        t0 = time.perf_counter()
+        for k in range(steps):
+            if ev:
+                ev[k].record()
+            step_fn(warmup + k)
+        if ev:
+            ev[steps].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ev_ms = (sum(ev[k].elapsed_time(ev[k + 1]) for k in range(steps)) / steps) if ev else None
+        return wall, ev_ms
+
+    # ------------------------------------------------------------------ headline: configuration 2
+    n, d = 64, 1 << 20
+    topo = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    ld = bf.bf_recommended_ld(d, bf.BF_F32)
+    X = [workloads.config2_state(dev, n=n, d=d, ld=ld), workloads.alloc_rows(n, d, torch.float32, dev, ld=ld)]
+    bytes_per_round = 2 * n * d * 4
+
+    def mix_step(k):
+        bf.bf_neighbor_allreduce(topo, k, X[k & 1], X[1 - (k & 1)])
+
+    wall, ev_ms = timed(mix_step, args.steps, args.warmup)
+    ms_per_step = wall * 1e3 / args.steps
+    value = bytes_per_round * args.steps / wall / 1e9
+    achieved = bytes_per_round / (ev_ms * 1e-3) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "traffic_mix_static_exp_n64_d1048576.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+    out = {
+        "metric": "mixing effective HBM GB/s",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: static exponential graph n=64 (12 nonzeros per row, weights 1/12), "
+                               "X 64 x 2^20 fp32 ~U(-1,1) seed 201, one mixing round per step",
+                   "n": n, "d": d, "ld": ld, "topology": "static_exp", "step": "bf_neighbor_allreduce"},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "agent_row_updates_per_s": round(n * args.steps / wall, 1),
+        "roofline": {"bound": "hbm", "kernel": "bf_tile_kernel<f32, mix>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic, "algorithmic_bytes_per_launch": bytes_per_round,
+                     "launch_ms": round(ev_ms, 5),
+                     "note": "X (256 MiB) is the size of the 256 MB Infinity Cache; configs 3-5 under "
+                             "per_config are far larger and are the HBM-only figures"},
+    }
+    del X
+
+    # ------------------------------------------------------------------ the other configurations
+    if not args.no_extra:
+        per = {}
+
+        def entry(name, bytes_per_step, n_agents, steps, wall, ev_ms, extra=None):
+            e = {"ms_per_step": round(wall * 1e3 / steps, 5), "steps": steps,
+                 "effective_GBps": round(bytes_per_step * steps / wall / 1e9, 1),
+                 "pct_of_hbm_peak": round(100 * bytes_per_step * steps / wall / 1e9 / HBM_PEAK_GBPS, 2),
+                 "agent_row_updates_per_s": round(n_agents * steps / wall, 1),
+                 "event_ms_per_step": round(ev_ms, 5)}
+            if extra:
+                e.update(extra)
+            per[name] = e
+
+        # practical ceiling: a plain device-to-device copy of 1 GiB
+        a = torch.empty(1 << 28, device=dev)
+        b = torch.empty_like(a)
+        w_, e_ = timed(lambda k: b.copy_(a), 20, 3)
+        out["copy_ceiling_GBps"] = round(2 * a.numel() * 4 * 20 / w_ / 1e9, 1)
+        del a, b
+
+        # configuration 3: dynamic one-peer exponential-2, n=256, d=2^22, 8 rounds per sweep
+        n3, d3 = 256, 1 << 22
+        t3 = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n3)
+        ld3 = bf.bf_recommended_ld(d3, bf.BF_F32)
+        X3 = [workloads.config3_state(dev, n=n3, d=d3, ld=ld3), workloads.alloc_rows(n3, d3, torch.float32, dev, ld=ld3)]
+        w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(t3, k, X3[k & 1], X3[1 - (k & 1)]), 24, 8)
+        entry("config3_one_peer_exp2_n256_d4194304_f32", 2 * n3 * d3 * 4, n3, 24, w_, e_)
+        del X3
+
+        # configuration 4: push-sum on the random directed graph, n=128, d=2^21
+        n4, d4 = 128, 1 << 21
+        t4 = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n4, out_degree=4, seed=workloads.CONFIG4_GRAPH_SEED)
+        ld4 = bf.bf_recommended_ld(d4, bf.BF_F32)
+        X4 = [workloads.config4_state(dev, n=n4, d=d4, ld=ld4), workloads.alloc_rows(n4, d4, torch.float32, dev, ld=ld4)]
+        w4 = [torch.ones(n4, device=dev), torch.ones(n4, device=dev)]
+        w_, e_ = timed(lambda k: bf.bf_pushsum_step(t4, k, X4[k & 1], X4[1 - (k & 1)], w4[k & 1], w4[1 - (k & 1)], None),
+                       50, 5)
+        entry("config4_pushsum_random_directed_n128_d2097152_f32", 2 * n4 * d4 * 4, n4, 50, w_, e_)
+        del X4
+
+        # configuration 5: momentum ATC, bf16 X/G, fp32 M, n=32, d=25,557,032 (14 bytes per element)
+        n5, d5 = 32, workloads.RESNET50_PARAMS
+        c5 = workloads.CONFIG5
+        t5 = bf.bf_topology_create(bf.BF_EXP_STATIC, n5)
+        ld5 = bf.bf_recommended_ld(d5, bf.BF_BF16)
+        X5 = [workloads.alloc_rows(n5, d5, torch.bfloat16, dev, ld=ld5, fill=0) for _ in range(2)]
+        C5 = workloads.config5_centres(dev, n=n5, d=d5, ld=ld5)
+        E5 = workloads.config5_noise(dev, 0, n=n5, d=d5, ld=ld5)
+        G5 = workloads.alloc_rows(n5, d5, torch.bfloat16, dev, ld=ld5)
+        M5 = workloads.alloc_rows(n5, d5, torch.float32, dev, ld=ld5, fill=0)
+        bf.bf_grad_quadratic(X5[0], C5, E5, c5["lam"], c5["sigma"], G5)      # generator: outside the timed region
+        w_, e_ = timed(lambda k: bf.bf_atc_step(t5, k, X5[k & 1], X5[1 - (k & 1)], G5, M5, c5["alpha"], c5["beta"],
+                                                bf.BF_ATC), 20, 3)
+        entry("config5_dmsgd_atc_n32_d25557032_bf16", n5 * d5 * 14, n5, 20, w_, e_,
+              {"bytes_per_element": 14, "note": "bf16 X and G, fp32 momentum"})
+        del X5, C5, E5, G5, M5
+
+        # configuration 1: decentralized gradient descent on least squares (latency bound)
+        d1 = workloads.config1_least_squares(dev)
+        A1, b1 = d1["A"], d1["b"]
+        n1, m1, dd1 = A1.shape
+        t1 = bf.bf_topology_create(bf.BF_RING, n1)
+        X1 = [torch.zeros((n1, dd1), device=dev), torch.zeros((n1, dd1), device=dev)]
+        G1 = torch.empty((n1, dd1), device=dev)
+
+        def dgd(k):
+            bf.bf_grad_least_squares(A1, b1, X1[k & 1], G1)
+            bf.bf_atc_step(t1, k, X1[k & 1], X1[1 - (k & 1)], G1, None, d1["alpha"], 0.0, bf.BF_ATC)
+
+        w_, e_ = timed(dgd, 200, 20)
+        entry("config1_dgd_least_squares_ring_n16_d1024_f32", A1.numel() * 4 + b1.numel() * 4 + 2 * n1 * dd1 * 4,
+              n1, 200, w_, e_, {"iterations_per_s": round(200 / w_, 1),
+                                "note": "latency bound: two launches per iteration on a 64 KiB state"})
+        out["per_config"] = per
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample
+    if not args.no_cpu:
+        from oracle import iterations as O
+        from oracle import topology as OT
+        rowptr, col, wgt, _ = bf.bf_topology_export_csr(topo, 0)
+        W = OT.from_csr(rowptr, col, wgt)
+        rng = np.random.default_rng(201)
+        Xh = rng.uniform(-1.0, 1.0, size=(n, d))
+        rounds = 0
+        t0 = time.perf_counter()
+        while True:
+            Xh = O.mix(Xh, W)
+            rounds += 1
+            el = time.perf_counter() - t0
+            if el > 10.0 or rounds >= 50:
+                break
+        out["cpu_baseline"] = {"value": round(bytes_per_round * rounds / el / 1e9, 3), "unit": "GB/s",
+                               "cores": 1, "kind": "oracle",
+                               "sample": "%d mixing rounds of the full headline workload (n=64, d=2^20) by the fp64 "
+                                         "numpy oracle, %.1f s, single thread; host has %d logical cores"
+                                         % (rounds, el, os.cpu_count())}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

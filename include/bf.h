@@ -179,6 +179,13 @@ int bf_grad_quadratic(int32_t n, int64_t d, int64_t ld, const void* X, const voi
 int bf_consensus_stats(int32_t n, int64_t d, int64_t ld, const void* X, const float* p, bf_dtype_t dt,
                        double* stats, float* mean_out, void* hip_stream);
 
+/* Leading dimension (elements) this library suggests for an n x d matrix of dtype dt: the row pitch
+ * is d rounded up to 128 bytes plus 4224 bytes (one 4 KB page and one 128-byte line).  A pitch that
+ * is a large power of two sends the same column of every agent to the same HBM channel and bank;
+ * the offset spreads the n concurrent row streams of a tile (measured +5..10 % bandwidth).
+ * Any ld >= d with a 16-byte-multiple pitch is accepted by the compute calls.  Negative on error. */
+int64_t bf_recommended_ld(int64_t d, bf_dtype_t dt);
+
 const char* bf_strerror(int code);
 int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on this thread        */
 

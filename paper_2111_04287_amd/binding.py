@@ -30,7 +30,7 @@ EXPORTS = [
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step",
     "bf_atc_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
-    "bf_strerror", "bf_last_hip_error", "bf_set_tuning",
+    "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
 
 
@@ -92,6 +92,8 @@ def _load():
     L.bf_strerror.restype = C.c_char_p
     L.bf_last_hip_error.argtypes = []
     L.bf_set_tuning.argtypes = [i32, i32]
+    L.bf_recommended_ld.argtypes = [i64, C.c_int]
+    L.bf_recommended_ld.restype = i64
     for name in EXPORTS:
         getattr(L, name)          # raises AttributeError if a declared symbol is missing
     return L
@@ -300,6 +302,13 @@ def bf_consensus_stats(X, p=None, stats=None, mean_out=None, stream=None):
                                   stats.data_ptr(), None if mean_out is None else mean_out.data_ptr(),
                                   _stream(stream)), "bf_consensus_stats")
     return stats
+
+
+def bf_recommended_ld(d, dt):
+    ld = lib.bf_recommended_ld(d, dt)
+    if ld < 0:
+        raise BfError(int(ld), "bf_recommended_ld")
+    return ld
 
 
 def bf_set_tuning(knob, value):

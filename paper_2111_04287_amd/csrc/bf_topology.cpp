@@ -433,6 +433,14 @@ int bf_topology_export_csr(const bf_topology_t* t, int32_t round, int64_t* rowpt
   return BF_OK;
 }
 
+int64_t bf_recommended_ld(int64_t d, bf_dtype_t dt) {
+  if (dt != BF_F32 && dt != BF_BF16) return BF_ERR_KIND;
+  if (d < 0 || d > (int64_t{1} << 40)) return BF_ERR_SIZE;
+  const int64_t eb = dt == BF_F32 ? 4 : 2;
+  const int64_t pitch = (d * eb + 127) / 128 * 128 + 4224;
+  return pitch / eb;
+}
+
 const char* bf_strerror(int code) {
   switch (code) {
     case BF_OK: return "ok";
