@@ -128,6 +128,16 @@ int32_t bf_topology_class(const bf_topology_t* t, int32_t round);     /* bf_wcla
 int bf_topology_export_csr(const bf_topology_t* t, int32_t round, int64_t* rowptr, int32_t* col,
                            float* wgt, uint64_t* accepted_seed);
 
+/* Diagnostic: the row-walk plan of a round whose off-diagonal graph is a union of paths and cycles
+ * (ring, one-peer rounds, matchings), which lets the kernels stream rows through registers.
+ * Returns n and, if steps is not NULL, writes n records of eight 32-bit words {row, flags,
+ * last_row, next_row, slots, w0, w1, w2 (float bits)}: flags bit 0 = first row of a chain, bit 1 =
+ * the chain is a cycle, bits 2-3 = source of the next row (0 load next_row, 1 the cycle's last row
+ * kept from its start, 2 the cycle's first row, 3 none); slots holds three 4-bit codes in CSR order
+ * (0 previous row of the walk, 1 this row, 2 next row, 15 no entry).  Returns 0 when the round has
+ * no such plan, negative on error. */
+int32_t bf_topology_chain_plan(const bf_topology_t* t, int32_t round, int32_t* steps);
+
 /* Partial averaging (eq. dsgd-2, eq. dgd-2; the neighbor_allreduce primitive):
  *   X_out[i,:] = sum_{(j,w) in row i of W^(round)} w * X_in[j,:].
  * Accumulation is fp32 in CSR order; BF_BF16 rounds the result to nearest-even on store. */
@@ -189,11 +199,16 @@ int64_t bf_recommended_ld(int64_t d, bf_dtype_t dt);
 const char* bf_strerror(int code);
 int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on this thread        */
 
-/* Launch-shape override for experiments and sweeps: 0 restores the built-in heuristic.
- * knob 0 = column-tile width in elements (64..1024, power of two), knob 1 = workgroups per
- * compute unit, knob 2 = 1 forces the cache-reliant row-gather fallback (out of place only),
- * knob 3 = upper bound on the number of persistent workgroups.
- * Values the kernels cannot honour give BF_ERR_UNSUPPORTED at the next compute call. */
+/* Launch-shape override for experiments and sweeps; value 0 restores the built-in heuristic.
+ *   knob 0: column-tile width of the LDS tile kernel in elements (power of two, 64..1024)
+ *   knob 1: workgroups per compute unit for the tile kernel
+ *   knob 2: 1 forces the cache-reliant row-gather fallback (out of place only)
+ *   knob 3: upper bound on the number of persistent workgroups
+ *   knob 5: 1 disables the row-streaming chain kernel
+ *   knob 6: forces the chain kernel (where the round has a chain plan) with 1, 2 or 4 16-byte
+ *           vectors per thread, whatever the matrix shape
+ * Values the kernels cannot honour give BF_ERR_UNSUPPORTED at the next compute call.  Process-wide,
+ * not thread safe: for benchmarks and tests only. */
 int bf_set_tuning(int32_t knob, int32_t value);
 
 #ifdef __cplusplus

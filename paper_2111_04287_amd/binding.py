@@ -28,7 +28,7 @@ BF_W_ANY, BF_W_PULL, BF_W_PUSH, BF_W_STANDARD = 0, 1, 2, 3
 EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
-    "bf_topology_export_csr", "bf_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step",
+    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step",
     "bf_atc_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -81,6 +81,7 @@ def _load():
     L.bf_topology_max_degree.argtypes = [vp, i32]
     L.bf_topology_class.argtypes = [vp, i32]
     L.bf_topology_export_csr.argtypes = [vp, i32, vp, vp, vp, C.POINTER(C.c_uint64)]
+    L.bf_topology_chain_plan.argtypes = [vp, i32, vp]
     L.bf_neighbor_allreduce.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_dense_mix.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_pushsum_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
@@ -195,6 +196,18 @@ def bf_topology_export_csr(t, rnd=0):
     _check(lib.bf_topology_export_csr(t.handle, rnd, rowptr.ctypes.data, col.ctypes.data, wgt.ctypes.data,
                                       C.byref(seed)), "bf_topology_export_csr")
     return rowptr, col, wgt, seed.value
+
+
+def bf_topology_chain_plan(t, rnd=0):
+    """None if the round has no chain plan, else an (n, 8) int32 array of walk steps."""
+    n = lib.bf_topology_chain_plan(t.handle, rnd, None)
+    if n < 0:
+        raise BfError(int(n), "bf_topology_chain_plan")
+    if n == 0:
+        return None
+    steps = np.empty((n, 8), dtype=np.int32)
+    lib.bf_topology_chain_plan(t.handle, rnd, steps.ctypes.data)
+    return steps
 
 
 # ---- tensor marshalling ----------------------------------------------------------------------

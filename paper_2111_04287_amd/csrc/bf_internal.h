@@ -11,6 +11,19 @@
 
 namespace bf {
 
+// One step of a chain walk (see build_chain_plan): the row to produce, what to load next, and the
+// row's at most three CSR entries as (slot, weight) in CSR order.  32 bytes: one scalar load.
+struct ChainStep {
+  int32_t row;        // output row of this step
+  int32_t flags;      // bit 0: first row of a chain; bit 1: the chain is a cycle;
+                      // bits 2-3: where the next row comes from: 0 load next_row, 1 the kept last
+                      // row of the cycle, 2 the kept first row of the cycle, 3 there is none
+  int32_t last_row;   // at the first step of a cycle: the cycle's last row (loaded up front)
+  int32_t next_row;   // row to load when bits 2-3 are 0
+  int32_t slots;      // three 4-bit codes, entry e in bits 4e..4e+3: 0 previous, 1 this row, 2 next, 15 none
+  float   w[3];       // the entries' weights, in CSR order
+};
+
 // One weight matrix W^(r) as receiver-major CSR: row i lists (j, w_ij), j ascending.
 struct Round {
   std::vector<int64_t> rowptr;   // n+1
@@ -18,6 +31,7 @@ struct Round {
   std::vector<float>   wgt;      // nnz
   int32_t max_degree = 0;
   int32_t wclass = 0;            // bf_wclass_t bit mask
+  std::vector<ChainStep> chain;  // n steps when the off-diagonal graph is a union of paths and cycles
 };
 
 // Device-resident copy of all rounds, built on first use on a device.
@@ -26,6 +40,7 @@ struct DeviceCopy {
   char*    blob = nullptr;               // [round]: int32 rowptr[n+1] (padded to 8 B) | {int32 col, f32 w}[nnz]
   std::vector<size_t> rowptr_off;        // byte offsets into blob, per round
   std::vector<size_t> entry_off;
+  std::vector<size_t> chain_off;         // byte offset of the round's ChainStep[n], or SIZE_MAX
   float*   dense_t = nullptr;            // [round][k][i] = w_ik, n_pad x n_pad, lazily built
   int32_t  n_pad = 0;
 };
@@ -46,6 +61,7 @@ namespace bf {
 // Host-only helpers implemented in bf_topology.cpp.
 int  finalize_round(Round& r, int32_t n);           // sort check, class, max degree; returns status
 void dense_transposed(const Round& r, int32_t n, int32_t n_pad, float* out);  // out[k*n_pad+i] = w_ik
+void build_chain_plan(Round& r, int32_t n);          // fills r.chain when the structure allows
 
 }  // namespace bf
 

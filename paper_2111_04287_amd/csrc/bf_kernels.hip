@@ -69,6 +69,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 #ifndef BF_NT_MSTORE
 #define BF_NT_MSTORE 0
 #endif
+#ifndef BF_NT_CHAIN_LOAD
+#define BF_NT_CHAIN_LOAD 1
+#endif
+#ifndef BF_INTERLEAVE
+#define BF_INTERLEAVE 1
+#endif
 template <typename T> __device__ __forceinline__ T ld_stream(const T* ptr) {
 #if BF_NT_LOAD
   return __builtin_nontemporal_load(ptr);
@@ -100,6 +106,7 @@ struct TileParams {
   const float* p_out;    // push-sum weights after this round (for y)
   const int32_t* rowptr; // device CSR of the round
   const u32x2*   ent;    // {col, weight bits}
+  const bf::ChainStep* chain;  // walk order of the round when it has chain structure, else null
   int64_t d, ld;
   int64_t ntiles;
   int32_t n;
@@ -193,10 +200,9 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   // once): a unit past the tile's end re-reads the last unit, a column at or past d re-reads the
   // row's last in-range vector.  Only the LDS write and the M store are predicated.
   const int64_t last_vec = d > 0 ? ((d - 1) >> UC_LOG) << UC_LOG : 0;
-  auto issue_loads = [&](int64_t tile) {
+  auto issue_one = [&](int64_t tile, int k) {
     const int64_t c0 = tile << log_c;
-#pragma unroll
-    for (int k = 0; k < MAXPF; ++k) {
+    {
       const int u = min(tid + k * THREADS, nunits - 1);
       const int row = u >> upr_log;
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
@@ -208,6 +214,10 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
         for (int q = 0; q < MV; ++q) mr[k * MV + q] = ld_stream(reinterpret_cast<const f32x4*>(p.m + off + 4 * q));
       }
     }
+  };
+  auto issue_loads = [&](int64_t tile) {
+#pragma unroll
+    for (int k = 0; k < MAXPF; ++k) issue_one(tile, k);
   };
 
   // Transform one staging unit (local update, momentum) and put it into the LDS tile.
@@ -280,15 +290,16 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   const csr_i32_ptr rowptr = (csr_i32_ptr)(uintptr_t)p.rowptr;
   const csr_ent_ptr ent = (csr_ent_ptr)(uintptr_t)p.ent;
 
-  auto reduce_and_store = [&](int64_t tile) {
-    constexpr int NW = THREADS / 64;
-    constexpr int SPAN_LOG = (LW == 4 ? 8 : (LW == 2 ? 7 : 6));      // log2(64*LW)
+  constexpr int NW = THREADS / 64;
+  constexpr int SPAN_LOG = (LW == 4 ? 8 : (LW == 2 ? 7 : 6));      // log2(64*LW)
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int spans_log = log_c - SPAN_LOG;
+  const int nops = p.n << spans_log;
+  // One output row-span: gather from LDS in CSR order, finish, store.
+  auto row_op = [&](int64_t tile, int op) {
     const int64_t c0 = tile << log_c;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lane = tid & 63;
-    const int spans_log = log_c - SPAN_LOG;
-    const int nops = p.n << spans_log;
-    for (int op = wave; op < nops; op += NW) {
+    {
       const int i = op >> spans_log;
       const int cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
       const int64_t col = c0 + cit;
@@ -342,17 +353,251 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       }
     }
   };
+  // Reduce phase of `tile`; the loads of tile `next` (if any) are issued one by one between the
+  // first row-spans so that reads and writes alternate on the memory pipe.
+  auto reduce_and_store = [&](int64_t tile, int64_t next, bool has_next) {
+    int op = wave;
+#if BF_INTERLEAVE
+#pragma unroll
+    for (int k = 0; k < MAXPF; ++k) {
+      if (has_next) issue_one(next, k);
+      if (op < nops) { row_op(tile, op); op += NW; }
+    }
+#else
+    if (has_next) issue_loads(next);
+#endif
+    for (; op < nops; op += NW) row_op(tile, op);
+  };
 
+#ifdef BF_PROFILE
+  // Development-only phase timing (100 MHz wall clock), wave 0 and the last wave of each workgroup.
+  unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.y);
+  const bool rec = dbg && !WITH_Y && (tid == 0 || tid == THREADS - 64);
+  int it = 0;
+#define BF_MARK(k) if (rec && it < 16) dbg[((static_cast<size_t>(blockIdx.x) * 2 + (tid != 0)) * 16 + it) * 8 + (k)] = wall_clock64()
+#else
+#define BF_MARK(k)
+#endif
   int64_t tile = blockIdx.x;
   if (tile < p.ntiles) issue_loads(tile);
   while (tile < p.ntiles) {
+    BF_MARK(0);
     stage(tile);
+    BF_MARK(1);
     __syncthreads();
+    BF_MARK(2);
     const int64_t next = tile + gridDim.x;
-    if (next < p.ntiles) issue_loads(next);
-    reduce_and_store(tile);
+    BF_MARK(3);
+    reduce_and_store(tile, next, next < p.ntiles);
+    BF_MARK(4);
     __syncthreads();
+    BF_MARK(5);
     tile = next;
+#ifdef BF_PROFILE
+    ++it;
+#endif
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Chain kernel.  When every agent exchanges with at most two partners (ring, one-peer exponential
+// rounds, matchings) the rows can be ordered into paths and cycles such that a row's in-neighbors
+// sit directly before or after it.  Each thread then owns CW 16-byte column vectors and walks the
+// rows in that order with three live values per vector (previous, this, next): every row is loaded
+// once, combined in CSR order, and stored once.  No LDS, no barriers; all 256 threads of a
+// workgroup read 4 KB of one row per step, and all workgroups walk the rows in the same order, so
+// at any moment the device streams through a few rows over their whole width, like a plain copy.
+// A cycle keeps its first and last rows in registers so that it closes without re-reading (which
+// also makes in-place updates safe: a row is stored only after its last use as an operand).
+static_assert(sizeof(bf::ChainStep) == 32, "ChainStep is read as eight dwords");
+
+template <int DT, int OP, bool WITH_Y, int CW>
+__global__ __launch_bounds__(256) void bf_chain_kernel(const TileParams p, const int64_t nchunks) {
+  constexpr int EB = Elem<DT>::bytes;
+  constexpr int UC = Elem<DT>::per16;
+  constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
+  constexpr bool MOM = (OP == OP_MOM_ATC || OP == OP_MOM_AWC);
+  constexpr bool G_ON_LOAD = (OP == OP_ATC || OP == OP_MOM_ATC);
+  constexpr bool G_ON_STORE = (OP == OP_AWC || OP == OP_MOM_AWC);
+  constexpr int CHUNK_LOG = 8 + UC_LOG;                 // columns per 256-thread sweep
+  const int64_t d = p.d, ld = p.ld;
+  const int64_t last_vec = ((d - 1) >> UC_LOG) << UC_LOG;
+  const csr_i32_ptr steps = (csr_i32_ptr)(uintptr_t)p.chain;
+  const int tid = threadIdx.x;
+
+  for (int64_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+    int64_t col[CW];
+    bool live[CW];
+#pragma unroll
+    for (int w = 0; w < CW; ++w) {
+      const int64_t c = ((chunk * CW + w) << CHUNK_LOG) + (static_cast<int64_t>(tid) << UC_LOG);
+      live[w] = c < d;
+      col[w] = min(c, last_vec);
+    }
+    float prev[CW][UC], cur[CW][UC], nxt[CW][UC], first[CW][UC], last[CW][UC];
+
+    // y_j = x_j, or x_j - alpha g_j, or (momentum) x_j - alpha (beta m_j + g_j) with m_j written back
+    auto load_y = [&](int row, float (*out)[UC]) {
+      u32x4 xr[CW], gr[CW];
+      f32x4 mr[CW][UC / 4];
+#pragma unroll
+      for (int w = 0; w < CW; ++w) {
+        const int64_t off = static_cast<int64_t>(row) * ld + col[w];
+#if BF_NT_CHAIN_LOAD
+        xr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
+        if constexpr (G_ON_LOAD) gr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g + off * EB));
+#else
+        xr[w] = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
+        if constexpr (G_ON_LOAD) gr[w] = *reinterpret_cast<const u32x4*>(p.g + off * EB);
+#endif
+        if constexpr (OP == OP_MOM_ATC) {
+#pragma unroll
+          for (int q = 0; q < UC / 4; ++q) mr[w][q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+        }
+      }
+#pragma unroll
+      for (int w = 0; w < CW; ++w) {
+        widen<DT>(xr[w], out[w]);
+        if constexpr (G_ON_LOAD) {
+          float gv[UC];
+          widen<DT>(gr[w], gv);
+          if constexpr (OP == OP_MOM_ATC) {
+            const int64_t off = static_cast<int64_t>(row) * ld + col[w];
+#pragma unroll
+            for (int q = 0; q < UC / 4; ++q) {
+              f32x4 mv = mr[w][q];
+              mv.x = fmaf(p.beta, mv.x, gv[4 * q + 0]); mv.y = fmaf(p.beta, mv.y, gv[4 * q + 1]);
+              mv.z = fmaf(p.beta, mv.z, gv[4 * q + 2]); mv.w = fmaf(p.beta, mv.w, gv[4 * q + 3]);
+              gv[4 * q + 0] = mv.x; gv[4 * q + 1] = mv.y; gv[4 * q + 2] = mv.z; gv[4 * q + 3] = mv.w;
+              if (live[w]) {
+                const int64_t rem = d - (col[w] + 4 * q);
+                if (rem >= 4) *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = mv;
+                else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = gv[4 * q + e];
+              }
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < UC; ++e) out[w][e] = fmaf(-p.alpha, gv[e], out[w][e]);
+        }
+      }
+    };
+
+    for (int k = 0; k < p.n; ++k) {
+      // one ChainStep = eight dwords through the scalar cache
+      struct { int row, flags, last_row, next_row, slots; float w[3]; } st;
+      st.row = steps[8 * k + 0]; st.flags = steps[8 * k + 1]; st.last_row = steps[8 * k + 2];
+      st.next_row = steps[8 * k + 3]; st.slots = steps[8 * k + 4];
+      st.w[0] = __int_as_float(steps[8 * k + 5]); st.w[1] = __int_as_float(steps[8 * k + 6]);
+      st.w[2] = __int_as_float(steps[8 * k + 7]);
+      const int flags = st.flags;
+      if (flags & 1) {
+        if (flags & 2) {
+          load_y(st.last_row, last);
+#pragma unroll
+          for (int w = 0; w < CW; ++w)
+#pragma unroll
+            for (int e = 0; e < UC; ++e) prev[w][e] = last[w][e];
+        }
+        load_y(st.row, cur);
+#pragma unroll
+        for (int w = 0; w < CW; ++w)
+#pragma unroll
+          for (int e = 0; e < UC; ++e) first[w][e] = cur[w][e];
+      }
+      const int nk = (flags >> 2) & 3;
+      if (nk == 0) {
+        load_y(st.next_row, nxt);
+      } else if (nk == 1) {
+#pragma unroll
+        for (int w = 0; w < CW; ++w)
+#pragma unroll
+          for (int e = 0; e < UC; ++e) nxt[w][e] = last[w][e];
+      } else if (nk == 2) {
+#pragma unroll
+        for (int w = 0; w < CW; ++w)
+#pragma unroll
+          for (int e = 0; e < UC; ++e) nxt[w][e] = first[w][e];
+      }
+      float acc[CW][UC];
+#pragma unroll
+      for (int w = 0; w < CW; ++w)
+#pragma unroll
+        for (int e = 0; e < UC; ++e) acc[w][e] = 0.0f;
+#pragma unroll
+      for (int en = 0; en < 3; ++en) {
+        const int code = (st.slots >> (4 * en)) & 15;
+        if (code != 15) {
+          const float wt = st.w[en];
+#pragma unroll
+          for (int w = 0; w < CW; ++w)
+#pragma unroll
+            for (int e = 0; e < UC; ++e) {
+              const float v = code == 0 ? prev[w][e] : (code == 1 ? cur[w][e] : nxt[w][e]);
+              acc[w][e] = fmaf(wt, v, acc[w][e]);
+            }
+        }
+      }
+      // finish row st.row
+#pragma unroll
+      for (int w = 0; w < CW; ++w) {
+        if (live[w]) {
+          const int64_t off = static_cast<int64_t>(st.row) * ld + col[w];
+          const int64_t rem = d - col[w];
+          if constexpr (G_ON_STORE) {
+            float gv[UC];
+            widen<DT>(*reinterpret_cast<const u32x4*>(p.g + off * EB), gv);
+            if constexpr (MOM) {
+#pragma unroll
+              for (int q = 0; q < UC / 4; ++q) {
+                float mv[4];
+                load_in<DT_F32, 4>(reinterpret_cast<const char*>(p.m), off + 4 * q, mv);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { mv[e] = fmaf(p.beta, mv[e], gv[4 * q + e]); gv[4 * q + e] = mv[e]; }
+                const int64_t r4 = rem - 4 * q;
+                if (r4 > 0) {
+                  if (r4 >= 4) { f32x4 t = {mv[0], mv[1], mv[2], mv[3]}; *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = t; }
+                  else for (int e = 0; e < 4; ++e) if (e < r4) p.m[off + 4 * q + e] = mv[e];
+                }
+              }
+            }
+#pragma unroll
+            for (int e = 0; e < UC; ++e) acc[w][e] = fmaf(-p.alpha, gv[e], acc[w][e]);
+          }
+          float rcp = 1.0f;
+          if constexpr (WITH_Y) rcp = 1.0f / p.p_out[st.row];
+#pragma unroll
+          for (int h = 0; h < UC / 4; ++h) {
+            const int64_t r4 = rem - 4 * h;
+            if (r4 > 0) {
+              const int valid = r4 >= 4 ? 4 : static_cast<int>(r4);
+              if constexpr (DT == DT_BF16) if (h == 0 && rem >= 8) {
+                // both halves at once: one 16-byte store of eight bf16
+                u32x4 t = {pack_bf16x2(acc[w][0], acc[w][1]), pack_bf16x2(acc[w][2], acc[w][3]),
+                           pack_bf16x2(acc[w][4], acc[w][5]), pack_bf16x2(acc[w][6], acc[w][7])};
+                st_stream(reinterpret_cast<u32x4*>(p.x_out + off * EB), t);
+                if constexpr (WITH_Y) {
+                  u32x4 ty = {pack_bf16x2(acc[w][0] * rcp, acc[w][1] * rcp), pack_bf16x2(acc[w][2] * rcp, acc[w][3] * rcp),
+                              pack_bf16x2(acc[w][4] * rcp, acc[w][5] * rcp), pack_bf16x2(acc[w][6] * rcp, acc[w][7] * rcp)};
+                  st_stream(reinterpret_cast<u32x4*>(p.y + off * EB), ty);
+                }
+                break;
+              }
+              store_out<DT, 4>(p.x_out, off + 4 * h, acc[w] + 4 * h, valid);
+              if constexpr (WITH_Y) {
+                float yv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) yv[e] = acc[w][4 * h + e] * rcp;
+                store_out<DT, 4>(p.y, off + 4 * h, yv, valid);
+              }
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int w = 0; w < CW; ++w)
+#pragma unroll
+        for (int e = 0; e < UC; ++e) { prev[w][e] = cur[w][e]; cur[w][e] = nxt[w][e]; }
+    }
   }
 }
 
@@ -688,6 +933,9 @@ int get_device_copy(bf_topology_t* t, bool need_dense, bf::DeviceCopy** out) {
       bytes += ((static_cast<size_t>(t->n) + 1 + 1) / 2) * 8;
       c.entry_off.push_back(bytes);
       bytes += r.col.size() * 8;
+      bytes = (bytes + 31) / 32 * 32;
+      c.chain_off.push_back(r.chain.empty() ? SIZE_MAX : bytes);
+      bytes += r.chain.size() * sizeof(bf::ChainStep);
     }
     std::vector<char> host(bytes, 0);
     for (size_t k = 0; k < t->rounds.size(); ++k) {
@@ -699,6 +947,7 @@ int get_device_copy(bf_topology_t* t, bool need_dense, bf::DeviceCopy** out) {
         en[2 * q] = static_cast<uint32_t>(r.col[q]);
         std::memcpy(&en[2 * q + 1], &r.wgt[q], 4);
       }
+      if (!r.chain.empty()) std::memcpy(host.data() + c.chain_off[k], r.chain.data(), r.chain.size() * sizeof(bf::ChainStep));
     }
     BF_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&c.blob), std::max<size_t>(bytes, 16)));
     hipError_t e = hipMemcpy(c.blob, host.data(), bytes, hipMemcpyHostToDevice);
@@ -726,8 +975,13 @@ int g_tune_tile = 0;      // column-tile width override (elements)
 int g_tune_wgs = 0;       // workgroups per CU override
 int g_tune_gather = 0;    // 1: force the gather fallback
 int g_tune_grid = 0;      // total workgroups override (capped by the resident slots)
+int g_tune_nochain = 0;   // 1: never use the chain kernel
+int g_tune_cw = 0;        // chain kernel: 16-byte vectors per thread (1, 2 or 4)
+#ifdef BF_PROFILE
+unsigned long long g_dbg_ptr = 0;
+#endif
 
-struct Shape { int log_c; int lw; int wgs_per_cu; size_t lds_bytes; };
+struct Shape { int log_c; int lw; int wgs_per_cu; int threads; size_t lds_bytes; };
 
 int ilog2(int64_t v) { int l = 0; while ((int64_t{1} << (l + 1)) <= v) ++l; return l; }
 
@@ -761,15 +1015,16 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s) {
   }
   s->log_c = log_c;
   s->lw = log_c >= 8 ? 4 : (log_c == 7 ? 2 : 1);
-  s->wgs_per_cu = std::max(1, std::min(wgs, 2));
+  s->threads = 1024;
+  s->wgs_per_cu = std::max(1, std::min(wgs, 2048 / s->threads));
   s->lds_bytes = static_cast<size_t>(n) * (size_t{1} << log_c) * 4;
   return BF_OK;
 }
 
-template <int DT, int OP, bool WITH_Y, int LW>
-int launch_tile_lw(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
-  constexpr int THREADS = 1024;
-  constexpr int MAXPF = DT == DT_F32 ? 4 : 2;   // a 64 KB tile is 4 (fp32) / 2 (bf16) vectors per thread
+template <int DT, int OP, bool WITH_Y, int LW, int THREADS>
+int launch_tile_thr(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
+  // prefetch depth: a 64 KB tile is 4 (fp32) / 2 (bf16) vectors per thread at 1024 threads
+  constexpr int MAXPF = DT == DT_F32 ? 4 : 2;
   auto kern = bf_tile_kernel<DT, OP, WITH_Y, LW, THREADS, MAXPF>;
   if (lds > 48 * 1024) {
     static thread_local size_t raised = 0;
@@ -784,12 +1039,19 @@ int launch_tile_lw(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
   return BF_OK;
 }
 
+// 1024 threads, two workgroups per CU: smaller workgroups (256, 512 threads, more per CU) were
+// measured 5..25 % slower at every tile width.
+template <int DT, int OP, bool WITH_Y, int LW>
+int launch_tile_lw(const TileParams& tp, int grid, size_t lds, int /*threads*/, hipStream_t st) {
+  return launch_tile_thr<DT, OP, WITH_Y, LW, 1024>(tp, grid, lds, st);
+}
+
 template <int DT, int OP, bool WITH_Y>
 int launch_tile(const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
   switch (s.lw) {
-    case 4: return launch_tile_lw<DT, OP, WITH_Y, 4>(tp, grid, s.lds_bytes, st);
-    case 2: return launch_tile_lw<DT, OP, WITH_Y, 2>(tp, grid, s.lds_bytes, st);
-    default: return launch_tile_lw<DT, OP, WITH_Y, 1>(tp, grid, s.lds_bytes, st);
+    case 4: return launch_tile_lw<DT, OP, WITH_Y, 4>(tp, grid, s.lds_bytes, s.threads, st);
+    case 2: return launch_tile_lw<DT, OP, WITH_Y, 2>(tp, grid, s.lds_bytes, s.threads, st);
+    default: return launch_tile_lw<DT, OP, WITH_Y, 1>(tp, grid, s.lds_bytes, s.threads, st);
   }
 }
 
@@ -825,6 +1087,30 @@ int check_matrix_shape(int32_t n, int64_t d, int64_t ld, int dt, MatArgs* ma) {
 
 bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+template <int DT, int CW>
+int launch_chain_cw(int op, bool with_y, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st) {
+#define BF_CHAIN(OPV, YV) hipLaunchKernelGGL((bf_chain_kernel<DT, OPV, YV, CW>), dim3(grid), dim3(256), 0, st, tp, nchunks)
+  switch (op) {
+    case OP_MIX: if (with_y) BF_CHAIN(OP_MIX, true); else BF_CHAIN(OP_MIX, false); break;
+    case OP_ATC: BF_CHAIN(OP_ATC, false); break;
+    case OP_AWC: BF_CHAIN(OP_AWC, false); break;
+    case OP_MOM_ATC: BF_CHAIN(OP_MOM_ATC, false); break;
+    default: BF_CHAIN(OP_MOM_AWC, false); break;
+  }
+#undef BF_CHAIN
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+template <int DT>
+int launch_chain(int op, bool with_y, int cw, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st) {
+  if constexpr (DT == DT_F32) {
+    if (cw == 4) return launch_chain_cw<DT, 4>(op, with_y, tp, nchunks, grid, st);
+  }
+  if (cw == 2) return launch_chain_cw<DT, 2>(op, with_y, tp, nchunks, grid, st);
+  return launch_chain_cw<DT, 1>(op, with_y, tp, nchunks, grid, st);
+}
+
 template <int DT>
 int launch_gather(int op, bool with_y, const TileParams& tp, int grid, hipStream_t st) {
 #define BF_GATHER(OPV, YV) hipLaunchKernelGGL((bf_gather_kernel<DT, OPV, YV>), dim3(grid), dim3(256), 0, st, tp)
@@ -852,6 +1138,25 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   tp.rowptr = reinterpret_cast<const int32_t*>(dc->blob + dc->rowptr_off[k]);
   tp.ent = reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[k]);
   tp.n = t->n;
+  if (dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather &&
+      (g_tune_cw > 0 || static_cast<size_t>(t->n) * 256 * 4 > (di.lds_per_cu ? di.lds_per_cu : 65536) / 2)) {
+    // Chain-structured round with too many agents for a 256-column LDS tile (measured: the tile
+    // kernel wins below that, the row-streaming kernel above): stream rows through registers when
+    // the matrix is wide enough to give every CU several 256-thread workgroups.
+    const int per16 = dt == BF_F32 ? 4 : 8;
+    int cw = g_tune_cw > 0 ? g_tune_cw : (dt == BF_F32 ? 4 : 2);
+    if (cw != 1 && cw != 2 && cw != 4) return BF_ERR_UNSUPPORTED;
+    if (dt != BF_F32 && cw == 4) cw = 2;
+    const int64_t chunk_cols = static_cast<int64_t>(256) * per16 * cw;
+    const int64_t nchunks = (tp.d + chunk_cols - 1) / chunk_cols;
+    if (nchunks >= 2 * static_cast<int64_t>(di.cus) || g_tune_cw > 0) {
+      tp.chain = reinterpret_cast<const bf::ChainStep*>(dc->blob + dc->chain_off[k]);
+      int grid = static_cast<int>(std::min<int64_t>(nchunks, static_cast<int64_t>(di.cus) * 8));
+      if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
+      return dt == BF_F32 ? launch_chain<DT_F32>(op, with_y, cw, tp, nchunks, grid, st)
+                          : launch_chain<DT_BF16>(op, with_y, cw, tp, nchunks, grid, st);
+    }
+  }
   Shape s;
   rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(t->n, tp.d, di, &s);
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
@@ -870,6 +1175,9 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     return dt == BF_F32 ? launch_gather<DT_F32>(op, with_y, tp, grid, st) : launch_gather<DT_BF16>(op, with_y, tp, grid, st);
   }
   if (rc != BF_OK) return rc;
+#ifdef BF_PROFILE
+  if (!with_y) tp.y = reinterpret_cast<char*>(g_dbg_ptr);
+#endif
   tp.log_c = s.log_c;
   tp.ntiles = (tp.d + (int64_t{1} << s.log_c) - 1) >> s.log_c;
   int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus) * s.wgs_per_cu));
@@ -885,11 +1193,19 @@ extern "C" {
 int bf_last_hip_error(void) { return g_last_hip_error; }
 
 int bf_set_tuning(int32_t knob, int32_t value) {
+#ifndef BF_PROFILE
   if (value < 0) return BF_ERR_SIZE;
+#endif
   if (knob == 0) g_tune_tile = value;
   else if (knob == 1) g_tune_wgs = value;
   else if (knob == 2) g_tune_gather = value;
   else if (knob == 3) g_tune_grid = value;
+  else if (knob == 5) g_tune_nochain = value;
+  else if (knob == 6) g_tune_cw = value;
+#ifdef BF_PROFILE
+  else if (knob == 100) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFF00000000ull) | static_cast<uint32_t>(value);
+  else if (knob == 101) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFFull) | (static_cast<unsigned long long>(static_cast<uint32_t>(value)) << 32);
+#endif
   else return BF_ERR_KIND;
   return BF_OK;
 }

@@ -198,7 +198,79 @@ int finalize_round(Round& r, int32_t n) {
   }
   r.max_degree = maxdeg;
   r.wclass = (pull ? BF_W_PULL : 0) | (push ? BF_W_PUSH : 0);
+  if (maxdeg <= 3) build_chain_plan(r, n);
   return BF_OK;
+}
+
+// Chain plan.  Take the undirected graph on agents with an edge {i, j} whenever w_ij or w_ji is
+// stored off the diagonal.  If no agent has more than two such partners the graph is a disjoint
+// union of paths and cycles (the ring; every round of the one-peer exponential schedule; any
+// matching), and walking each path or cycle in order visits, for every row, its in-neighbors
+// immediately before or after it.  A kernel can then stream the rows of a column strip through
+// three registers (previous, current, next) instead of staging all n rows.
+void build_chain_plan(Round& r, int32_t n) {
+  r.chain.clear();
+  std::vector<std::vector<int32_t>> adj(n);
+  for (int32_t i = 0; i < n; ++i)
+    for (int64_t p = r.rowptr[i]; p < r.rowptr[i + 1]; ++p) {
+      const int32_t j = r.col[p];
+      if (j == i) continue;
+      if (std::find(adj[i].begin(), adj[i].end(), j) == adj[i].end()) adj[i].push_back(j);
+      if (std::find(adj[j].begin(), adj[j].end(), i) == adj[j].end()) adj[j].push_back(i);
+      if (adj[i].size() > 2 || adj[j].size() > 2) return;
+    }
+  std::vector<char> done(n, 0);
+  std::vector<ChainStep> steps;
+  steps.reserve(n);
+  auto emit = [&](const std::vector<int32_t>& seq, bool cycle) {
+    const int32_t L = static_cast<int32_t>(seq.size());
+    for (int32_t k = 0; k < L; ++k) {
+      ChainStep st{};
+      st.row = seq[k];
+      const int32_t pred = k > 0 ? seq[k - 1] : (cycle ? seq[L - 1] : -1);
+      int32_t next_kind;
+      st.next_row = -1;
+      if (k + 1 < L) {
+        if (cycle && k + 1 == L - 1) next_kind = 1;          // the last row was loaded at the start
+        else { next_kind = 0; st.next_row = seq[k + 1]; }
+      } else {
+        next_kind = cycle ? 2 : 3;
+      }
+      st.flags = (k == 0 ? 1 : 0) | (cycle ? 2 : 0) | (next_kind << 2);
+      st.last_row = (k == 0 && cycle) ? seq[L - 1] : -1;
+      int32_t slots = 0xFFF;
+      int e = 0;
+      for (int64_t p = r.rowptr[st.row]; p < r.rowptr[st.row + 1]; ++p, ++e) {
+        const int32_t j = r.col[p];
+        const int32_t code = (j == st.row) ? 1 : (j == pred ? 0 : 2);
+        slots = (slots & ~(0xF << (4 * e))) | (code << (4 * e));
+        st.w[e] = r.wgt[p];
+      }
+      st.slots = slots;
+      steps.push_back(st);
+    }
+  };
+  // paths first (start from an end point), then cycles
+  for (int pass = 0; pass < 2; ++pass)
+    for (int32_t s0 = 0; s0 < n; ++s0) {
+      if (done[s0]) continue;
+      if (pass == 0 && adj[s0].size() == 2) continue;
+      std::vector<int32_t> seq;
+      int32_t prev = -1, cur = s0;
+      while (cur >= 0 && !done[cur]) {
+        done[cur] = 1;
+        seq.push_back(cur);
+        int32_t nxt = -1;
+        for (int32_t v : adj[cur])
+          if (v != prev && !done[v]) { nxt = v; break; }
+        prev = cur;
+        cur = nxt;
+      }
+      const bool cycle = pass == 1 && seq.size() >= 3;
+      emit(seq, cycle);
+    }
+  // a row with more than three stored entries cannot occur here (self + two partners at most)
+  r.chain = std::move(steps);
 }
 
 void dense_transposed(const Round& r, int32_t n, int32_t n_pad, float* out) {
@@ -419,6 +491,16 @@ int32_t bf_topology_class(const bf_topology_t* t, int32_t round) {
   if (!t) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   return t->rounds[slice_index(t, round)].wclass;
+}
+
+int32_t bf_topology_chain_plan(const bf_topology_t* t, int32_t round, int32_t* steps) {
+  if (!t) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  const Round& r = t->rounds[slice_index(t, round)];
+  if (r.chain.empty()) return 0;
+  static_assert(sizeof(bf::ChainStep) == 32, "ChainStep is exported as eight 32-bit words");
+  if (steps) std::memcpy(steps, r.chain.data(), r.chain.size() * sizeof(bf::ChainStep));
+  return t->n;
 }
 
 int bf_topology_export_csr(const bf_topology_t* t, int32_t round, int64_t* rowptr, int32_t* col,

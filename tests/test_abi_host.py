@@ -273,3 +273,91 @@ def test_compute_calls_validate_before_touching_the_device():
     assert cs(4, 64, 64, A, None, bf.BF_F32, M + 4, None, None) == bf.BF_ERR_ALIGN
     assert L.bf_set_tuning(9, 1) == bf.BF_ERR_KIND
     assert L.bf_set_tuning(0, 0) == bf.BF_OK
+
+
+def _walk_chain_plan(steps, X):
+    """Replay a chain plan the way the streaming kernel does: three live rows, each row loaded once."""
+    n = X.shape[0]
+    out = np.full_like(X, np.nan)
+    loads = []
+
+    def load(r):
+        loads.append(int(r))
+        return X[r].copy()
+
+    prev = cur = nxt = first = last = None
+    for k in range(n):
+        row, flags, last_row, next_row, slots = (int(v) for v in steps[k, :5])
+        w = steps[k, 5:8].view(np.float32).astype(np.float64)
+        if flags & 1:
+            prev = first = last = None
+            if flags & 2:
+                last = load(last_row)
+                prev = last
+            cur = load(row)
+            first = cur
+        nk = (flags >> 2) & 3
+        nxt = load(next_row) if nk == 0 else last if nk == 1 else first if nk == 2 else None
+        acc = np.zeros(X.shape[1])
+        for e in range(3):
+            code = (slots >> (4 * e)) & 15
+            if code != 15:
+                acc += w[e] * (prev, cur, nxt)[code]
+        assert np.isnan(out[row]).all()
+        out[row] = acc
+        prev, cur = cur, nxt
+    assert sorted(loads) == list(range(n))             # every row read exactly once
+    return out
+
+
+@pytest.mark.parametrize("make,rounds", [
+    (lambda: bf.bf_topology_create(bf.BF_RING, 16), 1),
+    (lambda: bf.bf_topology_create(bf.BF_RING, 3), 1),
+    (lambda: bf.bf_topology_create(bf.BF_RING, 2), 1),
+    (lambda: bf.bf_topology_create(bf.BF_RING, 1), 1),
+    (lambda: bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, 256), 8),
+    (lambda: bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, 12), 4),
+    (lambda: bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, 2), 1),
+    (lambda: bf.bf_topology_create(bf.BF_EXP_STATIC, 4), 1),      # neighbors +-1, 2: three partners -> no plan
+])
+def test_chain_plan_replays_to_the_oracle_mix(make, rounds):
+    from oracle import iterations as O
+    t = make()
+    n = bf.bf_topology_n(t) if hasattr(bf, "bf_topology_n") else t.n
+    rng = np.random.default_rng(n)
+    X = rng.normal(size=(n, 5))
+    for r in range(rounds):
+        steps = bf.bf_topology_chain_plan(t, r)
+        W = _lib_W(t, r)[0]
+        partners = max(len(set(j for j, _ in W[i] if j != i) | set(k for k in W if any(j == i for j, _ in W[k]) and k != i))
+                       for i in W)
+        if partners > 2:
+            assert steps is None
+            continue
+        assert steps is not None and steps.shape == (n, 8)
+        np.testing.assert_allclose(_walk_chain_plan(steps, X), O.mix(X, W), atol=1e-14)
+
+
+def test_chain_plan_on_a_directed_path_and_a_matching():
+    from oracle import iterations as O
+    # rows pull from the next row only, last row keeps itself: a path, not a cycle
+    n = 5
+    D = np.eye(n, dtype=np.float32) * 0.25
+    for i in range(n - 1):
+        D[i, i + 1] = 0.75
+    D[n - 1, n - 1] = 1.0
+    t = bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=D)
+    steps = bf.bf_topology_chain_plan(t, 0)
+    X = np.random.default_rng(1).normal(size=(n, 3))
+    np.testing.assert_allclose(_walk_chain_plan(steps, X), D.astype(np.float64) @ X, atol=1e-14)
+    assert not (steps[:, 1] & 2).any()
+    # a perfect matching with asymmetric weights, plus one isolated agent
+    n = 7
+    D = np.zeros((n, n), dtype=np.float32)
+    for a, b in ((0, 4), (1, 5), (2, 3)):
+        D[a, a], D[a, b], D[b, b], D[b, a] = 0.3, 0.7, 0.6, 0.4
+    D[6, 6] = 1.0
+    t = bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=D)
+    steps = bf.bf_topology_chain_plan(t, 0)
+    X = np.random.default_rng(2).normal(size=(n, 3))
+    np.testing.assert_allclose(_walk_chain_plan(steps, X), D.astype(np.float64) @ X, atol=1e-14)

@@ -479,3 +479,100 @@ def test_consensus_stats_and_quadratic_gradient(dtype):
     bf.bf_grad_quadratic(X, Cc, E, 1.5, 0.1, G)
     ref = O.quadratic_noise_grad(host(X), host(Cc), host(E), 1.5, float(np.float32(0.1)))
     assert_close(G, ref, 1e-6 if dtype == torch.float32 else 2.0 ** -8)
+
+
+# ------------------------------------------------------------------ chain (row-streaming) kernel
+class _chain:
+    """Force the chain kernel with cw vectors per thread (it is otherwise reserved for wide matrices)."""
+
+    def __init__(self, cw):
+        self.cw = cw
+
+    def __enter__(self):
+        bf.bf_set_tuning(6, self.cw)
+
+    def __exit__(self, *a):
+        bf.bf_set_tuning(6, 0)
+
+
+class _no_chain:
+    def __enter__(self):
+        bf.bf_set_tuning(5, 1)
+
+    def __exit__(self, *a):
+        bf.bf_set_tuning(5, 0)
+
+
+CHAIN_TOPOS = [
+    ("ring16", lambda: bf.bf_topology_create(bf.BF_RING, 16)),
+    ("ring3", lambda: bf.bf_topology_create(bf.BF_RING, 3)),
+    ("ring2", lambda: bf.bf_topology_create(bf.BF_RING, 2)),
+    ("one", lambda: bf.bf_topology_create(bf.BF_RING, 1)),
+    ("onepeer256", lambda: bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, 256)),
+    ("onepeer12", lambda: bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, 12)),
+]
+
+
+@pytest.mark.parametrize("name,make", CHAIN_TOPOS)
+@pytest.mark.parametrize("cw", [1, 2, 4])
+@pytest.mark.parametrize("d", [4, 1000, 4096 + 136])
+def test_chain_kernel_mix_fp32(name, make, cw, d):
+    t = make()
+    n = t.n
+    X = rows(n, d, 300 + n)
+    for r in range(bf.bf_topology_rounds(t)):
+        assert bf.bf_topology_chain_plan(t, r) is not None
+        ref = O.mix(host(X), lib_W(t, r))
+        out = empty_like_rows(X)
+        out.fill_(float("nan"))
+        with _chain(cw):
+            bf.bf_neighbor_allreduce(t, r, X, out)
+        assert_close(out, ref, TOL32, "%s r=%d" % (name, r))
+        with _no_chain():
+            tile = empty_like_rows(X)
+            bf.bf_neighbor_allreduce(t, r, X, tile)
+        assert torch.equal(out, tile)                     # same CSR order on both kernels: same bits
+        Xi = empty_like_rows(X)
+        Xi.copy_(X)
+        with _chain(cw):
+            bf.bf_neighbor_allreduce(t, r, Xi, Xi)        # in place
+        assert torch.equal(Xi, out)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("cw", [1, 2])
+def test_chain_kernel_fused_ops(dtype, cw):
+    n, d = 16, 2048 + 40
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    W = lib_W(t)
+    X, G = rows(n, d, 61, dtype=dtype), rows(n, d, 62, dtype=dtype)
+    alpha, beta = 0.1, 0.9
+    a64, b64 = float(np.float32(alpha)), float(np.float32(beta))
+    tol = TOL32 if dtype == torch.float32 else 2.0 ** -8
+    for mode in (bf.BF_ATC, bf.BF_AWC):
+        out = empty_like_rows(X)
+        with _chain(cw):
+            bf.bf_atc_step(t, 0, X, out, G, None, alpha=alpha, mode=mode)
+        ref = (O.atc_step if mode == bf.BF_ATC else O.awc_step)(host(X), host(G), W, a64)
+        assert_close(out, ref, tol, "mode %d" % mode)
+        M = workloads.normal_rows(n, d, 63, DEV, ld=X.stride(0))
+        M0 = host(M)
+        Xi = empty_like_rows(X)
+        Xi.copy_(X)
+        with _chain(cw):
+            bf.bf_atc_step(t, 0, Xi, Xi, G, M, alpha=alpha, beta=beta, mode=mode)     # in place, momentum
+        Mn = b64 * M0 + host(G)
+        ref = O.mix(host(X) - a64 * Mn, W) if mode == bf.BF_ATC else O.mix(host(X), W) - a64 * Mn
+        assert_close(M, Mn, 1e-6, "momentum")
+        assert_close(Xi, ref, tol, "momentum x, mode %d" % mode)
+    # push-sum ratio output on a one-peer round
+    t2 = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+    w0 = torch.rand(n, device=DEV) + 0.5
+    w1 = torch.empty_like(w0)
+    out, Y = empty_like_rows(X), empty_like_rows(X)
+    with _chain(cw):
+        bf.bf_pushsum_step(t2, 1, X, out, w0, w1, Y)
+    Xr, pr, Yr = O.pushsum_step(host(X), host(w0[:, None])[:, 0], lib_W(t2, 1))
+    assert_close(out, Xr, tol)
+    assert_close(w1, pr, TOL32)
+    assert_close(Y, Yr, 2e-5 if dtype == torch.float32 else 2.0 ** -7)
