@@ -63,7 +63,7 @@ def test_mix_fp32_matches_oracle(name, make, n, d):
         pytest.skip("needs a few agents")
     t = make(n)
     X = rows(n, d, 1000 + n)
-    for r in range(min(2, bf.bf_topology_rounds(t))):
+    for r in range(2):                            # odd rounds walk the tiles right to left
         out = empty_like_rows(X)
         out.fill_(float("nan"))
         bf.bf_neighbor_allreduce(t, r, X, out)
@@ -149,6 +149,30 @@ def test_mix_result_is_independent_of_tile_width(tile):
     finally:
         bf.bf_set_tuning(0, 0)
     assert torch.equal(out, ref)                  # same CSR order, same FMA chain: same bits
+
+
+@pytest.mark.parametrize("knob,value", [(7, 1), (8, 1), (8, 2), (1, 1), (3, 3)])
+def test_launch_policy_knobs_do_not_change_results(knob, value):
+    # tile order, cache policy, occupancy and grid size are scheduling choices: same bits
+    n, d = 64, 9000
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    X, G = rows(n, d, 78), rows(n, d, 79)
+    ref = [empty_like_rows(X) for _ in range(4)]
+    for r in range(2):
+        bf.bf_neighbor_allreduce(t, r, X, ref[r])
+        bf.bf_atc_step(t, r, X, ref[2 + r], G, None, alpha=0.1, mode=bf.BF_ATC)
+    try:
+        bf.bf_set_tuning(knob, value)
+        for r in range(2):
+            out = empty_like_rows(X)
+            bf.bf_neighbor_allreduce(t, r, X, out)
+            assert torch.equal(out, ref[r])
+            Xi = empty_like_rows(X)
+            Xi.copy_(X)
+            bf.bf_atc_step(t, r, Xi, Xi, G, None, alpha=0.1, mode=bf.BF_ATC)
+            assert torch.equal(Xi, ref[2 + r])
+    finally:
+        bf.bf_set_tuning(knob, 0)
 
 
 def test_mix_bf16_matches_oracle():
