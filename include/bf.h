@@ -170,6 +170,17 @@ int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X
                 float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld,
                 bf_dtype_t dt, void* hip_stream);
 
+/* One Exact-Diffusion iteration (appendix "Application example: Exact-Diffusion algorithm",
+ * eqs. ed-1, ed-2, ed-3), fused into one pass:
+ *   psi_i = x_i - alpha g_i;   phi_i = psi_i + x_i - psi_prev_i;   X_out[i,:] = sum_j w_ij phi_j;
+ *   Psi_prev[i,:] <- psi_i.
+ * Psi_prev is fp32, n x d with leading dimension ld, updated in place; before the first iteration
+ * the caller sets it to X (so that phi^(0) = psi^(0)).  G has the dtype and layout of X.  Needs an
+ * LDS tile or a chain plan (n <= 640 agents), else BF_ERR_UNSUPPORTED. */
+int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                            const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
+                            bf_dtype_t dt, void* hip_stream);
+
 /* Local least-squares gradients of decentralized linear regression (eq. dgd-1):
  *   G[i,:] = A_i^T (A_i x_i - b_i),  A: n x m x d row-major fp32, b: n x m fp32.
  * 1 <= m <= 64, d a multiple of 4.  G must not alias X. */

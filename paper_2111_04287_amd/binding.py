@@ -29,7 +29,7 @@ EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step",
-    "bf_atc_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
+    "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
 
@@ -86,6 +86,7 @@ def _load():
     L.bf_dense_mix.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_pushsum_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_atc_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, f32, C.c_int, i64, i64, C.c_int, vp]
+    L.bf_exact_diffusion_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, i64, i64, C.c_int, vp]
     L.bf_grad_least_squares.argtypes = [i32, i32, i64, vp, vp, vp, i64, vp, i64, vp]
     L.bf_grad_quadratic.argtypes = [i32, i64, i64, vp, vp, vp, f32, f32, vp, C.c_int, vp]
     L.bf_consensus_stats.argtypes = [i32, i64, i64, vp, vp, C.c_int, vp, vp, vp]
@@ -282,6 +283,18 @@ def bf_atc_step(t, rnd, X_in, X_out, G, M=None, alpha=0.0, beta=0.0, mode=BF_ATC
     _check(lib.bf_atc_step(t.handle, rnd, ptr, X_out.data_ptr(), G.data_ptr(),
                            None if M is None else M.data_ptr(), alpha, beta, mode, d, ld,
                            _dtype_code(X_in), _stream(stream)), "bf_atc_step")
+    return X_out
+
+
+def bf_exact_diffusion_step(t, rnd, X_in, X_out, G, Psi_prev, alpha, stream=None):
+    import torch
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _same_layout(X_in, X_out, "X_out")
+    _same_layout(X_in, G, "G")
+    if Psi_prev.dtype != torch.float32 or Psi_prev.shape != X_in.shape or (n > 1 and Psi_prev.stride(0) != ld):
+        raise ValueError("Psi_prev must be float32 with the shape and row stride of X_in")
+    _check(lib.bf_exact_diffusion_step(t.handle, rnd, ptr, X_out.data_ptr(), G.data_ptr(), Psi_prev.data_ptr(),
+                                       alpha, d, ld, _dtype_code(X_in), _stream(stream)), "bf_exact_diffusion_step")
     return X_out
 
 

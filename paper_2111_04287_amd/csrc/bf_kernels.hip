@@ -78,7 +78,7 @@ template <bool NT, typename T> __device__ __forceinline__ void st_stream(T* ptr,
 typedef const int32_t __attribute__((address_space(4)))* csr_i32_ptr;
 typedef const u32x2 __attribute__((address_space(4)))* csr_ent_ptr;
 
-enum { OP_MIX = 0, OP_ATC = 1, OP_AWC = 2, OP_MOM_ATC = 3, OP_MOM_AWC = 4 };
+enum { OP_MIX = 0, OP_ATC = 1, OP_AWC = 2, OP_MOM_ATC = 3, OP_MOM_AWC = 4, OP_ED = 5 };
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
 struct TileParams {
@@ -154,6 +154,27 @@ __device__ __forceinline__ void load_in(const char* base, int64_t off, float* v)
   }
 }
 
+// Local update of four columns of one agent while its row is staged, for the ops that carry an
+// fp32 state matrix.  In: xv = x, gv = g, st = state.  Out: xv = the value to be mixed, st = the new
+// state to write back.
+//   OP_MOM_ATC (heavy-ball momentum, adapt-then-combine): m <- beta m + g;  mixed value x - alpha m.
+//   OP_ED (Exact-Diffusion, eqs. ed-1, ed-2): psi = x - alpha g;  phi = psi + x - psi_prev;
+//          mixed value phi, state <- psi.
+template <int OP>
+__device__ __forceinline__ void local_update4(float* xv, const float* gv, float* st, float alpha, float beta) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    if constexpr (OP == OP_ED) {
+      const float psi = fmaf(-alpha, gv[e], xv[e]);
+      xv[e] = (psi + xv[e]) - st[e];
+      st[e] = psi;
+    } else {
+      st[e] = fmaf(beta, st[e], gv[e]);
+      xv[e] = fmaf(-alpha, st[e], xv[e]);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // The tile kernel.  DT: storage type of X/G/Y.  OP: what is staged and what is subtracted.
 // WITH_Y: also write the push-sum ratio.  LW: columns per lane in the reduce phase (a wave spans
@@ -166,8 +187,8 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   constexpr int EB = Elem<DT>::bytes;
   constexpr int UC = Elem<DT>::per16;               // columns per staging unit
   constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
-  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC);
-  constexpr bool STAGE_M = (OP == OP_MOM_ATC);
+  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED);
+  constexpr bool STAGE_M = (OP == OP_MOM_ATC || OP == OP_ED);
   constexpr int MV = UC / 4;                        // 16-byte vectors of M per unit
 
   const int tid = threadIdx.x;
@@ -220,21 +241,18 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
         const int64_t off = static_cast<int64_t>(row) * ld + col;
 #pragma unroll
         for (int q = 0; q < MV; ++q) {
-          f32x4 mv = mraw[q];
-          mv.x = fmaf(p.beta, mv.x, gv[4 * q + 0]);
-          mv.y = fmaf(p.beta, mv.y, gv[4 * q + 1]);
-          mv.z = fmaf(p.beta, mv.z, gv[4 * q + 2]);
-          mv.w = fmaf(p.beta, mv.w, gv[4 * q + 3]);
-          gv[4 * q + 0] = mv.x; gv[4 * q + 1] = mv.y; gv[4 * q + 2] = mv.z; gv[4 * q + 3] = mv.w;
+          float sv[4] = {mraw[q].x, mraw[q].y, mraw[q].z, mraw[q].w};
+          local_update4<OP>(xv + 4 * q, gv + 4 * q, sv, p.alpha, p.beta);
           if (live) {
             const int64_t rem = d - (col + 4 * q);
-            if (rem >= 4) *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = mv;
-            else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = gv[4 * q + e];
+            if (rem >= 4) { f32x4 t = {sv[0], sv[1], sv[2], sv[3]}; *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = t; }
+            else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = sv[e];
           }
         }
-      }
+      } else {
 #pragma unroll
-      for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
+        for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
+      }
     }
     if (live) {
       float* dst = lds + (row << log_c) + cit;
@@ -402,8 +420,9 @@ __global__ __launch_bounds__(256) void bf_chain_kernel(const TileParams p, const
   constexpr int UC = Elem<DT>::per16;
   constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
   constexpr bool MOM = (OP == OP_MOM_ATC || OP == OP_MOM_AWC);
-  constexpr bool G_ON_LOAD = (OP == OP_ATC || OP == OP_MOM_ATC);
+  constexpr bool G_ON_LOAD = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED);
   constexpr bool G_ON_STORE = (OP == OP_AWC || OP == OP_MOM_AWC);
+  constexpr bool STATE_ON_LOAD = (OP == OP_MOM_ATC || OP == OP_ED);
   constexpr int CHUNK_LOG = 8 + UC_LOG;                 // columns per 256-thread sweep
   const int64_t d = p.d, ld = p.ld;
   const int64_t last_vec = ((d - 1) >> UC_LOG) << UC_LOG;
@@ -436,7 +455,7 @@ __global__ __launch_bounds__(256) void bf_chain_kernel(const TileParams p, const
         xr[w] = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
         if constexpr (G_ON_LOAD) gr[w] = *reinterpret_cast<const u32x4*>(p.g + off * EB);
 #endif
-        if constexpr (OP == OP_MOM_ATC) {
+        if constexpr (STATE_ON_LOAD) {
 #pragma unroll
           for (int q = 0; q < UC / 4; ++q) mr[w][q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
         }
@@ -447,23 +466,22 @@ __global__ __launch_bounds__(256) void bf_chain_kernel(const TileParams p, const
         if constexpr (G_ON_LOAD) {
           float gv[UC];
           widen<DT>(gr[w], gv);
-          if constexpr (OP == OP_MOM_ATC) {
+          if constexpr (STATE_ON_LOAD) {
             const int64_t off = static_cast<int64_t>(row) * ld + col[w];
 #pragma unroll
             for (int q = 0; q < UC / 4; ++q) {
-              f32x4 mv = mr[w][q];
-              mv.x = fmaf(p.beta, mv.x, gv[4 * q + 0]); mv.y = fmaf(p.beta, mv.y, gv[4 * q + 1]);
-              mv.z = fmaf(p.beta, mv.z, gv[4 * q + 2]); mv.w = fmaf(p.beta, mv.w, gv[4 * q + 3]);
-              gv[4 * q + 0] = mv.x; gv[4 * q + 1] = mv.y; gv[4 * q + 2] = mv.z; gv[4 * q + 3] = mv.w;
+              float sv[4] = {mr[w][q].x, mr[w][q].y, mr[w][q].z, mr[w][q].w};
+              local_update4<OP>(out[w] + 4 * q, gv + 4 * q, sv, p.alpha, p.beta);
               if (live[w]) {
                 const int64_t rem = d - (col[w] + 4 * q);
-                if (rem >= 4) *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = mv;
-                else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = gv[4 * q + e];
+                if (rem >= 4) { f32x4 t = {sv[0], sv[1], sv[2], sv[3]}; *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = t; }
+                else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = sv[e];
               }
             }
-          }
+          } else {
 #pragma unroll
-          for (int e = 0; e < UC; ++e) out[w][e] = fmaf(-p.alpha, gv[e], out[w][e]);
+            for (int e = 0; e < UC; ++e) out[w][e] = fmaf(-p.alpha, gv[e], out[w][e]);
+          }
         }
       }
     };
@@ -1051,6 +1069,7 @@ int launch_tile_op(int op, bool with_y, const TileParams& tp, const Shape& s, in
     case OP_ATC: return launch_tile<DT, OP_ATC, false>(tp, s, grid, st);
     case OP_AWC: return launch_tile<DT, OP_AWC, false>(tp, s, grid, st);
     case OP_MOM_ATC: return launch_tile<DT, OP_MOM_ATC, false>(tp, s, grid, st);
+    case OP_ED: return launch_tile<DT, OP_ED, false>(tp, s, grid, st);
     default: return launch_tile<DT, OP_MOM_AWC, false>(tp, s, grid, st);
   }
 }
@@ -1084,6 +1103,7 @@ int launch_chain_cw(int op, bool with_y, const TileParams& tp, int64_t nchunks, 
     case OP_ATC: BF_CHAIN(OP_ATC, false); break;
     case OP_AWC: BF_CHAIN(OP_AWC, false); break;
     case OP_MOM_ATC: BF_CHAIN(OP_MOM_ATC, false); break;
+    case OP_ED: BF_CHAIN(OP_ED, false); break;
     default: BF_CHAIN(OP_MOM_AWC, false); break;
   }
 #undef BF_CHAIN
@@ -1151,7 +1171,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(t->n, tp.d, di, &s);
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
     // Too many agents for an LDS tile: row gather through the caches, out of place only.
-    if (tp.x_in == tp.x_out) return BF_ERR_UNSUPPORTED;
+    if (tp.x_in == tp.x_out || op == OP_ED) return BF_ERR_UNSUPPORTED;
     const int per16 = dt == BF_F32 ? 4 : 8;
     const int64_t units = (tp.d + per16 - 1) / per16 * t->n;
     const int grid = static_cast<int>(std::min<int64_t>((units + 255) / 256, static_cast<int64_t>(di.cus) * 32));
@@ -1355,6 +1375,31 @@ int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X
   tp.d = d; tp.ld = ld;
   const int op = M ? (mode == BF_ATC ? OP_MOM_ATC : OP_MOM_AWC) : (mode == BF_ATC ? OP_ATC : OP_AWC);
   return run_tile(const_cast<bf_topology_t*>(t), round, op, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                            const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
+                            bf_dtype_t dt, void* hip_stream) {
+  if (!t || !X_in || !X_out || !G || !Psi_prev) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  MatArgs ma;
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if ((ld * 4) % 16 != 0) return BF_ERR_ALIGN;
+  if (misaligned16(X_in) || misaligned16(X_out) || misaligned16(G) || misaligned16(Psi_prev)) return BF_ERR_ALIGN;
+  const size_t pb = static_cast<size_t>(t->n - 1) * ld * 4 + static_cast<size_t>(d) * 4;
+  if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (overlaps(G, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (overlaps(Psi_prev, pb, X_out, ma.bytes) || overlaps(Psi_prev, pb, X_in, ma.bytes) || overlaps(Psi_prev, pb, G, ma.bytes))
+    return BF_ERR_ALIAS;
+  TileParams tp{};
+  tp.x_in = static_cast<const char*>(X_in);
+  tp.x_out = static_cast<char*>(X_out);
+  tp.g = static_cast<const char*>(G);
+  tp.m = Psi_prev;
+  tp.alpha = alpha;
+  tp.d = d; tp.ld = ld;
+  return run_tile(const_cast<bf_topology_t*>(t), round, OP_ED, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
 int bf_grad_least_squares(int32_t n, int32_t m, int64_t d, const float* A, const float* b,

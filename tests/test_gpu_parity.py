@@ -600,3 +600,66 @@ def test_chain_kernel_fused_ops(dtype, cw):
     assert_close(out, Xr, tol)
     assert_close(w1, pr, TOL32)
     assert_close(Y, Yr, 2e-5 if dtype == torch.float32 else 2.0 ** -7)
+
+
+# ------------------------------------------------------------------ next row: Exact-Diffusion
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("kernel", ["tile", "chain"])
+def test_exact_diffusion_step_matches_oracle(dtype, kernel):
+    n, d = 16, 2048 + 40
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    W = lib_W(t)
+    X, G = rows(n, d, 91, dtype=dtype), rows(n, d, 92, dtype=dtype)
+    P = workloads.normal_rows(n, d, 93, DEV, ld=X.stride(0))
+    P0 = host(P)
+    alpha = 0.05
+    a64 = float(np.float32(alpha))
+    ref, psi = O.exact_diffusion_step(host(X), P0, host(G), W, a64)
+    out = empty_like_rows(X)
+    with (_chain(2) if kernel == "chain" else _no_chain()):
+        bf.bf_exact_diffusion_step(t, 0, X, out, G, P, alpha)
+    assert_close(P, psi, 1e-6, "psi")
+    assert_close(out, ref, TOL32 if dtype == torch.float32 else 2.0 ** -8, "x")
+    # in place on X, state advanced once more from the same start
+    P.copy_(torch.from_numpy(P0).to(DEV).float())
+    Xi = empty_like_rows(X)
+    Xi.copy_(X)
+    with (_chain(2) if kernel == "chain" else _no_chain()):
+        bf.bf_exact_diffusion_step(t, 0, Xi, Xi, G, P, alpha)
+    assert torch.equal(Xi, out)
+
+
+def test_exact_diffusion_removes_the_bias_of_dgd():
+    # eqs. ed-1..ed-3 on decentralized linear regression: the fixed point is the exact
+    # least-squares solution (DGD with the same step stalls at a biased point).
+    n, m, d, alpha = 16, 8, 64, 0.01
+    g = torch.Generator(device=DEV).manual_seed(95)
+    A = torch.randn((n, m, d), generator=g, device=DEV)
+    b = torch.randn((n, m), generator=g, device=DEV)
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    W = lib_W(t)
+    X = torch.zeros((n, d), device=DEV)
+    P = X.clone()                                   # psi^(-1) = x^(0)
+    G = torch.empty((n, d), device=DEV)
+    Ah, bh = host(A), host(b)
+    Xr, Pr = np.zeros((n, d)), np.zeros((n, d))
+    a64 = float(np.float32(alpha))
+    for k in range(3000):
+        bf.bf_grad_least_squares(A, b, X, G)
+        bf.bf_exact_diffusion_step(t, k, X, X, G, P, alpha)
+        if k < 300:
+            Xr, Pr = O.exact_diffusion_step(Xr, Pr, O.ls_grad(Ah, bh, Xr), W, a64)
+            if k % 20 == 19:
+                # the (x, psi) recursion has a marginally stable mode (its bias correction is an
+                # integrator), so fp32 rounding, about 5e-7 relative per step, adds up linearly at worst
+                assert_close(X, Xr, 5e-7 * (k + 1), "iteration %d" % k)
+    xs = np.linalg.lstsq(Ah.reshape(n * m, d), bh.reshape(n * m), rcond=None)[0]
+    # In fp32 the integrator mode has no restoring force, so rounding drifts it by ~1e-6 per
+    # iteration (a plain numpy fp32 run of the same recursion shows the same 3e-3 after 3000 steps;
+    # the fp64 oracle reaches 1e-8).  The bias of DGD with the same step is 0.57.
+    assert np.abs(host(X) - xs).max() < 1e-2 * np.abs(xs).max()
+    Xd = torch.zeros((n, d), device=DEV)
+    for k in range(3000):
+        bf.bf_grad_least_squares(A, b, Xd, G)
+        bf.bf_atc_step(t, k, Xd, Xd, G, None, alpha=alpha, mode=bf.BF_ATC)
+    assert np.abs(host(Xd) - xs).max() > 20 * np.abs(host(X) - xs).max()
