@@ -217,6 +217,7 @@ int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on t
  *   knob 3: upper bound on the number of persistent workgroups
  *   knob 5: 1 disables the row-streaming chain kernel
  *   knob 8: 1 forces non-temporal loads/stores in the tile kernel, 2 forbids them
+ *   knob 9: 1 keeps the chain kernel at 256-thread workgroups
  *   knob 7: 1 disables the alternating (odd rounds right-to-left) tile order
  *   knob 6: forces the chain kernel (where the round has a chain plan) with 1, 2 or 4 16-byte
  *           vectors per thread, whatever the matrix shape

@@ -414,8 +414,8 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
 // also makes in-place updates safe: a row is stored only after its last use as an operand).
 static_assert(sizeof(bf::ChainStep) == 32, "ChainStep is read as eight dwords");
 
-template <int DT, int OP, bool WITH_Y, int CW>
-__global__ __launch_bounds__(256) void bf_chain_kernel(const TileParams p, const int64_t nchunks) {
+template <int DT, int OP, bool WITH_Y, int CW, int THR>
+__global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const int64_t nchunks) {
   constexpr int EB = Elem<DT>::bytes;
   constexpr int UC = Elem<DT>::per16;
   constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(256) void bf_chain_kernel(const TileParams p, const
   constexpr bool G_ON_LOAD = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED);
   constexpr bool G_ON_STORE = (OP == OP_AWC || OP == OP_MOM_AWC);
   constexpr bool STATE_ON_LOAD = (OP == OP_MOM_ATC || OP == OP_ED);
-  constexpr int CHUNK_LOG = 8 + UC_LOG;                 // columns per 256-thread sweep
+  constexpr int CHUNK_LOG = (THR == 1024 ? 10 : 8) + UC_LOG;   // columns per workgroup sweep
   const int64_t d = p.d, ld = p.ld;
   const int64_t last_vec = ((d - 1) >> UC_LOG) << UC_LOG;
   const csr_i32_ptr steps = (csr_i32_ptr)(uintptr_t)p.chain;
@@ -1032,6 +1032,7 @@ int g_tune_gather = 0;    // 1: force the gather fallback
 int g_tune_grid = 0;      // total workgroups override (capped by the resident slots)
 int g_tune_nochain = 0;   // 1: never use the chain kernel
 int g_tune_noserp = 0;    // 1: always walk tiles left to right
+int g_tune_chain256 = 0;  // 1: chain kernel never uses 1024-thread workgroups
 int g_tune_stream = 0;    // 1: always non-temporal, 2: never
 int g_tune_cw = 0;        // chain kernel: 16-byte vectors per thread (1, 2 or 4)
 #ifdef BF_PROFILE
@@ -1059,14 +1060,21 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s) {
     if (bytes * wgs > lds_cu) return BF_ERR_UNSUPPORTED;
     log_c = lc;
   } else {
-    for (; wgs >= 1 && log_c < 0; --wgs) {
-      const size_t budget = std::min(lds_cu / wgs, lds_blk);
+    auto widest = [&](int w) {
+      const size_t budget = std::min(lds_cu / w, lds_blk);
       for (int lc = 10; lc >= 6; --lc)
-        if (static_cast<size_t>(n) * (size_t{1} << lc) * 4 <= budget) { log_c = lc; break; }
+        if (static_cast<size_t>(n) * (size_t{1} << lc) * 4 <= budget) return lc;
+      return -1;
+    };
+    for (; wgs >= 1; --wgs) {
+      log_c = widest(wgs);
       if (log_c >= 0) break;
     }
     if (log_c < 0) return BF_ERR_UNSUPPORTED;
     wgs = std::max(wgs, 1);
+    // 64-column tiles use 256 bytes of each of n row pages (12 % TLB misses at n = 256): one
+    // workgroup per CU with a tile twice as wide is faster there (58 % vs 45-57 % of peak).
+    if (g_tune_wgs == 0 && wgs == 2 && log_c == 6 && widest(1) > 6) { wgs = 1; log_c = widest(1); }
     const int64_t slots = static_cast<int64_t>(di.cus) * std::min(wgs, 2);
     while (log_c > 6 && ((d + (int64_t{1} << log_c) - 1) >> log_c) < slots) --log_c;
   }
@@ -1146,16 +1154,23 @@ int check_matrix_shape(int32_t n, int64_t d, int64_t ld, int dt, MatArgs* ma) {
 
 bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-template <int DT, int CW>
+template <int DT, int CW, int THR>
 int launch_chain_cw(int op, bool with_y, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st) {
-#define BF_CHAIN(OPV, YV) hipLaunchKernelGGL((bf_chain_kernel<DT, OPV, YV, CW>), dim3(grid), dim3(256), 0, st, tp, nchunks)
+#define BF_CHAIN(OPV, YV) hipLaunchKernelGGL((bf_chain_kernel<DT, OPV, YV, CW, THR>), dim3(grid), dim3(THR), 0, st, tp, nchunks)
   switch (op) {
     case OP_MIX: if (with_y) BF_CHAIN(OP_MIX, true); else BF_CHAIN(OP_MIX, false); break;
     case OP_ATC: BF_CHAIN(OP_ATC, false); break;
     case OP_AWC: BF_CHAIN(OP_AWC, false); break;
-    case OP_MOM_ATC: BF_CHAIN(OP_MOM_ATC, false); break;
-    case OP_ED: BF_CHAIN(OP_ED, false); break;
-    default: BF_CHAIN(OP_MOM_AWC, false); break;
+    case OP_MOM_AWC: BF_CHAIN(OP_MOM_AWC, false); break;
+    default:
+      // the ops that carry a state matrix through the load path need more than the 128 registers
+      // a 1024-thread workgroup allows: 256-thread variant only
+      if constexpr (THR == 256) {
+        if (op == OP_MOM_ATC) BF_CHAIN(OP_MOM_ATC, false); else BF_CHAIN(OP_ED, false);
+      } else {
+        return BF_ERR_UNSUPPORTED;
+      }
+      break;
   }
 #undef BF_CHAIN
   BF_HIP_TRY(hipGetLastError());
@@ -1163,12 +1178,16 @@ int launch_chain_cw(int op, bool with_y, const TileParams& tp, int64_t nchunks, 
 }
 
 template <int DT>
-int launch_chain(int op, bool with_y, int cw, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st) {
-  if constexpr (DT == DT_F32) {
-    if (cw == 4) return launch_chain_cw<DT, 4>(op, with_y, tp, nchunks, grid, st);
+int launch_chain(int op, bool with_y, int cw, bool wide, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st) {
+  if (wide) {   // 1024 threads: 64 KB of a row per workgroup per step
+    if constexpr (DT == DT_F32) return launch_chain_cw<DT, 4, 1024>(op, with_y, tp, nchunks, grid, st);
+    else return launch_chain_cw<DT, 2, 1024>(op, with_y, tp, nchunks, grid, st);
   }
-  if (cw == 2) return launch_chain_cw<DT, 2>(op, with_y, tp, nchunks, grid, st);
-  return launch_chain_cw<DT, 1>(op, with_y, tp, nchunks, grid, st);
+  if constexpr (DT == DT_F32) {
+    if (cw == 4) return launch_chain_cw<DT, 4, 256>(op, with_y, tp, nchunks, grid, st);
+  }
+  if (cw == 2) return launch_chain_cw<DT, 2, 256>(op, with_y, tp, nchunks, grid, st);
+  return launch_chain_cw<DT, 1, 256>(op, with_y, tp, nchunks, grid, st);
 }
 
 template <int DT>
@@ -1208,14 +1227,19 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     int cw = g_tune_cw > 0 ? g_tune_cw : (dt == BF_F32 ? 4 : 2);
     if (cw != 1 && cw != 2 && cw != 4) return BF_ERR_UNSUPPORTED;
     if (dt != BF_F32 && cw == 4) cw = 2;
-    const int64_t chunk_cols = static_cast<int64_t>(256) * per16 * cw;
+    // Widest first: 1024 threads x 4 vectors read 64 KB of a row per step (a plain row-walk copy
+    // peaks there: 5.55 TB/s vs 5.35 with 16 KB); needs at least one such chunk per CU.
+    const int64_t wide_cols = static_cast<int64_t>(1024) * per16 * (dt == BF_F32 ? 4 : 2);
+    const int64_t wide_chunks = (tp.d + wide_cols - 1) / wide_cols;
+    const bool wide = g_tune_cw == 0 && !g_tune_chain256 && wide_chunks >= di.cus && op != OP_MOM_ATC && op != OP_ED;
+    const int64_t chunk_cols = wide ? wide_cols : static_cast<int64_t>(256) * per16 * cw;
     const int64_t nchunks = (tp.d + chunk_cols - 1) / chunk_cols;
-    if (nchunks >= 2 * static_cast<int64_t>(di.cus) || g_tune_cw > 0) {
+    if (nchunks >= 2 * static_cast<int64_t>(di.cus) || g_tune_cw > 0 || wide) {
       tp.chain = reinterpret_cast<const bf::ChainStep*>(dc->blob + dc->chain_off[k]);
-      int grid = static_cast<int>(std::min<int64_t>(nchunks, static_cast<int64_t>(di.cus) * 8));
+      int grid = static_cast<int>(std::min<int64_t>(nchunks, static_cast<int64_t>(di.cus) * (wide ? 1 : 8)));
       if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
-      return dt == BF_F32 ? launch_chain<DT_F32>(op, with_y, cw, tp, nchunks, grid, st)
-                          : launch_chain<DT_BF16>(op, with_y, cw, tp, nchunks, grid, st);
+      return dt == BF_F32 ? launch_chain<DT_F32>(op, with_y, cw, wide, tp, nchunks, grid, st)
+                          : launch_chain<DT_BF16>(op, with_y, cw, wide, tp, nchunks, grid, st);
     }
   }
   Shape s;
@@ -1275,6 +1299,7 @@ int bf_set_tuning(int32_t knob, int32_t value) {
   else if (knob == 3) g_tune_grid = value;
   else if (knob == 5) g_tune_nochain = value;
   else if (knob == 7) g_tune_noserp = value;
+  else if (knob == 9) g_tune_chain256 = value;
   else if (knob == 8) g_tune_stream = value;
   else if (knob == 6) g_tune_cw = value;
 #ifdef BF_PROFILE
