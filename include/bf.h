@@ -160,6 +160,22 @@ int bf_pushsum_step(const bf_topology_t* t, int32_t round, const void* X_in, voi
                     const float* w_in, float* w_out, void* Y, int64_t d, int64_t ld,
                     bf_dtype_t dt, void* hip_stream);
 
+/* Push-sum round with a local update folded in -- the u, v, x lines of push-sum gradient tracking
+ * (appendix "Application example: Push-sum gradient tracking algorithm"):
+ *   X_out = W (X_in - alpha G),  w_out = W w_in,  Y[i,:] = X_out[i,:] / w_out[i]  (Y optional).
+ * With G the tracker y this is  u' = W(u - alpha y), v' = W v, x' = u'/v'.  Arguments as in
+ * bf_pushsum_step; G has the dtype and layout of X and may not overlap an output. */
+int bf_pushsum_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                        float alpha, const float* w_in, float* w_out, void* Y, int64_t d, int64_t ld,
+                        bf_dtype_t dt, void* hip_stream);
+
+/* Tracker update of gradient tracking (same appendix, last line of the recursion):
+ *   Y_out = W (Y_in + G_new - G_old).
+ * All four matrices share dtype and layout; Y_out may equal Y_in.  Needs an LDS tile or a chain
+ * plan (n <= 640 agents), else BF_ERR_UNSUPPORTED. */
+int bf_tracking_step(const bf_topology_t* t, int32_t round, const void* Y_in, void* Y_out, const void* G_new,
+                     const void* G_old, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+
 /* Local update fused with partial averaging (eqs. eq.atc / eq.awc; dsgd-1 + dsgd-2):
  *   M == NULL, BF_ATC:  X_out[i,:] = sum_j w_ij (X_in[j,:] - alpha G[j,:])
  *   M == NULL, BF_AWC:  X_out[i,:] = sum_j w_ij X_in[j,:] - alpha G[i,:]

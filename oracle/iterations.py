@@ -170,3 +170,24 @@ def mix_fp32_chain(X32, W):
                 acc = (prod + acc.astype(np.float64)).astype(np.float32)
         out[i, :] = acc
     return out
+
+
+def pushsum_gradient_tracking_step(U, v, Y, G_prev, W, alpha, grad):
+    """One iteration of push-sum gradient tracking over a (possibly time-varying) column-stochastic
+    W (appendix "Application example: Push-sum gradient tracking algorithm"):
+        u' = W (u - alpha y);  v' = W v;  x' = u' / v';  g' = grad(x');  y' = W (y + g' - g_prev).
+    ``grad`` maps the (n, d) matrix of iterates to the (n, d) matrix of local gradients.
+    Start: v = 1, y = g_prev = grad(x^0), u = x^0.  Returns (U', v', X', Y', G')."""
+    U = _f64(U)
+    v = _f64(v)
+    Y = _f64(Y)
+    G_prev = _f64(G_prev)
+    Un = mix(U - alpha * Y, W)
+    vn = np.zeros_like(v)
+    for i in range(v.shape[0]):
+        for j, w in W[i]:
+            vn[i] += w * v[j]
+    Xn = Un / vn[:, None]
+    Gn = _f64(grad(Xn))
+    Yn = mix(Y + Gn - G_prev, W)
+    return Un, vn, Xn, Yn, Gn

@@ -28,7 +28,7 @@ BF_W_ANY, BF_W_PULL, BF_W_PUSH, BF_W_STANDARD = 0, 1, 2, 3
 EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
-    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step",
+    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -85,6 +85,8 @@ def _load():
     L.bf_neighbor_allreduce.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_dense_mix.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_pushsum_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_pushsum_atc_step.argtypes = [vp, i32, vp, vp, vp, f32, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_tracking_step.argtypes = [vp, i32, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_atc_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, f32, C.c_int, i64, i64, C.c_int, vp]
     L.bf_exact_diffusion_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, i64, i64, C.c_int, vp]
     L.bf_grad_least_squares.argtypes = [i32, i32, i64, vp, vp, vp, i64, vp, i64, vp]
@@ -270,6 +272,27 @@ def bf_pushsum_step(t, rnd, X_in, X_out, w_in, w_out, Y=None, stream=None):
                                None if Y is None else Y.data_ptr(), d, ld, _dtype_code(X_in), _stream(stream)),
            "bf_pushsum_step")
     return X_out, w_out, Y
+
+
+def bf_pushsum_atc_step(t, rnd, X_in, X_out, G, alpha, w_in, w_out, Y=None, stream=None):
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _same_layout(X_in, X_out, "X_out")
+    _same_layout(X_in, G, "G")
+    if Y is not None:
+        _same_layout(X_in, Y, "Y")
+    _check(lib.bf_pushsum_atc_step(t.handle, rnd, ptr, X_out.data_ptr(), G.data_ptr(), alpha, w_in.data_ptr(),
+                                   w_out.data_ptr(), None if Y is None else Y.data_ptr(), d, ld,
+                                   _dtype_code(X_in), _stream(stream)), "bf_pushsum_atc_step")
+    return X_out, w_out, Y
+
+
+def bf_tracking_step(t, rnd, Y_in, Y_out, G_new, G_old, stream=None):
+    ptr, n, d, ld = _mat(Y_in, "Y_in")
+    for nm, o in (("Y_out", Y_out), ("G_new", G_new), ("G_old", G_old)):
+        _same_layout(Y_in, o, nm)
+    _check(lib.bf_tracking_step(t.handle, rnd, ptr, Y_out.data_ptr(), G_new.data_ptr(), G_old.data_ptr(), d, ld,
+                                _dtype_code(Y_in), _stream(stream)), "bf_tracking_step")
+    return Y_out
 
 
 def bf_atc_step(t, rnd, X_in, X_out, G, M=None, alpha=0.0, beta=0.0, mode=BF_ATC, stream=None):

@@ -78,13 +78,14 @@ template <bool NT, typename T> __device__ __forceinline__ void st_stream(T* ptr,
 typedef const int32_t __attribute__((address_space(4)))* csr_i32_ptr;
 typedef const u32x2 __attribute__((address_space(4)))* csr_ent_ptr;
 
-enum { OP_MIX = 0, OP_ATC = 1, OP_AWC = 2, OP_MOM_ATC = 3, OP_MOM_AWC = 4, OP_ED = 5 };
+enum { OP_MIX = 0, OP_ATC = 1, OP_AWC = 2, OP_MOM_ATC = 3, OP_MOM_AWC = 4, OP_ED = 5, OP_TRACK = 6 };
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
 struct TileParams {
   const char* x_in;      // n x ld, dtype DT
   char*       x_out;
   const char* g;         // gradient, dtype DT (ATC/AWC/momentum)
+  const char* g2;        // previous gradient, dtype DT (gradient-tracking update)
   float*      m;         // momentum, fp32 (momentum ops)
   char*       y;         // push-sum ratio output, dtype DT (optional)
   const float* p_out;    // push-sum weights after this round (for y)
@@ -187,7 +188,8 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   constexpr int EB = Elem<DT>::bytes;
   constexpr int UC = Elem<DT>::per16;               // columns per staging unit
   constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
-  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED);
+  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED || OP == OP_TRACK);
+  constexpr bool STAGE_G2 = (OP == OP_TRACK);
   constexpr bool STAGE_M = (OP == OP_MOM_ATC || OP == OP_ED);
   constexpr int MV = UC / 4;                        // 16-byte vectors of M per unit
 
@@ -200,6 +202,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
 
   u32x4 xr[MAXPF];
   u32x4 gr[STAGE_G ? MAXPF : 1];
+  u32x4 g2r[STAGE_G2 ? MAXPF : 1];
   f32x4 mr[STAGE_M ? MAXPF * MV : 1];
 
   // Loads are unconditional (uniform control flow keeps all of a tile's loads in flight at
@@ -215,6 +218,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const int64_t off = static_cast<int64_t>(row) * ld + col;
       xr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
       if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
+      if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
         for (int q = 0; q < MV; ++q) mr[k * MV + q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   };
 
   // Transform one staging unit (local update, momentum) and put it into the LDS tile.
-  auto stage_unit = [&](int u, int64_t c0, const u32x4& xraw, const u32x4& graw, const f32x4* mraw) {
+  auto stage_unit = [&](int u, int64_t c0, const u32x4& xraw, const u32x4& graw, const u32x4& g2raw, const f32x4* mraw) {
     const int row = u >> upr_log;
     const int cit = (u & upr_mask) << UC_LOG;       // column inside the tile
     const int64_t col = c0 + cit;
@@ -249,6 +253,12 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
             else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = sv[e];
           }
         }
+      } else if constexpr (STAGE_G2) {
+        // gradient tracking: the mixed value is y + g_new - g_old
+        float hv[UC];
+        widen<DT>(g2raw, hv);
+#pragma unroll
+        for (int e = 0; e < UC; ++e) xv[e] = (xv[e] + gv[e]) - hv[e];
       } else {
 #pragma unroll
         for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
@@ -268,21 +278,22 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
     const int64_t c0 = tile << log_c;
 #pragma unroll
     for (int k = 0; k < MAXPF; ++k)
-      stage_unit(tid + k * THREADS, c0, xr[k], gr[STAGE_G ? k : 0], &mr[STAGE_M ? k * MV : 0]);
+      stage_unit(tid + k * THREADS, c0, xr[k], gr[STAGE_G ? k : 0], g2r[STAGE_G2 ? k : 0], &mr[STAGE_M ? k * MV : 0]);
     // Tiles taller than THREADS*MAXPF units (many agents): the rest is loaded here, unprefetched.
     for (int u = tid + MAXPF * THREADS; u < nunits; u += THREADS) {
       const int row = u >> upr_log;
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
       const int64_t off = static_cast<int64_t>(row) * ld + col;
       const u32x4 xraw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
-      u32x4 graw = {0, 0, 0, 0};
+      u32x4 graw = {0, 0, 0, 0}, g2raw = {0, 0, 0, 0};
       f32x4 mraw[MV];
       if constexpr (STAGE_G) graw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
+      if constexpr (STAGE_G2) g2raw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
         for (int q = 0; q < MV; ++q) mraw[q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
       }
-      stage_unit(u, c0, xraw, graw, mraw);
+      stage_unit(u, c0, xraw, graw, g2raw, mraw);
     }
   };
 
@@ -420,7 +431,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
   constexpr int UC = Elem<DT>::per16;
   constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
   constexpr bool MOM = (OP == OP_MOM_ATC || OP == OP_MOM_AWC);
-  constexpr bool G_ON_LOAD = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED);
+  constexpr bool G_ON_LOAD = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED || OP == OP_TRACK);
   constexpr bool G_ON_STORE = (OP == OP_AWC || OP == OP_MOM_AWC);
   constexpr bool STATE_ON_LOAD = (OP == OP_MOM_ATC || OP == OP_ED);
   constexpr int CHUNK_LOG = (THR == 1024 ? 10 : 8) + UC_LOG;   // columns per workgroup sweep
@@ -443,7 +454,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
 
     // y_j = x_j, or x_j - alpha g_j, or (momentum) x_j - alpha (beta m_j + g_j) with m_j written back
     auto load_y = [&](int row, float (*out)[UC]) {
-      u32x4 xr[CW], gr[CW];
+      u32x4 xr[CW], gr[CW], g2r[CW];
       f32x4 mr[CW][UC / 4];
 #pragma unroll
       for (int w = 0; w < CW; ++w) {
@@ -455,6 +466,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
         xr[w] = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
         if constexpr (G_ON_LOAD) gr[w] = *reinterpret_cast<const u32x4*>(p.g + off * EB);
 #endif
+        if constexpr (OP == OP_TRACK) g2r[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
         if constexpr (STATE_ON_LOAD) {
 #pragma unroll
           for (int q = 0; q < UC / 4; ++q) mr[w][q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
@@ -478,6 +490,11 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
                 else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = sv[e];
               }
             }
+          } else if constexpr (OP == OP_TRACK) {
+            float hv[UC];
+            widen<DT>(g2r[w], hv);
+#pragma unroll
+            for (int e = 0; e < UC; ++e) out[w][e] = (out[w][e] + gv[e]) - hv[e];
           } else {
 #pragma unroll
             for (int e = 0; e < UC; ++e) out[w][e] = fmaf(-p.alpha, gv[e], out[w][e]);
@@ -1125,7 +1142,8 @@ template <int DT>
 int launch_tile_op(int op, bool with_y, const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
   switch (op) {
     case OP_MIX: return with_y ? launch_tile<DT, OP_MIX, true>(tp, s, grid, st) : launch_tile<DT, OP_MIX, false>(tp, s, grid, st);
-    case OP_ATC: return launch_tile<DT, OP_ATC, false>(tp, s, grid, st);
+    case OP_ATC: return with_y ? launch_tile<DT, OP_ATC, true>(tp, s, grid, st) : launch_tile<DT, OP_ATC, false>(tp, s, grid, st);
+    case OP_TRACK: return launch_tile<DT, OP_TRACK, false>(tp, s, grid, st);
     case OP_AWC: return launch_tile<DT, OP_AWC, false>(tp, s, grid, st);
     case OP_MOM_ATC: return launch_tile<DT, OP_MOM_ATC, false>(tp, s, grid, st);
     case OP_ED: return launch_tile<DT, OP_ED, false>(tp, s, grid, st);
@@ -1159,7 +1177,8 @@ int launch_chain_cw(int op, bool with_y, const TileParams& tp, int64_t nchunks, 
 #define BF_CHAIN(OPV, YV) hipLaunchKernelGGL((bf_chain_kernel<DT, OPV, YV, CW, THR>), dim3(grid), dim3(THR), 0, st, tp, nchunks)
   switch (op) {
     case OP_MIX: if (with_y) BF_CHAIN(OP_MIX, true); else BF_CHAIN(OP_MIX, false); break;
-    case OP_ATC: BF_CHAIN(OP_ATC, false); break;
+    case OP_ATC: if (with_y) BF_CHAIN(OP_ATC, true); else BF_CHAIN(OP_ATC, false); break;
+    case OP_TRACK: BF_CHAIN(OP_TRACK, false); break;
     case OP_AWC: BF_CHAIN(OP_AWC, false); break;
     case OP_MOM_AWC: BF_CHAIN(OP_MOM_AWC, false); break;
     default:
@@ -1195,7 +1214,7 @@ int launch_gather(int op, bool with_y, const TileParams& tp, int grid, hipStream
 #define BF_GATHER(OPV, YV) hipLaunchKernelGGL((bf_gather_kernel<DT, OPV, YV>), dim3(grid), dim3(256), 0, st, tp)
   switch (op) {
     case OP_MIX: if (with_y) BF_GATHER(OP_MIX, true); else BF_GATHER(OP_MIX, false); break;
-    case OP_ATC: BF_GATHER(OP_ATC, false); break;
+    case OP_ATC: if (with_y) BF_GATHER(OP_ATC, true); else BF_GATHER(OP_ATC, false); break;
     case OP_AWC: BF_GATHER(OP_AWC, false); break;
     case OP_MOM_ATC: BF_GATHER(OP_MOM_ATC, false); break;
     default: BF_GATHER(OP_MOM_AWC, false); break;
@@ -1246,7 +1265,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(t->n, tp.d, di, &s);
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
     // Too many agents for an LDS tile: row gather through the caches, out of place only.
-    if (tp.x_in == tp.x_out || op == OP_ED) return BF_ERR_UNSUPPORTED;
+    if (tp.x_in == tp.x_out || op == OP_ED || op == OP_TRACK) return BF_ERR_UNSUPPORTED;
     const int per16 = dt == BF_F32 ? 4 : 8;
     const int64_t units = (tp.d + per16 - 1) / per16 * t->n;
     const int grid = static_cast<int>(std::min<int64_t>((units + 255) / 256, static_cast<int64_t>(di.cus) * 32));
@@ -1271,6 +1290,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     const size_t eb = dt == BF_F32 ? 4 : 2;
     size_t footprint = static_cast<size_t>(t->n) * tp.ld * eb;
     if (tp.g) footprint *= 2;
+    if (tp.g2) footprint += static_cast<size_t>(t->n) * tp.ld * eb;
     if (tp.m) footprint += static_cast<size_t>(t->n) * tp.ld * 4;
     const bool cacheable = tp.x_in == tp.x_out && footprint <= (size_t{320} << 20);
     s.stream = g_tune_stream == 1 ? true : (g_tune_stream == 2 ? false : !cacheable);
@@ -1394,15 +1414,16 @@ int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* 
   return BF_OK;
 }
 
-int bf_pushsum_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
-                    const float* w_in, float* w_out, void* Y, int64_t d, int64_t ld,
-                    bf_dtype_t dt, void* hip_stream) {
+// Shared body of the push-sum entry points: optional local update x - alpha g before the mix.
+static int pushsum_common(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                          float alpha, const float* w_in, float* w_out, void* Y, int64_t d, int64_t ld,
+                          bf_dtype_t dt, void* hip_stream) {
   if (!t || !X_in || !X_out || !w_in || !w_out) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   MatArgs ma;
   int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
   if (rc != BF_OK) return rc;
-  if (misaligned16(X_in) || misaligned16(X_out) || (Y && misaligned16(Y))) return BF_ERR_ALIGN;
+  if (misaligned16(X_in) || misaligned16(X_out) || (Y && misaligned16(Y)) || (G && misaligned16(G))) return BF_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(w_in) & 3u) || (reinterpret_cast<uintptr_t>(w_out) & 3u)) return BF_ERR_ALIGN;
   const size_t wb = static_cast<size_t>(t->n) * 4;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
@@ -1412,6 +1433,9 @@ int bf_pushsum_step(const bf_topology_t* t, int32_t round, const void* X_in, voi
     return BF_ERR_ALIAS;
   if (Y && (overlaps(Y, ma.bytes, X_in, ma.bytes) || overlaps(Y, ma.bytes, X_out, ma.bytes) ||
             overlaps(Y, ma.bytes, w_in, wb) || overlaps(Y, ma.bytes, w_out, wb)))
+    return BF_ERR_ALIAS;
+  if (G && (overlaps(G, ma.bytes, X_out, ma.bytes) || overlaps(G, ma.bytes, w_out, wb) ||
+            (Y && overlaps(G, ma.bytes, Y, ma.bytes))))
     return BF_ERR_ALIAS;
   if (static_cast<size_t>(t->n) * 4 > 160 * 1024) return BF_ERR_UNSUPPORTED;
   bf_topology_t* tt = const_cast<bf_topology_t*>(t);
@@ -1437,10 +1461,44 @@ int bf_pushsum_step(const bf_topology_t* t, int32_t round, const void* X_in, voi
   TileParams tp{};
   tp.x_in = static_cast<const char*>(X_in);
   tp.x_out = static_cast<char*>(X_out);
+  tp.g = static_cast<const char*>(G);
+  tp.alpha = alpha;
   tp.y = static_cast<char*>(Y);
   tp.p_out = w_out;
   tp.d = d; tp.ld = ld;
-  return run_tile(tt, round, OP_MIX, Y != nullptr, tp, dt, st);
+  return run_tile(tt, round, G ? OP_ATC : OP_MIX, Y != nullptr, tp, dt, st);
+}
+
+int bf_pushsum_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                    const float* w_in, float* w_out, void* Y, int64_t d, int64_t ld,
+                    bf_dtype_t dt, void* hip_stream) {
+  return pushsum_common(t, round, X_in, X_out, nullptr, 0.0f, w_in, w_out, Y, d, ld, dt, hip_stream);
+}
+
+int bf_pushsum_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                        float alpha, const float* w_in, float* w_out, void* Y, int64_t d, int64_t ld,
+                        bf_dtype_t dt, void* hip_stream) {
+  if (!G) return BF_ERR_NULL;
+  return pushsum_common(t, round, X_in, X_out, G, alpha, w_in, w_out, Y, d, ld, dt, hip_stream);
+}
+
+int bf_tracking_step(const bf_topology_t* t, int32_t round, const void* Y_in, void* Y_out, const void* G_new,
+                     const void* G_old, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  if (!t || !Y_in || !Y_out || !G_new || !G_old) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  MatArgs ma;
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (misaligned16(Y_in) || misaligned16(Y_out) || misaligned16(G_new) || misaligned16(G_old)) return BF_ERR_ALIGN;
+  if (Y_in != Y_out && overlaps(Y_in, ma.bytes, Y_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (overlaps(G_new, ma.bytes, Y_out, ma.bytes) || overlaps(G_old, ma.bytes, Y_out, ma.bytes)) return BF_ERR_ALIAS;
+  TileParams tp{};
+  tp.x_in = static_cast<const char*>(Y_in);
+  tp.x_out = static_cast<char*>(Y_out);
+  tp.g = static_cast<const char*>(G_new);
+  tp.g2 = static_cast<const char*>(G_old);
+  tp.d = d; tp.ld = ld;
+  return run_tile(const_cast<bf_topology_t*>(t), round, OP_TRACK, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
 int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,

@@ -271,7 +271,14 @@ def test_compute_calls_validate_before_touching_the_device():
     cs = L.bf_consensus_stats
     assert cs(4, 64, 64, A, None, bf.BF_F32, None, None, None) == bf.BF_ERR_NULL
     assert cs(4, 64, 64, A, None, bf.BF_F32, M + 4, None, None) == bf.BF_ERR_ALIGN
-    assert L.bf_set_tuning(9, 1) == bf.BF_ERR_KIND
+    assert L.bf_set_tuning(99, 1) == bf.BF_ERR_KIND
+    assert L.bf_pushsum_atc_step(h, 0, A, B, None, 0.1, W1, W2, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert L.bf_pushsum_atc_step(h, 0, A, B, B, 0.1, W1, W2, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert L.bf_tracking_step(h, 0, A, B, G, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert L.bf_tracking_step(h, 0, A, B, B, G, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert L.bf_tracking_step(h, -1, A, B, G, M, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ROUND
+    assert L.bf_exact_diffusion_step(h, 0, A, B, G, None, 0.1, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert L.bf_exact_diffusion_step(h, 0, A, B, G, A, 0.1, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     assert L.bf_set_tuning(0, 0) == bf.BF_OK
 
 

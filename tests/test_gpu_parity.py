@@ -663,3 +663,74 @@ def test_exact_diffusion_removes_the_bias_of_dgd():
         bf.bf_grad_least_squares(A, b, Xd, G)
         bf.bf_atc_step(t, k, Xd, Xd, G, None, alpha=alpha, mode=bf.BF_ATC)
     assert np.abs(host(Xd) - xs).max() > 20 * np.abs(host(X) - xs).max()
+
+
+# ------------------------------------------------------------------ next row: push-sum gradient tracking
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("kind", ["push_tile", "onepeer_chain", "onepeer_tile"])
+def test_gradient_tracking_pieces_match_oracle(dtype, kind):
+    n, d = 16, 2048 + 40
+    if kind == "push_tile":
+        t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=3, seed=11)
+    else:
+        t = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+    ctx = _chain(2) if kind == "onepeer_chain" else _no_chain()
+    r = 1
+    W = lib_W(t, r)
+    U, Yt, Gn, Go = (rows(n, d, 110 + k, dtype=dtype) for k in range(4))
+    v = torch.rand(n, device=DEV) + 0.5
+    v2 = torch.empty_like(v)
+    alpha = 0.05
+    a64 = float(np.float32(alpha))
+    tol = TOL32 if dtype == torch.float32 else 2.0 ** -8
+    Uo, Xo, Yo = empty_like_rows(U), empty_like_rows(U), empty_like_rows(U)
+    with ctx:
+        bf.bf_pushsum_atc_step(t, r, U, Uo, Yt, alpha, v, v2, Xo)
+        bf.bf_tracking_step(t, r, Yt, Yo, Gn, Go)
+    Ur = O.mix(host(U) - a64 * host(Yt), W)
+    vr = OT.to_dense(W) @ host(v[:, None])[:, 0]
+    assert_close(Uo, Ur, tol, "u")
+    assert_close(v2, vr, TOL32, "v")
+    assert_close(Xo, Ur / vr[:, None], 2e-5 if dtype == torch.float32 else 2.0 ** -7, "x = u/v")
+    assert_close(Yo, O.mix(host(Yt) + host(Gn) - host(Go), W), tol, "y")
+    Yi = empty_like_rows(Yt)
+    Yi.copy_(Yt)
+    with ctx:
+        bf.bf_tracking_step(t, r, Yi, Yi, Gn, Go)               # in place
+    assert torch.equal(Yi, Yo)
+
+
+def test_gradient_tracking_run_on_time_varying_graph():
+    # the whole recursion on decentralized linear regression over the one-peer schedule:
+    # trajectory against the oracle, tracking invariant 1^T y = 1^T g, exact least-squares limit
+    n, m, d, alpha = 16, 8, 64, 0.01
+    g = torch.Generator(device=DEV).manual_seed(97)
+    A = torch.randn((n, m, d), generator=g, device=DEV)
+    b = torch.randn((n, m), generator=g, device=DEV)
+    t = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+    Ah, bh = host(A), host(b)
+    grad = lambda X: O.ls_grad(Ah, bh, X)
+    X = torch.zeros((n, d), device=DEV)
+    U = X.clone()
+    v = torch.ones(n, device=DEV)
+    G = [torch.empty((n, d), device=DEV), torch.empty((n, d), device=DEV)]
+    bf.bf_grad_least_squares(A, b, X, G[0])
+    Yt = G[0].clone()
+    Xr = np.zeros((n, d)); Ur = Xr.copy(); vr = np.ones(n); Gr = grad(Xr); Yr = Gr.copy()
+    a64 = float(np.float32(alpha))
+    for k in range(2500):
+        cur, new = G[k & 1], G[1 - (k & 1)]
+        bf.bf_pushsum_atc_step(t, k, U, U, Yt, alpha, v, v, X)
+        bf.bf_grad_least_squares(A, b, X, new)
+        bf.bf_tracking_step(t, k, Yt, Yt, new, cur)
+        if k < 200:
+            Ur, vr, Xr, Yr, Gr = O.pushsum_gradient_tracking_step(Ur, vr, Yr, Gr, lib_W(t, k), a64, grad)
+            if k % 20 == 19:
+                assert_close(X, Xr, 5e-7 * (k + 1), "x, iteration %d" % k)
+                assert_close(Yt, Yr, 2e-6 * (k + 1), "y, iteration %d" % k)
+        if k % 500 == 499:
+            ysum, gsum = host(Yt).sum(0), host(new).sum(0)
+            assert np.abs(ysum - gsum).max() < 1e-3 * max(1.0, np.abs(host(new)).max()) * n
+    xs = np.linalg.lstsq(Ah.reshape(n * m, d), bh.reshape(n * m), rcond=None)[0]
+    assert np.abs(host(X) - xs).max() < 1e-2 * np.abs(xs).max()
+    assert float((v - 1).abs().max()) < 1e-6

@@ -365,3 +365,62 @@ def test_mix_fp32_chain_one_peer_is_single_rounded_add():
         ref[i] = (X[i] + X[(i + 2) % 8]) / np.float32(2)   # one rounded add, exact halving
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
     np.testing.assert_allclose(got, O.mix(X, W), rtol=1e-7, atol=1e-7)
+
+
+# ---------------------------------------------------------------- push-sum gradient tracking (next row)
+def _gt_problem(seed, n=8, m=4, d=6):
+    rng = np.random.default_rng(seed)
+    A = rng.normal(size=(n, m, d))
+    b = rng.normal(size=(n, m))
+    xs = np.linalg.lstsq(A.reshape(n * m, d), b.reshape(n * m), rcond=None)[0]
+    return A, b, xs
+
+
+def test_gradient_tracking_invariants_and_exact_limit_on_directed_graph():
+    n = 8
+    A, b, xs = _gt_problem(20, n=n)
+    W, _ = T.random_directed_push(n, 2, 5)
+    grad = lambda X: O.ls_grad(A, b, X)
+    X = np.zeros((n, 6))
+    U, v = X.copy(), np.ones(n)
+    G = grad(X)
+    Y = G.copy()
+    for k in range(6000):
+        U, v, X, Y, G = O.pushsum_gradient_tracking_step(U, v, Y, G, W, 0.01, grad)
+        if k % 500 == 0:
+            np.testing.assert_allclose(Y.sum(0), G.sum(0), atol=1e-9)     # 1^T y = 1^T g (column-stochastic W)
+            assert abs(v.sum() - n) < 1e-10
+    np.testing.assert_allclose(X, np.tile(xs, (n, 1)), atol=1e-7)         # exact solution, no DGD bias
+    assert abs(v - 1).max() > 0.05                                         # push-sum weights are not trivial
+
+
+def test_gradient_tracking_on_time_varying_one_peer_graph():
+    n = 8
+    A, b, xs = _gt_problem(21, n=n)
+    grad = lambda X: O.ls_grad(A, b, X)
+    X = np.zeros((n, 6))
+    U, v = X.copy(), np.ones(n)
+    G = grad(X)
+    Y = G.copy()
+    for k in range(6000):
+        U, v, X, Y, G = O.pushsum_gradient_tracking_step(U, v, Y, G, T.one_peer_exponential(n, k), 0.01, grad)
+    np.testing.assert_allclose(X, np.tile(xs, (n, 1)), atol=1e-7)
+    np.testing.assert_allclose(v, 1.0, atol=1e-12)                          # doubly stochastic rounds keep v = 1
+
+
+def test_gradient_tracking_step_against_dense_formulas():
+    rng = np.random.default_rng(22)
+    n, d = 5, 3
+    D = np.abs(_rand_W(n, rng))
+    D = D / D.sum(0, keepdims=True)                                         # column stochastic, asymmetric
+    W = T.from_dense(D)
+    U, Y, Gp = (rng.normal(size=(n, d)) for _ in range(3))
+    v = rng.random(n) + 0.5
+    Q = rng.normal(size=(d, d))
+    grad = lambda X: X @ Q + 1.0
+    Un, vn, Xn, Yn, Gn = O.pushsum_gradient_tracking_step(U, v, Y, Gp, W, 0.3, grad)
+    np.testing.assert_allclose(Un, D @ (U - 0.3 * Y), atol=1e-13)
+    np.testing.assert_allclose(vn, D @ v, atol=1e-13)
+    np.testing.assert_allclose(Xn, (D @ (U - 0.3 * Y)) / (D @ v)[:, None], atol=1e-13)
+    np.testing.assert_allclose(Gn, Xn @ Q + 1.0, atol=1e-13)
+    np.testing.assert_allclose(Yn, D @ (Y + Gn - Gp), atol=1e-13)
