@@ -144,6 +144,16 @@ int32_t bf_topology_chain_plan(const bf_topology_t* t, int32_t round, int32_t* s
 int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
                           int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
+/* `count` consecutive rounds of partial averaging in one pass over the matrix (finite-time exact
+ * averaging over the one-peer exponential graph takes log2 n rounds; section "One-peer exponential
+ * graph"):  X_out = W^(round0+count-1) ... W^(round0+1) W^(round0) X_in.
+ * Every intermediate product stays on chip in fp32 (also for BF_BF16, which therefore rounds once,
+ * at the end, unlike `count` separate calls); for BF_F32 the result is bit-identical to `count`
+ * calls of bf_neighbor_allreduce.  1 <= count <= 8, else BF_ERR_SIZE; needs two n x 64 fp32 tiles
+ * in one CU's LDS (n <= 320 on MI355X), else BF_ERR_UNSUPPORTED.  X_out may equal X_in. */
+int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t count, const void* X_in,
+                                void* X_out, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+
 /* Same product through the dense n x n form of W^(round) on the fp32 matrix cores (BF_F32 only;
  * n <= 256).  Intended for dense / fully connected W (periodic global averaging is W = 11^T/n) and
  * as an independent cross-check of the sparse kernels. */

@@ -28,7 +28,7 @@ BF_W_ANY, BF_W_PULL, BF_W_PUSH, BF_W_STANDARD = 0, 1, 2, 3
 EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
-    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
+    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -83,6 +83,7 @@ def _load():
     L.bf_topology_export_csr.argtypes = [vp, i32, vp, vp, vp, C.POINTER(C.c_uint64)]
     L.bf_topology_chain_plan.argtypes = [vp, i32, vp]
     L.bf_neighbor_allreduce.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_neighbor_allreduce_multi.argtypes = [vp, i32, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_dense_mix.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_pushsum_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_pushsum_atc_step.argtypes = [vp, i32, vp, vp, vp, f32, vp, vp, vp, i64, i64, C.c_int, vp]
@@ -252,6 +253,14 @@ def bf_neighbor_allreduce(t, rnd, X_in, X_out, stream=None):
     _same_layout(X_in, X_out, "X_out")
     _check(lib.bf_neighbor_allreduce(t.handle, rnd, ptr, X_out.data_ptr(), d, ld, _dtype_code(X_in),
                                      _stream(stream)), "bf_neighbor_allreduce")
+    return X_out
+
+
+def bf_neighbor_allreduce_multi(t, rnd0, count, X_in, X_out, stream=None):
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _same_layout(X_in, X_out, "X_out")
+    _check(lib.bf_neighbor_allreduce_multi(t.handle, rnd0, count, ptr, X_out.data_ptr(), d, ld,
+                                           _dtype_code(X_in), _stream(stream)), "bf_neighbor_allreduce_multi")
     return X_out
 
 

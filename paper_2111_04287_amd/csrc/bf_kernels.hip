@@ -14,6 +14,7 @@
 // reduced, so HBM requests are in flight during the LDS phase.
 
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include <algorithm>
 #include <cstdint>
@@ -97,6 +98,14 @@ struct TileParams {
   int32_t n;
   int32_t log_c;         // tile width C = 1 << log_c elements
   int32_t reverse;       // walk the column tiles from the last to the first
+  int32_t fuse;          // rounds applied per pass (1 = a single mix); >1 needs two LDS tiles
+  // Fused rounds: the rounds before the last one (rowptr/ent hold the last) are found through the
+  // table at the head of the topology's device blob, {rowptr byte offset, entry byte offset} per
+  // round.  (A per-round pointer array in this struct would be indexed at run time, i.e. read from
+  // the kernel-argument segment inside the tile loop, which costs microseconds per read.)
+  const char* blob;
+  int32_t round_k0;      // first fused round, already reduced modulo nrounds
+  int32_t nrounds;
   float alpha, beta;
 };
 
@@ -180,7 +189,7 @@ __device__ __forceinline__ void local_update4(float* xv, const float* gv, float*
 // The tile kernel.  DT: storage type of X/G/Y.  OP: what is staged and what is subtracted.
 // WITH_Y: also write the push-sum ratio.  LW: columns per lane in the reduce phase (a wave spans
 // 64*LW columns of one output row).  MAXPF: staging units (16-byte vectors of X) per thread.
-template <int DT, int OP, bool WITH_Y, int LW, int THREADS, int MAXPF, bool STREAM>
+template <int DT, int OP, bool WITH_Y, int LW, int THREADS, int MAXPF, bool STREAM, bool MULTI = false>
 __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   extern __shared__ f32x4 lds_raw[];
   float* lds = reinterpret_cast<float*>(lds_raw);
@@ -306,6 +315,57 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   const int lane = tid & 63;
   const int spans_log = log_c - SPAN_LOG;
   const int nops = p.n << spans_log;
+  #ifndef BF_GATHER_ILP
+#define BF_GATHER_ILP 4
+#endif
+  // Weighted sum of one output row-span over the row's in-neighbor list, read from an LDS tile.
+  auto gather = [&](const float* tile_base, csr_i32_ptr rp, csr_ent_ptr en_list, int i, int cit, float* acc) {
+    const int beg = rp[i], end = rp[i + 1];
+#pragma unroll
+    for (int e = 0; e < LW; ++e) acc[e] = 0.0f;
+    const float* src = tile_base + cit;
+    // Entries go in batches of K (4, then 2, then 1): the K list entries and the K LDS reads of a
+    // batch are issued together and only then consumed, in list order, so a wave waits once per
+    // batch instead of once per entry.
+    auto batch = [&](int q, auto kc) {
+      constexpr int K = decltype(kc)::value;
+      u32x2 en[K];
+#pragma unroll
+      for (int u = 0; u < K; ++u) en[u] = en_list[q + u];
+      float v[K][LW];
+#pragma unroll
+      for (int u = 0; u < K; ++u) {
+        const float* s = src + (static_cast<int>(en[u].x) << log_c);
+        if constexpr (LW == 4) {
+          const f32x4 t = *reinterpret_cast<const f32x4*>(s);
+          v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
+        } else if constexpr (LW == 2) {
+          const f32x2 t = *reinterpret_cast<const f32x2*>(s);
+          v[u][0] = t.x; v[u][1] = t.y;
+        } else {
+          v[u][0] = s[0];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < K; ++u) {
+        const float w = __uint_as_float(en[u].y);
+#pragma unroll
+        for (int e = 0; e < LW; ++e) acc[e] = fmaf(w, v[u][e], acc[e]);
+      }
+    };
+    // The fp32 kernels with four columns per lane and no gradient operand fit two 1024-thread
+    // workgroups per CU only while they stay within 64 registers, which the batch of four would
+    // cost them; every other kernel is either well below or already above that line.
+    constexpr bool BATCHED = BF_GATHER_ILP >= 4 &&
+        !(DT == DT_F32 && LW == 4 && (OP == OP_MIX || OP == OP_AWC || OP == OP_MOM_AWC) && !MULTI);
+    int q = beg;
+    if constexpr (BATCHED) {
+      for (; q + 4 <= end; q += 4) batch(q, std::integral_constant<int, 4>{});
+      if (q + 2 <= end) { batch(q, std::integral_constant<int, 2>{}); q += 2; }
+    }
+    for (; q < end; ++q) batch(q, std::integral_constant<int, 1>{});
+  };
+  const float* final_src = lds;     // the LDS tile the last round reads (moves when rounds are fused)
   // One output row-span: gather from LDS in CSR order, finish, store.
   auto row_op = [&](int64_t tile, int op) {
     const int64_t c0 = tile << log_c;
@@ -313,27 +373,8 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const int i = op >> spans_log;
       const int cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
       const int64_t col = c0 + cit;
-      const int beg = rowptr[i], end = rowptr[i + 1];
       float acc[LW];
-#pragma unroll
-      for (int e = 0; e < LW; ++e) acc[e] = 0.0f;
-      const float* src = lds + cit;
-#pragma unroll 4
-      for (int q = beg; q < end; ++q) {
-        const u32x2 en = ent[q];
-        const float w = __uint_as_float(en.y);
-        const float* s = src + (static_cast<int>(en.x) << log_c);
-        if constexpr (LW == 4) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(s);
-          acc[0] = fmaf(w, v.x, acc[0]); acc[1] = fmaf(w, v.y, acc[1]);
-          acc[2] = fmaf(w, v.z, acc[2]); acc[3] = fmaf(w, v.w, acc[3]);
-        } else if constexpr (LW == 2) {
-          const f32x2 v = *reinterpret_cast<const f32x2*>(s);
-          acc[0] = fmaf(w, v.x, acc[0]); acc[1] = fmaf(w, v.y, acc[1]);
-        } else {
-          acc[0] = fmaf(w, s[0], acc[0]);
-        }
-      }
+      gather(final_src, rowptr, ent, i, cit, acc);
       if (col < d) {
         const int64_t rem = d - col;
         const int valid = rem >= LW ? LW : static_cast<int>(rem);
@@ -400,6 +441,92 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
     BF_MARK(1);
     __syncthreads();
     BF_MARK(2);
+    if constexpr (MULTI) {
+      // Fused rounds: apply the first fuse-1 weight matrices LDS tile to LDS tile (two tiles, used
+      // alternately); the last one goes through the normal reduce-and-store below.
+      float* tile_a = lds;
+      float* tile_b = lds + (p.n << log_c);
+      const csr_i32_ptr round_tab = (csr_i32_ptr)(uintptr_t)p.blob;
+      int k = p.round_k0;
+      for (int r = 0; r + 1 < p.fuse; ++r) {
+        const float* src_t = (r & 1) ? tile_b : tile_a;
+        float* dst_t = (r & 1) ? tile_a : tile_b;
+        const uint32_t rp_off = static_cast<uint32_t>(round_tab[2 * k]);
+        const uint32_t en_off = static_cast<uint32_t>(round_tab[2 * k + 1]);
+        const csr_i32_ptr rp = (csr_i32_ptr)(reinterpret_cast<uintptr_t>(p.blob) + rp_off);
+        const csr_ent_ptr en = (csr_ent_ptr)(reinterpret_cast<uintptr_t>(p.blob) + en_off);
+        k = k + 1 == p.nrounds ? 0 : k + 1;
+        // GRP rows per wave at a time: their list lookups and LDS reads are issued together, so one
+        // wait covers all of them (a single row at a time leaves the wave idle on each lookup).
+        // Each row still adds its entries in list order, as the one-round path does.
+        constexpr int GRP = 4;
+        for (int op0 = wave; op0 < nops; op0 += NW * GRP) {
+          int row[GRP], cit[GRP], beg[GRP], end[GRP];
+          int longest = 0;
+#pragma unroll
+          for (int u = 0; u < GRP; ++u) {
+            const int op = op0 + u * NW;
+            const int opc = op < nops ? op : op0;
+            row[u] = opc >> spans_log;
+            cit[u] = ((opc & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
+            beg[u] = rp[row[u]];
+            end[u] = op < nops ? rp[row[u] + 1] : beg[u];
+            longest = max(longest, end[u] - beg[u]);
+          }
+          float acc[GRP][LW];
+#pragma unroll
+          for (int u = 0; u < GRP; ++u)
+#pragma unroll
+            for (int e = 0; e < LW; ++e) acc[u][e] = 0.0f;
+#ifdef BF_PROFILE
+          if (r == 0 && op0 == wave) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); BF_MARK(6); }
+#endif
+          for (int q = 0; q < longest; ++q) {
+            u32x2 ent_u[GRP];
+#pragma unroll
+            for (int u = 0; u < GRP; ++u) ent_u[u] = en[max(min(beg[u] + q, end[u] - 1), 0)];
+            float v[GRP][LW];
+#pragma unroll
+            for (int u = 0; u < GRP; ++u) {
+              const float* sp = src_t + cit[u] + (static_cast<int>(ent_u[u].x) << log_c);
+              if constexpr (LW == 4) {
+                const f32x4 t = *reinterpret_cast<const f32x4*>(sp);
+                v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
+              } else if constexpr (LW == 2) {
+                const f32x2 t = *reinterpret_cast<const f32x2*>(sp);
+                v[u][0] = t.x; v[u][1] = t.y;
+              } else {
+                v[u][0] = sp[0];
+              }
+            }
+#pragma unroll
+            for (int u = 0; u < GRP; ++u) {
+              const bool valid = beg[u] + q < end[u];
+              const float w = __uint_as_float(ent_u[u].y);
+#pragma unroll
+              for (int e = 0; e < LW; ++e) {
+                const float f = fmaf(w, v[u][e], acc[u][e]);
+                acc[u][e] = valid ? f : acc[u][e];
+              }
+            }
+          }
+#ifdef BF_PROFILE
+          if (r == 0 && op0 == wave) { BF_MARK(7); }
+#endif
+#pragma unroll
+          for (int u = 0; u < GRP; ++u) {
+            if (op0 + u * NW < nops) {
+              float* o = dst_t + (row[u] << log_c) + cit[u];
+              if constexpr (LW == 4) { f32x4 t = {acc[u][0], acc[u][1], acc[u][2], acc[u][3]}; *reinterpret_cast<f32x4*>(o) = t; }
+              else if constexpr (LW == 2) { f32x2 t = {acc[u][0], acc[u][1]}; *reinterpret_cast<f32x2*>(o) = t; }
+              else { o[0] = acc[u][0]; }
+            }
+          }
+        }
+        __syncthreads();
+      }
+      final_src = ((p.fuse - 1) & 1) ? tile_b : tile_a;
+    }
     const int64_t next = seq + gridDim.x;
     BF_MARK(3);
     reduce_and_store(tile, phys(next), next < p.ntiles);
@@ -999,7 +1126,9 @@ int get_device_copy(bf_topology_t* t, bool need_dense, bf::DeviceCopy** out) {
   if (!dc) {
     bf::DeviceCopy c;
     c.device = dev;
-    size_t bytes = 0;
+    // head of the blob: {rowptr byte offset, entry byte offset} per round, for kernels that walk
+    // several rounds themselves
+    size_t bytes = (t->rounds.size() * 8 + 31) / 32 * 32;
     for (auto& r : t->rounds) {
       c.rowptr_off.push_back(bytes);
       bytes += ((static_cast<size_t>(t->n) + 1 + 1) / 2) * 8;
@@ -1009,9 +1138,13 @@ int get_device_copy(bf_topology_t* t, bool need_dense, bf::DeviceCopy** out) {
       c.chain_off.push_back(r.chain.empty() ? SIZE_MAX : bytes);
       bytes += r.chain.size() * sizeof(bf::ChainStep);
     }
+    if (bytes > UINT32_MAX) return BF_ERR_SIZE;
     std::vector<char> host(bytes, 0);
     for (size_t k = 0; k < t->rounds.size(); ++k) {
       auto& r = t->rounds[k];
+      uint32_t* tab = reinterpret_cast<uint32_t*>(host.data());
+      tab[2 * k] = static_cast<uint32_t>(c.rowptr_off[k]);
+      tab[2 * k + 1] = static_cast<uint32_t>(c.entry_off[k]);
       int32_t* rp = reinterpret_cast<int32_t*>(host.data() + c.rowptr_off[k]);
       for (int32_t i = 0; i <= t->n; ++i) rp[i] = static_cast<int32_t>(r.rowptr[i]);
       uint32_t* en = reinterpret_cast<uint32_t*>(host.data() + c.entry_off[k]);
@@ -1103,11 +1236,11 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s) {
   return BF_OK;
 }
 
-template <int DT, int OP, bool WITH_Y, int LW, int THREADS, bool STREAM>
+template <int DT, int OP, bool WITH_Y, int LW, int THREADS, bool STREAM, bool MULTI = false>
 int launch_tile_thr(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
   // prefetch depth: a 64 KB tile is 4 (fp32) / 2 (bf16) vectors per thread at 1024 threads
   constexpr int MAXPF = DT == DT_F32 ? 4 : 2;
-  auto kern = bf_tile_kernel<DT, OP, WITH_Y, LW, THREADS, MAXPF, STREAM>;
+  auto kern = bf_tile_kernel<DT, OP, WITH_Y, LW, THREADS, MAXPF, STREAM, MULTI>;
   if (lds > 48 * 1024) {
     static thread_local size_t raised = 0;
     if (raised < lds) {
@@ -1125,6 +1258,13 @@ int launch_tile_thr(const TileParams& tp, int grid, size_t lds, hipStream_t st) 
 // measured 5..25 % slower at every tile width.
 template <int DT, int OP, bool WITH_Y, int LW>
 int launch_tile_lw(const TileParams& tp, int grid, size_t lds, bool stream, hipStream_t st) {
+  if constexpr (OP == OP_MIX && !WITH_Y) {
+    // the several-rounds-per-pass form is a kernel of its own, so its extra registers cost the
+    // one-round kernel nothing
+    if (tp.fuse > 1)
+      return stream ? launch_tile_thr<DT, OP, WITH_Y, LW, 1024, true, true>(tp, grid, lds, st)
+                    : launch_tile_thr<DT, OP, WITH_Y, LW, 1024, false, true>(tp, grid, lds, st);
+  }
   return stream ? launch_tile_thr<DT, OP, WITH_Y, LW, 1024, true>(tp, grid, lds, st)
                 : launch_tile_thr<DT, OP, WITH_Y, LW, 1024, false>(tp, grid, lds, st);
 }
@@ -1237,7 +1377,21 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   tp.ent = reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[k]);
   tp.n = t->n;
   tp.reverse = g_tune_noserp ? 0 : (round & 1);
-  if (dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather &&
+  const int fuse = tp.fuse > 1 ? tp.fuse : 1;
+  tp.fuse = fuse;
+  if (fuse > 1) {
+    // Several consecutive rounds in one pass: the earlier rounds' lists go in the side arrays, the
+    // last round's in the usual place.  Only the plain mix has this form.
+    if (op != OP_MIX || with_y || fuse > 8) return BF_ERR_UNSUPPORTED;
+    tp.blob = dc->blob;
+    tp.round_k0 = static_cast<int32_t>(k);
+    tp.nrounds = static_cast<int32_t>(t->rounds.size());
+    const size_t kl = (static_cast<size_t>(round) + fuse - 1) % t->rounds.size();
+    tp.rowptr = reinterpret_cast<const int32_t*>(dc->blob + dc->rowptr_off[kl]);
+    tp.ent = reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[kl]);
+    tp.reverse = g_tune_noserp ? 0 : ((round / fuse) & 1);
+  }
+  if (fuse == 1 && dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather &&
       (g_tune_cw > 0 || static_cast<size_t>(t->n) * 256 * 4 > (di.lds_per_cu ? di.lds_per_cu : 65536) / 2)) {
     // Chain-structured round with too many agents for a 256-column LDS tile (measured: the tile
     // kernel wins below that, the row-streaming kernel above): stream rows through registers when
@@ -1262,7 +1416,8 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     }
   }
   Shape s;
-  rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(t->n, tp.d, di, &s);
+  rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(fuse > 1 ? 2 * t->n : t->n, tp.d, di, &s);
+  if (fuse > 1 && rc != BF_OK) return rc;   // fused rounds exist only as the two-tile LDS kernel
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
     // Too many agents for an LDS tile: row gather through the caches, out of place only.
     if (tp.x_in == tp.x_out || op == OP_ED || op == OP_TRACK) return BF_ERR_UNSUPPORTED;
@@ -1357,6 +1512,24 @@ int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_i
   tp.x_out = static_cast<char*>(X_out);
   tp.d = d; tp.ld = ld;
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_MIX, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t count, const void* X_in,
+                                void* X_out, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  if (!t || !X_in || !X_out) return BF_ERR_NULL;
+  if (round0 < 0) return BF_ERR_ROUND;
+  if (count < 1 || count > 8) return BF_ERR_SIZE;
+  MatArgs ma;
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
+  if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  TileParams tp{};
+  tp.x_in = static_cast<const char*>(X_in);
+  tp.x_out = static_cast<char*>(X_out);
+  tp.d = d; tp.ld = ld;
+  tp.fuse = count;
+  return run_tile(const_cast<bf_topology_t*>(t), round0, OP_MIX, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
 int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,

@@ -246,6 +246,13 @@ def test_compute_calls_validate_before_touching_the_device():
     assert na(h, 0, A, B, 0, 64, bf.BF_F32, None) == bf.BF_OK                  # empty: nothing to launch
     assert na(h, 0, A, A, 0, 64, bf.BF_F32, None) == bf.BF_OK
     assert L.bf_dense_mix(h, 0, A, B, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_UNSUPPORTED
+    nm = L.bf_neighbor_allreduce_multi
+    assert nm(h, 0, 0, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE       # count out of [1, 8]
+    assert nm(h, 0, 9, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert nm(h, -2, 2, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ROUND
+    assert nm(h, 0, 2, A, A + 256, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert nm(h, 0, 2, None, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert nm(h, 0, 2, A, B, 0, 64, bf.BF_F32, None) == bf.BF_OK
     ps = L.bf_pushsum_step
     W1, W2 = 0x30000000, 0x30001000
     assert ps(h, 0, A, B, None, W2, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL

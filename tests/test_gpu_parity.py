@@ -734,3 +734,64 @@ def test_gradient_tracking_run_on_time_varying_graph():
     xs = np.linalg.lstsq(Ah.reshape(n * m, d), bh.reshape(n * m), rcond=None)[0]
     assert np.abs(host(X) - xs).max() < 1e-2 * np.abs(xs).max()
     assert float((v - 1).abs().max()) < 1e-6
+
+
+# ------------------------------------------------------------------ several rounds in one pass
+@pytest.mark.parametrize("name,make", TOPOS)
+@pytest.mark.parametrize("n,d,round0,count", [(16, 1024, 0, 2), (64, 8192 + 520, 3, 5), (100, 3004, 1, 8),
+                                              (256, 4096 + 72, 0, 8), (37, 130, 2, 3), (1, 64, 0, 4), (320, 1000, 5, 2)])
+def test_fused_rounds_match_the_oracle_and_the_separate_calls(name, make, n, d, round0, count):
+    t = make(n)
+    X = rows(n, d, 1000 + n + count)
+    ref = host(X)
+    for r in range(round0, round0 + count):
+        ref = O.mix(ref, lib_W(t, r % bf.bf_topology_rounds(t)))
+    out = bf.bf_neighbor_allreduce_multi(t, round0, count, X, empty_like_rows(X))
+    assert_close(out, ref, TOL32 * count, "%s n=%d %d rounds" % (name, n, count))
+    seq = [empty_like_rows(X).copy_(X), empty_like_rows(X)]
+    for k, r in enumerate(range(round0, round0 + count)):
+        bf.bf_neighbor_allreduce(t, r, seq[k & 1], seq[1 - (k & 1)])
+    assert torch.equal(out, seq[count & 1]), "fused rounds differ in bits from separate rounds"
+    inplace = empty_like_rows(X).copy_(X)
+    bf.bf_neighbor_allreduce_multi(t, round0, count, inplace, inplace)
+    assert torch.equal(inplace, out)
+
+
+def test_fused_one_peer_rounds_give_the_exact_mean_in_one_pass():
+    # log2(n) one-peer rounds average exactly (section "One-peer exponential graph"); with
+    # power-of-two weights each fp32 step is one correctly rounded addition, so the bits are fixed.
+    n, d = 256, 4096 + 136
+    t = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+    X = workloads.config3_state(DEV, n=n, d=d, ld=workloads.padded_ld(d, 4))
+    emu = X.cpu().numpy()
+    for r in range(8):
+        emu = O.mix_fp32_chain(emu, lib_W(t, r))
+    out = bf.bf_neighbor_allreduce_multi(t, 0, 8, X, empty_like_rows(X))
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), emu.view(np.uint32))
+    mean = host(X).mean(0)
+    assert np.abs(host(out) - mean).max() <= 8 * 6e-8 * np.abs(host(X)).max()
+    assert float((out - out[0:1]).abs().max()) <= 8 * 6e-8 * float(X.abs().max())
+
+
+def test_fused_rounds_bf16_round_once():
+    n, d, count = 64, 2048 + 264, 6
+    t = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+    X = rows(n, d, 77, dtype=torch.bfloat16)
+    ref = host(X)
+    for r in range(count):
+        ref = O.mix(ref, lib_W(t, r))
+    out = bf.bf_neighbor_allreduce_multi(t, 0, count, X, empty_like_rows(X))
+    # intermediate products stay fp32: the only bf16 rounding is the final store (half an ulp of a
+    # 7-bit fraction: at most 2^-8 relative) on top of fp32 accumulation error
+    err = np.abs(host(out) - ref)
+    assert (err <= np.abs(ref) * 2.0 ** -8 + 1e-6).all()
+    assert_close(out, ref, TOL16, "bf16 fused")
+
+
+def test_fused_rounds_reject_what_does_not_fit():
+    n = 400
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    X = rows(n, 256, 5)
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_neighbor_allreduce_multi(t, 0, 2, X, empty_like_rows(X))
+    assert e.value.code == bf.BF_ERR_UNSUPPORTED
