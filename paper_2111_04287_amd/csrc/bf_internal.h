@@ -37,7 +37,8 @@ struct Round {
 // Device-resident copy of all rounds, built on first use on a device.
 struct DeviceCopy {
   int      device = -1;
-  char*    blob = nullptr;               // [round]: int32 rowptr[n+1] (padded to 8 B) | {int32 col, f32 w}[nnz]
+  char*    blob = nullptr;               // round table | per round: int32 rowptr[n+1] | {int32 col, f32 w}[nnz] |
+                                         // chain plan | sliced copy (headers, records of four rows side by side)
   std::vector<size_t> rowptr_off;        // byte offsets into blob, per round
   std::vector<size_t> entry_off;
   std::vector<size_t> chain_off;         // byte offset of the round's ChainStep[n], or SIZE_MAX

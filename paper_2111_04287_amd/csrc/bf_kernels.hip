@@ -27,6 +27,7 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -446,80 +447,112 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       // alternately); the last one goes through the normal reduce-and-store below.
       float* tile_a = lds;
       float* tile_b = lds + (p.n << log_c);
-      const csr_i32_ptr round_tab = (csr_i32_ptr)(uintptr_t)p.blob;
+      typedef const u32x4 __attribute__((address_space(4)))* csr_u4_ptr;
+      typedef const u32x8 __attribute__((address_space(4)))* csr_u8_ptr;
+      const csr_u4_ptr round_tab = (csr_u4_ptr)(uintptr_t)p.blob;
+      const int ngroups = (p.n + 3) >> 2;
+      const int nitems = ngroups << spans_log;
       int k = p.round_k0;
       for (int r = 0; r + 1 < p.fuse; ++r) {
         const float* src_t = (r & 1) ? tile_b : tile_a;
         float* dst_t = (r & 1) ? tile_a : tile_b;
-        const uint32_t rp_off = static_cast<uint32_t>(round_tab[2 * k]);
-        const uint32_t en_off = static_cast<uint32_t>(round_tab[2 * k + 1]);
-        const csr_i32_ptr rp = (csr_i32_ptr)(reinterpret_cast<uintptr_t>(p.blob) + rp_off);
-        const csr_ent_ptr en = (csr_ent_ptr)(reinterpret_cast<uintptr_t>(p.blob) + en_off);
+        const u32x4 offs = round_tab[k];
+        const csr_u4_ptr hdrs = (csr_u4_ptr)(reinterpret_cast<uintptr_t>(p.blob) + offs.z);
+        const uintptr_t recs = reinterpret_cast<uintptr_t>(p.blob) + offs.w;
         k = k + 1 == p.nrounds ? 0 : k + 1;
-        // GRP rows per wave at a time: their list lookups and LDS reads are issued together, so one
-        // wait covers all of them (a single row at a time leaves the wave idle on each lookup).
-        // Each row still adds its entries in list order, as the one-round path does.
-        constexpr int GRP = 4;
-        for (int op0 = wave; op0 < nops; op0 += NW * GRP) {
-          int row[GRP], cit[GRP], beg[GRP], end[GRP];
-          int longest = 0;
+        // NG groups of four rows per wave at a time, from the sliced copy of the round: one 32-byte
+        // scalar load brings the q-th entry of a group's four rows, the LDS reads of all groups go
+        // out together, and each row still adds its entries in list order, as the one-round path
+        // does.  (One group at a time leaves the wave waiting on each lookup: 16 waves per CU are
+        // all there is to hide it, because the two tiles fill the LDS.)
+        constexpr int NG = 1;
+        for (int item0 = wave; item0 < nitems; item0 += NW * NG) {
+          int g[NG], cit[NG];
+          u32x4 hdr[NG];
+          uint32_t longest = 0;
+          bool ragged = false;
 #pragma unroll
-          for (int u = 0; u < GRP; ++u) {
-            const int op = op0 + u * NW;
-            const int opc = op < nops ? op : op0;
-            row[u] = opc >> spans_log;
-            cit[u] = ((opc & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
-            beg[u] = rp[row[u]];
-            end[u] = op < nops ? rp[row[u] + 1] : beg[u];
-            longest = max(longest, end[u] - beg[u]);
+          for (int j = 0; j < NG; ++j) {
+            const int item = item0 + j * NW;
+            const int itc = item < nitems ? item : item0;
+            g[j] = itc >> spans_log;
+            cit[j] = ((itc & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
+            hdr[j] = hdrs[g[j]];
+            if (item >= nitems) hdr[j].y = 0;
           }
-          float acc[GRP][LW];
 #pragma unroll
-          for (int u = 0; u < GRP; ++u)
+          for (int j = 0; j < NG; ++j) {
+            longest = max(longest, hdr[j].y);
+            ragged = ragged || hdr[j].z != 0 || hdr[j].y != hdr[0].y;
+          }
+          float acc[NG][4][LW];
 #pragma unroll
-            for (int e = 0; e < LW; ++e) acc[u][e] = 0.0f;
-#ifdef BF_PROFILE
-          if (r == 0 && op0 == wave) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); BF_MARK(6); }
-#endif
-          for (int q = 0; q < longest; ++q) {
-            u32x2 ent_u[GRP];
+          for (int j = 0; j < NG; ++j)
 #pragma unroll
-            for (int u = 0; u < GRP; ++u) ent_u[u] = en[max(min(beg[u] + q, end[u] - 1), 0)];
-            float v[GRP][LW];
+            for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int u = 0; u < GRP; ++u) {
-              const float* sp = src_t + cit[u] + (static_cast<int>(ent_u[u].x) << log_c);
-              if constexpr (LW == 4) {
-                const f32x4 t = *reinterpret_cast<const f32x4*>(sp);
-                v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
-              } else if constexpr (LW == 2) {
-                const f32x2 t = *reinterpret_cast<const f32x2*>(sp);
-                v[u][0] = t.x; v[u][1] = t.y;
-              } else {
-                v[u][0] = sp[0];
+              for (int e = 0; e < LW; ++e) acc[j][u][e] = 0.0f;
+          auto records = [&](auto ragged_c) {
+            constexpr bool RAGGED = decltype(ragged_c)::value;
+            for (uint32_t q = 0; q < longest; ++q) {
+              u32x8 e8[NG];
+#pragma unroll
+              for (int j = 0; j < NG; ++j) {
+                // a group that has run out re-reads its last record (or record 0 of the table when
+                // it has none); every entry of such a read is skipped below
+                const uint32_t qc = RAGGED ? (q < hdr[j].y ? q : (hdr[j].y ? hdr[j].y - 1 : 0)) : q;
+                const uint32_t first = RAGGED && hdr[j].y == 0 ? 0 : hdr[j].x;
+                e8[j] = ((csr_u8_ptr)(recs + (static_cast<uintptr_t>(first + qc) << 5)))[0];
+              }
+              float v[NG][4][LW];
+#pragma unroll
+              for (int j = 0; j < NG; ++j) {
+                const uint32_t col[4] = {e8[j].s0, e8[j].s2, e8[j].s4, e8[j].s6};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  const float* sp = src_t + cit[j] + (static_cast<int>(RAGGED ? (col[u] & 0x7fffffffu) : col[u]) << log_c);
+                  if constexpr (LW == 4) {
+                    const f32x4 t = *reinterpret_cast<const f32x4*>(sp);
+                    v[j][u][0] = t.x; v[j][u][1] = t.y; v[j][u][2] = t.z; v[j][u][3] = t.w;
+                  } else if constexpr (LW == 2) {
+                    const f32x2 t = *reinterpret_cast<const f32x2*>(sp);
+                    v[j][u][0] = t.x; v[j][u][1] = t.y;
+                  } else {
+                    v[j][u][0] = sp[0];
+                  }
+                }
+              }
+#pragma unroll
+              for (int j = 0; j < NG; ++j) {
+                const uint32_t col[4] = {e8[j].s0, e8[j].s2, e8[j].s4, e8[j].s6};
+                const uint32_t wb[4] = {e8[j].s1, e8[j].s3, e8[j].s5, e8[j].s7};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  const float w = __uint_as_float(wb[u]);
+                  const bool live = !RAGGED || (static_cast<int32_t>(col[u]) >= 0 && q < hdr[j].y);
+#pragma unroll
+                  for (int e = 0; e < LW; ++e) {
+                    const float f = fmaf(w, v[j][u][e], acc[j][u][e]);
+                    acc[j][u][e] = live ? f : acc[j][u][e];
+                  }
+                }
               }
             }
+          };
+          if (ragged) records(std::true_type{}); else records(std::false_type{});
 #pragma unroll
-            for (int u = 0; u < GRP; ++u) {
-              const bool valid = beg[u] + q < end[u];
-              const float w = __uint_as_float(ent_u[u].y);
+          for (int j = 0; j < NG; ++j) {
+            if (item0 + j * NW < nitems) {
 #pragma unroll
-              for (int e = 0; e < LW; ++e) {
-                const float f = fmaf(w, v[u][e], acc[u][e]);
-                acc[u][e] = valid ? f : acc[u][e];
+              for (int u = 0; u < 4; ++u) {
+                const int row = (g[j] << 2) + u;
+                if (row < p.n) {
+                  float* o = dst_t + (row << log_c) + cit[j];
+                  if constexpr (LW == 4) { f32x4 t = {acc[j][u][0], acc[j][u][1], acc[j][u][2], acc[j][u][3]}; *reinterpret_cast<f32x4*>(o) = t; }
+                  else if constexpr (LW == 2) { f32x2 t = {acc[j][u][0], acc[j][u][1]}; *reinterpret_cast<f32x2*>(o) = t; }
+                  else { o[0] = acc[j][u][0]; }
+                }
               }
-            }
-          }
-#ifdef BF_PROFILE
-          if (r == 0 && op0 == wave) { BF_MARK(7); }
-#endif
-#pragma unroll
-          for (int u = 0; u < GRP; ++u) {
-            if (op0 + u * NW < nops) {
-              float* o = dst_t + (row[u] << log_c) + cit[u];
-              if constexpr (LW == 4) { f32x4 t = {acc[u][0], acc[u][1], acc[u][2], acc[u][3]}; *reinterpret_cast<f32x4*>(o) = t; }
-              else if constexpr (LW == 2) { f32x2 t = {acc[u][0], acc[u][1]}; *reinterpret_cast<f32x2*>(o) = t; }
-              else { o[0] = acc[u][0]; }
             }
           }
         }
@@ -1126,10 +1159,18 @@ int get_device_copy(bf_topology_t* t, bool need_dense, bf::DeviceCopy** out) {
   if (!dc) {
     bf::DeviceCopy c;
     c.device = dev;
-    // head of the blob: {rowptr byte offset, entry byte offset} per round, for kernels that walk
-    // several rounds themselves
-    size_t bytes = (t->rounds.size() * 8 + 31) / 32 * 32;
-    for (auto& r : t->rounds) {
+    // Head of the blob: four byte offsets per round {rowptr, entries, slice headers, slice entries},
+    // for kernels that walk several rounds themselves.  The sliced copy of a round groups rows in
+    // fours: a header {first 32-byte record, number of records, 1 if the four rows differ in
+    // length} per group, and per record the q-th entry of each of the four rows side by side
+    // {col, weight} x 4, so one 32-byte scalar load feeds four rows.  A row shorter than its group
+    // is filled with {0x80000000 | row, 0}, which the kernel skips.
+    const size_t ngroups = (static_cast<size_t>(t->n) + 3) / 4;
+    size_t bytes = (t->rounds.size() * 16 + 31) / 32 * 32;
+    std::vector<size_t> slice_hdr_off, slice_ent_off;
+    std::vector<std::vector<uint32_t>> slice_hdr(t->rounds.size()), slice_ent(t->rounds.size());
+    for (size_t k = 0; k < t->rounds.size(); ++k) {
+      auto& r = t->rounds[k];
       c.rowptr_off.push_back(bytes);
       bytes += ((static_cast<size_t>(t->n) + 1 + 1) / 2) * 8;
       c.entry_off.push_back(bytes);
@@ -1137,14 +1178,48 @@ int get_device_copy(bf_topology_t* t, bool need_dense, bf::DeviceCopy** out) {
       bytes = (bytes + 31) / 32 * 32;
       c.chain_off.push_back(r.chain.empty() ? SIZE_MAX : bytes);
       bytes += r.chain.size() * sizeof(bf::ChainStep);
+      bytes = (bytes + 31) / 32 * 32;
+      auto& hdr = slice_hdr[k];
+      auto& ent = slice_ent[k];
+      for (size_t g = 0; g < ngroups; ++g) {
+        int64_t longest = 0, shortest = INT64_MAX;
+        for (size_t u = 0; u < 4; ++u) {
+          const size_t row = g * 4 + u;
+          const int64_t len = row < static_cast<size_t>(t->n) ? r.rowptr[row + 1] - r.rowptr[row] : 0;
+          longest = std::max(longest, len);
+          shortest = std::min(shortest, len);
+        }
+        hdr.push_back(static_cast<uint32_t>(ent.size() / 8));
+        hdr.push_back(static_cast<uint32_t>(longest));
+        hdr.push_back(shortest != longest ? 1u : 0u);
+        hdr.push_back(0u);
+        for (int64_t q = 0; q < longest; ++q)
+          for (size_t u = 0; u < 4; ++u) {
+            const size_t row = std::min(g * 4 + u, static_cast<size_t>(t->n) - 1);
+            const bool live = g * 4 + u < static_cast<size_t>(t->n) && r.rowptr[row] + q < r.rowptr[row + 1];
+            uint32_t wbits = 0;
+            if (live) std::memcpy(&wbits, &r.wgt[r.rowptr[row] + q], 4);
+            ent.push_back(live ? static_cast<uint32_t>(r.col[r.rowptr[row] + q]) : (0x80000000u | static_cast<uint32_t>(row)));
+            ent.push_back(wbits);
+          }
+      }
+      slice_hdr_off.push_back(bytes);
+      bytes += (hdr.size() * 4 + 31) / 32 * 32;
+      slice_ent_off.push_back(bytes);
+      bytes += (ent.size() * 4 + 31) / 32 * 32;
     }
+    bytes += 64;   // wide scalar loads may read past the last record
     if (bytes > UINT32_MAX) return BF_ERR_SIZE;
     std::vector<char> host(bytes, 0);
     for (size_t k = 0; k < t->rounds.size(); ++k) {
       auto& r = t->rounds[k];
       uint32_t* tab = reinterpret_cast<uint32_t*>(host.data());
-      tab[2 * k] = static_cast<uint32_t>(c.rowptr_off[k]);
-      tab[2 * k + 1] = static_cast<uint32_t>(c.entry_off[k]);
+      tab[4 * k] = static_cast<uint32_t>(c.rowptr_off[k]);
+      tab[4 * k + 1] = static_cast<uint32_t>(c.entry_off[k]);
+      tab[4 * k + 2] = static_cast<uint32_t>(slice_hdr_off[k]);
+      tab[4 * k + 3] = static_cast<uint32_t>(slice_ent_off[k]);
+      if (!slice_hdr[k].empty()) std::memcpy(host.data() + slice_hdr_off[k], slice_hdr[k].data(), slice_hdr[k].size() * 4);
+      if (!slice_ent[k].empty()) std::memcpy(host.data() + slice_ent_off[k], slice_ent[k].data(), slice_ent[k].size() * 4);
       int32_t* rp = reinterpret_cast<int32_t*>(host.data() + c.rowptr_off[k]);
       for (int32_t i = 0; i <= t->n; ++i) rp[i] = static_cast<int32_t>(r.rowptr[i]);
       uint32_t* en = reinterpret_cast<uint32_t*>(host.data() + c.entry_off[k]);
