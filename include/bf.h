@@ -154,6 +154,19 @@ int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_i
 int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t count, const void* X_in,
                                 void* X_out, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
+/* Two-level neighbor averaging (section "Enabling hierarchical communication"): agents are grouped
+ * into machines of `local_size` consecutive ranks (machine_rank = rank / local_size); each machine
+ * first averages its agents, the machines then do one round of partial averaging over
+ * `machine_topology` (whose n is the number of machines M), and every agent of a machine takes its
+ * machine's result:  X_out[i,:] = sum_b W_machine[a(i), b] * (1/local_size) sum_{j in b} X_in[j,:].
+ * X has M * local_size rows.  One pass over X when two (M*local_size) x 64 fp32 tiles fit one CU's
+ * LDS, three passes otherwise (up to one such tile; beyond that BF_ERR_UNSUPPORTED).  The derived
+ * operator is built on first use and kept inside machine_topology (freed with it).  X_out may equal
+ * X_in.  local_size < 1: BF_ERR_SIZE. */
+int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, int32_t round, int32_t local_size,
+                                       const void* X_in, void* X_out, int64_t d, int64_t ld, bf_dtype_t dt,
+                                       void* hip_stream);
+
 /* Same product through the dense n x n form of W^(round) on the fp32 matrix cores (BF_F32 only;
  * n <= 256).  Intended for dense / fully connected W (periodic global averaging is W = 11^T/n) and
  * as an independent cross-check of the sparse kernels. */

@@ -191,3 +191,29 @@ def pushsum_gradient_tracking_step(U, v, Y, G_prev, W, alpha, grad):
     Gn = _f64(grad(Xn))
     Yn = mix(Y + Gn - G_prev, W)
     return Un, vn, Xn, Yn, Gn
+
+
+def hierarchical_neighbor_allreduce(X, W_machine, local_size):
+    """Two-level neighbor averaging (section "Enabling hierarchical communication"): machine a owns
+    the agents a*local_size .. (a+1)*local_size-1 (machine_rank = rank // local_size).
+    Stage 1: each machine averages its agents.  Stage 2: one round of partial averaging of those
+    machine values over the machine-level W.  Stage 3: every agent takes its machine's result."""
+    X = _f64(X)
+    n = X.shape[0]
+    L = int(local_size)
+    if L < 1 or n % L:
+        raise ValueError("the number of agents must be a multiple of local_size")
+    M = n // L
+    local_avg = np.zeros((M, X.shape[1]))
+    for a in range(M):
+        for l in range(L):
+            local_avg[a, :] += X[a * L + l, :]
+        local_avg[a, :] /= L
+    machine_out = np.zeros_like(local_avg)
+    for a in range(M):
+        for b, w in W_machine[a]:
+            machine_out[a, :] += w * local_avg[b, :]
+    out = np.zeros_like(X)
+    for i in range(n):
+        out[i, :] = machine_out[i // L, :]
+    return out

@@ -28,7 +28,7 @@ BF_W_ANY, BF_W_PULL, BF_W_PUSH, BF_W_STANDARD = 0, 1, 2, 3
 EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
-    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
+    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -84,6 +84,7 @@ def _load():
     L.bf_topology_chain_plan.argtypes = [vp, i32, vp]
     L.bf_neighbor_allreduce.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_neighbor_allreduce_multi.argtypes = [vp, i32, i32, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_hierarchical_neighbor_allreduce.argtypes = [vp, i32, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_dense_mix.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_pushsum_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_pushsum_atc_step.argtypes = [vp, i32, vp, vp, vp, f32, vp, vp, vp, i64, i64, C.c_int, vp]
@@ -243,6 +244,19 @@ def _stream(stream):
     return getattr(stream, "cuda_stream", stream)
 
 
+def _rows(t, n, per_agent=1):
+    """The C entry points take the row count from the topology: a tensor with fewer rows would be
+    read and written out of bounds, so the count is checked here, where the shapes are known."""
+    if n != t.n * per_agent:
+        raise ValueError("the matrix has %d rows, the topology %d agents" % (n, t.n * per_agent))
+
+
+def _vec(w, n, name):
+    import torch
+    if w.dtype != torch.float32 or w.dim() != 1 or w.numel() != n or not w.is_contiguous():
+        raise ValueError("%s must be a contiguous float32 vector with one entry per agent" % name)
+
+
 def _same_layout(ref, other, name):
     if other.shape != ref.shape or (ref.shape[0] > 1 and other.stride(0) != ref.stride(0)) or other.dtype != ref.dtype:
         raise ValueError("%s must match the shape, row stride and dtype of X_in" % name)
@@ -250,6 +264,7 @@ def _same_layout(ref, other, name):
 
 def bf_neighbor_allreduce(t, rnd, X_in, X_out, stream=None):
     ptr, n, d, ld = _mat(X_in, "X_in")
+    _rows(t, n)
     _same_layout(X_in, X_out, "X_out")
     _check(lib.bf_neighbor_allreduce(t.handle, rnd, ptr, X_out.data_ptr(), d, ld, _dtype_code(X_in),
                                      _stream(stream)), "bf_neighbor_allreduce")
@@ -258,14 +273,26 @@ def bf_neighbor_allreduce(t, rnd, X_in, X_out, stream=None):
 
 def bf_neighbor_allreduce_multi(t, rnd0, count, X_in, X_out, stream=None):
     ptr, n, d, ld = _mat(X_in, "X_in")
+    _rows(t, n)
     _same_layout(X_in, X_out, "X_out")
     _check(lib.bf_neighbor_allreduce_multi(t.handle, rnd0, count, ptr, X_out.data_ptr(), d, ld,
                                            _dtype_code(X_in), _stream(stream)), "bf_neighbor_allreduce_multi")
     return X_out
 
 
+def bf_hierarchical_neighbor_allreduce(machine_topology, rnd, local_size, X_in, X_out, stream=None):
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _same_layout(X_in, X_out, "X_out")
+    _rows(machine_topology, n, local_size)
+    _check(lib.bf_hierarchical_neighbor_allreduce(machine_topology.handle, rnd, local_size, ptr, X_out.data_ptr(), d, ld,
+                                                  _dtype_code(X_in), _stream(stream)),
+           "bf_hierarchical_neighbor_allreduce")
+    return X_out
+
+
 def bf_dense_mix(t, rnd, X_in, X_out, stream=None):
     ptr, n, d, ld = _mat(X_in, "X_in")
+    _rows(t, n)
     _same_layout(X_in, X_out, "X_out")
     _check(lib.bf_dense_mix(t.handle, rnd, ptr, X_out.data_ptr(), d, ld, _dtype_code(X_in), _stream(stream)),
            "bf_dense_mix")
@@ -274,9 +301,12 @@ def bf_dense_mix(t, rnd, X_in, X_out, stream=None):
 
 def bf_pushsum_step(t, rnd, X_in, X_out, w_in, w_out, Y=None, stream=None):
     ptr, n, d, ld = _mat(X_in, "X_in")
+    _rows(t, n)
     _same_layout(X_in, X_out, "X_out")
     if Y is not None:
         _same_layout(X_in, Y, "Y")
+    _vec(w_in, n, "w_in")
+    _vec(w_out, n, "w_out")
     _check(lib.bf_pushsum_step(t.handle, rnd, ptr, X_out.data_ptr(), w_in.data_ptr(), w_out.data_ptr(),
                                None if Y is None else Y.data_ptr(), d, ld, _dtype_code(X_in), _stream(stream)),
            "bf_pushsum_step")
@@ -285,10 +315,13 @@ def bf_pushsum_step(t, rnd, X_in, X_out, w_in, w_out, Y=None, stream=None):
 
 def bf_pushsum_atc_step(t, rnd, X_in, X_out, G, alpha, w_in, w_out, Y=None, stream=None):
     ptr, n, d, ld = _mat(X_in, "X_in")
+    _rows(t, n)
     _same_layout(X_in, X_out, "X_out")
     _same_layout(X_in, G, "G")
     if Y is not None:
         _same_layout(X_in, Y, "Y")
+    _vec(w_in, n, "w_in")
+    _vec(w_out, n, "w_out")
     _check(lib.bf_pushsum_atc_step(t.handle, rnd, ptr, X_out.data_ptr(), G.data_ptr(), alpha, w_in.data_ptr(),
                                    w_out.data_ptr(), None if Y is None else Y.data_ptr(), d, ld,
                                    _dtype_code(X_in), _stream(stream)), "bf_pushsum_atc_step")
@@ -297,6 +330,7 @@ def bf_pushsum_atc_step(t, rnd, X_in, X_out, G, alpha, w_in, w_out, Y=None, stre
 
 def bf_tracking_step(t, rnd, Y_in, Y_out, G_new, G_old, stream=None):
     ptr, n, d, ld = _mat(Y_in, "Y_in")
+    _rows(t, n)
     for nm, o in (("Y_out", Y_out), ("G_new", G_new), ("G_old", G_old)):
         _same_layout(Y_in, o, nm)
     _check(lib.bf_tracking_step(t.handle, rnd, ptr, Y_out.data_ptr(), G_new.data_ptr(), G_old.data_ptr(), d, ld,
@@ -306,6 +340,7 @@ def bf_tracking_step(t, rnd, Y_in, Y_out, G_new, G_old, stream=None):
 
 def bf_atc_step(t, rnd, X_in, X_out, G, M=None, alpha=0.0, beta=0.0, mode=BF_ATC, stream=None):
     ptr, n, d, ld = _mat(X_in, "X_in")
+    _rows(t, n)
     _same_layout(X_in, X_out, "X_out")
     _same_layout(X_in, G, "G")
     if M is not None:
@@ -321,6 +356,7 @@ def bf_atc_step(t, rnd, X_in, X_out, G, M=None, alpha=0.0, beta=0.0, mode=BF_ATC
 def bf_exact_diffusion_step(t, rnd, X_in, X_out, G, Psi_prev, alpha, stream=None):
     import torch
     ptr, n, d, ld = _mat(X_in, "X_in")
+    _rows(t, n)
     _same_layout(X_in, X_out, "X_out")
     _same_layout(X_in, G, "G")
     if Psi_prev.dtype != torch.float32 or Psi_prev.shape != X_in.shape or (n > 1 and Psi_prev.stride(0) != ld):

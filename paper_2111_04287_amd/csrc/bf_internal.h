@@ -4,6 +4,7 @@
 #define BF_INTERNAL_H_
 
 #include <cstdint>
+#include <map>
 #include <mutex>
 #include <vector>
 
@@ -53,8 +54,10 @@ struct bf_topology {
   int32_t  kind = 0;
   uint64_t accepted_seed = 0;
   std::vector<bf::Round> rounds;
-  std::mutex mu;                          // guards dev
+  std::mutex mu;                          // guards dev and two_level
   std::vector<bf::DeviceCopy> dev;
+  // Two-level operators built from this (machine-level) topology, keyed by local_size; owned.
+  std::map<int32_t, bf_topology*> two_level;
 };
 
 namespace bf {
@@ -63,6 +66,9 @@ namespace bf {
 int  finalize_round(Round& r, int32_t n);           // sort check, class, max degree; returns status
 void dense_transposed(const Round& r, int32_t n, int32_t n_pad, float* out);  // out[k*n_pad+i] = w_ik
 void build_chain_plan(Round& r, int32_t n);          // fills r.chain when the structure allows
+// Three rounds over M*local_size agents per round of the M-machine topology: machine a's local
+// average into row a, the machine-level round among rows 0..M-1, row i/local_size back to agent i.
+int  make_two_level(const bf_topology& machine, int32_t local_size, bf_topology** out);
 
 }  // namespace bf
 

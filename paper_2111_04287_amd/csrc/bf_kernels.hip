@@ -443,6 +443,9 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
     __syncthreads();
     BF_MARK(2);
     if constexpr (MULTI) {
+      // Only one such workgroup fits a CU (two tiles), so nothing else keeps the memory pipe busy
+      // during the LDS rounds: the next tile's loads go out now, not during the last round.
+      if (seq + gridDim.x < p.ntiles) issue_loads(phys(seq + gridDim.x));
       // Fused rounds: apply the first fuse-1 weight matrices LDS tile to LDS tile (two tiles, used
       // alternately); the last one goes through the normal reduce-and-store below.
       float* tile_a = lds;
@@ -562,7 +565,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
     }
     const int64_t next = seq + gridDim.x;
     BF_MARK(3);
-    reduce_and_store(tile, phys(next), next < p.ntiles);
+    reduce_and_store(tile, phys(next), !MULTI && next < p.ntiles);
     BF_MARK(4);
     __syncthreads();
     BF_MARK(5);
@@ -1271,10 +1274,10 @@ int ilog2(int64_t v) { int l = 0; while ((int64_t{1} << (l + 1)) <= v) ++l; retu
 // Choose the tile: the widest power-of-two C in [64, 1024] whose n x C fp32 tile fits the LDS share
 // of one of `wgs` workgroups per CU (two 1024-thread workgroups per CU when possible, so one can
 // stream while the other reduces), narrowed while the launch would leave workgroup slots idle.
-int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s) {
+int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_wgs = 2) {
   const size_t lds_cu = di.lds_per_cu ? di.lds_per_cu : 65536;
   const size_t lds_blk = di.lds_per_block_optin ? di.lds_per_block_optin : lds_cu;
-  int wgs = g_tune_wgs > 0 ? g_tune_wgs : 2;
+  int wgs = g_tune_wgs > 0 ? g_tune_wgs : max_wgs;
   int log_c = -1;
   if (g_tune_tile > 0) {
     const int lc = ilog2(g_tune_tile);
@@ -1491,7 +1494,8 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     }
   }
   Shape s;
-  rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(fuse > 1 ? 2 * t->n : t->n, tp.d, di, &s);
+  // (the fused kernel needs more than 64 registers, so one workgroup per CU is all that runs)
+  rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(fuse > 1 ? 2 * t->n : t->n, tp.d, di, &s, fuse > 1 ? 1 : 2);
   if (fuse > 1 && rc != BF_OK) return rc;   // fused rounds exist only as the two-tile LDS kernel
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
     // Too many agents for an LDS tile: row gather through the caches, out of place only.
@@ -1563,6 +1567,8 @@ int bf_set_tuning(int32_t knob, int32_t value) {
 int bf_topology_destroy(bf_topology_t* t) {
   if (!t) return BF_OK;
   int rc = BF_OK;
+  for (auto& kv : t->two_level)
+    if (bf_topology_destroy(kv.second) != BF_OK) rc = BF_ERR_HIP;
   for (auto& c : t->dev) {
     if (c.blob && hipFree(c.blob) != hipSuccess) rc = BF_ERR_HIP;
     if (c.dense_t && hipFree(c.dense_t) != hipSuccess) rc = BF_ERR_HIP;
@@ -1605,6 +1611,52 @@ int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t 
   tp.d = d; tp.ld = ld;
   tp.fuse = count;
   return run_tile(const_cast<bf_topology_t*>(t), round0, OP_MIX, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, int32_t round, int32_t local_size,
+                                       const void* X_in, void* X_out, int64_t d, int64_t ld, bf_dtype_t dt,
+                                       void* hip_stream) {
+  if (!machine_topology || !X_in || !X_out) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  if (local_size < 1 || static_cast<int64_t>(machine_topology->n) * local_size > (1 << 20)) return BF_ERR_SIZE;
+  const int32_t n = machine_topology->n * local_size;
+  MatArgs ma;
+  int rc = check_matrix_shape(n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
+  if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  bf_topology_t* mt = const_cast<bf_topology_t*>(machine_topology);
+  bf_topology_t* two = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(mt->mu);
+    auto it = mt->two_level.find(local_size);
+    if (it == mt->two_level.end()) {
+      rc = bf::make_two_level(*mt, local_size, &two);
+      if (rc != BF_OK) return rc;
+      mt->two_level[local_size] = two;
+    } else {
+      two = it->second;
+    }
+  }
+  const int32_t r3 = static_cast<int32_t>((static_cast<int64_t>(round) % static_cast<int64_t>(mt->rounds.size())) * 3);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  TileParams tp{};
+  tp.x_in = static_cast<const char*>(X_in);
+  tp.x_out = static_cast<char*>(X_out);
+  tp.d = d; tp.ld = ld;
+  tp.fuse = 3;
+  rc = run_tile(two, r3, OP_MIX, false, tp, dt, st);
+  if (rc != BF_ERR_UNSUPPORTED) return rc;
+  // Too many agents for two LDS tiles: the three stages as three passes.  The first may write
+  // X_out, the other two update it in place (every row of X_out is overwritten in the end, so the
+  // zeros the first two stages leave in rows M and up are never seen).
+  tp.fuse = 1;
+  rc = run_tile(two, r3, OP_MIX, false, tp, dt, st);
+  if (rc != BF_OK) return rc;
+  tp.x_in = tp.x_out;
+  rc = run_tile(two, r3 + 1, OP_MIX, false, tp, dt, st);
+  if (rc != BF_OK) return rc;
+  return run_tile(two, r3 + 2, OP_MIX, false, tp, dt, st);
 }
 
 int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,

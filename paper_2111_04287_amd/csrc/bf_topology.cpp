@@ -273,6 +273,49 @@ void build_chain_plan(Round& r, int32_t n) {
   r.chain = std::move(steps);
 }
 
+int make_two_level(const bf_topology& machine, int32_t local_size, bf_topology** out) {
+  const int32_t M = machine.n, L = local_size;
+  if (L < 1 || static_cast<int64_t>(M) * L > (1 << 20)) return BF_ERR_SIZE;
+  const int32_t n = M * L;
+  auto* t = new (std::nothrow) bf_topology;
+  if (!t) return BF_ERR_NOMEM;
+  t->n = n;
+  t->kind = machine.kind;
+  t->accepted_seed = machine.accepted_seed;
+  for (const Round& mr : machine.rounds) {
+    Round avg, mix, copy;
+    avg.rowptr.assign(1, 0);
+    mix.rowptr.assign(1, 0);
+    copy.rowptr.assign(1, 0);
+    const float inv = 1.0f / static_cast<float>(L);
+    // The machine values live in rows 0 .. M-1 between the stages (row a for machine a), so the
+    // rows that carry work are contiguous; the last stage hands row i / L to agent i.
+    for (int32_t i = 0; i < n; ++i) {
+      if (i < M) {
+        const int32_t a = i;
+        for (int32_t l = 0; l < L; ++l) { avg.col.push_back(a * L + l); avg.wgt.push_back(inv); }
+        for (int64_t q = mr.rowptr[a]; q < mr.rowptr[a + 1]; ++q) {
+          mix.col.push_back(mr.col[q]);
+          mix.wgt.push_back(mr.wgt[q]);
+        }
+      }
+      copy.col.push_back(i / L);                     // machine_rank = rank // local_size
+      copy.wgt.push_back(1.0f);
+      avg.rowptr.push_back(static_cast<int64_t>(avg.col.size()));
+      mix.rowptr.push_back(static_cast<int64_t>(mix.col.size()));
+      copy.rowptr.push_back(static_cast<int64_t>(copy.col.size()));
+    }
+    for (Round* r : {&avg, &mix, &copy}) {
+      const int st = finalize_round(*r, n);
+      if (st != BF_OK) { delete t; return st; }
+      r->chain.clear();                              // these rounds only run inside the fused kernel
+      t->rounds.push_back(std::move(*r));
+    }
+  }
+  *out = t;
+  return BF_OK;
+}
+
 void dense_transposed(const Round& r, int32_t n, int32_t n_pad, float* out) {
   std::fill(out, out + static_cast<size_t>(n_pad) * n_pad, 0.0f);
   for (int32_t i = 0; i < n; ++i)

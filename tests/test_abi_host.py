@@ -246,6 +246,13 @@ def test_compute_calls_validate_before_touching_the_device():
     assert na(h, 0, A, B, 0, 64, bf.BF_F32, None) == bf.BF_OK                  # empty: nothing to launch
     assert na(h, 0, A, A, 0, 64, bf.BF_F32, None) == bf.BF_OK
     assert L.bf_dense_mix(h, 0, A, B, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_UNSUPPORTED
+    hn = L.bf_hierarchical_neighbor_allreduce
+    assert hn(h, 0, 0, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE       # local_size < 1
+    assert hn(h, 0, 1 << 19, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert hn(None, 0, 2, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert hn(h, -1, 2, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ROUND
+    assert hn(h, 0, 2, A, A + 256, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert hn(h, 0, 2, A, B, 0, 64, bf.BF_F32, None) == bf.BF_OK
     nm = L.bf_neighbor_allreduce_multi
     assert nm(h, 0, 0, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE       # count out of [1, 8]
     assert nm(h, 0, 9, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE

@@ -795,3 +795,34 @@ def test_fused_rounds_reject_what_does_not_fit():
     with pytest.raises(bf.BfError) as e:
         bf.bf_neighbor_allreduce_multi(t, 0, 2, X, empty_like_rows(X))
     assert e.value.code == bf.BF_ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------ two-level (hierarchical) averaging
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("name,make", TOPOS)
+@pytest.mark.parametrize("M,L,d", [(4, 4, 1024), (8, 8, 4096 + 136), (16, 2, 3004), (5, 3, 130), (1, 7, 64), (32, 8, 2048 + 8),
+                                   (40, 8, 520), (80, 8, 264)])
+def test_hierarchical_neighbor_allreduce_matches_oracle(name, make, M, L, d, dtype):
+    if name == "push" and M < 2:
+        pytest.skip("a random directed graph needs two machines")
+    t = make(M)
+    X = rows(M * L, d, 4000 + M + L, dtype=dtype)
+    for rnd in range(min(2, bf.bf_topology_rounds(t))):
+        ref = O.hierarchical_neighbor_allreduce(host(X), lib_W(t, rnd), L)
+        out = bf.bf_hierarchical_neighbor_allreduce(t, rnd, L, X, empty_like_rows(X))
+        assert_close(out, ref, TOL32 if dtype == torch.float32 else TOL16, "%s M=%d L=%d round %d" % (name, M, L, rnd))
+        inplace = empty_like_rows(X).copy_(X)
+        bf.bf_hierarchical_neighbor_allreduce(t, rnd, L, inplace, inplace)
+        assert torch.equal(inplace, out)
+        # agents of one machine hold the same bits
+        o3 = out.reshape(M, L, d)
+        assert torch.equal(o3, o3[:, :1].expand(M, L, d))
+
+
+def test_hierarchical_checks_the_row_count():
+    t = bf.bf_topology_create(bf.BF_RING, 4)
+    X = rows(12, 64, 1)
+    with pytest.raises(ValueError):
+        bf.bf_hierarchical_neighbor_allreduce(t, 0, 2, X, empty_like_rows(X))
+    with pytest.raises(ValueError):
+        bf.bf_neighbor_allreduce(t, 0, X, empty_like_rows(X))

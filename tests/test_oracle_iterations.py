@@ -424,3 +424,38 @@ def test_gradient_tracking_step_against_dense_formulas():
     np.testing.assert_allclose(Xn, (D @ (U - 0.3 * Y)) / (D @ v)[:, None], atol=1e-13)
     np.testing.assert_allclose(Gn, Xn @ Q + 1.0, atol=1e-13)
     np.testing.assert_allclose(Yn, D @ (Y + Gn - Gp), atol=1e-13)
+
+
+# ------------------------------------------------------------------ two-level (hierarchical) averaging
+def test_hierarchical_equals_kronecker_product_operator():
+    # stages 1-3 compose to the n x n matrix kron(W_machine, 11^T / L): a dense product by a library
+    # routine, independent of the oracle's staged loops
+    rng = np.random.default_rng(21)
+    for M, L, topo in [(4, 3, T.ring(4)), (8, 2, T.static_exponential(8)), (5, 4, T.random_directed_push(5, 2, 7)[0])]:
+        X = rng.standard_normal((M * L, 6))
+        Wd = T.to_dense(topo)
+        ref = np.kron(Wd, np.full((L, L), 1.0 / L)) @ X
+        got = O.hierarchical_neighbor_allreduce(X, topo, L)
+        np.testing.assert_allclose(got, ref, rtol=0, atol=1e-14)
+
+
+def test_hierarchical_special_cases():
+    rng = np.random.default_rng(22)
+    X = rng.standard_normal((12, 5))
+    ring = T.ring(12)
+    # one agent per machine: nothing but the flat neighbor average
+    np.testing.assert_allclose(O.hierarchical_neighbor_allreduce(X, ring, 1), O.mix(X, ring), atol=1e-15)
+    # one machine holding everybody, W = [1]: the global average
+    one = {0: [(0, 1.0)]}
+    np.testing.assert_allclose(O.hierarchical_neighbor_allreduce(X, one, 12), np.tile(X.mean(0), (12, 1)), atol=1e-15)
+    # agents of a machine end up equal; a doubly stochastic machine matrix keeps the global mean
+    out = O.hierarchical_neighbor_allreduce(X, T.ring(4), 3)
+    for a in range(4):
+        assert np.ptp(out[3 * a:3 * a + 3], axis=0).max() == 0.0
+    np.testing.assert_allclose(out.mean(0), X.mean(0), atol=1e-15)
+    # worked example by hand: 2 machines x 2 agents, W = [[3/4, 1/4], [1/4, 3/4]], scalars 0, 2, 4, 10
+    W2 = {0: [(0, 0.75), (1, 0.25)], 1: [(0, 0.25), (1, 0.75)]}
+    got = O.hierarchical_neighbor_allreduce(np.array([[0.0], [2.0], [4.0], [10.0]]), W2, 2)
+    np.testing.assert_allclose(got[:, 0], [2.5, 2.5, 5.5, 5.5], atol=1e-15)
+    with pytest.raises(ValueError):
+        O.hierarchical_neighbor_allreduce(X, ring, 5)
