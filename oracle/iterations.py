@@ -217,3 +217,98 @@ def hierarchical_neighbor_allreduce(X, W_machine, local_size):
     for i in range(n):
         out[i, :] = machine_out[i // L, :]
     return out
+
+
+# --------------------------------------------------------------------------------------------------
+# Window (one-sided) primitives, section "Asynchronous decentralized communication".  Agent i owns a
+# window with one slot per in-neighbor, in the order of its in-neighbor list with the self entry
+# left out.  ``Win`` is the (E, d) matrix of all slots, agent 0's slots first; ``win_p`` the (E,)
+# vector of the matching slots of the push-sum scalar p.  ``active`` says which agents execute the
+# call (an agent that is not active does nothing, which is how the lack of a common clock is
+# simulated on one device); None means everybody.
+
+def window_slots(W):
+    """(slot_ptr, slot_src, slot_w, self_w): agent i's slots are slot_ptr[i] .. slot_ptr[i+1]-1,
+    slot e receives from agent slot_src[e] with weight slot_w[e] = w_{i,src}; self_w[i] = w_ii
+    (zero when the list has no self entry)."""
+    n = len(W)
+    slot_ptr, slot_src, slot_w, self_w = [0], [], [], [0.0] * n
+    for i in range(n):
+        for j, w in W[i]:
+            if j == i:
+                self_w[i] = w
+            else:
+                slot_src.append(j)
+                slot_w.append(w)
+        slot_ptr.append(len(slot_src))
+    return slot_ptr, slot_src, slot_w, self_w
+
+
+def _is_active(active, j):
+    return True if active is None else bool(active[j])
+
+
+def win_put(X, Win, W, active=None):
+    """neighbor_win_put without weights: every active agent j overwrites its slot in the window of
+    each of its out-neighbors with x_j.  Returns Win'."""
+    X = _f64(X)
+    Win = _f64(Win).copy()
+    slot_ptr, slot_src, _, _ = window_slots(W)
+    for e, j in enumerate(slot_src):
+        if _is_active(active, j):
+            Win[e, :] = X[j, :]
+    return Win
+
+
+def win_accumulate(X, p, Win, win_p, W, active=None):
+    """neighbor_win_accumulate in the push-sum use of the section "Asynchronous push-style partial
+    averaging": every active agent j adds w_ij x_j (and w_ij p_j) to its slot at each out-neighbor
+    i, then keeps w_jj x_j (and w_jj p_j) for itself.  Returns (X', p', Win', win_p')."""
+    X = _f64(X).copy()
+    p = _f64(p).copy()
+    Win = _f64(Win).copy()
+    win_p = _f64(win_p).copy()
+    slot_ptr, slot_src, slot_w, self_w = window_slots(W)
+    for e, j in enumerate(slot_src):
+        if _is_active(active, j):
+            Win[e, :] += slot_w[e] * X[j, :]
+            win_p[e] += slot_w[e] * p[j]
+    for j in range(X.shape[0]):
+        if _is_active(active, j):
+            X[j, :] *= self_w[j]
+            p[j] *= self_w[j]
+    return X, p, Win, win_p
+
+
+def win_update_then_collect(X, p, Win, win_p, W, active=None):
+    """win_update_then_collect: every active agent i adds all its slots to its own tensor and
+    resets them to zero, as one atomic step (so that the sum of p over tensors and windows never
+    changes).  Returns (X', p', Win', win_p')."""
+    X = _f64(X).copy()
+    p = _f64(p).copy()
+    Win = _f64(Win).copy()
+    win_p = _f64(win_p).copy()
+    slot_ptr, _, _, _ = window_slots(W)
+    for i in range(X.shape[0]):
+        if _is_active(active, i):
+            for e in range(slot_ptr[i], slot_ptr[i + 1]):
+                X[i, :] += Win[e, :]
+                p[i] += win_p[e]
+                Win[e, :] = 0.0
+                win_p[e] = 0.0
+    return X, p, Win, win_p
+
+
+def win_update(X, Win, W, active=None):
+    """win_update with the topology's weights: every active agent i returns
+    w_ii x_i + sum_j w_ij (slot of j); the window keeps its contents.  Returns X'."""
+    X = _f64(X).copy()
+    Win = _f64(Win)
+    slot_ptr, _, slot_w, self_w = window_slots(W)
+    for i in range(X.shape[0]):
+        if _is_active(active, i):
+            acc = self_w[i] * X[i, :]
+            for e in range(slot_ptr[i], slot_ptr[i + 1]):
+                acc = acc + slot_w[e] * Win[e, :]
+            X[i, :] = acc
+    return X

@@ -459,3 +459,74 @@ def test_hierarchical_special_cases():
     np.testing.assert_allclose(got[:, 0], [2.5, 2.5, 5.5, 5.5], atol=1e-15)
     with pytest.raises(ValueError):
         O.hierarchical_neighbor_allreduce(X, ring, 5)
+
+
+# ------------------------------------------------------------------ window primitives
+def _push_graph(n, k, seed):
+    return T.random_directed_push(n, k, seed)[0]
+
+
+def test_window_all_active_accumulate_then_collect_is_one_pushsum_round():
+    rng = np.random.default_rng(31)
+    W = _push_graph(9, 3, 5)
+    X = rng.standard_normal((9, 4))
+    p = np.ones(9)
+    E = O.window_slots(W)[0][-1]
+    X1, p1, Win, wp = O.win_accumulate(X, p, np.zeros((E, 4)), np.zeros(E), W)
+    X2, p2, Win2, wp2 = O.win_update_then_collect(X1, p1, Win, wp, W)
+    Xs, ps, _ = O.pushsum_step(X, p, W)
+    np.testing.assert_allclose(X2, Xs, atol=1e-14)
+    np.testing.assert_allclose(p2, ps, atol=1e-14)
+    assert np.abs(Win2).max() == 0.0 and np.abs(wp2).max() == 0.0
+
+
+def test_window_put_then_update_all_active_is_one_mix_round():
+    rng = np.random.default_rng(32)
+    W = T.static_exponential(8)
+    X = rng.standard_normal((8, 3))
+    E = O.window_slots(W)[0][-1]
+    Win = O.win_put(X, np.full((E, 3), 99.0), W)             # stale contents are overwritten
+    np.testing.assert_allclose(O.win_update(X, Win, W), O.mix(X, W), atol=1e-14)
+
+
+def test_window_hand_worked_two_agents_with_a_late_receiver():
+    # W = [[1/2, 1/3], [1/2, 2/3]] (columns sum to one); x = (6, 12), p = (1, 1).
+    W = {0: [(0, 0.5), (1, 1.0 / 3.0)], 1: [(0, 0.5), (1, 2.0 / 3.0)]}
+    X = np.array([[6.0], [12.0]])
+    p = np.ones(2)
+    Win, wp = np.zeros((2, 1)), np.zeros(2)
+    # both send: slot of agent 0 (from 1) holds 4, slot of agent 1 (from 0) holds 3
+    X, p, Win, wp = O.win_accumulate(X, p, Win, wp, W)
+    np.testing.assert_allclose(X[:, 0], [3.0, 8.0]); np.testing.assert_allclose(Win[:, 0], [4.0, 3.0])
+    np.testing.assert_allclose(p, [0.5, 2.0 / 3.0]); np.testing.assert_allclose(wp, [1.0 / 3.0, 0.5])
+    # only agent 0 collects; agent 1 is late and its slot keeps waiting
+    X, p, Win, wp = O.win_update_then_collect(X, p, Win, wp, W, active=[1, 0])
+    np.testing.assert_allclose(X[:, 0], [7.0, 8.0]); np.testing.assert_allclose(Win[:, 0], [0.0, 3.0])
+    np.testing.assert_allclose(p, [5.0 / 6.0, 2.0 / 3.0]); np.testing.assert_allclose(wp, [0.0, 0.5])
+    # agent 0 sends again before agent 1 has collected: the slot adds up (3 + 3.5)
+    X, p, Win, wp = O.win_accumulate(X, p, Win, wp, W, active=[1, 0])
+    np.testing.assert_allclose(X[:, 0], [3.5, 8.0]); np.testing.assert_allclose(Win[:, 0], [0.0, 6.5])
+    X, p, Win, wp = O.win_update_then_collect(X, p, Win, wp, W, active=[0, 1])
+    np.testing.assert_allclose(X[:, 0], [3.5, 14.5])
+    assert abs(X.sum() + Win.sum() - 18.0) < 1e-14 and abs(p.sum() + wp.sum() - 2.0) < 1e-14
+
+
+def test_window_mass_is_conserved_and_ratio_converges_under_random_activity():
+    rng = np.random.default_rng(33)
+    n, d = 12, 3
+    W = _push_graph(n, 3, 11)
+    X = rng.standard_normal((n, d)) * 3 + 1
+    mean = X.mean(0)
+    total = X.sum(0)
+    p = np.ones(n)
+    E = O.window_slots(W)[0][-1]
+    Win, wp = np.zeros((E, d)), np.zeros(E)
+    for k in range(400):
+        act = rng.random(n) < 0.6
+        X, p, Win, wp = O.win_accumulate(X, p, Win, wp, W, act)
+        act = rng.random(n) < 0.6
+        X, p, Win, wp = O.win_update_then_collect(X, p, Win, wp, W, act)
+        np.testing.assert_allclose(X.sum(0) + Win.sum(0), total, atol=1e-11)
+        assert abs(p.sum() + wp.sum() - n) < 1e-12
+    assert np.abs(X / p[:, None] - mean).max() < 1e-8
+    assert np.abs(X - mean).max() > 1e-3                     # x alone is biased
