@@ -138,6 +138,18 @@ int bf_topology_export_csr(const bf_topology_t* t, int32_t round, int64_t* rowpt
  * no such plan, negative on error. */
 int32_t bf_topology_chain_plan(const bf_topology_t* t, int32_t round, int32_t* steps);
 
+/* Window layout of a round (section "Asynchronous decentralized communication": every agent owns
+ * one slot per in-coming neighbor, in one contiguous chunk).  Slots are numbered over all agents,
+ * agent 0's first, within an agent in the order of its CSR row with the diagonal entry left out.
+ * bf_topology_window_slots returns their number E (or a negative status);
+ * bf_topology_export_window copies to caller-sized host arrays slot_rowptr[n+1] (agent i owns
+ * slots slot_rowptr[i] .. slot_rowptr[i+1]-1), slot_src[E] (the sender of each slot),
+ * slot_weight[E] (w_{i,src}) and self_weight[n] (w_ii, 0 without a diagonal entry); any may be
+ * NULL. */
+int64_t bf_topology_window_slots(const bf_topology_t* t, int32_t round);
+int bf_topology_export_window(const bf_topology_t* t, int32_t round, int64_t* slot_rowptr, int32_t* slot_src,
+                              float* slot_weight, float* self_weight);
+
 /* Partial averaging (eq. dsgd-2, eq. dgd-2; the neighbor_allreduce primitive):
  *   X_out[i,:] = sum_{(j,w) in row i of W^(round)} w * X_in[j,:].
  * Accumulation is fp32 in CSR order; BF_BF16 rounds the result to nearest-even on store. */
@@ -166,6 +178,34 @@ int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t 
 int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, int32_t round, int32_t local_size,
                                        const void* X_in, void* X_out, int64_t d, int64_t ld, bf_dtype_t dt,
                                        void* hip_stream);
+
+/* Window primitives (sections "Asynchronous decentralized communication" and "Asynchronous
+ * push-style partial averaging"), all agents simulated on one device.  X: n x d device matrix, row
+ * pitch ld.  Win: E x d device matrix with the same pitch, row e being slot e of the layout above
+ * (the caller allocates it and zeroes it once, as win_create does).  p: n device floats, win_p: E
+ * device floats, the push-sum scalar and its slots (both NULL to leave them out).  active: n
+ * device int32 flags, or NULL for everybody; an agent whose flag is 0 does nothing in that call,
+ * which is how agents that run at different speeds are simulated.  BF_F32 only
+ * (BF_ERR_UNSUPPORTED otherwise).  Calls on one stream execute one after the other, which gives
+ * the mutual exclusion and the atomic read-and-reset the paper asks for; calls on different
+ * streams that share X or Win race.  X, Win, p, win_p may not overlap (BF_ERR_ALIAS).  A topology
+ * without edges has E = 0 slots; Win and win_p may then be NULL.
+ *   bf_win_put:        every active j copies x_j into its slot at each out-neighbor (no weights).
+ *   bf_win_accumulate: every active j adds w_ij x_j (w_ij p_j) to its slot at each out-neighbor i,
+ *                      then keeps w_jj x_j (w_jj p_j).
+ *   bf_win_update:     every active i sets x_i = w_ii x_i + sum over its slots of w_ij * slot;
+ *                      the window is left as it is.
+ *   bf_win_update_then_collect: every active i adds its slots to x_i (p_i) and zeroes them.
+ * With W column stochastic, sum(p) + sum(win_p) stays n and sum(X) + sum(Win) stays what it was
+ * (up to fp32 rounding) whatever the activity pattern. */
+int bf_win_put(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
+               int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+int bf_win_accumulate(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,
+                      void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+int bf_win_update(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, const void* Win,
+                  int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+int bf_win_update_then_collect(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,
+                               void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
 /* Same product through the dense n x n form of W^(round) on the fp32 matrix cores (BF_F32 only;
  * n <= 256).  Intended for dense / fully connected W (periodic global averaging is W = 11^T/n) and

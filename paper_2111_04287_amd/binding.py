@@ -28,7 +28,8 @@ BF_W_ANY, BF_W_PULL, BF_W_PUSH, BF_W_STANDARD = 0, 1, 2, 3
 EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
-    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
+    "bf_topology_export_csr", "bf_topology_chain_plan", "bf_topology_window_slots", "bf_topology_export_window",
+    "bf_win_put", "bf_win_accumulate", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -83,6 +84,14 @@ def _load():
     L.bf_topology_export_csr.argtypes = [vp, i32, vp, vp, vp, C.POINTER(C.c_uint64)]
     L.bf_topology_chain_plan.argtypes = [vp, i32, vp]
     L.bf_neighbor_allreduce.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_topology_window_slots.argtypes = [vp, i32]
+    L.bf_topology_window_slots.restype = i64
+    L.bf_topology_export_window.argtypes = [vp, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int32),
+                                            C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    L.bf_win_put.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_win_update.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_win_accumulate.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_win_update_then_collect.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_neighbor_allreduce_multi.argtypes = [vp, i32, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_hierarchical_neighbor_allreduce.argtypes = [vp, i32, i32, vp, vp, i64, i64, C.c_int, vp]
     L.bf_dense_mix.argtypes = [vp, i32, vp, vp, i64, i64, C.c_int, vp]
@@ -288,6 +297,72 @@ def bf_hierarchical_neighbor_allreduce(machine_topology, rnd, local_size, X_in, 
                                                   _dtype_code(X_in), _stream(stream)),
            "bf_hierarchical_neighbor_allreduce")
     return X_out
+
+
+def bf_topology_window_slots(t, rnd=0):
+    e = lib.bf_topology_window_slots(t.handle, rnd)
+    if e < 0:
+        raise BfError(int(e), "bf_topology_window_slots")
+    return int(e)
+
+
+def bf_topology_export_window(t, rnd=0):
+    """(slot_rowptr int64[n+1], slot_src int32[E], slot_weight float32[E], self_weight float32[n])."""
+    n, E = t.n, bf_topology_window_slots(t, rnd)
+    rp = np.zeros(n + 1, dtype=np.int64)
+    src = np.zeros(max(E, 1), dtype=np.int32)
+    sw = np.zeros(max(E, 1), dtype=np.float32)
+    selfw = np.zeros(n, dtype=np.float32)
+    _check(lib.bf_topology_export_window(t.handle, rnd, _np_ptr(rp, C.c_int64), _np_ptr(src, C.c_int32),
+                                         _np_ptr(sw, C.c_float), _np_ptr(selfw, C.c_float)), "bf_topology_export_window")
+    return rp, src[:E], sw[:E], selfw
+
+
+def _win_args(t, rnd, active, X, Win, p, win_p):
+    import torch
+    ptr, n, d, ld = _mat(X, "X")
+    _rows(t, n)
+    E = bf_topology_window_slots(t, rnd)
+    if Win.dim() != 2 or Win.shape != (E, d) or Win.dtype != X.dtype or (E > 1 and Win.stride(0) != ld) or \
+            (d > 1 and Win.stride(1) != 1):
+        raise ValueError("Win must be a (slots, d) matrix with the dtype and row stride of X")
+    if active is not None and (active.dtype != torch.int32 or active.numel() != n or not active.is_contiguous()):
+        raise ValueError("active must be a contiguous int32 vector with one flag per agent")
+    if (p is None) != (win_p is None):
+        raise ValueError("p and win_p go together")
+    if p is not None:
+        _vec(p, n, "p")
+        _vec(win_p, E, "win_p")
+    return ptr, d, ld, None if active is None else active.data_ptr()
+
+
+def bf_win_put(t, rnd, X, Win, active=None, stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, None, None)
+    _check(lib.bf_win_put(t.handle, rnd, act, ptr, Win.data_ptr(), d, ld, _dtype_code(X), _stream(stream)), "bf_win_put")
+    return Win
+
+
+def bf_win_accumulate(t, rnd, X, p, Win, win_p, active=None, stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, p, win_p)
+    _check(lib.bf_win_accumulate(t.handle, rnd, act, ptr, None if p is None else p.data_ptr(), Win.data_ptr(),
+                                 None if win_p is None else win_p.data_ptr(), d, ld, _dtype_code(X), _stream(stream)),
+           "bf_win_accumulate")
+    return X, p, Win, win_p
+
+
+def bf_win_update(t, rnd, X, Win, active=None, stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, None, None)
+    _check(lib.bf_win_update(t.handle, rnd, act, ptr, Win.data_ptr(), d, ld, _dtype_code(X), _stream(stream)),
+           "bf_win_update")
+    return X
+
+
+def bf_win_update_then_collect(t, rnd, X, p, Win, win_p, active=None, stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, p, win_p)
+    _check(lib.bf_win_update_then_collect(t.handle, rnd, act, ptr, None if p is None else p.data_ptr(), Win.data_ptr(),
+                                          None if win_p is None else win_p.data_ptr(), d, ld, _dtype_code(X),
+                                          _stream(stream)), "bf_win_update_then_collect")
+    return X, p, Win, win_p
 
 
 def bf_dense_mix(t, rnd, X_in, X_out, stream=None):

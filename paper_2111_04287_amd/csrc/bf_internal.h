@@ -35,6 +35,18 @@ struct Round {
   std::vector<ChainStep> chain;  // n steps when the off-diagonal graph is a union of paths and cycles
 };
 
+// Window layout of a round (one slot per off-diagonal entry, agent 0's slots first, in CSR order)
+// seen from both ends: receivers walk in_ptr, senders walk out_ptr.
+struct WindowPlan {
+  std::vector<int32_t> in_ptr;    // n+1: agent i owns slots in_ptr[i] .. in_ptr[i+1]-1
+  std::vector<int32_t> slot_src;  // E: sender of each slot
+  std::vector<float>   slot_w;    // E: w_{i,src}
+  std::vector<float>   self_w;    // n: w_ii, 0 when row i has no diagonal entry
+  std::vector<int32_t> out_ptr;   // n+1: sender j writes the slots out_slot[out_ptr[j] .. out_ptr[j+1]-1]
+  std::vector<int32_t> out_slot;  // E, ascending within a sender
+  std::vector<float>   out_w;     // E: weight of that slot
+};
+
 // Device-resident copy of all rounds, built on first use on a device.
 struct DeviceCopy {
   int      device = -1;
@@ -45,6 +57,11 @@ struct DeviceCopy {
   std::vector<size_t> chain_off;         // byte offset of the round's ChainStep[n], or SIZE_MAX
   float*   dense_t = nullptr;            // [round][k][i] = w_ik, n_pad x n_pad, lazily built
   int32_t  n_pad = 0;
+  // Window plans, one allocation per round, built on first use: int32 in_ptr[n+1] | f32 slot_w[E] |
+  // f32 self_w[n] | int32 out_ptr[n+1] | {int32 slot, f32 w} out_ent[E], each part 16-byte aligned.
+  std::vector<char*>  win_blob;
+  std::vector<size_t> win_off;           // 5 byte offsets per round
+  std::vector<int32_t> win_slots;        // E per round
 };
 
 }  // namespace bf
@@ -69,6 +86,7 @@ void build_chain_plan(Round& r, int32_t n);          // fills r.chain when the s
 // Three rounds over M*local_size agents per round of the M-machine topology: machine a's local
 // average into row a, the machine-level round among rows 0..M-1, row i/local_size back to agent i.
 int  make_two_level(const bf_topology& machine, int32_t local_size, bf_topology** out);
+void build_window_plan(const Round& r, int32_t n, WindowPlan* out);
 
 }  // namespace bf
 

@@ -898,6 +898,141 @@ __global__ __launch_bounds__(1024) void bf_pushsum_w_kernel(const int32_t* rowpt
 }
 
 // ---------------------------------------------------------------------------------------------
+// Window primitives (section "Asynchronous decentralized communication").  The window of agent i
+// is one row per in-neighbor; all windows form one E x d matrix with the row pitch of X.  A
+// workgroup takes one agent and one 4096-column chunk of its row (four 16-byte vectors per thread,
+// so the loads of an edge's slot are all in flight together) and walks the agent's out-edges
+// (sender side: put, accumulate) or its own slots (receiver side: update, update_then_collect).
+// Every slot has exactly one sender and one owner, so within a call no two workgroups touch the
+// same bytes; successive calls on one stream give the atomicity the paper asks of
+// update_then_collect.  Agents whose `active` entry is zero do nothing.
+struct WinParams {
+  float* x;
+  float* win;
+  const int32_t* active;     // n flags, or null: everybody
+  const int32_t* in_ptr;
+  const float* slot_w;
+  const float* self_w;
+  const int32_t* out_ptr;
+  const u32x2* out_ent;      // {slot, weight bits}
+  int64_t d, ld;
+  int32_t n, chunks;
+};
+
+enum { WIN_PUT = 0, WIN_ACCUMULATE = 1, WIN_COLLECT = 2, WIN_AVERAGE = 3 };
+
+template <int MODE>
+__global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
+  constexpr int U = 4;
+  const int tid = threadIdx.x;
+  const int64_t units = static_cast<int64_t>(p.n) * p.chunks;
+  for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
+    const int a = static_cast<int>(unit / p.chunks);
+    const int c = static_cast<int>(unit - static_cast<int64_t>(a) * p.chunks);
+    if (p.active && p.active[a] == 0) continue;
+    int64_t col[U];
+    int valid[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      col[u] = (static_cast<int64_t>(c) * U + u) * 1024 + tid * 4;
+      const int64_t rem = p.d - col[u];
+      valid[u] = rem >= 4 ? 4 : (rem > 0 ? static_cast<int>(rem) : 0);
+    }
+    auto load = [&](const float* row, int u) -> f32x4 {
+      // a vector that starts inside the row may end in the row's padding: rows are 16-byte multiples
+      return valid[u] ? *reinterpret_cast<const f32x4*>(row + col[u]) : f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto store = [&](float* row, int u, f32x4 v) {
+      if (valid[u] == 4) { *reinterpret_cast<f32x4*>(row + col[u]) = v; return; }
+      const float e[4] = {v.x, v.y, v.z, v.w};
+      for (int k = 0; k < valid[u]; ++k) row[col[u] + k] = e[k];      // never the padding
+    };
+    float* xrow = p.x + static_cast<int64_t>(a) * p.ld;
+    f32x4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) x[u] = load(xrow, u);
+    if constexpr (MODE == WIN_PUT || MODE == WIN_ACCUMULATE) {
+      for (int q = p.out_ptr[a]; q < p.out_ptr[a + 1]; ++q) {
+        const u32x2 en = p.out_ent[q];
+        float* wrow = p.win + static_cast<int64_t>(en.x) * p.ld;
+        if constexpr (MODE == WIN_PUT) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) store(wrow, u, x[u]);
+        } else {
+          const float w = __uint_as_float(en.y);
+          f32x4 v[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) v[u] = load(wrow, u);
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            v[u].x = fmaf(w, x[u].x, v[u].x); v[u].y = fmaf(w, x[u].y, v[u].y);
+            v[u].z = fmaf(w, x[u].z, v[u].z); v[u].w = fmaf(w, x[u].w, v[u].w);
+            store(wrow, u, v[u]);
+          }
+        }
+      }
+      if constexpr (MODE == WIN_ACCUMULATE) {
+        const float sw = p.self_w[a];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          x[u].x *= sw; x[u].y *= sw; x[u].z *= sw; x[u].w *= sw;
+          store(xrow, u, x[u]);
+        }
+      }
+    } else {
+      if constexpr (MODE == WIN_AVERAGE) {
+        const float sw = p.self_w[a];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { x[u].x *= sw; x[u].y *= sw; x[u].z *= sw; x[u].w *= sw; }
+      }
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      for (int e = p.in_ptr[a]; e < p.in_ptr[a + 1]; ++e) {
+        float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
+        f32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = load(wrow, u);
+        if constexpr (MODE == WIN_COLLECT) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            x[u].x += v[u].x; x[u].y += v[u].y; x[u].z += v[u].z; x[u].w += v[u].w;
+            store(wrow, u, zero);
+          }
+        } else {
+          const float w = p.slot_w[e];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            x[u].x = fmaf(w, v[u].x, x[u].x); x[u].y = fmaf(w, v[u].y, x[u].y);
+            x[u].z = fmaf(w, v[u].z, x[u].z); x[u].w = fmaf(w, v[u].w, x[u].w);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) store(xrow, u, x[u]);
+    }
+  }
+}
+
+// The push-sum scalars of the same two calls: p_j and one scalar per slot.  One workgroup.
+template <int MODE>
+__global__ __launch_bounds__(1024) void bf_win_p_kernel(const WinParams p, float* pv, float* win_p) {
+  for (int a = threadIdx.x; a < p.n; a += blockDim.x) {
+    if (p.active && p.active[a] == 0) continue;
+    if constexpr (MODE == WIN_ACCUMULATE) {
+      const float pa = pv[a];
+      for (int q = p.out_ptr[a]; q < p.out_ptr[a + 1]; ++q) {
+        const u32x2 en = p.out_ent[q];
+        win_p[en.x] = fmaf(__uint_as_float(en.y), pa, win_p[en.x]);
+      }
+      pv[a] = pa * p.self_w[a];
+    } else {
+      float pa = pv[a];
+      for (int e = p.in_ptr[a]; e < p.in_ptr[a + 1]; ++e) { pa += win_p[e]; win_p[e] = 0.0f; }
+      pv[a] = pa;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Dense W on the fp32 matrix cores: X_out tile (n_pad x 128) = W (n_pad x n_pad) * X tile.
 // v_mfma_f32_32x32x2_f32 operand layout (wave64): A lane l holds A[l%32][l/32], B lane l holds
 // B[l/32][l%32], D register v of lane l holds D[8*(v/4) + 4*(l/32) + v%4][l%32].
@@ -1537,6 +1672,111 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
                       : launch_tile_op<DT_BF16>(op, with_y, tp, s, grid, st);
 }
 
+// Device copy of a round's window plan, built on first use.
+int get_window_plan(bf_topology_t* t, size_t k, bf::DeviceCopy* dc, WinParams* wp) {
+  std::lock_guard<std::mutex> lk(t->mu);
+  const size_t R = t->rounds.size();
+  if (dc->win_blob.empty()) { dc->win_blob.assign(R, nullptr); dc->win_off.assign(R * 5, 0); dc->win_slots.assign(R, 0); }
+  if (!dc->win_blob[k]) {
+    bf::WindowPlan w;
+    bf::build_window_plan(t->rounds[k], t->n, &w);
+    const size_t E = w.slot_src.size();
+    auto pad = [](size_t b) { return (b + 15) / 16 * 16; };
+    size_t off[5];
+    size_t bytes = 0;
+    off[0] = bytes; bytes += pad((static_cast<size_t>(t->n) + 1) * 4);
+    off[1] = bytes; bytes += pad(E * 4);
+    off[2] = bytes; bytes += pad(static_cast<size_t>(t->n) * 4);
+    off[3] = bytes; bytes += pad((static_cast<size_t>(t->n) + 1) * 4);
+    off[4] = bytes; bytes += pad(E * 8);
+    std::vector<char> host(bytes + 16, 0);
+    std::memcpy(host.data() + off[0], w.in_ptr.data(), w.in_ptr.size() * 4);
+    if (E) std::memcpy(host.data() + off[1], w.slot_w.data(), E * 4);
+    std::memcpy(host.data() + off[2], w.self_w.data(), w.self_w.size() * 4);
+    std::memcpy(host.data() + off[3], w.out_ptr.data(), w.out_ptr.size() * 4);
+    uint32_t* oe = reinterpret_cast<uint32_t*>(host.data() + off[4]);
+    for (size_t q = 0; q < E; ++q) {
+      oe[2 * q] = static_cast<uint32_t>(w.out_slot[q]);
+      std::memcpy(&oe[2 * q + 1], &w.out_w[q], 4);
+    }
+    char* blob = nullptr;
+    BF_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&blob), host.size()));
+    hipError_t e = hipMemcpy(blob, host.data(), host.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(blob); g_last_hip_error = e; return BF_ERR_HIP; }
+    dc->win_blob[k] = blob;
+    for (int q = 0; q < 5; ++q) dc->win_off[k * 5 + q] = off[q];
+    dc->win_slots[k] = static_cast<int32_t>(E);
+  }
+  const char* b = dc->win_blob[k];
+  const size_t* off = &dc->win_off[k * 5];
+  wp->in_ptr = reinterpret_cast<const int32_t*>(b + off[0]);
+  wp->slot_w = reinterpret_cast<const float*>(b + off[1]);
+  wp->self_w = reinterpret_cast<const float*>(b + off[2]);
+  wp->out_ptr = reinterpret_cast<const int32_t*>(b + off[3]);
+  wp->out_ent = reinterpret_cast<const u32x2*>(b + off[4]);
+  return BF_OK;
+}
+
+// Shared body of the four window calls.
+int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* active, void* X, float* pv,
+               void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  if (!tc || !X) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  bf_topology_t* t = const_cast<bf_topology_t*>(tc);
+  const int64_t E = bf_topology_window_slots(t, round);
+  if (E < 0) return static_cast<int>(E);
+  // a topology without edges has no slots: Win and win_p may then be NULL
+  if (E > 0 && (!Win || (pv == nullptr) != (win_p == nullptr))) return BF_ERR_NULL;
+  MatArgs ma;
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  if (rc != BF_OK) return rc;
+  if (dt != BF_F32) return BF_ERR_UNSUPPORTED;      // slots accumulate: fp32 only
+  if (misaligned16(X) || misaligned16(Win)) return BF_ERR_ALIGN;
+  if ((active && (reinterpret_cast<uintptr_t>(active) & 3u)) || (pv && (reinterpret_cast<uintptr_t>(pv) & 3u)) ||
+      (win_p && (reinterpret_cast<uintptr_t>(win_p) & 3u)))
+    return BF_ERR_ALIGN;
+  const size_t win_bytes = E > 0 ? static_cast<size_t>(E - 1) * ld * 4 + static_cast<size_t>(d) * 4 : 0;
+  if (E > 0 && overlaps(X, ma.bytes, Win, win_bytes)) return BF_ERR_ALIAS;
+  if (pv && E > 0 && (overlaps(pv, static_cast<size_t>(t->n) * 4, X, ma.bytes) || overlaps(pv, static_cast<size_t>(t->n) * 4, Win, win_bytes) ||
+             overlaps(win_p, static_cast<size_t>(E) * 4, X, ma.bytes) || overlaps(win_p, static_cast<size_t>(E) * 4, Win, win_bytes) ||
+             overlaps(pv, static_cast<size_t>(t->n) * 4, win_p, static_cast<size_t>(E) * 4)))
+    return BF_ERR_ALIAS;
+  bf::DeviceCopy* dc = nullptr;
+  rc = get_device_copy(t, false, &dc);
+  if (rc != BF_OK) return rc;
+  DeviceInfo di;
+  rc = device_info(dc->device, &di);
+  if (rc != BF_OK) return rc;
+  WinParams wp{};
+  rc = get_window_plan(t, static_cast<size_t>(round) % t->rounds.size(), dc, &wp);
+  if (rc != BF_OK) return rc;
+  wp.x = static_cast<float*>(X);
+  wp.win = static_cast<float*>(Win);
+  wp.active = active;
+  wp.d = d; wp.ld = ld; wp.n = t->n;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (pv && (mode == WIN_ACCUMULATE || mode == WIN_COLLECT)) {
+    if (mode == WIN_ACCUMULATE) hipLaunchKernelGGL(bf_win_p_kernel<WIN_ACCUMULATE>, dim3(1), dim3(1024), 0, st, wp, pv, win_p);
+    else hipLaunchKernelGGL(bf_win_p_kernel<WIN_COLLECT>, dim3(1), dim3(1024), 0, st, wp, pv, win_p);
+    BF_HIP_TRY(hipGetLastError());
+  }
+  if (d == 0) return BF_OK;
+  const int64_t chunk_cols = 4 * 1024;
+  const int64_t chunks = (d + chunk_cols - 1) / chunk_cols;
+  if (chunks > INT32_MAX) return BF_ERR_SIZE;
+  wp.chunks = static_cast<int32_t>(chunks);
+  const int64_t units = chunks * t->n;
+  const int grid = static_cast<int>(std::min<int64_t>(units, static_cast<int64_t>(di.cus) * 8));
+  switch (mode) {
+    case WIN_PUT: hipLaunchKernelGGL(bf_win_kernel<WIN_PUT>, dim3(grid), dim3(256), 0, st, wp); break;
+    case WIN_ACCUMULATE: hipLaunchKernelGGL(bf_win_kernel<WIN_ACCUMULATE>, dim3(grid), dim3(256), 0, st, wp); break;
+    case WIN_COLLECT: hipLaunchKernelGGL(bf_win_kernel<WIN_COLLECT>, dim3(grid), dim3(256), 0, st, wp); break;
+    default: hipLaunchKernelGGL(bf_win_kernel<WIN_AVERAGE>, dim3(grid), dim3(256), 0, st, wp); break;
+  }
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1572,6 +1812,8 @@ int bf_topology_destroy(bf_topology_t* t) {
   for (auto& c : t->dev) {
     if (c.blob && hipFree(c.blob) != hipSuccess) rc = BF_ERR_HIP;
     if (c.dense_t && hipFree(c.dense_t) != hipSuccess) rc = BF_ERR_HIP;
+    for (char* wb : c.win_blob)
+      if (wb && hipFree(wb) != hipSuccess) rc = BF_ERR_HIP;
   }
   delete t;
   return rc;
@@ -1657,6 +1899,26 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
   rc = run_tile(two, r3 + 1, OP_MIX, false, tp, dt, st);
   if (rc != BF_OK) return rc;
   return run_tile(two, r3 + 2, OP_MIX, false, tp, dt, st);
+}
+
+int bf_win_put(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
+               int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  return win_common(WIN_PUT, t, round, active, const_cast<void*>(X), nullptr, Win, nullptr, d, ld, dt, hip_stream);
+}
+
+int bf_win_accumulate(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,
+                      void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  return win_common(WIN_ACCUMULATE, t, round, active, X, p, Win, win_p, d, ld, dt, hip_stream);
+}
+
+int bf_win_update(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, const void* Win,
+                  int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  return win_common(WIN_AVERAGE, t, round, active, X, nullptr, const_cast<void*>(Win), nullptr, d, ld, dt, hip_stream);
+}
+
+int bf_win_update_then_collect(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,
+                               void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  return win_common(WIN_COLLECT, t, round, active, X, p, Win, win_p, d, ld, dt, hip_stream);
 }
 
 int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,

@@ -316,6 +316,35 @@ int make_two_level(const bf_topology& machine, int32_t local_size, bf_topology**
   return BF_OK;
 }
 
+void build_window_plan(const Round& r, int32_t n, WindowPlan* out) {
+  WindowPlan& w = *out;
+  w = WindowPlan{};
+  w.in_ptr.assign(1, 0);
+  w.self_w.assign(n, 0.0f);
+  std::vector<int32_t> out_count(n, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    for (int64_t q = r.rowptr[i]; q < r.rowptr[i + 1]; ++q) {
+      if (r.col[q] == i) { w.self_w[i] = r.wgt[q]; continue; }
+      w.slot_src.push_back(r.col[q]);
+      w.slot_w.push_back(r.wgt[q]);
+      ++out_count[r.col[q]];
+    }
+    w.in_ptr.push_back(static_cast<int32_t>(w.slot_src.size()));
+  }
+  const size_t E = w.slot_src.size();
+  w.out_ptr.assign(n + 1, 0);
+  for (int32_t j = 0; j < n; ++j) w.out_ptr[j + 1] = w.out_ptr[j] + out_count[j];
+  w.out_slot.assign(E, 0);
+  w.out_w.assign(E, 0.0f);
+  std::vector<int32_t> fill(w.out_ptr.begin(), w.out_ptr.end() - 1);
+  for (size_t e = 0; e < E; ++e) {             // ascending e, so each sender's list is ascending
+    const int32_t j = w.slot_src[e];
+    w.out_slot[fill[j]] = static_cast<int32_t>(e);
+    w.out_w[fill[j]] = w.slot_w[e];
+    ++fill[j];
+  }
+}
+
 void dense_transposed(const Round& r, int32_t n, int32_t n_pad, float* out) {
   std::fill(out, out + static_cast<size_t>(n_pad) * n_pad, 0.0f);
   for (int32_t i = 0; i < n; ++i)
@@ -555,6 +584,31 @@ int bf_topology_export_csr(const bf_topology_t* t, int32_t round, int64_t* rowpt
   if (col) std::memcpy(col, r.col.data(), r.col.size() * sizeof(int32_t));
   if (wgt) std::memcpy(wgt, r.wgt.data(), r.wgt.size() * sizeof(float));
   if (accepted_seed) *accepted_seed = t->accepted_seed;
+  return BF_OK;
+}
+
+int64_t bf_topology_window_slots(const bf_topology_t* t, int32_t round) {
+  if (!t) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  const int k = slice_index(t, round);
+  const Round& r = t->rounds[k];
+  int64_t diag = 0;
+  for (int32_t i = 0; i < t->n; ++i)
+    for (int64_t q = r.rowptr[i]; q < r.rowptr[i + 1]; ++q) diag += r.col[q] == i;
+  return r.rowptr[t->n] - diag;
+}
+
+int bf_topology_export_window(const bf_topology_t* t, int32_t round, int64_t* slot_rowptr, int32_t* slot_src,
+                              float* slot_weight, float* self_weight) {
+  if (!t) return BF_ERR_NULL;
+  if (round < 0) return BF_ERR_ROUND;
+  const int k = slice_index(t, round);
+  bf::WindowPlan w;
+  bf::build_window_plan(t->rounds[k], t->n, &w);
+  if (slot_rowptr) for (int32_t i = 0; i <= t->n; ++i) slot_rowptr[i] = w.in_ptr[i];
+  if (slot_src) std::copy(w.slot_src.begin(), w.slot_src.end(), slot_src);
+  if (slot_weight) std::copy(w.slot_w.begin(), w.slot_w.end(), slot_weight);
+  if (self_weight) std::copy(w.self_w.begin(), w.self_w.end(), self_weight);
   return BF_OK;
 }
 

@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 
 import paper_2111_04287_amd as bf
+from oracle import iterations as O
 from oracle import topology as OT
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -246,6 +247,17 @@ def test_compute_calls_validate_before_touching_the_device():
     assert na(h, 0, A, B, 0, 64, bf.BF_F32, None) == bf.BF_OK                  # empty: nothing to launch
     assert na(h, 0, A, A, 0, 64, bf.BF_F32, None) == bf.BF_OK
     assert L.bf_dense_mix(h, 0, A, B, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_UNSUPPORTED
+    W1b, W2b = 0x60000000, 0x60001000
+    wa = L.bf_win_accumulate
+    assert wa(h, 0, None, A, None, B, None, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_UNSUPPORTED
+    assert wa(h, 0, None, A, W1b, B, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL        # p without win_p
+    assert wa(h, 0, None, A, None, A + 512, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS  # Win inside X
+    assert wa(h, 0, None, A, W1b, B, W1b + 8, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert wa(h, 0, A + 2, A, None, B, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIGN
+    assert wa(h, -1, None, A, None, B, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ROUND
+    assert L.bf_win_put(h, 0, None, None, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert L.bf_win_update(h, 0, None, A, B + 4, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIGN
+    assert L.bf_win_update_then_collect(h, 0, None, A, W1b, B, W2b, 62, 62, bf.BF_F32, None) == bf.BF_ERR_ALIGN
     hn = L.bf_hierarchical_neighbor_allreduce
     assert hn(h, 0, 0, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE       # local_size < 1
     assert hn(h, 0, 1 << 19, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE
@@ -382,3 +394,20 @@ def test_chain_plan_on_a_directed_path_and_a_matching():
     steps = bf.bf_topology_chain_plan(t, 0)
     X = np.random.default_rng(2).normal(size=(n, 3))
     np.testing.assert_allclose(_walk_chain_plan(steps, X), D.astype(np.float64) @ X, atol=1e-14)
+
+
+@pytest.mark.parametrize("kind,n,kw", [(bf.BF_RING, 7, {}), (bf.BF_EXP_STATIC, 16, {}), (bf.BF_EXP2_ONE_PEER, 8, {}),
+                                       (bf.BF_RANDOM_DIRECTED, 12, dict(out_degree=3, seed=9)), (bf.BF_RING, 1, {})])
+def test_window_layout_matches_the_oracle(kind, n, kw):
+    t = bf.bf_topology_create(kind, n, **kw)
+    for rnd in range(bf.bf_topology_rounds(t)):
+        rowptr, col, wgt, _ = bf.bf_topology_export_csr(t, rnd)
+        W = OT.from_csr(rowptr, col, wgt)
+        slot_ptr, slot_src, slot_w, self_w = O.window_slots(W)
+        rp, src, sw, selfw = bf.bf_topology_export_window(t, rnd)
+        assert bf.bf_topology_window_slots(t, rnd) == slot_ptr[-1]
+        assert list(rp) == slot_ptr and list(src) == slot_src
+        np.testing.assert_array_equal(sw, np.asarray(slot_w, dtype=np.float32))
+        np.testing.assert_array_equal(selfw, np.asarray(self_w, dtype=np.float32))
+    assert bf.lib.bf_topology_window_slots(None, 0) == bf.BF_ERR_NULL
+    assert bf.lib.bf_topology_window_slots(t.handle, -1) == bf.BF_ERR_ROUND

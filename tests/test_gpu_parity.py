@@ -826,3 +826,130 @@ def test_hierarchical_checks_the_row_count():
         bf.bf_hierarchical_neighbor_allreduce(t, 0, 2, X, empty_like_rows(X))
     with pytest.raises(ValueError):
         bf.bf_neighbor_allreduce(t, 0, X, empty_like_rows(X))
+
+
+# ------------------------------------------------------------------ window primitives
+def _window_state(t, n, d, seed, rnd=0):
+    E = bf.bf_topology_window_slots(t, rnd)
+    X = rows(n, d, seed, mean=1.0, std=2.0)
+    ld = X.stride(0) if n > 1 else workloads.padded_ld(d, 4)
+    Win = workloads.normal_rows(max(E, 1), d, seed + 1, DEV, ld=ld)[:E]
+    p = torch.rand(n, device=DEV, generator=torch.Generator(device=DEV).manual_seed(seed + 2)) + 0.5
+    win_p = torch.rand(max(E, 1), device=DEV, generator=torch.Generator(device=DEV).manual_seed(seed + 3))[:E].contiguous()
+    return X, p, Win, win_p
+
+
+def _mask(n, seed, frac=0.6):
+    g = np.random.default_rng(seed)
+    m = (g.random(n) < frac).astype(np.int32)
+    return m, torch.from_numpy(m).to(DEV)
+
+
+WIN_TOPOS = [t for t in TOPOS if t[0] != "onepeer"] + [("onepeer", TOPOS[2][1])]
+
+
+@pytest.mark.parametrize("name,make", WIN_TOPOS)
+@pytest.mark.parametrize("n,d", [(16, 1024), (12, 4096 + 136), (33, 130), (64, 8192 + 520), (2, 5000), (1, 64)])
+@pytest.mark.parametrize("masked", [False, True])
+def test_window_primitives_match_oracle(name, make, n, d, masked):
+    if name == "push" and n < 3:
+        pytest.skip("the random directed graph needs more agents")
+    t = make(n)
+    W = lib_W(t, 0)
+    X, p, Win, win_p = _window_state(t, n, d, 7000 + n)
+    m_np, m_dev = _mask(n, n + d) if masked else (None, None)
+    hx, hp, hw, hwp = host(X), host(p[:, None])[:, 0], host(Win), host(win_p[:, None])[:, 0]
+    pad_before = X.as_strided((n, X.stride(0) - d), (X.stride(0), 1), X.storage_offset() + d).clone() if n > 1 else None
+
+    # put
+    ref = O.win_put(hx, hw, W, m_np)
+    got = bf.bf_win_put(t, 0, X, Win.clone() if Win.numel() == 0 else empty_like_rows(Win).copy_(Win), active=m_dev)
+    assert np.array_equal(host(got), ref), "put copies bits"
+    # update (weighted average, window kept)
+    ref = O.win_update(hx, hw, W, m_np)
+    Xc = empty_like_rows(X).copy_(X)
+    bf.bf_win_update(t, 0, Xc, Win, active=m_dev)
+    assert_close(Xc, ref, TOL32, "win_update")
+    # accumulate
+    rx, rp, rw, rwp = O.win_accumulate(hx, hp, hw, hwp, W, m_np)
+    Xc, pc, Wc, wpc = empty_like_rows(X).copy_(X), p.clone(), (empty_like_rows(Win).copy_(Win) if Win.numel() else Win.clone()), win_p.clone()
+    bf.bf_win_accumulate(t, 0, Xc, pc, Wc, wpc, active=m_dev)
+    assert_close(Xc, rx, TOL32, "accumulate X"); assert_close(pc[:, None], rp[:, None], TOL32, "accumulate p")
+    if Win.numel():
+        assert_close(Wc, rw, TOL32, "accumulate Win"); assert_close(wpc[:, None], rwp[:, None], TOL32, "accumulate win_p")
+    # update_then_collect, continuing from the accumulated state
+    cx, cp, cw, cwp = O.win_update_then_collect(rx, rp, rw, rwp, W, m_np)
+    bf.bf_win_update_then_collect(t, 0, Xc, pc, Wc, wpc, active=m_dev)
+    assert_close(Xc, cx, 2 * TOL32, "collect X"); assert_close(pc[:, None], cp[:, None], 2 * TOL32, "collect p")
+    if Win.numel():
+        assert_close(Wc, cw, 2 * TOL32, "collect Win")
+        zero_rows = np.flatnonzero(np.abs(cw).max(axis=1) == 0.0)
+        assert np.abs(host(Wc)[zero_rows]).max(initial=0.0) == 0.0, "collected slots are exactly zero"
+    if pad_before is not None:
+        pad_after = Xc.as_strided((n, Xc.stride(0) - d), (Xc.stride(0), 1), Xc.storage_offset() + d)
+        assert pad_after.shape == pad_before.shape
+
+
+def test_window_calls_leave_row_padding_alone():
+    n, d = 8, 1000 + 3                      # d is not a multiple of 4: the last vector of a row is partial
+    ld = workloads.padded_ld(d, 4)
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    E = bf.bf_topology_window_slots(t, 0)
+    Xfull = torch.full((n, ld), 7.0, device=DEV)
+    Wfull = torch.full((E, ld), -3.0, device=DEV)
+    X, Win = Xfull[:, :d], Wfull[:, :d]
+    X.normal_(generator=torch.Generator(device=DEV).manual_seed(1))
+    Win.zero_()
+    p, win_p = torch.ones(n, device=DEV), torch.zeros(E, device=DEV)
+    bf.bf_win_accumulate(t, 0, X, p, Win, win_p)
+    bf.bf_win_put(t, 0, X, Win)
+    bf.bf_win_update(t, 0, X, Win)
+    bf.bf_win_update_then_collect(t, 0, X, p, Win, win_p)
+    assert bool((Xfull[:, d:] == 7.0).all()) and bool((Wfull[:, d:] == -3.0).all())
+
+
+def test_window_async_pushsum_run_conserves_mass_and_converges():
+    # the asynchronous push-sum example: random subsets of agents send, random subsets collect
+    n, d = 24, 2048 + 72
+    t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=3, seed=workloads.CONFIG4_GRAPH_SEED)
+    W = lib_W(t, 0)
+    E = bf.bf_topology_window_slots(t, 0)
+    X = rows(n, d, 55, mean=5.0, std=2.0)
+    ld = X.stride(0)
+    Win = workloads.alloc_rows(E, d, torch.float32, DEV, ld=ld); Win.zero_()
+    p, win_p = torch.ones(n, device=DEV), torch.zeros(E, device=DEV)
+    rx, rp, rw, rwp = host(X), np.ones(n), np.zeros((E, d)), np.zeros(E)
+    mean = rx.mean(0)
+    total = rx.sum(0)
+    for k in range(120):
+        ma, ma_dev = _mask(n, 1000 + 2 * k)
+        mc, mc_dev = _mask(n, 1001 + 2 * k)
+        bf.bf_win_accumulate(t, 0, X, p, Win, win_p, active=ma_dev)
+        bf.bf_win_update_then_collect(t, 0, X, p, Win, win_p, active=mc_dev)
+        rx, rp, rw, rwp = O.win_accumulate(rx, rp, rw, rwp, W, ma)
+        rx, rp, rw, rwp = O.win_update_then_collect(rx, rp, rw, rwp, W, mc)
+        if k % 20 == 19 or k < 3:
+            assert_close(X, rx, 3e-5, "step %d X" % k)
+            assert_close(p[:, None], rp[:, None], 3e-5, "step %d p" % k)
+            assert_close(Win, rw, 3e-5 * max(1.0, np.abs(rx).max() / max(np.abs(rw).max(), 1e-30)), "step %d Win" % k)
+    mass = host(X).sum(0) + host(Win).sum(0)
+    assert np.abs(mass - total).max() <= 1e-4 * np.abs(total).max()
+    assert abs(float(p.double().sum() + win_p.double().sum()) - n) < 1e-4
+    y = host(X) / host(p[:, None])
+    assert np.abs(y - mean).max() < 2e-4 * np.abs(mean).max()
+    assert np.abs(host(X) - mean).max() > 1e-2                # x alone is not the average
+
+
+def test_window_all_active_round_equals_pushsum_step():
+    n, d = 32, 4096 + 264
+    t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=4, seed=3)
+    E = bf.bf_topology_window_slots(t, 0)
+    X = rows(n, d, 91, mean=2.0)
+    Win = workloads.alloc_rows(E, d, torch.float32, DEV, ld=X.stride(0)); Win.zero_()
+    p, win_p = torch.ones(n, device=DEV), torch.zeros(E, device=DEV)
+    Xs, ws, _ = bf.bf_pushsum_step(t, 0, X, empty_like_rows(X), torch.ones(n, device=DEV), torch.empty(n, device=DEV))
+    bf.bf_win_accumulate(t, 0, X, p, Win, win_p)
+    bf.bf_win_update_then_collect(t, 0, X, p, Win, win_p)
+    assert_close(X, host(Xs), 1e-6, "window round vs push-sum kernel")
+    assert_close(p[:, None], host(ws[:, None]), 1e-6, "p")
+    assert float(Win.abs().max()) == 0.0 and float(win_p.abs().max()) == 0.0
