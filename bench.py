@@ -206,10 +206,74 @@ def main():
             bf.bf_atc_step(t1, k, X1[k & 1], X1[1 - (k & 1)], G1, None, d1["alpha"], 0.0, bf.BF_ATC)
 
         w_, e_ = timed(dgd, 200, 20)
+        # the same 200 iterations as 10 replays of a HIP graph holding 20 of them (40 kernel nodes)
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            dgd(0)
+            dgd(1)
+        torch.cuda.current_stream().wait_stream(side)
+        with torch.cuda.graph(graph):
+            for k in range(20):
+                dgd(k)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(10):
+            graph.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter() - tg
         entry("config1_dgd_least_squares_ring_n16_d1024_f32", A1.numel() * 4 + b1.numel() * 4 + 2 * n1 * dd1 * 4,
               n1, 200, w_, e_, {"iterations_per_s": round(200 / w_, 1),
-                                "note": "latency bound: two launches per iteration on a 64 KiB state"})
+                                "iterations_per_s_hip_graph": round(200 / tg, 1),
+                                "note": "latency bound: two launches per iteration on a 64 KiB state; the second "
+                                        "figure replays a HIP graph of 20 iterations"})
+        del graph
         out["per_config"] = per
+
+        # -------------------------------------------------------------- rows beyond the five configurations
+        # Reported apart from the per-round figures above: the fused passes move each element through
+        # HBM once for several rounds, so their "effective GB/s" is per PASS (one read + one write of X).
+        nxt = {}
+        X3 = workloads.config3_state(dev, n=n3, d=d3, ld=ld3)
+        for cnt in (2, 4, 8):
+            w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce_multi(t3, (k * cnt) % 8, cnt, X3, X3), 16, 4)
+            nxt["fused_rounds_one_peer_n256_d4194304_x%d" % cnt] = {
+                "rounds_per_pass": cnt, "ms_per_pass": round(w_ * 1e3 / 16, 4),
+                "ms_per_round_equivalent": round(w_ * 1e3 / 16 / cnt, 4),
+                "separate_rounds_ms": round(cnt * per["config3_one_peer_exp2_n256_d4194304_f32"]["ms_per_step"], 4),
+                "pass_GBps": round(2 * n3 * d3 * 4 * 16 / w_ / 1e9, 1)}
+        del X3
+        nh, Lh, dh = 8, 8, 1 << 22
+        th = bf.bf_topology_create(bf.BF_EXP_STATIC, nh)
+        ldh = bf.bf_recommended_ld(dh, bf.BF_F32)
+        Xh2 = workloads.normal_rows(nh * Lh, dh, 601, dev, ld=ldh)
+        w_, e_ = timed(lambda k: bf.bf_hierarchical_neighbor_allreduce(th, k, Lh, Xh2, Xh2), 30, 5)
+        nxt["hierarchical_8_machines_x_8_agents_d4194304"] = {
+            "ms_per_step": round(w_ * 1e3 / 30, 4), "effective_GBps": round(2 * nh * Lh * dh * 4 * 30 / w_ / 1e9, 1),
+            "pct_of_hbm_peak": round(100 * 2 * nh * Lh * dh * 4 * 30 / w_ / 1e9 / HBM_PEAK_GBPS, 2),
+            "note": "local average, machine-level round, copy back: three fused rounds, one pass over X"}
+        del Xh2
+        Ew = bf.bf_topology_window_slots(t4, 0)
+        Xw = workloads.config4_state(dev, n=n4, d=d4, ld=ld4)
+        Ww = workloads.alloc_rows(Ew, d4, torch.float32, dev, ld=ld4, fill=0)
+        pw, wpw = torch.ones(n4, device=dev), torch.zeros(Ew, device=dev)
+
+        def async_round(k):
+            bf.bf_win_accumulate(t4, 0, Xw, pw, Ww, wpw)
+            bf.bf_win_update_then_collect(t4, 0, Xw, pw, Ww, wpw)
+
+        w_, e_ = timed(async_round, 10, 2)
+        wbytes = 2 * (2 * n4 + 2 * Ew) * d4 * 4
+        nxt["window_pushsum_round_n128_slots%d_d2097152" % Ew] = {
+            "ms_per_step": round(w_ * 1e3 / 10, 4), "effective_GBps": round(wbytes * 10 / w_ / 1e9, 1),
+            "pct_of_hbm_peak": round(100 * wbytes * 10 / w_ / 1e9 / HBM_PEAK_GBPS, 2),
+            "note": "win_accumulate + win_update_then_collect, everybody active; bytes = x read and written "
+                    "and every slot read and written, in each of the two calls"}
+        del Xw, Ww
+        out["next_rows"] = nxt
     del X
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample

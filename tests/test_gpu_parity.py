@@ -953,3 +953,45 @@ def test_window_all_active_round_equals_pushsum_step():
     assert_close(X, host(Xs), 1e-6, "window round vs push-sum kernel")
     assert_close(p[:, None], host(ws[:, None]), 1e-6, "p")
     assert float(Win.abs().max()) == 0.0 and float(win_p.abs().max()) == 0.0
+
+
+# ------------------------------------------------------------------ HIP graph replay of the DGD iteration
+def test_dgd_iterations_replayed_from_a_hip_graph_match_eager():
+    data = workloads.config1_least_squares(DEV)
+    A, b = data["A"], data["b"]
+    n, m, d = A.shape
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    X = [torch.zeros((n, d), device=DEV), torch.zeros((n, d), device=DEV)]
+    G = torch.empty((n, d), device=DEV)
+
+    def dgd(k):
+        bf.bf_grad_least_squares(A, b, X[k & 1], G)
+        bf.bf_atc_step(t, k, X[k & 1], X[1 - (k & 1)], G, None, data["alpha"], 0.0, bf.BF_ATC)
+
+    for k in range(12):
+        dgd(k)
+    torch.cuda.synchronize()
+    eager = [X[0].clone()]                          # after 12 iterations; then after 16, 20, 24
+    for rep in range(3):
+        for k in range(4):
+            dgd(k)
+        eager.append(X[0].clone())
+    X[0].zero_(); X[1].zero_()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dgd(0); dgd(1)
+    torch.cuda.current_stream().wait_stream(side)
+    X[0].zero_(); X[1].zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for k in range(4):
+            dgd(k)
+    X[0].zero_(); X[1].zero_()
+    scratch = torch.zeros(1 << 16, device=DEV)
+    for rep in range(6):
+        graph.replay()
+        scratch.add_(1.0)                           # eager work and a synchronisation between the replays
+        torch.cuda.synchronize()
+        if rep >= 2:
+            assert torch.equal(X[0], eager[rep - 2]), "replay %d differs from eager" % rep
