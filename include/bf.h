@@ -48,7 +48,7 @@ typedef enum {
   BF_ERR_NOT_STOCHASTIC = -7,  /* required row / column sums differ from 1 by more than 1e-6   */
   BF_ERR_NOT_CONNECTED = -8,   /* no strongly connected draw found / user graph not connected  */
   BF_ERR_CSR = -9,             /* malformed CSR: bad rowptr, column out of range, unsorted or
-                                  duplicate columns, missing diagonal, non-finite weight       */
+                                  duplicate columns, non-finite weight                        */
   BF_ERR_TOPO_MISMATCH = -10,  /* a sender's dst list and a receiver's src list disagree       */
   BF_ERR_UNSUPPORTED = -11,    /* valid request this build has no kernel for (says which)      */
   BF_ERR_HIP = -12,            /* a HIP runtime call failed; bf_last_hip_error() has the code  */
@@ -86,7 +86,7 @@ typedef struct {
                                            topology check, done once at create time)             */
   const int64_t* rowptr;                /* rounds*(n+1) entries; slice r uses rowptr[r*(n+1)..],
                                            offsets are absolute positions in col/wgt             */
-  const int32_t* col;                   /* ascending and unique within a row; diagonal present   */
+  const int32_t* col;                   /* ascending and unique within a row; a row may be empty  */
   const float*   wgt;
   const float*   dense_w;               /* rounds*n*n, entry [r][i][j] = w_ij of round r         */
 } bf_topo_params_t;

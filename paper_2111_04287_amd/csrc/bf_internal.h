@@ -4,6 +4,7 @@
 #define BF_INTERNAL_H_
 
 #include <cstdint>
+#include <list>
 #include <map>
 #include <mutex>
 #include <vector>
@@ -72,7 +73,7 @@ struct bf_topology {
   uint64_t accepted_seed = 0;
   std::vector<bf::Round> rounds;
   std::mutex mu;                          // guards dev and two_level
-  std::vector<bf::DeviceCopy> dev;
+  std::list<bf::DeviceCopy> dev;           // a list: pointers to entries stay valid when one is added
   // Two-level operators built from this (machine-level) topology, keyed by local_size; owned.
   std::map<int32_t, bf_topology*> two_level;
 };

@@ -147,3 +147,69 @@ def test_config5_full_size_momentum_20_steps():
         Xr, Mr = O.dmsgd_atc_step(Xr, Mr, O.quadratic_noise_grad(Xr, Ch, take(E, cols), cfg["lam"], s64), W, a64, b64)
         check(X[b], cols, Xr, 2e-2, "step %d" % k)
         check(M, cols, Mr, 2e-2, "momentum, step %d" % k)
+
+
+# ------------------------------------------------------------------ rows beyond the five configurations
+def test_fused_eight_rounds_full_size_reach_the_exact_mean_in_one_pass():
+    n, d = 256, 1 << 22
+    t = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+    ld = bf.bf_recommended_ld(d, bf.BF_F32)
+    X = workloads.config3_state(DEV, n=n, d=d, ld=ld)
+    cols = sample_columns(d, 13)
+    ref = take(X, cols)
+    emu = X[:, cols].cpu().numpy()
+    mean0 = torch.empty(d, device=DEV)
+    bf.bf_consensus_stats(X, None, mean_out=mean0)
+    for r in range(8):
+        W = lib_W(t, r)
+        ref = O.mix(ref, W)
+        emu = O.mix_fp32_chain(emu, W)
+    bf.bf_neighbor_allreduce_multi(t, 0, 8, X, X)             # in place, as bench.py runs it
+    check(X, cols, ref, 1e-5, "8 fused rounds")
+    assert np.array_equal(X[:, cols].cpu().numpy().view(np.uint32), emu.view(np.uint32))
+    st = bf.bf_consensus_stats(X, None)
+    assert float(st[1]) <= 8 * 6e-8 * float(st[2]) + 1e-30, "every row is the column mean"
+    assert float((X[0] - mean0).abs().max()) <= 2e-6
+
+
+def test_hierarchical_full_size():
+    M, L, d = 8, 8, 1 << 22
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, M)
+    ld = bf.bf_recommended_ld(d, bf.BF_F32)
+    X = workloads.normal_rows(M * L, d, 601, DEV, ld=ld)
+    cols = sample_columns(d, 14)
+    ref = O.hierarchical_neighbor_allreduce(take(X, cols), lib_W(t), L)
+    out = bf.bf_hierarchical_neighbor_allreduce(t, 0, L, X, workloads.alloc_rows(M * L, d, torch.float32, DEV, ld=ld))
+    check(out, cols, ref, 1e-5, "hierarchical")
+    bf.bf_hierarchical_neighbor_allreduce(t, 0, L, X, X)
+    assert torch.equal(X[:, cols], out[:, cols])
+    o3 = out[:, cols].reshape(M, L, -1)
+    assert torch.equal(o3, o3[:, :1].expand_as(o3))
+
+
+def test_window_pushsum_round_full_size():
+    n, d = 128, 1 << 21
+    t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=4, seed=workloads.CONFIG4_GRAPH_SEED)
+    W = lib_W(t)
+    E = bf.bf_topology_window_slots(t, 0)
+    ld = bf.bf_recommended_ld(d, bf.BF_F32)
+    X = workloads.config4_state(DEV, n=n, d=d, ld=ld)
+    Win = workloads.alloc_rows(E, d, torch.float32, DEV, ld=ld, fill=0)
+    p, win_p = torch.ones(n, device=DEV), torch.zeros(E, device=DEV)
+    cols = sample_columns(d, 15)
+    rx, rp, rw, rwp = take(X, cols), np.ones(n), np.zeros((E, len(cols))), np.zeros(E)
+    rng = np.random.default_rng(15)
+    for k in range(6):
+        ma = (rng.random(n) < 0.7).astype(np.int32)
+        mc = (rng.random(n) < 0.7).astype(np.int32)
+        bf.bf_win_accumulate(t, 0, X, p, Win, win_p, active=torch.from_numpy(ma).to(DEV))
+        rx, rp, rw, rwp = O.win_accumulate(rx, rp, rw, rwp, W, ma)
+        check(X, cols, rx, 1e-5, "accumulate %d X" % k)
+        check(Win, cols, rw, 1e-5, "accumulate %d Win" % k)
+        bf.bf_win_update_then_collect(t, 0, X, p, Win, win_p, active=torch.from_numpy(mc).to(DEV))
+        rx, rp, rw, rwp = O.win_update_then_collect(rx, rp, rw, rwp, W, mc)
+        check(X, cols, rx, 1e-5, "collect %d X" % k)
+        got_w = take(Win, cols)
+        assert np.abs(got_w - rw).max() <= 1e-5 * max(np.abs(rw).max(), np.abs(rx).max())
+        np.testing.assert_allclose(p.cpu().numpy(), rp, rtol=1e-5)
+    assert abs(float(p.double().sum() + win_p.double().sum()) - n) < 1e-4
