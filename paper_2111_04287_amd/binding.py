@@ -131,6 +131,8 @@ class Topology:
 
     def __init__(self, handle):
         self.handle = handle
+        self._n = None                      # a topology never changes after creation: ask once
+        self._rounds = None
 
     def __del__(self):
         h, self.handle = getattr(self, "handle", None), None
@@ -139,11 +141,15 @@ class Topology:
 
     @property
     def n(self):
-        return lib.bf_topology_n(self.handle)
+        if self._n is None:
+            self._n = lib.bf_topology_n(self.handle)
+        return self._n
 
     @property
     def rounds(self):
-        return lib.bf_topology_rounds(self.handle)
+        if self._rounds is None:
+            self._rounds = lib.bf_topology_rounds(self.handle)
+        return self._rounds
 
 
 def bf_topology_create(kind, n, out_degree=0, seed=0, require_strongly_connected=True,
@@ -246,9 +252,20 @@ def _mat(t, name):
     return t.data_ptr(), n, d, ld
 
 
+_raw_stream = None
+
+
 def _stream(stream):
-    import torch
+    """HIP stream handle: the given torch stream (or raw handle), else torch's current stream.  The
+    raw getter is several times cheaper than building a torch.cuda.Stream object, which matters for
+    the latency-bound small configurations."""
+    global _raw_stream
     if stream is None:
+        import torch
+        if _raw_stream is None:
+            _raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", False)
+        if _raw_stream:
+            return _raw_stream(torch.cuda.current_device())
         return torch.cuda.current_stream().cuda_stream
     return getattr(stream, "cuda_stream", stream)
 
