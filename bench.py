@@ -81,8 +81,11 @@ def main():
             ev[steps].record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        ev_ms = (sum(ev[k].elapsed_time(ev[k + 1]) for k in range(steps)) / steps) if ev else None
-        return wall, ev_ms
+        if not ev:
+            return wall, None
+        per_step = sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(steps))
+        timed.last = {"event_ms_median": round(per_step[len(per_step) // 2], 5), "event_ms_min": round(per_step[0], 5)}
+        return wall, sum(per_step) / steps
 
     # ------------------------------------------------------------------ headline: configuration 2
     n, d = 64, 1 << 20
@@ -125,7 +128,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "bf_tile_kernel<f32, mix>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "algorithmic_bytes_per_launch": bytes_per_round,
-                     "launch_ms": round(ev_ms, 5),
+                     "launch_ms": round(ev_ms, 5), "launch_ms_median": timed.last["event_ms_median"],
+                     "launch_ms_min": timed.last["event_ms_min"],
                      "note": "X (256 MiB) is the size of the 256 MB memory-side Infinity Cache, which an in-place "
                              "round can partly reuse; configs 3-5 under per_config are 1-4.6 GB and are the "
                              "HBM-only figures"},
@@ -141,6 +145,7 @@ def main():
                  "pct_of_hbm_peak": round(100 * bytes_per_step * steps / wall / 1e9 / HBM_PEAK_GBPS, 2),
                  "agent_row_updates_per_s": round(n_agents * steps / wall, 1),
                  "event_ms_per_step": round(ev_ms, 5)}
+            e.update(timed.last)
             if extra:
                 e.update(extra)
             per[name] = e
