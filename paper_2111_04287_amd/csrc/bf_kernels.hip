@@ -13,870 +13,15 @@
 // Workgroups are persistent: tile t+1's global loads are issued into registers before tile t is
 // reduced, so HBM requests are in flight during the LDS phase.
 
-#include <hip/hip_runtime.h>
-#include <type_traits>
-
-#include <algorithm>
-#include <cstdint>
-#include <cstring>
 #include <new>
 
-#include "bf_internal.h"
+#include "bf_device.h"
+
+thread_local int bf::g_last_hip_error = 0;
 
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-thread_local int g_last_hip_error = 0;
-
-#define BF_HIP_TRY(expr)                                  \
-  do {                                                    \
-    hipError_t e_ = (expr);                               \
-    if (e_ != hipSuccess) {                               \
-      g_last_hip_error = static_cast<int>(e_);            \
-      return BF_ERR_HIP;                                  \
-    }                                                     \
-  } while (0)
-
-// ---------------------------------------------------------------------------------------------
-// bf16 <-> fp32 (bfloat16 = upper half of binary32; round to nearest, ties to even)
-__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xFFFF0000u); }
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;   // quiet NaN
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
-}
-
-// Streaming accesses.  Every element of X, G and M is read once and written once per call, so
-// loads of X and G and stores of X_out and Y carry the non-temporal hint (measured +2..5 %).
-// The momentum matrix does not: with bf16 storage a lane's two 16-byte halves of M are moved by
-// separate instructions, and with the hint every 128-byte line became two partial transfers
-// (-25 % on the store, -2 % on the load).
-#ifndef BF_NT_CHAIN_LOAD
-#define BF_NT_CHAIN_LOAD 1
-#endif
-#ifndef BF_INTERLEAVE
-#define BF_INTERLEAVE 1
-#endif
-template <bool NT, typename T> __device__ __forceinline__ T ld_stream(const T* ptr) {
-  if constexpr (NT) return __builtin_nontemporal_load(ptr);
-  else return *ptr;
-}
-template <bool NT, typename T> __device__ __forceinline__ void st_stream(T* ptr, const T& v) {
-  if constexpr (NT) __builtin_nontemporal_store(v, ptr);
-  else *ptr = v;
-}
-
-// Scalar-cache view of the topology: uniform addresses into these become s_load instructions.
-typedef const int32_t __attribute__((address_space(4)))* csr_i32_ptr;
-typedef const u32x2 __attribute__((address_space(4)))* csr_ent_ptr;
-
-enum { OP_MIX = 0, OP_ATC = 1, OP_AWC = 2, OP_MOM_ATC = 3, OP_MOM_AWC = 4, OP_ED = 5, OP_TRACK = 6 };
-enum { DT_F32 = 0, DT_BF16 = 1 };
-
-struct TileParams {
-  const char* x_in;      // n x ld, dtype DT
-  char*       x_out;
-  const char* g;         // gradient, dtype DT (ATC/AWC/momentum)
-  const char* g2;        // previous gradient, dtype DT (gradient-tracking update)
-  float*      m;         // momentum, fp32 (momentum ops)
-  char*       y;         // push-sum ratio output, dtype DT (optional)
-  const float* p_out;    // push-sum weights after this round (for y)
-  const int32_t* rowptr; // device CSR of the round
-  const u32x2*   ent;    // {col, weight bits}
-  const bf::ChainStep* chain;  // walk order of the round when it has chain structure, else null
-  int64_t d, ld;
-  int64_t ntiles;
-  int32_t n;
-  int32_t log_c;         // tile width C = 1 << log_c elements
-  int32_t reverse;       // walk the column tiles from the last to the first
-  int32_t fuse;          // rounds applied per pass (1 = a single mix); >1 needs two LDS tiles
-  // Fused rounds: the rounds before the last one (rowptr/ent hold the last) are found through the
-  // table at the head of the topology's device blob, {rowptr byte offset, entry byte offset} per
-  // round.  (A per-round pointer array in this struct would be indexed at run time, i.e. read from
-  // the kernel-argument segment inside the tile loop, which costs microseconds per read.)
-  const char* blob;
-  int32_t round_k0;      // first fused round, already reduced modulo nrounds
-  int32_t nrounds;
-  float alpha, beta;
-};
-
-template <int DT> struct Elem { static constexpr int bytes = DT == DT_F32 ? 4 : 2; static constexpr int per16 = 16 / bytes; };
-
-// Load 16 bytes of X/G and widen to fp32.
-template <int DT>
-__device__ __forceinline__ void widen(const u32x4& raw, float* out) {
-  if constexpr (DT == DT_F32) {
-    out[0] = __uint_as_float(raw.x); out[1] = __uint_as_float(raw.y);
-    out[2] = __uint_as_float(raw.z); out[3] = __uint_as_float(raw.w);
-  } else {
-    out[0] = bf16_lo(raw.x); out[1] = bf16_hi(raw.x); out[2] = bf16_lo(raw.y); out[3] = bf16_hi(raw.y);
-    out[4] = bf16_lo(raw.z); out[5] = bf16_hi(raw.z); out[6] = bf16_lo(raw.w); out[7] = bf16_hi(raw.w);
-  }
-}
-
-// Store LW consecutive results of dtype DT at element offset `off` of row base `base`;
-// `valid` = how many of them lie below d.
-template <int DT, int LW, bool NT = true>
-__device__ __forceinline__ void store_out(char* base, int64_t off, const float* v, int valid) {
-  if constexpr (DT == DT_F32) {
-    float* ptr = reinterpret_cast<float*>(base) + off;
-    if (valid >= LW) {
-      if constexpr (LW == 4) { f32x4 t = {v[0], v[1], v[2], v[3]}; st_stream<NT>(reinterpret_cast<f32x4*>(ptr), t); }
-      else if constexpr (LW == 2) { f32x2 t = {v[0], v[1]}; st_stream<NT>(reinterpret_cast<f32x2*>(ptr), t); }
-      else { st_stream<NT>(ptr, v[0]); }
-    } else {
-      for (int k = 0; k < LW; ++k) if (k < valid) ptr[k] = v[k];
-    }
-  } else {
-    uint16_t* ptr = reinterpret_cast<uint16_t*>(base) + off;
-    if (valid >= LW) {
-      if constexpr (LW == 4) { u32x2 t = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; st_stream<NT>(reinterpret_cast<u32x2*>(ptr), t); }
-      else if constexpr (LW == 2) { st_stream<NT>(reinterpret_cast<uint32_t*>(ptr), pack_bf16x2(v[0], v[1])); }
-      else { ptr[0] = static_cast<uint16_t>(f32_to_bf16_bits(v[0])); }
-    } else {
-      for (int k = 0; k < LW; ++k) if (k < valid) ptr[k] = static_cast<uint16_t>(f32_to_bf16_bits(v[k]));
-    }
-  }
-}
-
-// Load LW consecutive values of dtype DT (all below ld, so in bounds) and widen.
-template <int DT, int LW>
-__device__ __forceinline__ void load_in(const char* base, int64_t off, float* v) {
-  if constexpr (DT == DT_F32) {
-    const float* ptr = reinterpret_cast<const float*>(base) + off;
-    if constexpr (LW == 4) { f32x4 t = *reinterpret_cast<const f32x4*>(ptr); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
-    else if constexpr (LW == 2) { f32x2 t = *reinterpret_cast<const f32x2*>(ptr); v[0] = t.x; v[1] = t.y; }
-    else { v[0] = ptr[0]; }
-  } else {
-    const uint16_t* ptr = reinterpret_cast<const uint16_t*>(base) + off;
-    if constexpr (LW == 4) { u32x2 t = *reinterpret_cast<const u32x2*>(ptr); v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y); }
-    else if constexpr (LW == 2) { uint32_t t = *reinterpret_cast<const uint32_t*>(ptr); v[0] = bf16_lo(t); v[1] = bf16_hi(t); }
-    else { v[0] = __uint_as_float(static_cast<uint32_t>(ptr[0]) << 16); }
-  }
-}
-
-// Local update of four columns of one agent while its row is staged, for the ops that carry an
-// fp32 state matrix.  In: xv = x, gv = g, st = state.  Out: xv = the value to be mixed, st = the new
-// state to write back.
-//   OP_MOM_ATC (heavy-ball momentum, adapt-then-combine): m <- beta m + g;  mixed value x - alpha m.
-//   OP_ED (Exact-Diffusion, eqs. ed-1, ed-2): psi = x - alpha g;  phi = psi + x - psi_prev;
-//          mixed value phi, state <- psi.
-template <int OP>
-__device__ __forceinline__ void local_update4(float* xv, const float* gv, float* st, float alpha, float beta) {
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    if constexpr (OP == OP_ED) {
-      const float psi = fmaf(-alpha, gv[e], xv[e]);
-      xv[e] = (psi + xv[e]) - st[e];
-      st[e] = psi;
-    } else {
-      st[e] = fmaf(beta, st[e], gv[e]);
-      xv[e] = fmaf(-alpha, st[e], xv[e]);
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// The tile kernel.  DT: storage type of X/G/Y.  OP: what is staged and what is subtracted.
-// WITH_Y: also write the push-sum ratio.  LW: columns per lane in the reduce phase (a wave spans
-// 64*LW columns of one output row).  MAXPF: staging units (16-byte vectors of X) per thread.
-template <int DT, int OP, bool WITH_Y, int LW, int THREADS, int MAXPF, bool STREAM, bool MULTI = false>
-__global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
-  extern __shared__ f32x4 lds_raw[];
-  float* lds = reinterpret_cast<float*>(lds_raw);
-
-  constexpr int EB = Elem<DT>::bytes;
-  constexpr int UC = Elem<DT>::per16;               // columns per staging unit
-  constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
-  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED || OP == OP_TRACK);
-  constexpr bool STAGE_G2 = (OP == OP_TRACK);
-  constexpr bool STAGE_M = (OP == OP_MOM_ATC || OP == OP_ED);
-  constexpr int MV = UC / 4;                        // 16-byte vectors of M per unit
-
-  const int tid = threadIdx.x;
-  const int log_c = p.log_c;
-  const int upr_log = log_c - UC_LOG;               // staging units per tile row (log2)
-  const int upr_mask = (1 << upr_log) - 1;
-  const int nunits = p.n << upr_log;
-  const int64_t d = p.d, ld = p.ld;
-
-  u32x4 xr[MAXPF];
-  u32x4 gr[STAGE_G ? MAXPF : 1];
-  u32x4 g2r[STAGE_G2 ? MAXPF : 1];
-  f32x4 mr[STAGE_M ? MAXPF * MV : 1];
-
-  // Loads are unconditional (uniform control flow keeps all of a tile's loads in flight at
-  // once): a unit past the tile's end re-reads the last unit, a column at or past d re-reads the
-  // row's last in-range vector.  Only the LDS write and the M store are predicated.
-  const int64_t last_vec = d > 0 ? ((d - 1) >> UC_LOG) << UC_LOG : 0;
-  auto issue_one = [&](int64_t tile, int k) {
-    const int64_t c0 = tile << log_c;
-    {
-      const int u = min(tid + k * THREADS, nunits - 1);
-      const int row = u >> upr_log;
-      const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
-      const int64_t off = static_cast<int64_t>(row) * ld + col;
-      xr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
-      if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
-      if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
-      if constexpr (STAGE_M) {
-#pragma unroll
-        for (int q = 0; q < MV; ++q) mr[k * MV + q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
-      }
-    }
-  };
-  auto issue_loads = [&](int64_t tile) {
-#pragma unroll
-    for (int k = 0; k < MAXPF; ++k) issue_one(tile, k);
-  };
-
-  // Transform one staging unit (local update, momentum) and put it into the LDS tile.
-  auto stage_unit = [&](int u, int64_t c0, const u32x4& xraw, const u32x4& graw, const u32x4& g2raw, const f32x4* mraw) {
-    const int row = u >> upr_log;
-    const int cit = (u & upr_mask) << UC_LOG;       // column inside the tile
-    const int64_t col = c0 + cit;
-    const bool live = u < nunits && col < d;
-    float xv[UC];
-    widen<DT>(xraw, xv);
-    if constexpr (STAGE_G) {
-      float gv[UC];
-      widen<DT>(graw, gv);
-      if constexpr (STAGE_M) {
-        const int64_t off = static_cast<int64_t>(row) * ld + col;
-#pragma unroll
-        for (int q = 0; q < MV; ++q) {
-          float sv[4] = {mraw[q].x, mraw[q].y, mraw[q].z, mraw[q].w};
-          local_update4<OP>(xv + 4 * q, gv + 4 * q, sv, p.alpha, p.beta);
-          if (live) {
-            const int64_t rem = d - (col + 4 * q);
-            if (rem >= 4) { f32x4 t = {sv[0], sv[1], sv[2], sv[3]}; *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = t; }
-            else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = sv[e];
-          }
-        }
-      } else if constexpr (STAGE_G2) {
-        // gradient tracking: the mixed value is y + g_new - g_old
-        float hv[UC];
-        widen<DT>(g2raw, hv);
-#pragma unroll
-        for (int e = 0; e < UC; ++e) xv[e] = (xv[e] + gv[e]) - hv[e];
-      } else {
-#pragma unroll
-        for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
-      }
-    }
-    if (live) {
-      float* dst = lds + (row << log_c) + cit;
-#pragma unroll
-      for (int q = 0; q < MV; ++q) {
-        f32x4 t = {xv[4 * q], xv[4 * q + 1], xv[4 * q + 2], xv[4 * q + 3]};
-        *reinterpret_cast<f32x4*>(dst + 4 * q) = t;
-      }
-    }
-  };
-
-  auto stage = [&](int64_t tile) {
-    const int64_t c0 = tile << log_c;
-#pragma unroll
-    for (int k = 0; k < MAXPF; ++k)
-      stage_unit(tid + k * THREADS, c0, xr[k], gr[STAGE_G ? k : 0], g2r[STAGE_G2 ? k : 0], &mr[STAGE_M ? k * MV : 0]);
-    // Tiles taller than THREADS*MAXPF units (many agents): the rest is loaded here, unprefetched.
-    for (int u = tid + MAXPF * THREADS; u < nunits; u += THREADS) {
-      const int row = u >> upr_log;
-      const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
-      const int64_t off = static_cast<int64_t>(row) * ld + col;
-      const u32x4 xraw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
-      u32x4 graw = {0, 0, 0, 0}, g2raw = {0, 0, 0, 0};
-      f32x4 mraw[MV];
-      if constexpr (STAGE_G) graw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
-      if constexpr (STAGE_G2) g2raw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
-      if constexpr (STAGE_M) {
-#pragma unroll
-        for (int q = 0; q < MV; ++q) mraw[q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
-      }
-      stage_unit(u, c0, xraw, graw, g2raw, mraw);
-    }
-  };
-
-  const csr_i32_ptr rowptr = (csr_i32_ptr)(uintptr_t)p.rowptr;
-  const csr_ent_ptr ent = (csr_ent_ptr)(uintptr_t)p.ent;
-
-  constexpr int NW = THREADS / 64;
-  constexpr int SPAN_LOG = (LW == 4 ? 8 : (LW == 2 ? 7 : 6));      // log2(64*LW)
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int lane = tid & 63;
-  const int spans_log = log_c - SPAN_LOG;
-  const int nops = p.n << spans_log;
-  #ifndef BF_GATHER_ILP
-#define BF_GATHER_ILP 4
-#endif
-  // Weighted sum of one output row-span over the row's in-neighbor list, read from an LDS tile.
-  auto gather = [&](const float* tile_base, csr_i32_ptr rp, csr_ent_ptr en_list, int i, int cit, float* acc) {
-    const int beg = rp[i], end = rp[i + 1];
-#pragma unroll
-    for (int e = 0; e < LW; ++e) acc[e] = 0.0f;
-    const float* src = tile_base + cit;
-    // Entries go in batches of K (4, then 2, then 1): the K list entries and the K LDS reads of a
-    // batch are issued together and only then consumed, in list order, so a wave waits once per
-    // batch instead of once per entry.
-    auto batch = [&](int q, auto kc) {
-      constexpr int K = decltype(kc)::value;
-      u32x2 en[K];
-#pragma unroll
-      for (int u = 0; u < K; ++u) en[u] = en_list[q + u];
-      float v[K][LW];
-#pragma unroll
-      for (int u = 0; u < K; ++u) {
-        const float* s = src + (static_cast<int>(en[u].x) << log_c);
-        if constexpr (LW == 4) {
-          const f32x4 t = *reinterpret_cast<const f32x4*>(s);
-          v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
-        } else if constexpr (LW == 2) {
-          const f32x2 t = *reinterpret_cast<const f32x2*>(s);
-          v[u][0] = t.x; v[u][1] = t.y;
-        } else {
-          v[u][0] = s[0];
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < K; ++u) {
-        const float w = __uint_as_float(en[u].y);
-#pragma unroll
-        for (int e = 0; e < LW; ++e) acc[e] = fmaf(w, v[u][e], acc[e]);
-      }
-    };
-    // The fp32 kernels with four columns per lane and no gradient operand fit two 1024-thread
-    // workgroups per CU only while they stay within 64 registers, which the batch of four would
-    // cost them; every other kernel is either well below or already above that line.
-    constexpr bool BATCHED = BF_GATHER_ILP >= 4 &&
-        !(DT == DT_F32 && LW == 4 && (OP == OP_MIX || OP == OP_AWC || OP == OP_MOM_AWC) && !MULTI);
-    int q = beg;
-    if constexpr (BATCHED) {
-      for (; q + 4 <= end; q += 4) batch(q, std::integral_constant<int, 4>{});
-      if (q + 2 <= end) { batch(q, std::integral_constant<int, 2>{}); q += 2; }
-    }
-    for (; q < end; ++q) batch(q, std::integral_constant<int, 1>{});
-  };
-  const float* final_src = lds;     // the LDS tile the last round reads (moves when rounds are fused)
-  // One output row-span: gather from LDS in CSR order, finish, store.
-  auto row_op = [&](int64_t tile, int op) {
-    const int64_t c0 = tile << log_c;
-    {
-      const int i = op >> spans_log;
-      const int cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
-      const int64_t col = c0 + cit;
-      float acc[LW];
-      gather(final_src, rowptr, ent, i, cit, acc);
-      if (col < d) {
-        const int64_t rem = d - col;
-        const int valid = rem >= LW ? LW : static_cast<int>(rem);
-        const int64_t off = static_cast<int64_t>(i) * ld + col;
-        if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
-          // Adapt-while-communicate: the receiver's own gradient is subtracted after the mix.
-          float gv[LW];
-          load_in<DT, LW>(p.g, off, gv);
-          if constexpr (OP == OP_MOM_AWC) {
-            float mv[LW];
-            load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), off, mv);
-#pragma unroll
-            for (int e = 0; e < LW; ++e) gv[e] = fmaf(p.beta, mv[e], gv[e]);
-            store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), off, gv, valid);
-          }
-#pragma unroll
-          for (int e = 0; e < LW; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);
-        }
-        store_out<DT, LW, STREAM>(p.x_out, off, acc, valid);
-        if constexpr (WITH_Y) {
-          const float rcp = 1.0f / p.p_out[i];
-          float yv[LW];
-#pragma unroll
-          for (int e = 0; e < LW; ++e) yv[e] = acc[e] * rcp;
-          store_out<DT, LW, STREAM>(p.y, off, yv, valid);
-        }
-      }
-    }
-  };
-  // Reduce phase of `tile`; the loads of tile `next` (if any) are issued one by one between the
-  // first row-spans so that reads and writes alternate on the memory pipe.
-  auto reduce_and_store = [&](int64_t tile, int64_t next, bool has_next) {
-    int op = wave;
-#if BF_INTERLEAVE
-#pragma unroll
-    for (int k = 0; k < MAXPF; ++k) {
-      if (has_next) issue_one(next, k);
-      if (op < nops) { row_op(tile, op); op += NW; }
-    }
-#else
-    if (has_next) issue_loads(next);
-#endif
-    for (; op < nops; op += NW) row_op(tile, op);
-  };
-
-#ifdef BF_PROFILE
-  // Development-only phase timing (100 MHz wall clock), wave 0 and the last wave of each workgroup.
-  unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.y);
-  const bool rec = dbg && !WITH_Y && (tid == 0 || tid == THREADS - 64);
-  int it = 0;
-#define BF_MARK(k) if (rec && it < 16) dbg[((static_cast<size_t>(blockIdx.x) * 2 + (tid != 0)) * 16 + it) * 8 + (k)] = wall_clock64()
-#else
-#define BF_MARK(k)
-#endif
-  // Odd rounds walk the tiles backwards: the columns a round wrote last are the first ones the
-  // next round reads, so whatever the memory-side cache still holds of them is reused.
-  auto phys = [&](int64_t seq) { return p.reverse ? p.ntiles - 1 - seq : seq; };
-  int64_t seq = blockIdx.x;
-  if (seq < p.ntiles) issue_loads(phys(seq));
-  while (seq < p.ntiles) {
-    const int64_t tile = phys(seq);
-    BF_MARK(0);
-    stage(tile);
-    BF_MARK(1);
-    __syncthreads();
-    BF_MARK(2);
-    if constexpr (MULTI) {
-      // Only one such workgroup fits a CU (two tiles), so nothing else keeps the memory pipe busy
-      // during the LDS rounds: the next tile's loads go out now, not during the last round.
-      if (seq + gridDim.x < p.ntiles) issue_loads(phys(seq + gridDim.x));
-      // Fused rounds: apply the first fuse-1 weight matrices LDS tile to LDS tile (two tiles, used
-      // alternately); the last one goes through the normal reduce-and-store below.
-      float* tile_a = lds;
-      float* tile_b = lds + (p.n << log_c);
-      typedef const u32x4 __attribute__((address_space(4)))* csr_u4_ptr;
-      typedef const u32x8 __attribute__((address_space(4)))* csr_u8_ptr;
-      const csr_u4_ptr round_tab = (csr_u4_ptr)(uintptr_t)p.blob;
-      const int ngroups = (p.n + 3) >> 2;
-      const int nitems = ngroups << spans_log;
-      int k = p.round_k0;
-      for (int r = 0; r + 1 < p.fuse; ++r) {
-        const float* src_t = (r & 1) ? tile_b : tile_a;
-        float* dst_t = (r & 1) ? tile_a : tile_b;
-        const u32x4 offs = round_tab[k];
-        const csr_u4_ptr hdrs = (csr_u4_ptr)(reinterpret_cast<uintptr_t>(p.blob) + offs.z);
-        const uintptr_t recs = reinterpret_cast<uintptr_t>(p.blob) + offs.w;
-        k = k + 1 == p.nrounds ? 0 : k + 1;
-        // NG groups of four rows per wave at a time, from the sliced copy of the round: one 32-byte
-        // scalar load brings the q-th entry of a group's four rows, the LDS reads of all groups go
-        // out together, and each row still adds its entries in list order, as the one-round path
-        // does.  (One group at a time leaves the wave waiting on each lookup: 16 waves per CU are
-        // all there is to hide it, because the two tiles fill the LDS.)
-        constexpr int NG = 1;
-        for (int item0 = wave; item0 < nitems; item0 += NW * NG) {
-          int g[NG], cit[NG];
-          u32x4 hdr[NG];
-          uint32_t longest = 0;
-          bool ragged = false;
-#pragma unroll
-          for (int j = 0; j < NG; ++j) {
-            const int item = item0 + j * NW;
-            const int itc = item < nitems ? item : item0;
-            g[j] = itc >> spans_log;
-            cit[j] = ((itc & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
-            hdr[j] = hdrs[g[j]];
-            if (item >= nitems) hdr[j].y = 0;
-          }
-#pragma unroll
-          for (int j = 0; j < NG; ++j) {
-            longest = max(longest, hdr[j].y);
-            ragged = ragged || hdr[j].z != 0 || hdr[j].y != hdr[0].y;
-          }
-          float acc[NG][4][LW];
-#pragma unroll
-          for (int j = 0; j < NG; ++j)
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-              for (int e = 0; e < LW; ++e) acc[j][u][e] = 0.0f;
-          auto records = [&](auto ragged_c) {
-            constexpr bool RAGGED = decltype(ragged_c)::value;
-            for (uint32_t q = 0; q < longest; ++q) {
-              u32x8 e8[NG];
-#pragma unroll
-              for (int j = 0; j < NG; ++j) {
-                // a group that has run out re-reads its last record (or record 0 of the table when
-                // it has none); every entry of such a read is skipped below
-                const uint32_t qc = RAGGED ? (q < hdr[j].y ? q : (hdr[j].y ? hdr[j].y - 1 : 0)) : q;
-                const uint32_t first = RAGGED && hdr[j].y == 0 ? 0 : hdr[j].x;
-                e8[j] = ((csr_u8_ptr)(recs + (static_cast<uintptr_t>(first + qc) << 5)))[0];
-              }
-              float v[NG][4][LW];
-#pragma unroll
-              for (int j = 0; j < NG; ++j) {
-                const uint32_t col[4] = {e8[j].s0, e8[j].s2, e8[j].s4, e8[j].s6};
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                  const float* sp = src_t + cit[j] + (static_cast<int>(RAGGED ? (col[u] & 0x7fffffffu) : col[u]) << log_c);
-                  if constexpr (LW == 4) {
-                    const f32x4 t = *reinterpret_cast<const f32x4*>(sp);
-                    v[j][u][0] = t.x; v[j][u][1] = t.y; v[j][u][2] = t.z; v[j][u][3] = t.w;
-                  } else if constexpr (LW == 2) {
-                    const f32x2 t = *reinterpret_cast<const f32x2*>(sp);
-                    v[j][u][0] = t.x; v[j][u][1] = t.y;
-                  } else {
-                    v[j][u][0] = sp[0];
-                  }
-                }
-              }
-#pragma unroll
-              for (int j = 0; j < NG; ++j) {
-                const uint32_t col[4] = {e8[j].s0, e8[j].s2, e8[j].s4, e8[j].s6};
-                const uint32_t wb[4] = {e8[j].s1, e8[j].s3, e8[j].s5, e8[j].s7};
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                  const float w = __uint_as_float(wb[u]);
-                  const bool live = !RAGGED || (static_cast<int32_t>(col[u]) >= 0 && q < hdr[j].y);
-#pragma unroll
-                  for (int e = 0; e < LW; ++e) {
-                    const float f = fmaf(w, v[j][u][e], acc[j][u][e]);
-                    acc[j][u][e] = live ? f : acc[j][u][e];
-                  }
-                }
-              }
-            }
-          };
-          if (ragged) records(std::true_type{}); else records(std::false_type{});
-#pragma unroll
-          for (int j = 0; j < NG; ++j) {
-            if (item0 + j * NW < nitems) {
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                const int row = (g[j] << 2) + u;
-                if (row < p.n) {
-                  float* o = dst_t + (row << log_c) + cit[j];
-                  if constexpr (LW == 4) { f32x4 t = {acc[j][u][0], acc[j][u][1], acc[j][u][2], acc[j][u][3]}; *reinterpret_cast<f32x4*>(o) = t; }
-                  else if constexpr (LW == 2) { f32x2 t = {acc[j][u][0], acc[j][u][1]}; *reinterpret_cast<f32x2*>(o) = t; }
-                  else { o[0] = acc[j][u][0]; }
-                }
-              }
-            }
-          }
-        }
-        __syncthreads();
-      }
-      final_src = ((p.fuse - 1) & 1) ? tile_b : tile_a;
-    }
-    const int64_t next = seq + gridDim.x;
-    BF_MARK(3);
-    reduce_and_store(tile, phys(next), !MULTI && next < p.ntiles);
-    BF_MARK(4);
-    __syncthreads();
-    BF_MARK(5);
-    seq = next;
-#ifdef BF_PROFILE
-    ++it;
-#endif
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Chain kernel.  When every agent exchanges with at most two partners (ring, one-peer exponential
-// rounds, matchings) the rows can be ordered into paths and cycles such that a row's in-neighbors
-// sit directly before or after it.  Each thread then owns CW 16-byte column vectors and walks the
-// rows in that order with three live values per vector (previous, this, next): every row is loaded
-// once, combined in CSR order, and stored once.  No LDS, no barriers; all 256 threads of a
-// workgroup read 4 KB of one row per step, and all workgroups walk the rows in the same order, so
-// at any moment the device streams through a few rows over their whole width, like a plain copy.
-// A cycle keeps its first and last rows in registers so that it closes without re-reading (which
-// also makes in-place updates safe: a row is stored only after its last use as an operand).
-static_assert(sizeof(bf::ChainStep) == 32, "ChainStep is read as eight dwords");
-
-template <int DT, int OP, bool WITH_Y, int CW, int THR>
-__global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const int64_t nchunks) {
-  constexpr int EB = Elem<DT>::bytes;
-  constexpr int UC = Elem<DT>::per16;
-  constexpr int UC_LOG = DT == DT_F32 ? 2 : 3;
-  constexpr bool MOM = (OP == OP_MOM_ATC || OP == OP_MOM_AWC);
-  constexpr bool G_ON_LOAD = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED || OP == OP_TRACK);
-  constexpr bool G_ON_STORE = (OP == OP_AWC || OP == OP_MOM_AWC);
-  constexpr bool STATE_ON_LOAD = (OP == OP_MOM_ATC || OP == OP_ED);
-  constexpr int CHUNK_LOG = (THR == 1024 ? 10 : 8) + UC_LOG;   // columns per workgroup sweep
-  const int64_t d = p.d, ld = p.ld;
-  const int64_t last_vec = ((d - 1) >> UC_LOG) << UC_LOG;
-  const csr_i32_ptr steps = (csr_i32_ptr)(uintptr_t)p.chain;
-  const int tid = threadIdx.x;
-
-  for (int64_t cseq = blockIdx.x; cseq < nchunks; cseq += gridDim.x) {
-    const int64_t chunk = p.reverse ? nchunks - 1 - cseq : cseq;   // odd rounds run right to left
-    int64_t col[CW];
-    bool live[CW];
-#pragma unroll
-    for (int w = 0; w < CW; ++w) {
-      const int64_t c = ((chunk * CW + w) << CHUNK_LOG) + (static_cast<int64_t>(tid) << UC_LOG);
-      live[w] = c < d;
-      col[w] = min(c, last_vec);
-    }
-    float prev[CW][UC], cur[CW][UC], nxt[CW][UC], first[CW][UC], last[CW][UC];
-
-    // y_j = x_j, or x_j - alpha g_j, or (momentum) x_j - alpha (beta m_j + g_j) with m_j written back
-    auto load_y = [&](int row, float (*out)[UC]) {
-      u32x4 xr[CW], gr[CW], g2r[CW];
-      f32x4 mr[CW][UC / 4];
-#pragma unroll
-      for (int w = 0; w < CW; ++w) {
-        const int64_t off = static_cast<int64_t>(row) * ld + col[w];
-#if BF_NT_CHAIN_LOAD
-        xr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
-        if constexpr (G_ON_LOAD) gr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g + off * EB));
-#else
-        xr[w] = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
-        if constexpr (G_ON_LOAD) gr[w] = *reinterpret_cast<const u32x4*>(p.g + off * EB);
-#endif
-        if constexpr (OP == OP_TRACK) g2r[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
-        if constexpr (STATE_ON_LOAD) {
-#pragma unroll
-          for (int q = 0; q < UC / 4; ++q) mr[w][q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
-        }
-      }
-#pragma unroll
-      for (int w = 0; w < CW; ++w) {
-        widen<DT>(xr[w], out[w]);
-        if constexpr (G_ON_LOAD) {
-          float gv[UC];
-          widen<DT>(gr[w], gv);
-          if constexpr (STATE_ON_LOAD) {
-            const int64_t off = static_cast<int64_t>(row) * ld + col[w];
-#pragma unroll
-            for (int q = 0; q < UC / 4; ++q) {
-              float sv[4] = {mr[w][q].x, mr[w][q].y, mr[w][q].z, mr[w][q].w};
-              local_update4<OP>(out[w] + 4 * q, gv + 4 * q, sv, p.alpha, p.beta);
-              if (live[w]) {
-                const int64_t rem = d - (col[w] + 4 * q);
-                if (rem >= 4) { f32x4 t = {sv[0], sv[1], sv[2], sv[3]}; *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = t; }
-                else for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + 4 * q + e] = sv[e];
-              }
-            }
-          } else if constexpr (OP == OP_TRACK) {
-            float hv[UC];
-            widen<DT>(g2r[w], hv);
-#pragma unroll
-            for (int e = 0; e < UC; ++e) out[w][e] = (out[w][e] + gv[e]) - hv[e];
-          } else {
-#pragma unroll
-            for (int e = 0; e < UC; ++e) out[w][e] = fmaf(-p.alpha, gv[e], out[w][e]);
-          }
-        }
-      }
-    };
-
-    for (int k = 0; k < p.n; ++k) {
-      // one ChainStep = eight dwords through the scalar cache
-      struct { int row, flags, last_row, next_row, slots; float w[3]; } st;
-      st.row = steps[8 * k + 0]; st.flags = steps[8 * k + 1]; st.last_row = steps[8 * k + 2];
-      st.next_row = steps[8 * k + 3]; st.slots = steps[8 * k + 4];
-      st.w[0] = __int_as_float(steps[8 * k + 5]); st.w[1] = __int_as_float(steps[8 * k + 6]);
-      st.w[2] = __int_as_float(steps[8 * k + 7]);
-      const int flags = st.flags;
-      if (flags & 1) {
-        if (flags & 2) {
-          load_y(st.last_row, last);
-#pragma unroll
-          for (int w = 0; w < CW; ++w)
-#pragma unroll
-            for (int e = 0; e < UC; ++e) prev[w][e] = last[w][e];
-        }
-        load_y(st.row, cur);
-#pragma unroll
-        for (int w = 0; w < CW; ++w)
-#pragma unroll
-          for (int e = 0; e < UC; ++e) first[w][e] = cur[w][e];
-      }
-      const int nk = (flags >> 2) & 3;
-      if (nk == 0) {
-        load_y(st.next_row, nxt);
-      } else if (nk == 1) {
-#pragma unroll
-        for (int w = 0; w < CW; ++w)
-#pragma unroll
-          for (int e = 0; e < UC; ++e) nxt[w][e] = last[w][e];
-      } else if (nk == 2) {
-#pragma unroll
-        for (int w = 0; w < CW; ++w)
-#pragma unroll
-          for (int e = 0; e < UC; ++e) nxt[w][e] = first[w][e];
-      }
-      float acc[CW][UC];
-#pragma unroll
-      for (int w = 0; w < CW; ++w)
-#pragma unroll
-        for (int e = 0; e < UC; ++e) acc[w][e] = 0.0f;
-#pragma unroll
-      for (int en = 0; en < 3; ++en) {
-        const int code = (st.slots >> (4 * en)) & 15;
-        if (code != 15) {
-          const float wt = st.w[en];
-#pragma unroll
-          for (int w = 0; w < CW; ++w)
-#pragma unroll
-            for (int e = 0; e < UC; ++e) {
-              const float v = code == 0 ? prev[w][e] : (code == 1 ? cur[w][e] : nxt[w][e]);
-              acc[w][e] = fmaf(wt, v, acc[w][e]);
-            }
-        }
-      }
-      // finish row st.row
-#pragma unroll
-      for (int w = 0; w < CW; ++w) {
-        if (live[w]) {
-          const int64_t off = static_cast<int64_t>(st.row) * ld + col[w];
-          const int64_t rem = d - col[w];
-          if constexpr (G_ON_STORE) {
-            float gv[UC];
-            widen<DT>(*reinterpret_cast<const u32x4*>(p.g + off * EB), gv);
-            if constexpr (MOM) {
-#pragma unroll
-              for (int q = 0; q < UC / 4; ++q) {
-                float mv[4];
-                load_in<DT_F32, 4>(reinterpret_cast<const char*>(p.m), off + 4 * q, mv);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { mv[e] = fmaf(p.beta, mv[e], gv[4 * q + e]); gv[4 * q + e] = mv[e]; }
-                const int64_t r4 = rem - 4 * q;
-                if (r4 > 0) {
-                  if (r4 >= 4) { f32x4 t = {mv[0], mv[1], mv[2], mv[3]}; *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = t; }
-                  else for (int e = 0; e < 4; ++e) if (e < r4) p.m[off + 4 * q + e] = mv[e];
-                }
-              }
-            }
-#pragma unroll
-            for (int e = 0; e < UC; ++e) acc[w][e] = fmaf(-p.alpha, gv[e], acc[w][e]);
-          }
-          float rcp = 1.0f;
-          if constexpr (WITH_Y) rcp = 1.0f / p.p_out[st.row];
-#pragma unroll
-          for (int h = 0; h < UC / 4; ++h) {
-            const int64_t r4 = rem - 4 * h;
-            if (r4 > 0) {
-              const int valid = r4 >= 4 ? 4 : static_cast<int>(r4);
-              if constexpr (DT == DT_BF16) if (h == 0 && rem >= 8) {
-                // both halves at once: one 16-byte store of eight bf16
-                u32x4 t = {pack_bf16x2(acc[w][0], acc[w][1]), pack_bf16x2(acc[w][2], acc[w][3]),
-                           pack_bf16x2(acc[w][4], acc[w][5]), pack_bf16x2(acc[w][6], acc[w][7])};
-                st_stream<true>(reinterpret_cast<u32x4*>(p.x_out + off * EB), t);
-                if constexpr (WITH_Y) {
-                  u32x4 ty = {pack_bf16x2(acc[w][0] * rcp, acc[w][1] * rcp), pack_bf16x2(acc[w][2] * rcp, acc[w][3] * rcp),
-                              pack_bf16x2(acc[w][4] * rcp, acc[w][5] * rcp), pack_bf16x2(acc[w][6] * rcp, acc[w][7] * rcp)};
-                  st_stream<true>(reinterpret_cast<u32x4*>(p.y + off * EB), ty);
-                }
-                break;
-              }
-              store_out<DT, 4>(p.x_out, off + 4 * h, acc[w] + 4 * h, valid);
-              if constexpr (WITH_Y) {
-                float yv[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) yv[e] = acc[w][4 * h + e] * rcp;
-                store_out<DT, 4>(p.y, off + 4 * h, yv, valid);
-              }
-            }
-          }
-        }
-      }
-#pragma unroll
-      for (int w = 0; w < CW; ++w)
-#pragma unroll
-        for (int e = 0; e < UC; ++e) { prev[w][e] = cur[w][e]; cur[w][e] = nxt[w][e]; }
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Fallback for agent counts whose n x 64 tile does not fit LDS: a plain row gather.  Each thread
-// owns one 16-byte vector of one output row and walks the row's in-neighbor list, reading neighbor
-// vectors from global memory (re-reads are served by L2 / Infinity Cache as far as they fit).
-// Out of place only.  For the momentum ops M has already been advanced by bf_momentum_kernel and
-// stands in for the gradient.
-template <int DT, int OP, bool WITH_Y>
-__global__ __launch_bounds__(256) void bf_gather_kernel(const TileParams p) {
-  constexpr int EB = Elem<DT>::bytes;
-  constexpr int UC = Elem<DT>::per16;
-  constexpr bool MOM = (OP == OP_MOM_ATC || OP == OP_MOM_AWC);
-  constexpr bool G_IN_SUM = (OP == OP_ATC || OP == OP_MOM_ATC);
-  constexpr bool G_AFTER = (OP == OP_AWC || OP == OP_MOM_AWC);
-  const int64_t d = p.d, ld = p.ld;
-  const int64_t upr = (d + UC - 1) / UC;
-  const int64_t total = upr * p.n;
-  auto load_g = [&](int64_t off, float* gv) {
-    if constexpr (MOM) {
-#pragma unroll
-      for (int q = 0; q < UC / 4; ++q) {
-        const f32x4 t = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
-        gv[4 * q] = t.x; gv[4 * q + 1] = t.y; gv[4 * q + 2] = t.z; gv[4 * q + 3] = t.w;
-      }
-    } else {
-      widen<DT>(*reinterpret_cast<const u32x4*>(p.g + off * EB), gv);
-    }
-  };
-  for (int64_t u = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; u < total;
-       u += static_cast<int64_t>(gridDim.x) * blockDim.x) {
-    const int i = static_cast<int>(u / upr);
-    const int64_t col = (u % upr) * UC;
-    float acc[UC];
-#pragma unroll
-    for (int e = 0; e < UC; ++e) acc[e] = 0.0f;
-    for (int q = p.rowptr[i]; q < p.rowptr[i + 1]; ++q) {
-      const u32x2 en = p.ent[q];
-      const float w = __uint_as_float(en.y);
-      const int64_t off = static_cast<int64_t>(en.x) * ld + col;
-      float xv[UC];
-      widen<DT>(*reinterpret_cast<const u32x4*>(p.x_in + off * EB), xv);
-      if constexpr (G_IN_SUM) {
-        float gv[UC];
-        load_g(off, gv);
-#pragma unroll
-        for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
-      }
-#pragma unroll
-      for (int e = 0; e < UC; ++e) acc[e] = fmaf(w, xv[e], acc[e]);
-    }
-    const int64_t off = static_cast<int64_t>(i) * ld + col;
-    if constexpr (G_AFTER) {
-      float gv[UC];
-      load_g(off, gv);
-#pragma unroll
-      for (int e = 0; e < UC; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);
-    }
-    const int64_t rem = d - col;
-#pragma unroll
-    for (int h = 0; h < UC / 4; ++h) {
-      const int valid = rem - 4 * h >= 4 ? 4 : (rem - 4 * h > 0 ? static_cast<int>(rem - 4 * h) : 0);
-      if (valid > 0) {
-        store_out<DT, 4>(p.x_out, off + 4 * h, acc + 4 * h, valid);
-        if constexpr (WITH_Y) {
-          const float rcp = 1.0f / p.p_out[i];
-          float yv[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) yv[e] = acc[4 * h + e] * rcp;
-          store_out<DT, 4>(p.y, off + 4 * h, yv, valid);
-        }
-      }
-    }
-  }
-}
-
-// M <- beta M + G, elementwise (pre-pass of the gather fallback's momentum ops).
-template <int DT>
-__global__ __launch_bounds__(256) void bf_momentum_kernel(float* M, const char* G, int n, int64_t d, int64_t ld, float beta) {
-  constexpr int EB = Elem<DT>::bytes;
-  const int64_t upr = (d + 3) / 4;
-  const int64_t total = upr * n;
-  for (int64_t u = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; u < total;
-       u += static_cast<int64_t>(gridDim.x) * blockDim.x) {
-    const int64_t off = (u / upr) * ld + (u % upr) * 4;
-    const int64_t rem = d - (u % upr) * 4;
-    float gv[4], mv[4];
-    load_in<DT, 4>(G, off, gv);
-    load_in<DT_F32, 4>(reinterpret_cast<const char*>(M), off, mv);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) mv[e] = fmaf(beta, mv[e], gv[e]);
-    store_out<DT_F32, 4, false>(reinterpret_cast<char*>(M), off, mv, rem >= 4 ? 4 : static_cast<int>(rem));
-  }
-}
+using namespace bf;
 
 // ---------------------------------------------------------------------------------------------
 // Push-sum weights: w_out = W w_in for n scalars (the p_i of the push-sum recursion).  One
@@ -1402,7 +547,6 @@ int g_tune_cw = 0;        // chain kernel: 16-byte vectors per thread (1, 2 or 4
 unsigned long long g_dbg_ptr = 0;
 #endif
 
-struct Shape { int log_c; int lw; int wgs_per_cu; int threads; size_t lds_bytes; bool stream; };
 
 int ilog2(int64_t v) { int l = 0; while ((int64_t{1} << (l + 1)) <= v) ++l; return l; }
 
@@ -1449,61 +593,6 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_wgs =
   return BF_OK;
 }
 
-template <int DT, int OP, bool WITH_Y, int LW, int THREADS, bool STREAM, bool MULTI = false>
-int launch_tile_thr(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
-  // prefetch depth: a 64 KB tile is 4 (fp32) / 2 (bf16) vectors per thread at 1024 threads
-  constexpr int MAXPF = DT == DT_F32 ? 4 : 2;
-  auto kern = bf_tile_kernel<DT, OP, WITH_Y, LW, THREADS, MAXPF, STREAM, MULTI>;
-  if (lds > 48 * 1024) {
-    static thread_local size_t raised = 0;
-    if (raised < lds) {
-      BF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     static_cast<int>(lds)));
-      raised = lds;
-    }
-  }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(THREADS), lds, st, tp);
-  BF_HIP_TRY(hipGetLastError());
-  return BF_OK;
-}
-
-// 1024 threads, two workgroups per CU: smaller workgroups (256, 512 threads, more per CU) were
-// measured 5..25 % slower at every tile width.
-template <int DT, int OP, bool WITH_Y, int LW>
-int launch_tile_lw(const TileParams& tp, int grid, size_t lds, bool stream, hipStream_t st) {
-  if constexpr (OP == OP_MIX && !WITH_Y) {
-    // the several-rounds-per-pass form is a kernel of its own, so its extra registers cost the
-    // one-round kernel nothing
-    if (tp.fuse > 1)
-      return stream ? launch_tile_thr<DT, OP, WITH_Y, LW, 1024, true, true>(tp, grid, lds, st)
-                    : launch_tile_thr<DT, OP, WITH_Y, LW, 1024, false, true>(tp, grid, lds, st);
-  }
-  return stream ? launch_tile_thr<DT, OP, WITH_Y, LW, 1024, true>(tp, grid, lds, st)
-                : launch_tile_thr<DT, OP, WITH_Y, LW, 1024, false>(tp, grid, lds, st);
-}
-
-template <int DT, int OP, bool WITH_Y>
-int launch_tile(const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
-  switch (s.lw) {
-    case 4: return launch_tile_lw<DT, OP, WITH_Y, 4>(tp, grid, s.lds_bytes, s.stream, st);
-    case 2: return launch_tile_lw<DT, OP, WITH_Y, 2>(tp, grid, s.lds_bytes, s.stream, st);
-    default: return launch_tile_lw<DT, OP, WITH_Y, 1>(tp, grid, s.lds_bytes, s.stream, st);
-  }
-}
-
-template <int DT>
-int launch_tile_op(int op, bool with_y, const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
-  switch (op) {
-    case OP_MIX: return with_y ? launch_tile<DT, OP_MIX, true>(tp, s, grid, st) : launch_tile<DT, OP_MIX, false>(tp, s, grid, st);
-    case OP_ATC: return with_y ? launch_tile<DT, OP_ATC, true>(tp, s, grid, st) : launch_tile<DT, OP_ATC, false>(tp, s, grid, st);
-    case OP_TRACK: return launch_tile<DT, OP_TRACK, false>(tp, s, grid, st);
-    case OP_AWC: return launch_tile<DT, OP_AWC, false>(tp, s, grid, st);
-    case OP_MOM_ATC: return launch_tile<DT, OP_MOM_ATC, false>(tp, s, grid, st);
-    case OP_ED: return launch_tile<DT, OP_ED, false>(tp, s, grid, st);
-    default: return launch_tile<DT, OP_MOM_AWC, false>(tp, s, grid, st);
-  }
-}
-
 // Overlap test on byte ranges [a, a+na) and [b, b+nb).
 bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
@@ -1524,58 +613,6 @@ int check_matrix_shape(int32_t n, int64_t d, int64_t ld, int dt, MatArgs* ma) {
 }
 
 bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
-
-template <int DT, int CW, int THR>
-int launch_chain_cw(int op, bool with_y, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st) {
-#define BF_CHAIN(OPV, YV) hipLaunchKernelGGL((bf_chain_kernel<DT, OPV, YV, CW, THR>), dim3(grid), dim3(THR), 0, st, tp, nchunks)
-  switch (op) {
-    case OP_MIX: if (with_y) BF_CHAIN(OP_MIX, true); else BF_CHAIN(OP_MIX, false); break;
-    case OP_ATC: if (with_y) BF_CHAIN(OP_ATC, true); else BF_CHAIN(OP_ATC, false); break;
-    case OP_TRACK: BF_CHAIN(OP_TRACK, false); break;
-    case OP_AWC: BF_CHAIN(OP_AWC, false); break;
-    case OP_MOM_AWC: BF_CHAIN(OP_MOM_AWC, false); break;
-    default:
-      // the ops that carry a state matrix through the load path need more than the 128 registers
-      // a 1024-thread workgroup allows: 256-thread variant only
-      if constexpr (THR == 256) {
-        if (op == OP_MOM_ATC) BF_CHAIN(OP_MOM_ATC, false); else BF_CHAIN(OP_ED, false);
-      } else {
-        return BF_ERR_UNSUPPORTED;
-      }
-      break;
-  }
-#undef BF_CHAIN
-  BF_HIP_TRY(hipGetLastError());
-  return BF_OK;
-}
-
-template <int DT>
-int launch_chain(int op, bool with_y, int cw, bool wide, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st) {
-  if (wide) {   // 1024 threads: 64 KB of a row per workgroup per step
-    if constexpr (DT == DT_F32) return launch_chain_cw<DT, 4, 1024>(op, with_y, tp, nchunks, grid, st);
-    else return launch_chain_cw<DT, 2, 1024>(op, with_y, tp, nchunks, grid, st);
-  }
-  if constexpr (DT == DT_F32) {
-    if (cw == 4) return launch_chain_cw<DT, 4, 256>(op, with_y, tp, nchunks, grid, st);
-  }
-  if (cw == 2) return launch_chain_cw<DT, 2, 256>(op, with_y, tp, nchunks, grid, st);
-  return launch_chain_cw<DT, 1, 256>(op, with_y, tp, nchunks, grid, st);
-}
-
-template <int DT>
-int launch_gather(int op, bool with_y, const TileParams& tp, int grid, hipStream_t st) {
-#define BF_GATHER(OPV, YV) hipLaunchKernelGGL((bf_gather_kernel<DT, OPV, YV>), dim3(grid), dim3(256), 0, st, tp)
-  switch (op) {
-    case OP_MIX: if (with_y) BF_GATHER(OP_MIX, true); else BF_GATHER(OP_MIX, false); break;
-    case OP_ATC: if (with_y) BF_GATHER(OP_ATC, true); else BF_GATHER(OP_ATC, false); break;
-    case OP_AWC: BF_GATHER(OP_AWC, false); break;
-    case OP_MOM_ATC: BF_GATHER(OP_MOM_ATC, false); break;
-    default: BF_GATHER(OP_MOM_AWC, false); break;
-  }
-#undef BF_GATHER
-  BF_HIP_TRY(hipGetLastError());
-  return BF_OK;
-}
 
 int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp, int dt, hipStream_t st) {
   if (tp.d == 0) return BF_OK;
@@ -1624,8 +661,8 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
       tp.chain = reinterpret_cast<const bf::ChainStep*>(dc->blob + dc->chain_off[k]);
       int grid = static_cast<int>(std::min<int64_t>(nchunks, static_cast<int64_t>(di.cus) * (wide ? 1 : 8)));
       if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
-      return dt == BF_F32 ? launch_chain<DT_F32>(op, with_y, cw, wide, tp, nchunks, grid, st)
-                          : launch_chain<DT_BF16>(op, with_y, cw, wide, tp, nchunks, grid, st);
+      return dt == BF_F32 ? launch_chain_f32(op, with_y, cw, wide, tp, nchunks, grid, st)
+                          : launch_chain_bf16(op, with_y, cw, wide, tp, nchunks, grid, st);
     }
   }
   Shape s;
@@ -1641,11 +678,10 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     if (op == OP_MOM_ATC || op == OP_MOM_AWC) {
       const int64_t u4 = (tp.d + 3) / 4 * t->n;
       const int g2 = static_cast<int>(std::min<int64_t>((u4 + 255) / 256, static_cast<int64_t>(di.cus) * 32));
-      if (dt == BF_F32) hipLaunchKernelGGL(bf_momentum_kernel<DT_F32>, dim3(g2), dim3(256), 0, st, tp.m, tp.g, t->n, tp.d, tp.ld, tp.beta);
-      else hipLaunchKernelGGL(bf_momentum_kernel<DT_BF16>, dim3(g2), dim3(256), 0, st, tp.m, tp.g, t->n, tp.d, tp.ld, tp.beta);
-      BF_HIP_TRY(hipGetLastError());
+      rc = launch_momentum(dt, tp.m, tp.g, t->n, tp.d, tp.ld, tp.beta, g2, st);
+      if (rc != BF_OK) return rc;
     }
-    return dt == BF_F32 ? launch_gather<DT_F32>(op, with_y, tp, grid, st) : launch_gather<DT_BF16>(op, with_y, tp, grid, st);
+    return dt == BF_F32 ? launch_gather_f32(op, with_y, tp, grid, st) : launch_gather_bf16(op, with_y, tp, grid, st);
   }
   if (rc != BF_OK) return rc;
 #ifdef BF_PROFILE
@@ -1668,8 +704,8 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   tp.ntiles = (tp.d + (int64_t{1} << s.log_c) - 1) >> s.log_c;
   int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus) * s.wgs_per_cu));
   if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
-  return dt == BF_F32 ? launch_tile_op<DT_F32>(op, with_y, tp, s, grid, st)
-                      : launch_tile_op<DT_BF16>(op, with_y, tp, s, grid, st);
+  return dt == BF_F32 ? launch_tile_op_f32(op, with_y, tp, s, grid, st)
+                      : launch_tile_op_bf16(op, with_y, tp, s, grid, st);
 }
 
 // Device copy of a round's window plan, built on first use.
