@@ -191,6 +191,7 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
  * streams that share X or Win race.  X, Win, p, win_p may not overlap (BF_ERR_ALIAS).  A topology
  * without edges has E = 0 slots; Win and win_p may then be NULL.
  *   bf_win_put:        every active j copies x_j into its slot at each out-neighbor (no weights).
+ *   bf_win_get:        every active i copies x_j of each in-neighbor j into its own slot for j.
  *   bf_win_accumulate: every active j adds w_ij x_j (w_ij p_j) to its slot at each out-neighbor i,
  *                      then keeps w_jj x_j (w_jj p_j).
  *   bf_win_update:     every active i sets x_i = w_ii x_i + sum over its slots of w_ij * slot;
@@ -199,6 +200,8 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
  * With W column stochastic, sum(p) + sum(win_p) stays n and sum(X) + sum(Win) stays what it was
  * (up to fp32 rounding) whatever the activity pattern. */
 int bf_win_put(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
+               int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+int bf_win_get(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
                int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 int bf_win_accumulate(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,
                       void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);

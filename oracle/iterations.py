@@ -260,6 +260,19 @@ def win_put(X, Win, W, active=None):
     return Win
 
 
+def win_get(X, Win, W, active=None):
+    """neighbor_win_get without weights: every active agent i fetches x_j of each in-neighbor j
+    into its own slot for j (pull style).  Returns Win'."""
+    X = _f64(X)
+    Win = _f64(Win).copy()
+    slot_ptr, slot_src, _, _ = window_slots(W)
+    for i in range(X.shape[0]):
+        if _is_active(active, i):
+            for e in range(slot_ptr[i], slot_ptr[i + 1]):
+                Win[e, :] = X[slot_src[e], :]
+    return Win
+
+
 def win_accumulate(X, p, Win, win_p, W, active=None):
     """neighbor_win_accumulate in the push-sum use of the section "Asynchronous push-style partial
     averaging": every active agent j adds w_ij x_j (and w_ij p_j) to its slot at each out-neighbor

@@ -29,7 +29,7 @@ EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_topology_chain_plan", "bf_topology_window_slots", "bf_topology_export_window",
-    "bf_win_put", "bf_win_accumulate", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
+    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -89,6 +89,7 @@ def _load():
     L.bf_topology_export_window.argtypes = [vp, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int32),
                                             C.POINTER(C.c_float), C.POINTER(C.c_float)]
     L.bf_win_put.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_win_get.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_update.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_accumulate.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_update_then_collect.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
@@ -356,6 +357,12 @@ def _win_args(t, rnd, active, X, Win, p, win_p):
 def bf_win_put(t, rnd, X, Win, active=None, stream=None):
     ptr, d, ld, act = _win_args(t, rnd, active, X, Win, None, None)
     _check(lib.bf_win_put(t.handle, rnd, act, ptr, Win.data_ptr(), d, ld, _dtype_code(X), _stream(stream)), "bf_win_put")
+    return Win
+
+
+def bf_win_get(t, rnd, X, Win, active=None, stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, None, None)
+    _check(lib.bf_win_get(t.handle, rnd, act, ptr, Win.data_ptr(), d, ld, _dtype_code(X), _stream(stream)), "bf_win_get")
     return Win
 
 

@@ -59,9 +59,10 @@ struct DeviceCopy {
   float*   dense_t = nullptr;            // [round][k][i] = w_ik, n_pad x n_pad, lazily built
   int32_t  n_pad = 0;
   // Window plans, one allocation per round, built on first use: int32 in_ptr[n+1] | f32 slot_w[E] |
-  // f32 self_w[n] | int32 out_ptr[n+1] | {int32 slot, f32 w} out_ent[E], each part 16-byte aligned.
+  // f32 self_w[n] | int32 out_ptr[n+1] | {int32 slot, f32 w} out_ent[E] | int32 slot_src[E], each
+  // part 16-byte aligned.
   std::vector<char*>  win_blob;
-  std::vector<size_t> win_off;           // 5 byte offsets per round
+  std::vector<size_t> win_off;           // 6 byte offsets per round
   std::vector<int32_t> win_slots;        // E per round
 };
 

@@ -57,6 +57,7 @@ struct WinParams {
   const int32_t* active;     // n flags, or null: everybody
   const int32_t* in_ptr;
   const float* slot_w;
+  const int32_t* slot_src;
   const float* self_w;
   const int32_t* out_ptr;
   const u32x2* out_ent;      // {slot, weight bits}
@@ -64,7 +65,7 @@ struct WinParams {
   int32_t n, chunks;
 };
 
-enum { WIN_PUT = 0, WIN_ACCUMULATE = 1, WIN_COLLECT = 2, WIN_AVERAGE = 3 };
+enum { WIN_PUT = 0, WIN_ACCUMULATE = 1, WIN_COLLECT = 2, WIN_AVERAGE = 3, WIN_GET = 4 };
 
 template <int MODE>
 __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
@@ -92,6 +93,18 @@ __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
       const float e[4] = {v.x, v.y, v.z, v.w};
       for (int k = 0; k < valid[u]; ++k) row[col[u] + k] = e[k];      // never the padding
     };
+    if constexpr (MODE == WIN_GET) {
+      for (int e = p.in_ptr[a]; e < p.in_ptr[a + 1]; ++e) {
+        const float* srow = p.x + static_cast<int64_t>(p.slot_src[e]) * p.ld;
+        float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
+        f32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = load(srow, u);
+#pragma unroll
+        for (int u = 0; u < U; ++u) store(wrow, u, v[u]);
+      }
+      continue;
+    }
     float* xrow = p.x + static_cast<int64_t>(a) * p.ld;
     f32x4 x[U];
 #pragma unroll
@@ -712,24 +725,26 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
 int get_window_plan(bf_topology_t* t, size_t k, bf::DeviceCopy* dc, WinParams* wp) {
   std::lock_guard<std::mutex> lk(t->mu);
   const size_t R = t->rounds.size();
-  if (dc->win_blob.empty()) { dc->win_blob.assign(R, nullptr); dc->win_off.assign(R * 5, 0); dc->win_slots.assign(R, 0); }
+  if (dc->win_blob.empty()) { dc->win_blob.assign(R, nullptr); dc->win_off.assign(R * 6, 0); dc->win_slots.assign(R, 0); }
   if (!dc->win_blob[k]) {
     bf::WindowPlan w;
     bf::build_window_plan(t->rounds[k], t->n, &w);
     const size_t E = w.slot_src.size();
     auto pad = [](size_t b) { return (b + 15) / 16 * 16; };
-    size_t off[5];
+    size_t off[6];
     size_t bytes = 0;
     off[0] = bytes; bytes += pad((static_cast<size_t>(t->n) + 1) * 4);
     off[1] = bytes; bytes += pad(E * 4);
     off[2] = bytes; bytes += pad(static_cast<size_t>(t->n) * 4);
     off[3] = bytes; bytes += pad((static_cast<size_t>(t->n) + 1) * 4);
     off[4] = bytes; bytes += pad(E * 8);
+    off[5] = bytes; bytes += pad(E * 4);
     std::vector<char> host(bytes + 16, 0);
     std::memcpy(host.data() + off[0], w.in_ptr.data(), w.in_ptr.size() * 4);
     if (E) std::memcpy(host.data() + off[1], w.slot_w.data(), E * 4);
     std::memcpy(host.data() + off[2], w.self_w.data(), w.self_w.size() * 4);
     std::memcpy(host.data() + off[3], w.out_ptr.data(), w.out_ptr.size() * 4);
+    if (E) std::memcpy(host.data() + off[5], w.slot_src.data(), E * 4);
     uint32_t* oe = reinterpret_cast<uint32_t*>(host.data() + off[4]);
     for (size_t q = 0; q < E; ++q) {
       oe[2 * q] = static_cast<uint32_t>(w.out_slot[q]);
@@ -740,16 +755,17 @@ int get_window_plan(bf_topology_t* t, size_t k, bf::DeviceCopy* dc, WinParams* w
     hipError_t e = hipMemcpy(blob, host.data(), host.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) { (void)hipFree(blob); g_last_hip_error = e; return BF_ERR_HIP; }
     dc->win_blob[k] = blob;
-    for (int q = 0; q < 5; ++q) dc->win_off[k * 5 + q] = off[q];
+    for (int q = 0; q < 6; ++q) dc->win_off[k * 6 + q] = off[q];
     dc->win_slots[k] = static_cast<int32_t>(E);
   }
   const char* b = dc->win_blob[k];
-  const size_t* off = &dc->win_off[k * 5];
+  const size_t* off = &dc->win_off[k * 6];
   wp->in_ptr = reinterpret_cast<const int32_t*>(b + off[0]);
   wp->slot_w = reinterpret_cast<const float*>(b + off[1]);
   wp->self_w = reinterpret_cast<const float*>(b + off[2]);
   wp->out_ptr = reinterpret_cast<const int32_t*>(b + off[3]);
   wp->out_ent = reinterpret_cast<const u32x2*>(b + off[4]);
+  wp->slot_src = reinterpret_cast<const int32_t*>(b + off[5]);
   return BF_OK;
 }
 
@@ -807,6 +823,7 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
     case WIN_PUT: hipLaunchKernelGGL(bf_win_kernel<WIN_PUT>, dim3(grid), dim3(256), 0, st, wp); break;
     case WIN_ACCUMULATE: hipLaunchKernelGGL(bf_win_kernel<WIN_ACCUMULATE>, dim3(grid), dim3(256), 0, st, wp); break;
     case WIN_COLLECT: hipLaunchKernelGGL(bf_win_kernel<WIN_COLLECT>, dim3(grid), dim3(256), 0, st, wp); break;
+    case WIN_GET: hipLaunchKernelGGL(bf_win_kernel<WIN_GET>, dim3(grid), dim3(256), 0, st, wp); break;
     default: hipLaunchKernelGGL(bf_win_kernel<WIN_AVERAGE>, dim3(grid), dim3(256), 0, st, wp); break;
   }
   BF_HIP_TRY(hipGetLastError());
@@ -940,6 +957,11 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
 int bf_win_put(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
                int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
   return win_common(WIN_PUT, t, round, active, const_cast<void*>(X), nullptr, Win, nullptr, d, ld, dt, hip_stream);
+}
+
+int bf_win_get(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
+               int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  return win_common(WIN_GET, t, round, active, const_cast<void*>(X), nullptr, Win, nullptr, d, ld, dt, hip_stream);
 }
 
 int bf_win_accumulate(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,

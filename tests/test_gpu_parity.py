@@ -865,6 +865,10 @@ def test_window_primitives_match_oracle(name, make, n, d, masked):
     ref = O.win_put(hx, hw, W, m_np)
     got = bf.bf_win_put(t, 0, X, Win.clone() if Win.numel() == 0 else empty_like_rows(Win).copy_(Win), active=m_dev)
     assert np.array_equal(host(got), ref), "put copies bits"
+    # get: the pull side
+    ref = O.win_get(hx, hw, W, m_np)
+    got = bf.bf_win_get(t, 0, X, Win.clone() if Win.numel() == 0 else empty_like_rows(Win).copy_(Win), active=m_dev)
+    assert np.array_equal(host(got), ref), "get copies bits"
     # update (weighted average, window kept)
     ref = O.win_update(hx, hw, W, m_np)
     Xc = empty_like_rows(X).copy_(X)

@@ -489,6 +489,26 @@ def test_window_put_then_update_all_active_is_one_mix_round():
     np.testing.assert_allclose(O.win_update(X, Win, W), O.mix(X, W), atol=1e-14)
 
 
+def test_window_get_is_the_pull_side_of_put():
+    rng = np.random.default_rng(34)
+    W = _push_graph(10, 3, 2)
+    X = rng.standard_normal((10, 3))
+    slot_ptr, slot_src, _, _ = O.window_slots(W)
+    E = slot_ptr[-1]
+    stale = np.full((E, 3), -7.0)
+    # everybody active: pulling every slot and pushing every slot fill the window identically
+    np.testing.assert_array_equal(O.win_get(X, stale, W), O.win_put(X, stale, W))
+    np.testing.assert_allclose(O.win_update(X, O.win_get(X, stale, W), W), O.mix(X, W), atol=1e-14)
+    # masks act on different ends: get refreshes the slots OWNED by active agents, put those FED by them
+    act = np.zeros(10, dtype=int); act[3] = 1
+    got = O.win_get(X, stale, W, act)
+    put = O.win_put(X, stale, W, act)
+    for e in range(E):
+        owner = next(i for i in range(10) if slot_ptr[i] <= e < slot_ptr[i + 1])
+        assert (got[e] == (X[slot_src[e]] if owner == 3 else -7.0)).all()
+        assert (put[e] == (X[3] if slot_src[e] == 3 else -7.0)).all()
+
+
 def test_window_hand_worked_two_agents_with_a_late_receiver():
     # W = [[1/2, 1/3], [1/2, 2/3]] (columns sum to one); x = (6, 12), p = (1, 1).
     W = {0: [(0, 0.5), (1, 1.0 / 3.0)], 1: [(0, 0.5), (1, 2.0 / 3.0)]}
