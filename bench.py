@@ -230,11 +230,26 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         tg = time.perf_counter() - tg
+        # the same 200 iterations in one launch: A_i resident in LDS, one workgroup per agent, a grid
+        # barrier per iteration
+        Xp = torch.zeros((n1, dd1), device=dev)
+        workp = torch.empty(2 * n1 * dd1, device=dev)
+        for _ in range(3):
+            bf.bf_dgd_least_squares_run(t1, 0, 200, A1, b1, Xp, workp, d1["alpha"])
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
+        for _ in range(10):
+            bf.bf_dgd_least_squares_run(t1, 0, 200, A1, b1, Xp, workp, d1["alpha"])
+        gave_up = bf.bf_dgd_status(t1)                  # waits for the stream
+        tp = time.perf_counter() - tp
         entry("config1_dgd_least_squares_ring_n16_d1024_f32", A1.numel() * 4 + b1.numel() * 4 + 2 * n1 * dd1 * 4,
               n1, 200, w_, e_, {"iterations_per_s": round(200 / w_, 1),
                                 "iterations_per_s_hip_graph": round(200 / tg, 1),
+                                "iterations_per_s_one_launch": None if gave_up else round(2000 / tp, 1),
                                 "note": "latency bound: two launches per iteration on a 64 KiB state; the second "
-                                        "figure replays a HIP graph of 20 iterations"})
+                                        "figure replays a HIP graph of 20 iterations; the third runs 200 iterations "
+                                        "per launch with A_i resident in LDS and a grid barrier per iteration "
+                                        "(bf_dgd_least_squares_run)"})
         del graph
         out["per_config"] = per
 

@@ -263,6 +263,27 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
                             const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
                             bf_dtype_t dt, void* hip_stream);
 
+/* Decentralized gradient descent on least squares (section "Decentralized linear regression",
+ * eqs. dgd-1 and dgd-2; the adapt-then-combine form of bf_grad_least_squares + bf_atc_step):
+ * `iterations` iterations in ONE launch,
+ *   x_i <- sum_j w_ij^(round0+k) (x_j - alpha A_j^T (A_j x_j - b_j)),   k = 0 .. iterations-1,
+ * for problems small enough that one agent's A_i (m x d fp32) fits one CU's LDS next to 20 KB of
+ * working storage (the paper's example, m = 32, d = 1024, does) and n is at most the number of CUs;
+ * otherwise BF_ERR_UNSUPPORTED and the two-call path is the one to use.  One workgroup per agent
+ * keeps A_i in LDS for the whole run and the agents meet at a grid barrier once per iteration.
+ * A: n x m x d row-major fp32, b: n x m, X: n x d with pitch ld, updated in place; work: device
+ * scratch of 2 * n * ld floats (contents undefined afterwards).  1 <= m <= 64, d a multiple of 4,
+ * 4 <= d <= 4096.  Every barrier wait is bounded: if the workgroups cannot all be resident at once
+ * (the device is busy with other kernels for about a second) the run gives up, X is undefined and
+ * bf_dgd_status reports it.  One such run at a time per topology object (they share the barrier
+ * words); runs on one stream are ordered and safe.
+ * bf_dgd_status: waits for `hip_stream` and writes 1 to *timed_out (host) if the last run on this
+ * topology gave up, else 0. */
+int bf_dgd_least_squares_run(const bf_topology_t* t, int32_t round0, int32_t iterations, int32_t m,
+                             const float* A, const float* b, float* X, float* work, float alpha,
+                             int64_t d, int64_t ld, void* hip_stream);
+int bf_dgd_status(const bf_topology_t* t, int32_t* timed_out, void* hip_stream);
+
 /* Local least-squares gradients of decentralized linear regression (eq. dgd-1):
  *   G[i,:] = A_i^T (A_i x_i - b_i),  A: n x m x d row-major fp32, b: n x m fp32.
  * 1 <= m <= 64, d a multiple of 4.  G must not alias X. */
@@ -303,6 +324,8 @@ int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on t
  *   knob 7: 1 disables the alternating (odd rounds right-to-left) tile order
  *   knob 6: forces the chain kernel (where the round has a chain plan) with 1, 2 or 4 16-byte
  *           vectors per thread, whatever the matrix shape
+ *   knob 10: number of polls a grid-barrier wait of bf_dgd_least_squares_run may take before it
+ *           gives up (tests of the give-up path use a tiny value)
  * Values the kernels cannot honour give BF_ERR_UNSUPPORTED at the next compute call.  Process-wide,
  * not thread safe: for benchmarks and tests only. */
 int bf_set_tuning(int32_t knob, int32_t value);

@@ -29,7 +29,7 @@ EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_topology_chain_plan", "bf_topology_window_slots", "bf_topology_export_window",
-    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
+    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_dgd_least_squares_run", "bf_dgd_status", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -89,6 +89,8 @@ def _load():
     L.bf_topology_export_window.argtypes = [vp, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int32),
                                             C.POINTER(C.c_float), C.POINTER(C.c_float)]
     L.bf_win_put.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_dgd_least_squares_run.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, C.c_float, i64, i64, vp]
+    L.bf_dgd_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
     L.bf_win_get.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_update.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_accumulate.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
@@ -463,6 +465,27 @@ def bf_exact_diffusion_step(t, rnd, X_in, X_out, G, Psi_prev, alpha, stream=None
     _check(lib.bf_exact_diffusion_step(t.handle, rnd, ptr, X_out.data_ptr(), G.data_ptr(), Psi_prev.data_ptr(),
                                        alpha, d, ld, _dtype_code(X_in), _stream(stream)), "bf_exact_diffusion_step")
     return X_out
+
+
+def bf_dgd_least_squares_run(t, rnd0, iterations, A, b, X, work, alpha, stream=None):
+    import torch
+    n, m, d = A.shape
+    xp, xn, xd, ldx = _mat(X, "X")
+    _rows(t, xn)
+    if not A.is_contiguous() or not b.is_contiguous() or (xn, xd) != (n, d) or tuple(b.shape) != (n, m) or \
+            A.dtype != torch.float32 or b.dtype != torch.float32 or X.dtype != torch.float32:
+        raise ValueError("shapes: A (n,m,d) contiguous, b (n,m) contiguous, X (n,d), all float32")
+    if work.dtype != torch.float32 or not work.is_contiguous() or work.numel() < 2 * n * ldx:
+        raise ValueError("work must be a contiguous float32 tensor of at least 2 * n * ld elements")
+    _check(lib.bf_dgd_least_squares_run(t.handle, rnd0, iterations, m, A.data_ptr(), b.data_ptr(), xp, work.data_ptr(),
+                                        alpha, d, ldx, _stream(stream)), "bf_dgd_least_squares_run")
+    return X
+
+
+def bf_dgd_status(t, stream=None):
+    out = C.c_int32(0)
+    _check(lib.bf_dgd_status(t.handle, C.byref(out), _stream(stream)), "bf_dgd_status")
+    return int(out.value)
 
 
 def bf_grad_least_squares(A, b, X, G, stream=None):

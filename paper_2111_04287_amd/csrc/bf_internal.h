@@ -64,6 +64,7 @@ struct DeviceCopy {
   std::vector<char*>  win_blob;
   std::vector<size_t> win_off;           // 6 byte offsets per round
   std::vector<int32_t> win_slots;        // E per round
+  unsigned int* sync = nullptr;          // arrival counter and error word of the grid-barrier kernel
 };
 
 }  // namespace bf

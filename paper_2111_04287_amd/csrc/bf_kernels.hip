@@ -364,6 +364,154 @@ __global__ __launch_bounds__(256) void bf_grad_quadratic_kernel(const char* X, c
 }
 
 // ---------------------------------------------------------------------------------------------
+// Decentralized gradient descent on least squares (eqs. dgd-1, dgd-2), many iterations in ONE
+// launch, for problems small enough that each agent's A_i fits the LDS of one CU (the paper's
+// linear-regression example: 32 x 1024 fp32 = 128 KB).  One 1024-thread workgroup per agent keeps
+// A_i, b_i and x_i in LDS for the whole run.  Per iteration: residual r = A_i x_i - b_i (a wave per
+// row), half step h_i = x_i - alpha A_i^T r (rows split over the threads that share a column
+// vector), publish h_i to global memory, cross the grid barrier, combine the neighbors' half steps
+// in list order.  The half steps are double buffered by iteration parity, so one barrier per
+// iteration is enough: nobody can be more than one iteration ahead.
+//
+// The barrier is a monotonic arrival counter.  Every wait is bounded: after `spin_limit` polls (or
+// as soon as anyone has set the error word) a workgroup sets the error word and leaves, and so
+// does everybody else, so the grid always drains; the result is then undefined and the error word
+// tells the host.  The exchange uses agent-scope atomic stores and loads (the L2 caches of the
+// XCDs are not coherent with each other for ordinary accesses).
+struct DgdParams {
+  const float* A;
+  const float* b;
+  float* X;
+  float* H;                  // 2 x n x ld half steps
+  const char* blob;          // round table + CSR of every round
+  unsigned int* sync;        // [0] arrivals, [1] error
+  int64_t d, ld;
+  int32_t n, m, iters, round_k0, nrounds;
+  float alpha;
+  uint32_t spin_limit;
+};
+
+__global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
+  extern __shared__ f32x4 lds_raw[];
+  float* As = reinterpret_cast<float*>(lds_raw);                 // m x d
+  float* xs = As + static_cast<size_t>(p.m) * p.d;               // d
+  f32x4* part = reinterpret_cast<f32x4*>(xs + p.d);              // 1024 partial column sums
+  float* resid = reinterpret_cast<float*>(part + 1024);          // 64
+  float* bs = resid + 64;                                        // 64
+  __shared__ int failed;
+  const int i = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int d = static_cast<int>(p.d), m = p.m;
+  const int nvec = d >> 2;
+  {
+    const f32x4* src = reinterpret_cast<const f32x4*>(p.A + static_cast<int64_t>(i) * m * d);
+    f32x4* dst = reinterpret_cast<f32x4*>(As);
+    for (int v = tid; v < m * nvec; v += 1024) dst[v] = src[v];
+    for (int c = tid; c < d; c += 1024) xs[c] = p.X[static_cast<int64_t>(i) * p.ld + c];
+    if (tid < m) bs[tid] = p.b[static_cast<int64_t>(i) * m + tid];
+    if (tid == 0) failed = 0;
+  }
+  __syncthreads();
+  int vt = 1024;                                                  // threads side by side on column vectors
+  while (vt > 16 && vt / 2 >= nvec) vt >>= 1;
+  const int rg_count = 1024 / vt, cv = tid % vt, rg = tid / vt;
+  typedef const u32x4 __attribute__((address_space(4)))* csr_u4_ptr;
+  const csr_u4_ptr round_tab = (csr_u4_ptr)(uintptr_t)p.blob;
+  int k_round = p.round_k0;
+  for (int it = 0; it < p.iters; ++it) {
+    // residual
+    for (int k = wave; k < m; k += 16) {
+      const float* row = As + k * d;
+      float s0 = 0.0f, s1 = 0.0f;
+      int c = lane * 4;
+      for (; c + 256 < d; c += 512) {
+        const f32x4 a0 = *reinterpret_cast<const f32x4*>(row + c), x0 = *reinterpret_cast<const f32x4*>(xs + c);
+        const f32x4 a1 = *reinterpret_cast<const f32x4*>(row + c + 256), x1 = *reinterpret_cast<const f32x4*>(xs + c + 256);
+        s0 = fmaf(a0.x, x0.x, s0); s0 = fmaf(a0.y, x0.y, s0); s0 = fmaf(a0.z, x0.z, s0); s0 = fmaf(a0.w, x0.w, s0);
+        s1 = fmaf(a1.x, x1.x, s1); s1 = fmaf(a1.y, x1.y, s1); s1 = fmaf(a1.z, x1.z, s1); s1 = fmaf(a1.w, x1.w, s1);
+      }
+      if (c < d) {
+        const f32x4 a0 = *reinterpret_cast<const f32x4*>(row + c), x0 = *reinterpret_cast<const f32x4*>(xs + c);
+        s0 = fmaf(a0.x, x0.x, s0); s0 = fmaf(a0.y, x0.y, s0); s0 = fmaf(a0.z, x0.z, s0); s0 = fmaf(a0.w, x0.w, s0);
+      }
+      float sum = s0 + s1;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+      if (lane == 0) resid[k] = sum - bs[k];
+    }
+    __syncthreads();
+    // half step, published for the neighbors
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (cv < nvec) {
+      for (int k = rg; k < m; k += rg_count) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(As + k * d + (cv << 2));
+        const float r = resid[k];
+        acc.x = fmaf(a.x, r, acc.x); acc.y = fmaf(a.y, r, acc.y); acc.z = fmaf(a.z, r, acc.z); acc.w = fmaf(a.w, r, acc.w);
+      }
+    }
+    part[tid] = acc;
+    __syncthreads();
+    float* hbase = p.H + (static_cast<int64_t>(it & 1) * p.n) * p.ld;
+    if (rg == 0 && cv < nvec) {
+      for (int q = 1; q < rg_count; ++q) {
+        const f32x4 t = part[q * vt + cv];
+        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+      }
+      const f32x4 x = *reinterpret_cast<const f32x4*>(xs + (cv << 2));
+      float* h = hbase + static_cast<int64_t>(i) * p.ld + (cv << 2);
+      __hip_atomic_store(h + 0, fmaf(-p.alpha, acc.x, x.x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(h + 1, fmaf(-p.alpha, acc.y, x.y), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(h + 2, fmaf(-p.alpha, acc.z, x.z), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(h + 3, fmaf(-p.alpha, acc.w, x.w), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // Grid barrier number it+1.  The half steps went out as agent-scope stores; each wave waits for
+    // its own to be acknowledged (workgroup-scope release), the workgroup meets, and one thread
+    // signals with an agent-scope release.  It polls with relaxed loads (an acquire load per poll
+    // would invalidate the L2 each time) and takes one agent-scope acquire fence at the end.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0) {
+      __hip_atomic_fetch_add(p.sync, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned int target = static_cast<unsigned int>(p.n) * static_cast<unsigned int>(it + 1);
+      uint32_t polls = 0;
+      while (__hip_atomic_load(p.sync, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        if (++polls > p.spin_limit || __hip_atomic_load(p.sync + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+          __hip_atomic_store(p.sync + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          failed = 1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    __syncthreads();
+    if (failed) break;                                            // uniform: every thread reads the same LDS word
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    // combine (eq. dgd-2) in list order
+    const u32x4 offs = round_tab[k_round];
+    const csr_i32_ptr rp = (csr_i32_ptr)(reinterpret_cast<uintptr_t>(p.blob) + offs.x);
+    const csr_ent_ptr en = (csr_ent_ptr)(reinterpret_cast<uintptr_t>(p.blob) + offs.y);
+    k_round = k_round + 1 == p.nrounds ? 0 : k_round + 1;
+    const int beg = rp[i], end = rp[i + 1];
+    for (int c = tid; c < d; c += 1024) {
+      float a = 0.0f;
+      for (int q = beg; q < end; ++q) {
+        const u32x2 e = en[q];
+        const float hv = __hip_atomic_load(hbase + static_cast<int64_t>(e.x) * p.ld + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a = fmaf(__uint_as_float(e.y), hv, a);
+      }
+      xs[c] = a;
+    }
+    __syncthreads();
+  }
+  for (int c = tid; c < d; c += 1024) p.X[static_cast<int64_t>(i) * p.ld + c] = xs[c];
+}
+
+__global__ void bf_sync_clear_kernel(unsigned int* sync) {
+  if (threadIdx.x < 2) sync[threadIdx.x] = 0u;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Consensus diagnostics in fp64: one thread per column, two passes over the n rows.
 __global__ void bf_stats_clear_kernel(double* stats) {
   if (threadIdx.x < 3) stats[threadIdx.x] = 0.0;
@@ -556,6 +704,7 @@ int g_tune_noserp = 0;    // 1: always walk tiles left to right
 int g_tune_chain256 = 0;  // 1: chain kernel never uses 1024-thread workgroups
 int g_tune_stream = 0;    // 1: always non-temporal, 2: never
 int g_tune_cw = 0;        // chain kernel: 16-byte vectors per thread (1, 2 or 4)
+int g_tune_spin = 0;      // polls a grid-barrier wait may take before it gives up (0: default)
 #ifdef BF_PROFILE
 unsigned long long g_dbg_ptr = 0;
 #endif
@@ -849,6 +998,7 @@ int bf_set_tuning(int32_t knob, int32_t value) {
   else if (knob == 9) g_tune_chain256 = value;
   else if (knob == 8) g_tune_stream = value;
   else if (knob == 6) g_tune_cw = value;
+  else if (knob == 10) g_tune_spin = value;
 #ifdef BF_PROFILE
   else if (knob == 100) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFF00000000ull) | static_cast<uint32_t>(value);
   else if (knob == 101) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFFull) | (static_cast<unsigned long long>(static_cast<uint32_t>(value)) << 32);
@@ -867,6 +1017,7 @@ int bf_topology_destroy(bf_topology_t* t) {
     if (c.dense_t && hipFree(c.dense_t) != hipSuccess) rc = BF_ERR_HIP;
     for (char* wb : c.win_blob)
       if (wb && hipFree(wb) != hipSuccess) rc = BF_ERR_HIP;
+    if (c.sync && hipFree(c.sync) != hipSuccess) rc = BF_ERR_HIP;
   }
   delete t;
   return rc;
@@ -1171,6 +1322,79 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
   tp.alpha = alpha;
   tp.d = d; tp.ld = ld;
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_ED, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int bf_dgd_least_squares_run(const bf_topology_t* tc, int32_t round0, int32_t iterations, int32_t m,
+                             const float* A, const float* b, float* X, float* work, float alpha,
+                             int64_t d, int64_t ld, void* hip_stream) {
+  if (!tc || !A || !b || !X || !work) return BF_ERR_NULL;
+  if (round0 < 0) return BF_ERR_ROUND;
+  bf_topology_t* t = const_cast<bf_topology_t*>(tc);
+  const int32_t n = t->n;
+  if (iterations < 0 || m < 1 || m > 64 || d < 4 || (d % 4) != 0 || ld < d || (ld % 4) != 0) return BF_ERR_SIZE;
+  if (static_cast<uint64_t>(n) * static_cast<uint64_t>(iterations) >= (uint64_t{1} << 32)) return BF_ERR_SIZE;
+  if (misaligned16(A) || misaligned16(X) || misaligned16(work) || (reinterpret_cast<uintptr_t>(b) & 3u)) return BF_ERR_ALIGN;
+  const size_t xb = (static_cast<size_t>(n - 1) * ld + d) * 4, wb = (static_cast<size_t>(2 * n - 1) * ld + d) * 4;
+  const size_t ab = static_cast<size_t>(n) * m * d * 4, bb = static_cast<size_t>(n) * m * 4;
+  if (overlaps(X, xb, work, wb) || overlaps(X, xb, A, ab) || overlaps(X, xb, b, bb) || overlaps(work, wb, A, ab) ||
+      overlaps(work, wb, b, bb))
+    return BF_ERR_ALIAS;
+  if (d > 4096) return BF_ERR_UNSUPPORTED;
+  if (iterations == 0) return BF_OK;
+  bf::DeviceCopy* dc = nullptr;
+  int rc = get_device_copy(t, false, &dc);
+  if (rc != BF_OK) return rc;
+  DeviceInfo di;
+  rc = device_info(dc->device, &di);
+  if (rc != BF_OK) return rc;
+  // one workgroup per agent, all resident at once, A_i in LDS
+  const size_t lds = static_cast<size_t>(m) * d * 4 + static_cast<size_t>(d) * 4 + 1024 * 16 + 128 * 4;
+  const size_t lds_max = std::min(di.lds_per_cu ? di.lds_per_cu : size_t{65536},
+                                  di.lds_per_block_optin ? di.lds_per_block_optin : size_t{65536});
+  if (lds + 64 > lds_max || n > di.cus) return BF_ERR_UNSUPPORTED;   // 64: the kernel's static LDS
+  {
+    std::lock_guard<std::mutex> lk(t->mu);
+    if (!dc->sync) BF_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&dc->sync), 256));
+  }
+  if (lds > 48 * 1024) {
+    static thread_local size_t raised = 0;
+    if (raised < lds) {
+      BF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bf_dgd_ls_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+      raised = lds;
+    }
+  }
+  DgdParams p{};
+  p.A = A; p.b = b; p.X = X; p.H = work;
+  p.blob = dc->blob;
+  p.sync = dc->sync;
+  p.d = d; p.ld = ld; p.n = n; p.m = m; p.iters = iterations;
+  p.round_k0 = static_cast<int32_t>(static_cast<size_t>(round0) % t->rounds.size());
+  p.nrounds = static_cast<int32_t>(t->rounds.size());
+  p.alpha = alpha;
+  p.spin_limit = g_tune_spin > 0 ? static_cast<uint32_t>(g_tune_spin) : (1u << 20);   // of the order of a second of polling
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(bf_sync_clear_kernel, dim3(1), dim3(64), 0, st, dc->sync);
+  BF_HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(bf_dgd_ls_kernel, dim3(n), dim3(1024), lds, st, p);
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+int bf_dgd_status(const bf_topology_t* tc, int32_t* timed_out, void* hip_stream) {
+  if (!tc || !timed_out) return BF_ERR_NULL;
+  bf_topology_t* t = const_cast<bf_topology_t*>(tc);
+  bf::DeviceCopy* dc = nullptr;
+  int rc = get_device_copy(t, false, &dc);
+  if (rc != BF_OK) return rc;
+  *timed_out = 0;
+  if (!dc->sync) return BF_OK;                       // never run on this device
+  unsigned int host[2] = {0u, 0u};
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  BF_HIP_TRY(hipMemcpyAsync(host, dc->sync, sizeof(host), hipMemcpyDeviceToHost, st));
+  BF_HIP_TRY(hipStreamSynchronize(st));
+  *timed_out = host[1] != 0u ? 1 : 0;
+  return BF_OK;
 }
 
 int bf_grad_least_squares(int32_t n, int32_t m, int64_t d, const float* A, const float* b,

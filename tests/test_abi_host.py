@@ -258,6 +258,21 @@ def test_compute_calls_validate_before_touching_the_device():
     assert L.bf_win_put(h, 0, None, None, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
     assert L.bf_win_update(h, 0, None, A, B + 4, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIGN
     assert L.bf_win_update_then_collect(h, 0, None, A, W1b, B, W2b, 62, 62, bf.BF_F32, None) == bf.BF_ERR_ALIGN
+    dg = L.bf_dgd_least_squares_run
+    WK, G = 0x70000000, 0x40000000
+    assert dg(None, 0, 5, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_NULL
+    assert dg(h, 0, 5, 32, A, B, G, None, 1e-3, 1024, 1024, None) == bf.BF_ERR_NULL
+    assert dg(h, -1, 5, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_ROUND
+    assert dg(h, 0, -1, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_SIZE
+    assert dg(h, 0, 5, 0, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_SIZE
+    assert dg(h, 0, 5, 65, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_SIZE
+    assert dg(h, 0, 5, 32, A, B, G, WK, 1e-3, 1022, 1024, None) == bf.BF_ERR_SIZE      # d not a multiple of 4
+    assert dg(h, 0, 5, 32, A, B, G, WK, 1e-3, 1024, 1000, None) == bf.BF_ERR_SIZE      # ld < d
+    assert dg(h, 0, 5, 32, A, B, G + 4, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_ALIGN
+    assert dg(h, 0, 5, 32, A, B, G, G + 4096, 1e-3, 1024, 1024, None) == bf.BF_ERR_ALIAS  # work inside X
+    assert dg(h, 0, 5, 32, A, B, G, WK, 1e-3, 8192, 8192, None) == bf.BF_ERR_UNSUPPORTED
+    assert dg(h, 0, 0, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_OK              # nothing to do
+    assert L.bf_dgd_status(None, None, None) == bf.BF_ERR_NULL
     hn = L.bf_hierarchical_neighbor_allreduce
     assert hn(h, 0, 0, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE       # local_size < 1
     assert hn(h, 0, 1 << 19, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE

@@ -999,3 +999,89 @@ def test_dgd_iterations_replayed_from_a_hip_graph_match_eager():
         torch.cuda.synchronize()
         if rep >= 2:
             assert torch.equal(X[0], eager[rep - 2]), "replay %d differs from eager" % rep
+
+
+# ------------------------------------------------------------------ many DGD iterations in one launch
+def _dgd_reference(A, b, W_of_round, alpha, iters, X0):
+    x = X0.copy()
+    for k in range(iters):
+        x = O.atc_step(x, O.ls_grad(A, b, x), W_of_round(k), alpha)
+    return x
+
+
+@pytest.mark.parametrize("name,make", [TOPOS[0], TOPOS[1], TOPOS[2]])
+@pytest.mark.parametrize("n,m,d,iters", [(16, 32, 1024, 1), (16, 32, 1024, 2), (16, 32, 1024, 25), (8, 16, 520, 9),
+                                         (5, 7, 64, 12), (1, 3, 16, 4), (32, 64, 256, 6), (16, 4, 4096, 3)])
+def test_dgd_run_in_one_launch_matches_oracle(name, make, n, m, d, iters):
+    t = make(n)
+    R = bf.bf_topology_rounds(t)
+    Ws = [lib_W(t, r) for r in range(R)]
+    g = torch.Generator(device=DEV).manual_seed(900 + n + m)
+    A = torch.randn((n, m, d), device=DEV, generator=g) / (d ** 0.5)
+    b = torch.randn((n, m), device=DEV, generator=g)
+    X = rows(n, d, 901 + n, std=0.5)
+    alpha = float(np.float32(0.4))
+    ref = _dgd_reference(host(A.reshape(n * m, d)).reshape(n, m, d), host(b), lambda k: Ws[(1 + k) % R], alpha, iters, host(X))
+    ld = X.stride(0) if n > 1 else d
+    work = torch.empty(2 * n * ld, device=DEV)
+    bf.bf_dgd_least_squares_run(t, 1, iters, A, b, X, work, alpha)
+    assert bf.bf_dgd_status(t) == 0
+    assert_close(X, ref, 2e-5, "%s n=%d m=%d d=%d after %d iterations" % (name, n, m, d, iters))
+
+
+def test_dgd_run_config1_200_iterations_and_two_runs_in_a_row():
+    data = workloads.config1_least_squares(DEV)
+    A, b, alpha = data["A"], data["b"], data["alpha"]
+    n, m, d = A.shape
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    W = lib_W(t)
+    X = torch.zeros((n, d), device=DEV)
+    work = torch.empty(2 * n * d, device=DEV)
+    Ah, bh = host(A.reshape(n * m, d)).reshape(n, m, d), host(b)
+    ref = _dgd_reference(Ah, bh, lambda k: W, float(np.float32(alpha)), 120, np.zeros((n, d)))
+    bf.bf_dgd_least_squares_run(t, 0, 120, A, b, X, work, alpha)
+    assert_close(X, ref, 2e-5, "120 iterations")
+    ref = _dgd_reference(Ah, bh, lambda k: W, float(np.float32(alpha)), 80, ref)
+    bf.bf_dgd_least_squares_run(t, 0, 80, A, b, X, work, alpha)       # continues from the state of the first run
+    assert bf.bf_dgd_status(t) == 0
+    assert_close(X, ref, 3e-5, "200 iterations in two runs")
+    # the same 200 iterations by the two-call path
+    Y = [torch.zeros((n, d), device=DEV), torch.zeros((n, d), device=DEV)]
+    G = torch.empty((n, d), device=DEV)
+    for k in range(200):
+        bf.bf_grad_least_squares(A, b, Y[k & 1], G)
+        bf.bf_atc_step(t, k, Y[k & 1], Y[1 - (k & 1)], G, None, alpha, 0.0, bf.BF_ATC)
+    assert float((X - Y[0]).abs().max()) <= 2e-5 * float(Y[0].abs().max())
+
+
+def test_dgd_run_gives_up_instead_of_hanging_when_its_wait_is_cut_short():
+    # the host shrinks the barrier's poll budget to one poll: the first workgroup to arrive cannot see
+    # the others in time, raises the error word, and every workgroup leaves; nothing hangs
+    data = workloads.config1_least_squares(DEV)
+    A, b = data["A"], data["b"]
+    n, m, d = A.shape
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    X = torch.zeros((n, d), device=DEV)
+    work = torch.empty(2 * n * d, device=DEV)
+    bf.bf_set_tuning(10, 1)
+    try:
+        bf.bf_dgd_least_squares_run(t, 0, 50, A, b, X, work, data["alpha"])
+        gave_up = bf.bf_dgd_status(t)
+    finally:
+        bf.bf_set_tuning(10, 0)
+    assert gave_up == 1
+    # and the next run, with the normal budget, is clean
+    X.zero_()
+    bf.bf_dgd_least_squares_run(t, 0, 3, A, b, X, work, data["alpha"])
+    assert bf.bf_dgd_status(t) == 0
+    assert bool(torch.isfinite(X).all())
+
+
+def test_dgd_run_refuses_what_does_not_fit():
+    n, m, d = 4, 64, 1024                   # 256 KB of A_i: more than one CU's LDS
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    A = torch.zeros((n, m, d), device=DEV); b = torch.zeros((n, m), device=DEV)
+    X = torch.zeros((n, d), device=DEV); work = torch.empty(2 * n * d, device=DEV)
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_dgd_least_squares_run(t, 0, 2, A, b, X, work, 1e-3)
+    assert e.value.code == bf.BF_ERR_UNSUPPORTED
