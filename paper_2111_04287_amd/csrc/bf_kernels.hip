@@ -495,10 +495,22 @@ __global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
     const int beg = rp[i], end = rp[i + 1];
     for (int c = tid; c < d; c += 1024) {
       float a = 0.0f;
-      for (int q = beg; q < end; ++q) {
-        const u32x2 e = en[q];
-        const float hv = __hip_atomic_load(hbase + static_cast<int64_t>(e.x) * p.ld + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        a = fmaf(__uint_as_float(e.y), hv, a);
+      // up to eight neighbors' values are requested before the first is used: each is a round trip
+      // to the memory the XCDs share
+      for (int q0 = beg; q0 < end; q0 += 8) {
+        const int cnt = end - q0 < 8 ? end - q0 : 8;
+        float hv[8], wv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (u < cnt) {
+            const u32x2 e = en[q0 + u];
+            wv[u] = __uint_as_float(e.y);
+            hv[u] = __hip_atomic_load(hbase + static_cast<int64_t>(e.x) * p.ld + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (u < cnt) a = fmaf(wv[u], hv[u], a);
       }
       xs[c] = a;
     }
