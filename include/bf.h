@@ -325,7 +325,9 @@ int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on t
  *   knob 6: forces the chain kernel (where the round has a chain plan) with 1, 2 or 4 16-byte
  *           vectors per thread, whatever the matrix shape
  *   knob 10: number of polls a grid-barrier wait of bf_dgd_least_squares_run may take before it
- *           gives up (tests of the give-up path use a tiny value)
+ *           gives up
+ *   knob 11: 1 makes that barrier wait for one arrival more than there are workgroups, so that it
+ *           must give up (with knob 10 small, the test of the give-up path: the kernel still exits)
  * Values the kernels cannot honour give BF_ERR_UNSUPPORTED at the next compute call.  Process-wide,
  * not thread safe: for benchmarks and tests only. */
 int bf_set_tuning(int32_t knob, int32_t value);

@@ -389,6 +389,7 @@ struct DgdParams {
   int32_t n, m, iters, round_k0, nrounds;
   float alpha;
   uint32_t spin_limit;
+  uint32_t extra_arrivals;   // 0; a test sets 1 so that the barrier can never complete and must give up
 };
 
 __global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
@@ -472,7 +473,7 @@ __global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
     __syncthreads();
     if (tid == 0) {
       __hip_atomic_fetch_add(p.sync, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-      const unsigned int target = static_cast<unsigned int>(p.n) * static_cast<unsigned int>(it + 1);
+      const unsigned int target = static_cast<unsigned int>(p.n) * static_cast<unsigned int>(it + 1) + p.extra_arrivals;
       uint32_t polls = 0;
       while (__hip_atomic_load(p.sync, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
         if (++polls > p.spin_limit || __hip_atomic_load(p.sync + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
@@ -717,6 +718,7 @@ int g_tune_chain256 = 0;  // 1: chain kernel never uses 1024-thread workgroups
 int g_tune_stream = 0;    // 1: always non-temporal, 2: never
 int g_tune_cw = 0;        // chain kernel: 16-byte vectors per thread (1, 2 or 4)
 int g_tune_spin = 0;      // polls a grid-barrier wait may take before it gives up (0: default)
+int g_tune_extra = 0;     // 1: the grid barrier waits for an arrival that never comes (give-up test)
 #ifdef BF_PROFILE
 unsigned long long g_dbg_ptr = 0;
 #endif
@@ -1011,6 +1013,7 @@ int bf_set_tuning(int32_t knob, int32_t value) {
   else if (knob == 8) g_tune_stream = value;
   else if (knob == 6) g_tune_cw = value;
   else if (knob == 10) g_tune_spin = value;
+  else if (knob == 11) g_tune_extra = value;
 #ifdef BF_PROFILE
   else if (knob == 100) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFF00000000ull) | static_cast<uint32_t>(value);
   else if (knob == 101) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFFull) | (static_cast<unsigned long long>(static_cast<uint32_t>(value)) << 32);
@@ -1384,6 +1387,7 @@ int bf_dgd_least_squares_run(const bf_topology_t* tc, int32_t round0, int32_t it
   p.round_k0 = static_cast<int32_t>(static_cast<size_t>(round0) % t->rounds.size());
   p.nrounds = static_cast<int32_t>(t->rounds.size());
   p.alpha = alpha;
+  p.extra_arrivals = g_tune_extra ? 1u : 0u;
   p.spin_limit = g_tune_spin > 0 ? static_cast<uint32_t>(g_tune_spin) : (1u << 20);   // of the order of a second of polling
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(bf_sync_clear_kernel, dim3(1), dim3(64), 0, st, dc->sync);

@@ -1054,23 +1054,26 @@ def test_dgd_run_config1_200_iterations_and_two_runs_in_a_row():
     assert float((X - Y[0]).abs().max()) <= 2e-5 * float(Y[0].abs().max())
 
 
-def test_dgd_run_gives_up_instead_of_hanging_when_its_wait_is_cut_short():
-    # the host shrinks the barrier's poll budget to one poll: the first workgroup to arrive cannot see
-    # the others in time, raises the error word, and every workgroup leaves; nothing hangs
+def test_dgd_run_gives_up_instead_of_hanging_when_the_barrier_cannot_complete():
+    # the host makes the barrier wait for one arrival more than there are workgroups and gives it a
+    # small poll budget: every workgroup runs out of polls (or sees that another did), raises the
+    # error word and leaves; nothing hangs, and the host is told
     data = workloads.config1_least_squares(DEV)
     A, b = data["A"], data["b"]
     n, m, d = A.shape
     t = bf.bf_topology_create(bf.BF_RING, n)
     X = torch.zeros((n, d), device=DEV)
     work = torch.empty(2 * n * d, device=DEV)
-    bf.bf_set_tuning(10, 1)
+    bf.bf_set_tuning(10, 200)
+    bf.bf_set_tuning(11, 1)
     try:
         bf.bf_dgd_least_squares_run(t, 0, 50, A, b, X, work, data["alpha"])
         gave_up = bf.bf_dgd_status(t)
     finally:
         bf.bf_set_tuning(10, 0)
+        bf.bf_set_tuning(11, 0)
     assert gave_up == 1
-    # and the next run, with the normal budget, is clean
+    # and the next run, with the normal settings, is clean
     X.zero_()
     bf.bf_dgd_least_squares_run(t, 0, 3, A, b, X, work, data["alpha"])
     assert bf.bf_dgd_status(t) == 0
