@@ -161,6 +161,15 @@ def main():
         b = torch.empty_like(a)
         w_, e_ = timed(lambda k: b.copy_(a), 20, 3)
         out["copy_ceiling_GBps"] = round(2 * a.numel() * 4 * 20 / w_ / 1e9, 1)
+        # the library's own plain 128-bit streaming kernels, best persistent-grid size of a small sweep
+        ceil = {}
+        for mode, name, nbytes in ((0, "copy", 2 * a.numel() * 4), (1, "read_only", a.numel() * 4), (2, "write_only", a.numel() * 4)):
+            best = 0.0
+            for wgs in (1, 2, 4, 8, 16):
+                w_, e_ = timed(lambda k: bf.bf_stream_probe(mode, None if mode == 2 else a, b, wgs), 10, 2)
+                best = max(best, nbytes * 10 / w_ / 1e9)
+            ceil[name + "_GBps"] = round(best, 1)
+        out["stream_ceilings_128bit"] = ceil
         del a, b
 
         # configuration 3: dynamic one-peer exponential-2, n=256, d=2^22, 8 rounds per sweep

@@ -310,6 +310,15 @@ int bf_consensus_stats(int32_t n, int64_t d, int64_t ld, const void* X, const fl
  * Any ld >= d with a 16-byte-multiple pitch is accepted by the compute calls.  Negative on error. */
 int64_t bf_recommended_ld(int64_t d, bf_dtype_t dt);
 
+/* Plain streaming kernels with 128-bit accesses, for measuring the practical bandwidth ceilings the
+ * mixing kernels are compared with (not part of the method).  mode 0: dst <- src (bytes read and
+ * bytes written); mode 1: read src only (dst, at least 16 * 256 * workgroups bytes, is written
+ * only if the data sum to a particular value, which keeps the loads alive); mode 2: fill dst with
+ * a constant.  bytes is a multiple of 16; workgroups_per_cu (1..64) sets the size of the
+ * persistent grid. */
+int bf_stream_probe(int32_t mode, const void* src, void* dst, int64_t bytes, int32_t workgroups_per_cu,
+                    void* hip_stream);
+
 const char* bf_strerror(int code);
 int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on this thread        */
 

@@ -29,7 +29,7 @@ EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_topology_chain_plan", "bf_topology_window_slots", "bf_topology_export_window",
-    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_dgd_least_squares_run", "bf_dgd_status", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
+    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_dgd_least_squares_run", "bf_dgd_status", "bf_stream_probe", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -91,6 +91,7 @@ def _load():
     L.bf_win_put.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_dgd_least_squares_run.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, C.c_float, i64, i64, vp]
     L.bf_dgd_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
+    L.bf_stream_probe.argtypes = [i32, vp, vp, i64, i32, vp]
     L.bf_win_get.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_update.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_accumulate.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
@@ -486,6 +487,16 @@ def bf_dgd_status(t, stream=None):
     out = C.c_int32(0)
     _check(lib.bf_dgd_status(t.handle, C.byref(out), _stream(stream)), "bf_dgd_status")
     return int(out.value)
+
+
+def bf_stream_probe(mode, src, dst, workgroups_per_cu=1, stream=None):
+    """mode 0 copy, 1 read only, 2 write only, over dst.numel() * element_size bytes."""
+    nbytes = dst.numel() * dst.element_size()
+    if not dst.is_contiguous() or (src is not None and (not src.is_contiguous() or src.numel() * src.element_size() < nbytes)):
+        raise ValueError("contiguous tensors, src at least as large as dst")
+    _check(lib.bf_stream_probe(mode, None if src is None else src.data_ptr(), dst.data_ptr(), nbytes, workgroups_per_cu,
+                               _stream(stream)), "bf_stream_probe")
+    return dst
 
 
 def bf_grad_least_squares(A, b, X, G, stream=None):

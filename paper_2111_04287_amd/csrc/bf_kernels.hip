@@ -525,6 +525,40 @@ __global__ void bf_sync_clear_kernel(unsigned int* sync) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Plain streaming kernels with 128-bit accesses: the practical ceilings (copy, read only, write
+// only) that the mixing kernels' bandwidth is compared with.  Persistent grid-stride loops, four
+// vectors in flight per thread, non-temporal hints.
+template <int MODE>
+__global__ __launch_bounds__(256) void bf_stream_probe_kernel(const f32x4* src, f32x4* dst, int64_t n4) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * 256;
+  int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  const f32x4 fill = {1.f, 2.f, 3.f, 4.f};
+  for (; i + 3 * stride < n4; i += 4 * stride) {
+    f32x4 v[4];
+    if constexpr (MODE != 2) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if constexpr (MODE == 0) __builtin_nontemporal_store(v[u], dst + i + u * stride);
+      else if constexpr (MODE == 1) acc += v[u];
+      else __builtin_nontemporal_store(fill, dst + i + u * stride);
+    }
+  }
+  for (; i < n4; i += stride) {
+    if constexpr (MODE == 0) dst[i] = src[i];
+    else if constexpr (MODE == 1) acc += src[i];
+    else dst[i] = fill;
+  }
+  if constexpr (MODE == 1) {
+    // one partial sum per thread of the first workgroup's worth of slots keeps the loads alive
+    if (acc.x + acc.y + acc.z + acc.w == 0.12345f) dst[blockIdx.x] = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Consensus diagnostics in fp64: one thread per column, two passes over the n rows.
 __global__ void bf_stats_clear_kernel(double* stats) {
   if (threadIdx.x < 3) stats[threadIdx.x] = 0.0;
@@ -1410,6 +1444,31 @@ int bf_dgd_status(const bf_topology_t* tc, int32_t* timed_out, void* hip_stream)
   BF_HIP_TRY(hipMemcpyAsync(host, dc->sync, sizeof(host), hipMemcpyDeviceToHost, st));
   BF_HIP_TRY(hipStreamSynchronize(st));
   *timed_out = host[1] != 0u ? 1 : 0;
+  return BF_OK;
+}
+
+int bf_stream_probe(int32_t mode, const void* src, void* dst, int64_t bytes, int32_t workgroups_per_cu,
+                    void* hip_stream) {
+  if (mode < 0 || mode > 2) return BF_ERR_KIND;
+  if ((mode != 2 && !src) || !dst) return BF_ERR_NULL;
+  if (bytes < 0 || (bytes % 16) != 0 || workgroups_per_cu < 1 || workgroups_per_cu > 64) return BF_ERR_SIZE;
+  if ((src && misaligned16(src)) || misaligned16(dst)) return BF_ERR_ALIGN;
+  if (mode == 0 && overlaps(src, static_cast<size_t>(bytes), dst, static_cast<size_t>(bytes))) return BF_ERR_ALIAS;
+  if (bytes == 0) return BF_OK;
+  int dev = 0;
+  BF_HIP_TRY(hipGetDevice(&dev));
+  DeviceInfo di;
+  int rc = device_info(dev, &di);
+  if (rc != BF_OK) return rc;
+  const int64_t n4 = bytes / 16;
+  const int grid = static_cast<int>(std::min<int64_t>((n4 + 255) / 256, static_cast<int64_t>(di.cus) * workgroups_per_cu));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const f32x4* s4 = static_cast<const f32x4*>(src);
+  f32x4* d4 = static_cast<f32x4*>(dst);
+  if (mode == 0) hipLaunchKernelGGL(bf_stream_probe_kernel<0>, dim3(grid), dim3(256), 0, st, s4, d4, n4);
+  else if (mode == 1) hipLaunchKernelGGL(bf_stream_probe_kernel<1>, dim3(grid), dim3(256), 0, st, s4, d4, n4);
+  else hipLaunchKernelGGL(bf_stream_probe_kernel<2>, dim3(grid), dim3(256), 0, st, s4, d4, n4);
+  BF_HIP_TRY(hipGetLastError());
   return BF_OK;
 }
 

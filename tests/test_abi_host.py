@@ -273,6 +273,15 @@ def test_compute_calls_validate_before_touching_the_device():
     assert dg(h, 0, 5, 32, A, B, G, WK, 1e-3, 8192, 8192, None) == bf.BF_ERR_UNSUPPORTED
     assert dg(h, 0, 0, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_OK              # nothing to do
     assert L.bf_dgd_status(None, None, None) == bf.BF_ERR_NULL
+    sp = L.bf_stream_probe
+    assert sp(3, A, B, 1024, 1, None) == bf.BF_ERR_KIND
+    assert sp(0, None, B, 1024, 1, None) == bf.BF_ERR_NULL
+    assert sp(2, None, None, 1024, 1, None) == bf.BF_ERR_NULL
+    assert sp(0, A, B, 1000, 1, None) == bf.BF_ERR_SIZE
+    assert sp(0, A, B, 1024, 0, None) == bf.BF_ERR_SIZE
+    assert sp(0, A, A + 512, 1024, 1, None) == bf.BF_ERR_ALIAS
+    assert sp(0, A + 8, B, 1024, 1, None) == bf.BF_ERR_ALIGN
+    assert sp(0, A, B, 0, 1, None) == bf.BF_OK
     hn = L.bf_hierarchical_neighbor_allreduce
     assert hn(h, 0, 0, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE       # local_size < 1
     assert hn(h, 0, 1 << 19, A, B, 64, 64, bf.BF_F32, None) == bf.BF_ERR_SIZE

@@ -1088,3 +1088,17 @@ def test_dgd_run_refuses_what_does_not_fit():
     with pytest.raises(bf.BfError) as e:
         bf.bf_dgd_least_squares_run(t, 0, 2, A, b, X, work, 1e-3)
     assert e.value.code == bf.BF_ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------ bandwidth probes
+def test_stream_probe_copies_and_fills():
+    src = torch.randn(3 * 1000 * 1000 + 4, device=DEV)          # 12 MB + a ragged tail of one vector
+    dst = torch.zeros_like(src)
+    for wgs in (1, 8):
+        dst.zero_()
+        bf.bf_stream_probe(0, src, dst, wgs)
+        assert torch.equal(src, dst)
+    bf.bf_stream_probe(1, src, dst, 4)                           # read only: nothing may change
+    assert torch.equal(src, dst)
+    bf.bf_stream_probe(2, None, dst, 4)
+    assert torch.equal(dst.view(-1, 4), torch.tensor([1.0, 2.0, 3.0, 4.0], device=DEV).expand(dst.numel() // 4, 4))
