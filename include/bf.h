@@ -284,6 +284,15 @@ int bf_dgd_least_squares_run(const bf_topology_t* t, int32_t round0, int32_t ite
                              int64_t d, int64_t ld, void* hip_stream);
 int bf_dgd_status(const bf_topology_t* t, int32_t* timed_out, void* hip_stream);
 
+/* Exact-Diffusion on the same problem in the same way (appendix "Application example:
+ * Exact-Diffusion algorithm", eqs. ed-1, ed-2, ed-3 with the least-squares gradient):
+ *   psi_i = x_i - alpha A_i^T (A_i x_i - b_i);  phi_i = psi_i + x_i - psi_prev_i;  x_i <- sum_j w_ij phi_j.
+ * Psi_prev: n x d with pitch ld, in and out (set it to X before the first run).  Everything else,
+ * bf_dgd_status included, as for bf_dgd_least_squares_run; needs 4 * d more bytes of LDS. */
+int bf_exact_diffusion_least_squares_run(const bf_topology_t* t, int32_t round0, int32_t iterations, int32_t m,
+                                         const float* A, const float* b, float* X, float* Psi_prev, float* work,
+                                         float alpha, int64_t d, int64_t ld, void* hip_stream);
+
 /* Local least-squares gradients of decentralized linear regression (eq. dgd-1):
  *   G[i,:] = A_i^T (A_i x_i - b_i),  A: n x m x d row-major fp32, b: n x m fp32.
  * 1 <= m <= 64, d a multiple of 4.  G must not alias X. */

@@ -383,6 +383,7 @@ struct DgdParams {
   const float* b;
   float* X;
   float* H;                  // 2 x n x ld half steps
+  float* Psi;                // null: DGD.  Else Exact-Diffusion: n x ld, psi of the previous iteration, in/out
   const char* blob;          // round table + CSR of every round
   unsigned int* sync;        // [0] arrivals, [1] error
   int64_t d, ld;
@@ -399,6 +400,7 @@ __global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
   f32x4* part = reinterpret_cast<f32x4*>(xs + p.d);              // 1024 partial column sums
   float* resid = reinterpret_cast<float*>(part + 1024);          // 64
   float* bs = resid + 64;                                        // 64
+  float* psi_prev = bs + 64;                                     // d, Exact-Diffusion only
   __shared__ int failed;
   const int i = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -410,6 +412,8 @@ __global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
     for (int v = tid; v < m * nvec; v += 1024) dst[v] = src[v];
     for (int c = tid; c < d; c += 1024) xs[c] = p.X[static_cast<int64_t>(i) * p.ld + c];
     if (tid < m) bs[tid] = p.b[static_cast<int64_t>(i) * m + tid];
+    if (p.Psi)
+      for (int c = tid; c < d; c += 1024) psi_prev[c] = p.Psi[static_cast<int64_t>(i) * p.ld + c];
     if (tid == 0) failed = 0;
   }
   __syncthreads();
@@ -459,11 +463,21 @@ __global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
         acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
       }
       const f32x4 x = *reinterpret_cast<const f32x4*>(xs + (cv << 2));
+      float hv[4] = {fmaf(-p.alpha, acc.x, x.x), fmaf(-p.alpha, acc.y, x.y), fmaf(-p.alpha, acc.z, x.z),
+                     fmaf(-p.alpha, acc.w, x.w)};
+      if (p.Psi) {
+        // Exact-Diffusion (eqs. ed-1, ed-2): psi = x - alpha g;  phi = psi + x - psi_prev is what goes out
+        const float xv[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float psi = hv[e];
+          hv[e] = (psi + xv[e]) - psi_prev[(cv << 2) + e];
+          psi_prev[(cv << 2) + e] = psi;
+        }
+      }
       float* h = hbase + static_cast<int64_t>(i) * p.ld + (cv << 2);
-      __hip_atomic_store(h + 0, fmaf(-p.alpha, acc.x, x.x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(h + 1, fmaf(-p.alpha, acc.y, x.y), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(h + 2, fmaf(-p.alpha, acc.z, x.z), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(h + 3, fmaf(-p.alpha, acc.w, x.w), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) __hip_atomic_store(h + e, hv[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // Grid barrier number it+1.  The half steps went out as agent-scope stores; each wave waits for
     // its own to be acknowledged (workgroup-scope release), the workgroup meets, and one thread
@@ -518,6 +532,8 @@ __global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
     __syncthreads();
   }
   for (int c = tid; c < d; c += 1024) p.X[static_cast<int64_t>(i) * p.ld + c] = xs[c];
+  if (p.Psi)
+    for (int c = tid; c < d; c += 1024) p.Psi[static_cast<int64_t>(i) * p.ld + c] = psi_prev[c];
 }
 
 __global__ void bf_sync_clear_kernel(unsigned int* sync) {
@@ -1373,10 +1389,10 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_ED, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
-int bf_dgd_least_squares_run(const bf_topology_t* tc, int32_t round0, int32_t iterations, int32_t m,
-                             const float* A, const float* b, float* X, float* work, float alpha,
-                             int64_t d, int64_t ld, void* hip_stream) {
-  if (!tc || !A || !b || !X || !work) return BF_ERR_NULL;
+static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t iterations, int32_t m,
+                          const float* A, const float* b, float* X, float* Psi, bool want_psi, float* work,
+                          float alpha, int64_t d, int64_t ld, void* hip_stream) {
+  if (!tc || !A || !b || !X || !work || (want_psi && !Psi)) return BF_ERR_NULL;
   if (round0 < 0) return BF_ERR_ROUND;
   bf_topology_t* t = const_cast<bf_topology_t*>(tc);
   const int32_t n = t->n;
@@ -1388,6 +1404,9 @@ int bf_dgd_least_squares_run(const bf_topology_t* tc, int32_t round0, int32_t it
   if (overlaps(X, xb, work, wb) || overlaps(X, xb, A, ab) || overlaps(X, xb, b, bb) || overlaps(work, wb, A, ab) ||
       overlaps(work, wb, b, bb))
     return BF_ERR_ALIAS;
+  if (Psi && (misaligned16(Psi))) return BF_ERR_ALIGN;
+  if (Psi && (overlaps(Psi, xb, X, xb) || overlaps(Psi, xb, work, wb) || overlaps(Psi, xb, A, ab) || overlaps(Psi, xb, b, bb)))
+    return BF_ERR_ALIAS;
   if (d > 4096) return BF_ERR_UNSUPPORTED;
   if (iterations == 0) return BF_OK;
   bf::DeviceCopy* dc = nullptr;
@@ -1397,7 +1416,7 @@ int bf_dgd_least_squares_run(const bf_topology_t* tc, int32_t round0, int32_t it
   rc = device_info(dc->device, &di);
   if (rc != BF_OK) return rc;
   // one workgroup per agent, all resident at once, A_i in LDS
-  const size_t lds = static_cast<size_t>(m) * d * 4 + static_cast<size_t>(d) * 4 + 1024 * 16 + 128 * 4;
+  const size_t lds = static_cast<size_t>(m) * d * 4 + static_cast<size_t>(d) * 4 * (Psi ? 2 : 1) + 1024 * 16 + 128 * 4;
   const size_t lds_max = std::min(di.lds_per_cu ? di.lds_per_cu : size_t{65536},
                                   di.lds_per_block_optin ? di.lds_per_block_optin : size_t{65536});
   if (lds + 64 > lds_max || n > di.cus) return BF_ERR_UNSUPPORTED;   // 64: the kernel's static LDS
@@ -1414,7 +1433,7 @@ int bf_dgd_least_squares_run(const bf_topology_t* tc, int32_t round0, int32_t it
     }
   }
   DgdParams p{};
-  p.A = A; p.b = b; p.X = X; p.H = work;
+  p.A = A; p.b = b; p.X = X; p.H = work; p.Psi = Psi;
   p.blob = dc->blob;
   p.sync = dc->sync;
   p.d = d; p.ld = ld; p.n = n; p.m = m; p.iters = iterations;
@@ -1429,6 +1448,18 @@ int bf_dgd_least_squares_run(const bf_topology_t* tc, int32_t round0, int32_t it
   hipLaunchKernelGGL(bf_dgd_ls_kernel, dim3(n), dim3(1024), lds, st, p);
   BF_HIP_TRY(hipGetLastError());
   return BF_OK;
+}
+
+int bf_dgd_least_squares_run(const bf_topology_t* t, int32_t round0, int32_t iterations, int32_t m,
+                             const float* A, const float* b, float* X, float* work, float alpha,
+                             int64_t d, int64_t ld, void* hip_stream) {
+  return dgd_run_common(t, round0, iterations, m, A, b, X, nullptr, false, work, alpha, d, ld, hip_stream);
+}
+
+int bf_exact_diffusion_least_squares_run(const bf_topology_t* t, int32_t round0, int32_t iterations, int32_t m,
+                                         const float* A, const float* b, float* X, float* Psi_prev, float* work,
+                                         float alpha, int64_t d, int64_t ld, void* hip_stream) {
+  return dgd_run_common(t, round0, iterations, m, A, b, X, Psi_prev, true, work, alpha, d, ld, hip_stream);
 }
 
 int bf_dgd_status(const bf_topology_t* tc, int32_t* timed_out, void* hip_stream) {

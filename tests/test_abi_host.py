@@ -273,6 +273,10 @@ def test_compute_calls_validate_before_touching_the_device():
     assert dg(h, 0, 5, 32, A, B, G, WK, 1e-3, 8192, 8192, None) == bf.BF_ERR_UNSUPPORTED
     assert dg(h, 0, 0, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_OK              # nothing to do
     assert L.bf_dgd_status(None, None, None) == bf.BF_ERR_NULL
+    ed = L.bf_exact_diffusion_least_squares_run
+    assert ed(h, 0, 5, 32, A, B, G, None, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_NULL
+    assert ed(h, 0, 5, 32, A, B, G, G + 16, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_ALIAS
+    assert ed(h, 0, 0, 32, A, B, G, 0x50000000, WK, 1e-3, 1024, 1024, None) == bf.BF_OK
     sp = L.bf_stream_probe
     assert sp(3, A, B, 1024, 1, None) == bf.BF_ERR_KIND
     assert sp(0, None, B, 1024, 1, None) == bf.BF_ERR_NULL

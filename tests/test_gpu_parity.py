@@ -1102,3 +1102,46 @@ def test_stream_probe_copies_and_fills():
     assert torch.equal(src, dst)
     bf.bf_stream_probe(2, None, dst, 4)
     assert torch.equal(dst.view(-1, 4), torch.tensor([1.0, 2.0, 3.0, 4.0], device=DEV).expand(dst.numel() // 4, 4))
+
+
+@pytest.mark.parametrize("name,make", [TOPOS[0], TOPOS[2]])
+@pytest.mark.parametrize("n,m,d,iters", [(16, 32, 1024, 1), (16, 32, 1024, 2), (16, 32, 1024, 30), (8, 16, 520, 9), (1, 3, 16, 4)])
+def test_exact_diffusion_run_in_one_launch_matches_oracle(name, make, n, m, d, iters):
+    t = make(n)
+    R = bf.bf_topology_rounds(t)
+    Ws = [lib_W(t, r) for r in range(R)]
+    g = torch.Generator(device=DEV).manual_seed(950 + n + m)
+    A = torch.randn((n, m, d), device=DEV, generator=g) / (d ** 0.5)
+    b = torch.randn((n, m), device=DEV, generator=g)
+    X = rows(n, d, 951 + n, std=0.5)
+    P = empty_like_rows(X).copy_(X)
+    alpha = float(np.float32(0.4))
+    Ah, bh = host(A.reshape(n * m, d)).reshape(n, m, d), host(b)
+    xr, pr = host(X), host(X)
+    for k in range(iters):
+        xr, pr = O.exact_diffusion_step(xr, pr, O.ls_grad(Ah, bh, xr), Ws[k % R], alpha)
+    ld = X.stride(0) if n > 1 else d
+    work = torch.empty(2 * n * ld, device=DEV)
+    bf.bf_exact_diffusion_least_squares_run(t, 0, iters, A, b, X, P, work, alpha)
+    assert bf.bf_dgd_status(t) == 0
+    assert_close(X, xr, 2e-5 + 5e-7 * iters, "x after %d iterations" % iters)
+    assert_close(P, pr, 2e-5 + 5e-7 * iters, "psi after %d iterations" % iters)
+
+
+def test_exact_diffusion_run_reaches_the_least_squares_solution_where_dgd_stalls():
+    n, m, d, alpha = 16, 8, 64, 0.01
+    g = torch.Generator(device=DEV).manual_seed(95)
+    A = torch.randn((n, m, d), generator=g, device=DEV)
+    b = torch.randn((n, m), generator=g, device=DEV)
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    X = torch.zeros((n, d), device=DEV); P = torch.zeros((n, d), device=DEV)
+    work = torch.empty(2 * n * d, device=DEV)
+    for _ in range(3):                                  # 3 runs of 1000 iterations: the state carries over
+        bf.bf_exact_diffusion_least_squares_run(t, 0, 1000, A, b, X, P, work, alpha)
+    xs = np.linalg.lstsq(host(A).reshape(n * m, d), host(b).reshape(n * m), rcond=None)[0]
+    err_ed = np.abs(host(X) - xs).max()
+    assert err_ed < 1e-2 * np.abs(xs).max()
+    Xd = torch.zeros((n, d), device=DEV)
+    bf.bf_dgd_least_squares_run(t, 0, 3000, A, b, Xd, work, alpha)
+    assert bf.bf_dgd_status(t) == 0
+    assert np.abs(host(Xd) - xs).max() > 20 * err_ed
