@@ -171,8 +171,9 @@ int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t 
  * first averages its agents, the machines then do one round of partial averaging over
  * `machine_topology` (whose n is the number of machines M), and every agent of a machine takes its
  * machine's result:  X_out[i,:] = sum_b W_machine[a(i), b] * (1/local_size) sum_{j in b} X_in[j,:].
- * X has M * local_size rows.  One pass over X when two (M*local_size) x 64 fp32 tiles fit one CU's
- * LDS, three passes otherwise (up to one such tile; beyond that BF_ERR_UNSUPPORTED).  The derived
+ * X has M * local_size rows.  One pass over X when an (M*local_size + M) x 64 fp32 tile fits one
+ * CU's LDS (the M machine values sit beside the staged rows), three passes otherwise (up to an
+ * (M*local_size) x 64 tile; beyond that BF_ERR_UNSUPPORTED).  The derived
  * operator is built on first use and kept inside machine_topology (freed with it).  X_out may equal
  * X_in.  local_size < 1: BF_ERR_SIZE. */
 int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, int32_t round, int32_t local_size,

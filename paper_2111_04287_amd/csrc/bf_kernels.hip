@@ -779,7 +779,7 @@ int ilog2(int64_t v) { int l = 0; while ((int64_t{1} << (l + 1)) <= v) ++l; retu
 // Choose the tile: the widest power-of-two C in [64, 1024] whose n x C fp32 tile fits the LDS share
 // of one of `wgs` workgroups per CU (two 1024-thread workgroups per CU when possible, so one can
 // stream while the other reduces), narrowed while the launch would leave workgroup slots idle.
-int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_wgs = 2) {
+int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_wgs = 2, int max_log_c = 10) {
   const size_t lds_cu = di.lds_per_cu ? di.lds_per_cu : 65536;
   const size_t lds_blk = di.lds_per_block_optin ? di.lds_per_block_optin : lds_cu;
   int wgs = g_tune_wgs > 0 ? g_tune_wgs : max_wgs;
@@ -795,7 +795,7 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_wgs =
   } else {
     auto widest = [&](int w) {
       const size_t budget = std::min(lds_cu / w, lds_blk);
-      for (int lc = 10; lc >= 6; --lc)
+      for (int lc = max_log_c; lc >= 6; --lc)
         if (static_cast<size_t>(n) * (size_t{1} << lc) * 4 <= budget) return lc;
       return -1;
     };
@@ -893,7 +893,9 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   }
   Shape s;
   // (the fused kernel needs more than 64 registers, so one workgroup per CU is all that runs)
-  rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(fuse > 1 ? 2 * t->n : t->n, tp.d, di, &s, fuse > 1 ? 1 : 2);
+  const int rows_b = fuse > 1 ? (tp.rows_b > 0 && tp.rows_b < t->n ? tp.rows_b : t->n) : 0;
+  rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(t->n + rows_b, tp.d, di, &s, fuse > 1 ? 1 : 2,
+                                                                 fuse > 1 ? 8 : 10);   // fused: 256 columns at most (512 measured slower)
   if (fuse > 1 && rc != BF_OK) return rc;   // fused rounds exist only as the two-tile LDS kernel
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
     // Too many agents for an LDS tile: row gather through the caches, out of place only.
@@ -1156,12 +1158,15 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
   tp.x_out = static_cast<char*>(X_out);
   tp.d = d; tp.ld = ld;
   tp.fuse = 3;
+  // stage A writes rows 0..M-1 of the second LDS tile and stage B reads only those: the tile needs M rows
+  tp.rows_b = mt->n;
   rc = run_tile(two, r3, OP_MIX, false, tp, dt, st);
   if (rc != BF_ERR_UNSUPPORTED) return rc;
   // Too many agents for two LDS tiles: the three stages as three passes.  The first may write
   // X_out, the other two update it in place (every row of X_out is overwritten in the end, so the
   // zeros the first two stages leave in rows M and up are never seen).
   tp.fuse = 1;
+  tp.rows_b = 0;
   rc = run_tile(two, r3, OP_MIX, false, tp, dt, st);
   if (rc != BF_OK) return rc;
   tp.x_in = tp.x_out;

@@ -274,12 +274,14 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       typedef const u32x4 __attribute__((address_space(4)))* csr_u4_ptr;
       typedef const u32x8 __attribute__((address_space(4)))* csr_u8_ptr;
       const csr_u4_ptr round_tab = (csr_u4_ptr)(uintptr_t)p.blob;
-      const int ngroups = (p.n + 3) >> 2;
-      const int nitems = ngroups << spans_log;
+      const int rows_b = p.rows_b > 0 ? p.rows_b : p.n;
       int k = p.round_k0;
       for (int r = 0; r + 1 < p.fuse; ++r) {
         const float* src_t = (r & 1) ? tile_b : tile_a;
         float* dst_t = (r & 1) ? tile_a : tile_b;
+        const int row_limit = (r & 1) ? p.n : rows_b;          // rows the destination tile has
+        const int ngroups = (row_limit + 3) >> 2;
+        const int nitems = ngroups << spans_log;
         const u32x4 offs = round_tab[k];
         const csr_u4_ptr hdrs = (csr_u4_ptr)(reinterpret_cast<uintptr_t>(p.blob) + offs.z);
         const uintptr_t recs = reinterpret_cast<uintptr_t>(p.blob) + offs.w;
@@ -370,7 +372,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
 #pragma unroll
               for (int u = 0; u < 4; ++u) {
                 const int row = (g[j] << 2) + u;
-                if (row < p.n) {
+                if (row < row_limit) {
                   float* o = dst_t + (row << log_c) + cit[j];
                   if constexpr (LW == 4) { f32x4 t = {acc[j][u][0], acc[j][u][1], acc[j][u][2], acc[j][u][3]}; *reinterpret_cast<f32x4*>(o) = t; }
                   else if constexpr (LW == 2) { f32x2 t = {acc[j][u][0], acc[j][u][1]}; *reinterpret_cast<f32x2*>(o) = t; }
