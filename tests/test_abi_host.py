@@ -439,3 +439,26 @@ def test_window_layout_matches_the_oracle(kind, n, kw):
         np.testing.assert_array_equal(selfw, np.asarray(self_w, dtype=np.float32))
     assert bf.lib.bf_topology_window_slots(None, 0) == bf.BF_ERR_NULL
     assert bf.lib.bf_topology_window_slots(t.handle, -1) == bf.BF_ERR_ROUND
+
+
+def test_host_code_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The topology code (generators, validators, chain / window / two-level plans, exports) built
+    with g++ -fsanitize=address,undefined and driven over every kind and a range of sizes."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "driver")
+    cmd = ["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-static-libasan", "-static-libubsan",
+           "-fno-omit-frame-pointer", "-I" + os.path.join(root, "include"),
+           "-I" + os.path.join(root, "paper_2111_04287_amd", "csrc"),
+           os.path.join(root, "tests", "host_sanitizer_driver.cpp"),
+           os.path.join(root, "paper_2111_04287_amd", "csrc", "bf_topology.cpp"), "-o", exe]
+    b = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if b.returncode != 0 and "sanitize" in b.stdout:
+        pytest.skip("this g++ has no sanitizer runtime")
+    assert b.returncode == 0, b.stdout
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1", UBSAN_OPTIONS="halt_on_error=1")
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=300)
+    assert r.returncode == 0 and "0 failures" in r.stdout, r.stdout[-2000:]
