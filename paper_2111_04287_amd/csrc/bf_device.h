@@ -98,6 +98,7 @@ struct TileParams {
   const char* blob;
   int32_t round_k0;      // first fused round, already reduced modulo nrounds
   int32_t nrounds;
+  int32_t long_rows;     // 1: the round's longest row has 5 entries or more (fp32 mix: batched LDS reads)
   int32_t rows_b;        // rows of the second LDS tile (0: n).  Smaller when the rounds that write it leave
                          // all rows from rows_b on empty and the rounds that read it never refer to them
   float alpha, beta;

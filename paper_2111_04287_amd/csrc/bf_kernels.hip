@@ -852,6 +852,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   tp.rowptr = reinterpret_cast<const int32_t*>(dc->blob + dc->rowptr_off[k]);
   tp.ent = reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[k]);
   tp.n = t->n;
+  tp.long_rows = t->rounds[k].max_degree >= 5 ? 1 : 0;
   tp.reverse = g_tune_noserp ? 0 : (round & 1);
   const int fuse = tp.fuse > 1 ? tp.fuse : 1;
   tp.fuse = fuse;

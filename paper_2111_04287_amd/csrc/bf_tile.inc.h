@@ -177,9 +177,10 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
     };
     // The fp32 kernels with four columns per lane and no gradient operand fit two 1024-thread
     // workgroups per CU only while they stay within 64 registers, which the batch of four would
-    // cost them; every other kernel is either well below or already above that line.
+    // cost them (unless they prefetch only half the tile, MAXPF == 2, the form used for long rows);
+    // every other kernel is either well below or already above that line.
     constexpr bool BATCHED = BF_GATHER_ILP >= 4 &&
-        !(DT == DT_F32 && LW == 4 && (OP == OP_MIX || OP == OP_AWC || OP == OP_MOM_AWC) && !MULTI);
+        !(DT == DT_F32 && LW == 4 && (OP == OP_MIX || OP == OP_AWC || OP == OP_MOM_AWC) && !MULTI && MAXPF == 4);
     int q = beg;
     if constexpr (BATCHED) {
       for (; q + 4 <= end; q += 4) batch(q, std::integral_constant<int, 4>{});
@@ -399,10 +400,12 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   }
 }
 
-template <int DT, int OP, bool WITH_Y, int LW, int THREADS, bool STREAM, bool MULTI = false>
+template <int DT, int OP, bool WITH_Y, int LW, int THREADS, bool STREAM, bool MULTI = false, bool LONG_ROWS = false>
 int launch_tile_thr(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
-  // prefetch depth: a 64 KB tile is 4 (fp32) / 2 (bf16) vectors per thread at 1024 threads
-  constexpr int MAXPF = DT == DT_F32 ? 4 : 2;
+  // prefetch depth: a 64 KB tile is 4 (fp32) / 2 (bf16) vectors per thread at 1024 threads.  The
+  // long-row form of the fp32 mix prefetches half the tile and spends the registers on batched LDS
+  // reads instead (see the kernel's reduce phase).
+  constexpr int MAXPF = DT == DT_F32 ? (LONG_ROWS ? 2 : 4) : 2;
   auto kern = bf_tile_kernel<DT, OP, WITH_Y, LW, THREADS, MAXPF, STREAM, MULTI>;
   if (lds > 48 * 1024) {
     static thread_local size_t raised = 0;
@@ -427,6 +430,16 @@ int launch_tile_lw(const TileParams& tp, int grid, size_t lds, bool stream, hipS
     if (tp.fuse > 1)
       return stream ? launch_tile_thr<DT, OP, WITH_Y, LW, 1024, true, true>(tp, grid, lds, st)
                     : launch_tile_thr<DT, OP, WITH_Y, LW, 1024, false, true>(tp, grid, lds, st);
+  }
+  if constexpr (DT == DT_F32 && LW == 4 && (OP == OP_MIX || OP == OP_AWC)) {
+    // Rows with many entries (the static exponential graph has 12): the reduce phase, one LDS read
+    // at a time, is then as long as the tile's HBM transfers.  Batching the reads needs 12 more
+    // registers, which a prefetch of half the tile pays for, so two workgroups still fit a CU:
+    // config 2 in place 72 -> 75 % of peak; rows of 2 or 3 entries lose about 1 %, so they keep
+    // the full prefetch.
+    if (tp.long_rows)
+      return stream ? launch_tile_thr<DT, OP, WITH_Y, LW, 1024, true, false, true>(tp, grid, lds, st)
+                    : launch_tile_thr<DT, OP, WITH_Y, LW, 1024, false, false, true>(tp, grid, lds, st);
   }
   return stream ? launch_tile_thr<DT, OP, WITH_Y, LW, 1024, true>(tp, grid, lds, st)
                 : launch_tile_thr<DT, OP, WITH_Y, LW, 1024, false>(tp, grid, lds, st);
