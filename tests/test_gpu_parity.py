@@ -1145,3 +1145,34 @@ def test_exact_diffusion_run_reaches_the_least_squares_solution_where_dgd_stalls
     bf.bf_dgd_least_squares_run(t, 0, 3000, A, b, Xd, work, alpha)
     assert bf.bf_dgd_status(t) == 0
     assert np.abs(host(Xd) - xs).max() > 20 * err_ed
+
+
+# ------------------------------------------------------------------ long rows at four columns per lane
+@pytest.mark.parametrize("what", ["mix", "awc", "pushsum_ratio"])
+def test_long_row_form_of_the_wide_tile_kernels_matches_oracle(what):
+    # 256-column tiles are only chosen for wide matrices; forcing them here runs the kernel form used
+    # for rows of five entries or more (batched LDS reads, half-tile prefetch) on a small case with
+    # several tiles per workgroup slot and a ragged last tile
+    n, d = 64, 3 * 256 * 7 + 100
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    W = lib_W(t)
+    X = rows(n, d, 1234)
+    try:
+        bf.bf_set_tuning(0, 256)
+        bf.bf_set_tuning(3, 3)                      # three workgroups: each walks several tiles
+        if what == "mix":
+            out = bf.bf_neighbor_allreduce(t, 0, X, empty_like_rows(X))
+            assert_close(out, O.mix(host(X), W), TOL32, what)
+        elif what == "awc":
+            G = rows(n, d, 1235)
+            out = bf.bf_atc_step(t, 0, X, empty_like_rows(X), G, None, alpha=0.05, mode=bf.BF_AWC)
+            assert_close(out, O.awc_step(host(X), host(G), W, float(np.float32(0.05))), TOL32, what)
+        else:
+            w = torch.rand(n, device=DEV) + 0.5
+            Y = empty_like_rows(X)
+            Xo, wo, _ = bf.bf_pushsum_step(t, 0, X, empty_like_rows(X), w, torch.empty_like(w), Y)
+            rx, rp, ry = O.pushsum_step(host(X), host(w[:, None])[:, 0], W)
+            assert_close(Xo, rx, TOL32, "x"); assert_close(Y, ry, TOL32, "ratio")
+    finally:
+        bf.bf_set_tuning(0, 0)
+        bf.bf_set_tuning(3, 0)
