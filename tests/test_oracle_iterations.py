@@ -322,6 +322,50 @@ def test_dmsgd_column_sums():
     np.testing.assert_allclose(Mn, 0.9 * M + G, atol=0)
 
 
+def test_dmsgd_bf16_storage_equals_plain_step_when_nothing_needs_rounding():
+    # One-peer weights (1/2, 1/2), alpha = 1/4, beta = 1/2, X integers, G multiples of 4, M multiples
+    # of 8: m' = beta m + g is a multiple of 4, x - alpha m' an integer, the mix a multiple of 1/2
+    # below 64 in magnitude -- seven significant bits, exact in bfloat16.  The storage twin then has
+    # nothing to round and must return the plain step's values bit for bit.
+    rng = np.random.default_rng(41)
+    n, d = 8, 33
+    W = T.one_peer_exponential(n, 1)
+    X = rng.integers(-8, 9, size=(n, d)).astype(np.float32)
+    G = (4 * rng.integers(-4, 5, size=(n, d))).astype(np.float32)
+    M = (8 * rng.integers(-4, 5, size=(n, d))).astype(np.float32)
+    Xs, Ms = O.dmsgd_atc_step_bf16_storage(X, M, G, W, 0.25, 0.5)
+    Xp, Mp = O.dmsgd_atc_step(X, M, G, W, 0.25, 0.5)
+    assert Xs.dtype == np.float32 and Ms.dtype == np.float32
+    np.testing.assert_array_equal(Xs.astype(np.float64), Xp)
+    np.testing.assert_array_equal(Ms.astype(np.float64), Mp)
+    assert np.array_equal(O.round_to_bf16(Xs), Xs)           # the guard: the result is a bfloat16 value
+
+
+def test_dmsgd_bf16_storage_hand_worked_ties_and_rounding_order():
+    one = {0: [(0, 1.0)]}
+    f = lambda v: np.array([[v]], dtype=np.float32)
+    # x' = 1 - 2^-8 * (-1) = 1 + 2^-8: halfway between the bfloat16 values 1 (even) and 1 + 2^-7 (odd)
+    Xs, Ms = O.dmsgd_atc_step_bf16_storage(f(1.0), f(0.0), f(-1.0), one, 2.0 ** -8, 0.0)
+    assert Xs[0, 0] == 1.0 and Ms[0, 0] == -1.0
+    # x' = 1 + 3 * 2^-8: halfway between 1 + 2^-7 (odd) and 1 + 2^-6 (even)
+    Xs, _ = O.dmsgd_atc_step_bf16_storage(f(1.0), f(0.0), f(-3.0), one, 2.0 ** -8, 0.0)
+    assert Xs[0, 0] == 1.0 + 2.0 ** -6
+    # just above / below a tie go to the nearer neighbour
+    Xs, _ = O.dmsgd_atc_step_bf16_storage(f(1.0), f(0.0), f(-1.0 - 2.0 ** -7), one, 2.0 ** -8, 0.0)
+    assert Xs[0, 0] == 1.0 + 2.0 ** -7
+    # the momentum is rounded to fp32 (ties to even): 1 + 2^-24 -> 1, 1 + 3 * 2^-24 -> 1 + 2^-22
+    _, Ms = O.dmsgd_atc_step_bf16_storage(f(0.0), f(1.0), f(2.0 ** -24), one, 0.0, 1.0)
+    assert Ms[0, 0] == np.float32(1.0)
+    _, Ms = O.dmsgd_atc_step_bf16_storage(f(0.0), f(1.0), f(3 * 2.0 ** -24), one, 0.0, 1.0)
+    assert Ms[0, 0] == np.float32(1.0 + 2.0 ** -22)
+    # order of the roundings: x' is formed from the STORED (fp32) momentum.  m' = 1 + 2^-8 + 2^-30
+    # stores as 1 + 2^-8; x' = 0 - (-1) m' is then exactly the tie 1 + 2^-8 and goes to 1 (even).
+    # Rounding the unrounded m' straight to bfloat16 would give 1 + 2^-7 instead.
+    Xs, Ms = O.dmsgd_atc_step_bf16_storage(f(0.0), f(1.0 + 2.0 ** -8), f(2.0 ** -30), one, -1.0, 1.0)
+    assert Ms[0, 0] == np.float32(1.0 + 2.0 ** -8)
+    assert Xs[0, 0] == 1.0
+
+
 # ---------------------------------------------------------------- Exact-Diffusion (next row)
 def test_exact_diffusion_fixed_point_is_least_squares_solution():
     rng = np.random.default_rng(17)
@@ -335,6 +379,34 @@ def test_exact_diffusion_fixed_point_is_least_squares_solution():
         X, psi_prev = O.exact_diffusion_step(X, psi_prev, O.ls_grad(A, b, X), W, alpha)
     xs = np.linalg.lstsq(A.reshape(n * m, d), b.reshape(n * m), rcond=None)[0]
     np.testing.assert_allclose(X, np.tile(xs, (n, 1)), atol=1e-8)
+
+
+def test_exact_diffusion_step_against_dense_formula_and_two_step_recursion():
+    rng = np.random.default_rng(42)
+    n, d, alpha = 7, 4, 0.05
+    D = _rand_W(n, rng)
+    W = T.from_dense(D)
+    X, Psi, G = (rng.normal(size=(n, d)) for _ in range(3))
+    Xn, psi = O.exact_diffusion_step(X, Psi, G, W, alpha)
+    # eqs. ed-1..ed-3 in matrix form: psi = X - alpha G, X' = W (2X - alpha G - Psi_prev)
+    np.testing.assert_allclose(psi, X - alpha * G, atol=0)
+    np.testing.assert_allclose(Xn, D @ (2 * X - alpha * G - Psi), atol=1e-13)
+    # Eliminating psi from two consecutive iterations leaves the two-step recursion
+    #   x^{k+1} = W (2 x^k - x^{k-1} - alpha (g^k - g^{k-1})),  started with x^1 = W (x^0 - alpha g^0).
+    A = rng.normal(size=(n, 3, d))
+    b = rng.normal(size=(n, 3))
+    X0 = rng.normal(size=(n, d))
+    xs, gs = [X0], [O.ls_grad(A, b, X0)]
+    Xk, Pk = X0, X0.copy()
+    for k in range(6):
+        Xk, Pk = O.exact_diffusion_step(Xk, Pk, gs[-1], W, alpha)
+        if k == 0:
+            expect = D @ (xs[0] - alpha * gs[0])
+        else:
+            expect = D @ (2 * xs[-1] - xs[-2] - alpha * (gs[-1] - gs[-2]))
+        np.testing.assert_allclose(Xk, expect, rtol=1e-11, atol=1e-11)
+        xs.append(Xk)
+        gs.append(O.ls_grad(A, b, Xk))
 
 
 # ---------------------------------------------------------------- bf16 rounding and fp32 chain
@@ -550,3 +622,51 @@ def test_window_mass_is_conserved_and_ratio_converges_under_random_activity():
         assert abs(p.sum() + wp.sum() - n) < 1e-12
     assert np.abs(X / p[:, None] - mean).max() < 1e-8
     assert np.abs(X - mean).max() > 1e-3                     # x alone is biased
+
+
+def test_window_slots_paper_sizing_example(golden_dir):
+    # The paper's example (section "Asynchronous decentralized communication"): node 1 with in-coming
+    # neighbors 3 and 5 and a 5 x 5 x 3 tensor registers one chunk of 150 = 5*5*3*2 values, first
+    # half for node 3, second half for node 5.
+    fx = {}
+    for line in open(golden_dir + "/window_sizing_example.txt"):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split(":")
+            fx[k.strip()] = [int(t) for t in v.split()]
+    node, senders, shape = fx["node"][0], fx["in_coming"], fx["tensor_shape"]
+    numel = int(np.prod(shape))
+    n = 5
+    W = {i: [(i, 1.0)] for i in range(n)}
+    W[node - 1] = sorted([(node - 1, 1.0 / 3.0)] + [(s_ - 1, 1.0 / 3.0) for s_ in senders])
+    slot_ptr, slot_src, slot_w, self_w = O.window_slots(W)
+    lo, hi = slot_ptr[node - 1], slot_ptr[node]
+    assert (hi - lo) * numel == fx["chunk_length"][0]
+    assert [j + 1 for j in slot_src[lo:hi]] == senders                 # first half node 3, second half node 5
+    assert slot_ptr[-1] == len(senders)                                # nobody else owns a slot
+    assert self_w[node - 1] == 1.0 / 3.0 and slot_w[lo:hi] == [1.0 / 3.0] * 2
+    # filling the window: the chunk is x_3 followed by x_5
+    X = np.arange(n * numel, dtype=np.float64).reshape(n, numel)
+    chunk = O.win_put(X, np.zeros((slot_ptr[-1], numel)), W)[lo:hi].reshape(-1)
+    assert chunk.shape == (fx["chunk_length"][0],)
+    np.testing.assert_array_equal(chunk[:numel], X[senders[0] - 1])
+    np.testing.assert_array_equal(chunk[numel:], X[senders[1] - 1])
+
+
+def test_window_update_hand_worked_three_agents_with_a_mask():
+    # rows of W: agent 0 hears 1 and 2, agent 1 hears 0, agent 2 hears 1.  Slots in order:
+    # (0 <- 1), (0 <- 2), (1 <- 0), (2 <- 1).
+    W = {0: [(0, 0.5), (1, 0.25), (2, 0.25)], 1: [(0, 0.5), (1, 0.5)], 2: [(1, 1.0 / 3.0), (2, 2.0 / 3.0)]}
+    slot_ptr, slot_src, slot_w, self_w = O.window_slots(W)
+    assert slot_ptr == [0, 2, 3, 4] and slot_src == [1, 2, 0, 1]
+    assert slot_w == [0.25, 0.25, 0.5, 1.0 / 3.0] and self_w == [0.5, 0.5, 2.0 / 3.0]
+    X = np.array([[4.0], [8.0], [12.0]])
+    Win = np.array([[1.0], [2.0], [3.0], [5.0]])
+    # agents 0 and 2 update, agent 1 is busy elsewhere: x0 = 4/2 + 1/4 + 2/4, x2 = 2*12/3 + 5/3
+    out = O.win_update(X, Win, W, active=[1, 0, 1])
+    np.testing.assert_allclose(out[:, 0], [2.75, 8.0, 8.0 + 5.0 / 3.0], rtol=1e-15)
+    # only agent 1: x1 = 8/2 + 3/2
+    out = O.win_update(X, Win, W, active=[0, 1, 0])
+    np.testing.assert_allclose(out[:, 0], [4.0, 5.5, 12.0], rtol=1e-15)
+    # nobody: nothing moves; the window is never written by an update
+    np.testing.assert_array_equal(O.win_update(X, Win, W, active=[0, 0, 0]), X)
+    np.testing.assert_array_equal(Win[:, 0], [1.0, 2.0, 3.0, 5.0])
