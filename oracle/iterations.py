@@ -325,3 +325,127 @@ def win_update(X, Win, W, active=None):
                 acc = acc + slot_w[e] * Win[e, :]
             X[i, :] = acc
     return X
+
+
+# --------------------------------------------------------------------------------------------------
+# The same primitives with the per-call weight arguments of the section "Asynchronous decentralized
+# communication": neighbor_win_put / neighbor_win_accumulate(tensor, name, [self_weight,
+# dst_weights]), neighbor_win_get(tensor, name, [src_weights]), win_update(name, [self_weight,
+# src_weights]).  ``dst_weights[j]`` is a dictionary {i: weight} over a SUBSET of j's out-neighbors
+# in the static topology, ``src_weights[i]`` a dictionary {j: weight} over a subset of i's
+# in-neighbors; an edge that is not named is not touched (put, accumulate, get) or not included
+# (update).  ``self_weight[j]`` scales the caller's own tensor.  None means: no such argument.
+
+def _slot_index(W):
+    """{(receiver i, sender j): slot number} in the layout of ``window_slots``."""
+    slot_ptr, slot_src, _, _ = window_slots(W)
+    index = {}
+    for i in range(len(W)):
+        for e in range(slot_ptr[i], slot_ptr[i + 1]):
+            index[(i, slot_src[e])] = e
+    return index
+
+
+def _check_subset(index, i, j):
+    if (i, j) not in index:
+        raise ValueError("edge %d -> %d is not in the static topology" % (j, i))
+    return index[(i, j)]
+
+
+def win_put_weighted(X, Win, W, active=None, self_weight=None, dst_weights=None):
+    """neighbor_win_put(tensor, name, [self_weight, dst_weights]): every active agent j overwrites
+    its slot at each named out-neighbor i with dst_weights[j][i] * x_j (all out-neighbors, weight 1,
+    without the argument), then keeps self_weight[j] * x_j (x_j itself without the argument).
+    Returns (X', Win')."""
+    X = _f64(X).copy()
+    Win = _f64(Win).copy()
+    index = _slot_index(W)
+    n = X.shape[0]
+    for j in range(n):
+        if not _is_active(active, j):
+            continue
+        if dst_weights is None:
+            targets = {i: 1.0 for (i, jj) in index if jj == j}
+        else:
+            targets = dst_weights[j]
+        for i, w in targets.items():
+            Win[_check_subset(index, i, j), :] = w * X[j, :]
+    if self_weight is not None:
+        for j in range(n):
+            if _is_active(active, j):
+                X[j, :] *= self_weight[j]
+    return X, Win
+
+
+def win_accumulate_weighted(X, p, Win, win_p, W, active=None, self_weight=None, dst_weights=None):
+    """neighbor_win_accumulate(tensor, name, [self_weight, dst_weights]): as the put, but the slot
+    is added to; the push-sum scalar p travels with x.  Without the arguments the topology's own
+    column of weights is used, as in ``win_accumulate``.  Returns (X', p', Win', win_p')."""
+    X = _f64(X).copy()
+    p = _f64(p).copy()
+    Win = _f64(Win).copy()
+    win_p = _f64(win_p).copy()
+    index = _slot_index(W)
+    _, _, slot_w, self_w = window_slots(W)
+    n = X.shape[0]
+    for j in range(n):
+        if not _is_active(active, j):
+            continue
+        if dst_weights is None:
+            targets = {i: slot_w[e] for (i, jj), e in index.items() if jj == j}
+        else:
+            targets = dst_weights[j]
+        for i, w in targets.items():
+            e = _check_subset(index, i, j)
+            Win[e, :] += w * X[j, :]
+            win_p[e] += w * p[j]
+    for j in range(n):
+        if _is_active(active, j):
+            sw = self_w[j] if self_weight is None else self_weight[j]
+            X[j, :] *= sw
+            p[j] *= sw
+    return X, p, Win, win_p
+
+
+def win_get_weighted(X, Win, W, active=None, src_weights=None):
+    """neighbor_win_get(tensor, name, [src_weights]): every active agent i fetches
+    src_weights[i][j] * x_j of each named in-neighbor j into its own slot for j (all in-neighbors,
+    weight 1, without the argument).  Returns Win'."""
+    X = _f64(X)
+    Win = _f64(Win).copy()
+    index = _slot_index(W)
+    for i in range(X.shape[0]):
+        if not _is_active(active, i):
+            continue
+        if src_weights is None:
+            sources = {j: 1.0 for (ii, j) in index if ii == i}
+        else:
+            sources = src_weights[i]
+        for j, w in sources.items():
+            Win[_check_subset(index, i, j), :] = w * X[j, :]
+    return Win
+
+
+def win_update_weighted(X, Win, W, active=None, self_weight=None, src_weights=None):
+    """win_update(name, [self_weight, src_weights]): every active agent i returns
+    self_weight[i] x_i + sum over the named in-neighbors j of src_weights[i][j] * (slot of j); the
+    window keeps its contents.  Without the arguments the topology's weights are used, as in
+    ``win_update``.  Returns X'."""
+    X = _f64(X).copy()
+    Win = _f64(Win)
+    index = _slot_index(W)
+    _, _, slot_w, self_w = window_slots(W)
+    out = X.copy()
+    for i in range(X.shape[0]):
+        if not _is_active(active, i):
+            continue
+        sw = self_w[i] if self_weight is None else self_weight[i]
+        if src_weights is None:
+            sources = {j: slot_w[e] for (ii, j), e in index.items() if ii == i}
+        else:
+            sources = src_weights[i]
+        acc = sw * X[i, :]
+        for j in sorted(sources):
+            acc = acc + sources[j] * Win[_check_subset(index, i, j), :]
+        out[i, :] = acc
+    return out

@@ -670,3 +670,72 @@ def test_window_update_hand_worked_three_agents_with_a_mask():
     # nobody: nothing moves; the window is never written by an update
     np.testing.assert_array_equal(O.win_update(X, Win, W, active=[0, 0, 0]), X)
     np.testing.assert_array_equal(Win[:, 0], [1.0, 2.0, 3.0, 5.0])
+
+
+# ------------------------------------------------------------------ window primitives with per-call weights
+def test_weighted_window_calls_without_arguments_are_the_plain_calls():
+    rng = np.random.default_rng(51)
+    W = _push_graph(9, 3, 5)
+    n, d = 9, 4
+    X = rng.standard_normal((n, d)); p = rng.random(n) + 0.5
+    E = O.window_slots(W)[0][-1]
+    Win = rng.standard_normal((E, d)); wp = rng.random(E)
+    act = rng.random(n) < 0.6
+    Xo, Wo = O.win_put_weighted(X, Win, W, act)
+    np.testing.assert_array_equal(Wo, O.win_put(X, Win, W, act)); np.testing.assert_array_equal(Xo, X)
+    np.testing.assert_array_equal(O.win_get_weighted(X, Win, W, act), O.win_get(X, Win, W, act))
+    for a, b in zip(O.win_accumulate_weighted(X, p, Win, wp, W, act), O.win_accumulate(X, p, Win, wp, W, act)):
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(O.win_update_weighted(X, Win, W, act), O.win_update(X, Win, W, act), rtol=0, atol=1e-15)
+
+
+def test_weighted_window_calls_hand_worked_subsets():
+    # rows of W: agent 0 hears 1 and 2, agent 1 hears 0, agent 2 hears 1 (slots: 0<-1, 0<-2, 1<-0, 2<-1)
+    W = {0: [(0, 0.5), (1, 0.25), (2, 0.25)], 1: [(0, 0.5), (1, 0.5)], 2: [(1, 1.0 / 3.0), (2, 2.0 / 3.0)]}
+    X = np.array([[4.0], [8.0], [12.0]])
+    Win = np.array([[1.0], [2.0], [3.0], [5.0]])
+    # agent 1 puts 2 x_1 to agent 0 only and keeps x_1 / 4; agent 2 puts nothing (empty subset)
+    Xo, Wo = O.win_put_weighted(X, Win, W, None, self_weight=[1.0, 0.25, 1.0], dst_weights={0: {}, 1: {0: 2.0}, 2: {}})
+    np.testing.assert_array_equal(Wo[:, 0], [16.0, 2.0, 3.0, 5.0]); np.testing.assert_array_equal(Xo[:, 0], [4.0, 2.0, 12.0])
+    # accumulate: agent 1 adds x_1 / 2 at agent 2 (slot 3) and p_1 / 2 with it, keeps half
+    p = np.array([1.0, 2.0, 1.0]); wp = np.zeros(4)
+    Xo, po, Wo, wpo = O.win_accumulate_weighted(X, p, Win, wp, W, [0, 1, 0], self_weight=[9.0, 0.5, 9.0],
+                                                dst_weights={0: {}, 1: {2: 0.5}, 2: {}})
+    np.testing.assert_array_equal(Wo[:, 0], [1.0, 2.0, 3.0, 9.0]); np.testing.assert_array_equal(wpo, [0.0, 0.0, 0.0, 1.0])
+    np.testing.assert_array_equal(Xo[:, 0], [4.0, 4.0, 12.0]); np.testing.assert_array_equal(po, [1.0, 1.0, 1.0])
+    assert Xo.sum() + Wo.sum() == X.sum() + Win.sum() and po.sum() + wpo.sum() == p.sum()      # mass stays
+    # get: agent 0 fetches 3 x_2 only
+    Wo = O.win_get_weighted(X, Win, W, None, src_weights={0: {2: 3.0}, 1: {}, 2: {}})
+    np.testing.assert_array_equal(Wo[:, 0], [1.0, 36.0, 3.0, 5.0])
+    # update: agent 0 averages itself (weight 1/2) with the slot of agent 2 only (weight 1/2)
+    Xo = O.win_update_weighted(X, Win, W, [1, 0, 0], self_weight=[0.5, 1.0, 1.0], src_weights={0: {2: 0.5}, 1: {}, 2: {}})
+    np.testing.assert_array_equal(Xo[:, 0], [3.0, 8.0, 12.0])
+    # an edge outside the static topology is refused (the paper: the ranks must be a subset of the neighbors)
+    with pytest.raises(ValueError):
+        O.win_put_weighted(X, Win, W, None, dst_weights={0: {2: 1.0}, 1: {}, 2: {}})
+
+
+def test_weighted_accumulate_with_any_column_stochastic_split_conserves_mass_and_converges():
+    # asynchronous push-sum over a dynamic sub-topology: each call, every active sender picks a random
+    # subset of its out-neighbors and splits its mass evenly between them and itself
+    rng = np.random.default_rng(52)
+    n, d = 10, 2
+    W = _push_graph(n, 3, 4)
+    outs = T.out_lists(W)
+    X = rng.standard_normal((n, d)) + 2.0
+    mean, total = X.mean(0), X.sum(0)
+    p = np.ones(n)
+    E = O.window_slots(W)[0][-1]
+    Win, wp = np.zeros((E, d)), np.zeros(E)
+    for k in range(600):
+        act = rng.random(n) < 0.7
+        dst, sw = {}, np.ones(n)
+        for j in range(n):
+            nb = [i for i in outs[j] if i != j and rng.random() < 0.6]
+            dst[j] = {i: 1.0 / (len(nb) + 1) for i in nb}
+            sw[j] = 1.0 / (len(nb) + 1)
+        X, p, Win, wp = O.win_accumulate_weighted(X, p, Win, wp, W, act, sw, dst)
+        X, p, Win, wp = O.win_update_then_collect(X, p, Win, wp, W, rng.random(n) < 0.7)
+        np.testing.assert_allclose(X.sum(0) + Win.sum(0), total, atol=1e-11)
+        assert abs(p.sum() + wp.sum() - n) < 1e-12
+    assert np.abs(X / p[:, None] - mean).max() < 1e-6
