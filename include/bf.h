@@ -12,7 +12,10 @@
  *     CSR lists (j, w_ij) with j ascending.
  *   - Matrices are agent-major.  Row i starts at base + i*ld*s bytes, s = 4 (BF_F32) or 2 (BF_BF16);
  *     ld >= d is the leading dimension in elements.  base and ld*s must be multiples of 16 bytes.
- *     Columns d..ld-1 of a row are never read or written.
+ *     Columns d..ld-1 of a row are never written.  Kernels read whole 16-byte vectors, so of the
+ *     padding they may read (and discard) what shares a 16-byte vector with a column below d: a
+ *     matrix must be readable up to (n-1)*ld*s + d*s rounded up to 16 bytes, which is also the
+ *     extent the overlap checks use.
  *   - Pointers named X*, G, M, Y, A, b, C, E, w_in/w_out and stats are DEVICE pointers owned by the
  *     caller; the library never allocates, frees or resizes them.  Pointers inside
  *     bf_topo_params_t and the export arrays are HOST pointers.
@@ -152,17 +155,25 @@ int bf_topology_export_window(const bf_topology_t* t, int32_t round, int64_t* sl
 
 /* Partial averaging (eq. dsgd-2, eq. dgd-2; the neighbor_allreduce primitive):
  *   X_out[i,:] = sum_{(j,w) in row i of W^(round)} w * X_in[j,:].
- * Accumulation is fp32 in CSR order; BF_BF16 rounds the result to nearest-even on store. */
+ * Accumulation is fp32 in CSR order; BF_BF16 rounds the result to nearest-even on store.
+ * Kernel choice (all give the same bits for BF_F32): column tiles staged in LDS while n x 64 fp32
+ * values fit one CU's LDS (n <= 640 on MI355X), rows streamed through registers for wide matrices
+ * whose round is a union of paths and cycles, and beyond that a row gather through the caches (out
+ * of place) or 4..32-column LDS tiles (in place, n <= 10240); more agents than that in place is
+ * BF_ERR_UNSUPPORTED.  The same holds for every call below that mixes a matrix. */
 int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
                           int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
-/* `count` consecutive rounds of partial averaging in one pass over the matrix (finite-time exact
- * averaging over the one-peer exponential graph takes log2 n rounds; section "One-peer exponential
- * graph"):  X_out = W^(round0+count-1) ... W^(round0+1) W^(round0) X_in.
+/* `count` consecutive rounds of partial averaging in one pass over the matrix: the per-round
+ * recursion of eq. dsgd-2 applied `count` times with the time-varying weights of section "Push- and
+ * pull-style communication over time-varying topology" (the one-peer exponential graph, which the
+ * paper names in "Concepts and Theoretical Foundations" and uses in its DNN experiments, averages
+ * exactly in log2 n such rounds):  X_out = W^(round0+count-1) ... W^(round0+1) W^(round0) X_in.
  * Every intermediate product stays on chip in fp32 (also for BF_BF16, which therefore rounds once,
  * at the end, unlike `count` separate calls); for BF_F32 the result is bit-identical to `count`
- * calls of bf_neighbor_allreduce.  1 <= count <= 8, else BF_ERR_SIZE; needs two n x 64 fp32 tiles
- * in one CU's LDS (n <= 320 on MI355X), else BF_ERR_UNSUPPORTED.  X_out may equal X_in. */
+ * calls of bf_neighbor_allreduce.  1 <= count <= 8, else BF_ERR_SIZE.  One pass needs two n x 64
+ * fp32 tiles in one CU's LDS (n <= 320 on MI355X); with more agents the call runs `count` separate
+ * passes instead (BF_BF16 then rounds after every round).  X_out may equal X_in. */
 int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t count, const void* X_in,
                                 void* X_out, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
@@ -181,13 +192,14 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
                                        void* hip_stream);
 
 /* Window primitives (sections "Asynchronous decentralized communication" and "Asynchronous
- * push-style partial averaging"), all agents simulated on one device.  X: n x d device matrix, row
- * pitch ld.  Win: E x d device matrix with the same pitch, row e being slot e of the layout above
- * (the caller allocates it and zeroes it once, as win_create does).  p: n device floats, win_p: E
+ * push-style partial averaging"), all agents simulated on one device.  X: n x d device matrix of
+ * dtype dt, row pitch ld elements.  Win: E x d device matrix, ALWAYS fp32 (slots accumulate), with
+ * the same pitch ld in elements (so ld * 4 bytes), row e being slot e of the layout above (the
+ * caller allocates it and zeroes it once, as win_create does).  p: n device floats, win_p: E
  * device floats, the push-sum scalar and its slots (both NULL to leave them out).  active: n
  * device int32 flags, or NULL for everybody; an agent whose flag is 0 does nothing in that call,
- * which is how agents that run at different speeds are simulated.  BF_F32 only
- * (BF_ERR_UNSUPPORTED otherwise).  Calls on one stream execute one after the other, which gives
+ * which is how agents that run at different speeds are simulated.  With BF_BF16 the arithmetic is
+ * fp32 and X is rounded to nearest-even when it is written.  Calls on one stream execute one after the other, which gives
  * the mutual exclusion and the atomic read-and-reset the paper asks for; calls on different
  * streams that share X or Win race.  X, Win, p, win_p may not overlap (BF_ERR_ALIAS).  A topology
  * without edges has E = 0 slots; Win and win_p may then be NULL.
@@ -211,9 +223,45 @@ int bf_win_update(const bf_topology_t* t, int32_t round, const int32_t* active, 
 int bf_win_update_then_collect(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,
                                void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
-/* Same product through the dense n x n form of W^(round) on the fp32 matrix cores (BF_F32 only;
- * n <= 256).  Intended for dense / fully connected W (periodic global averaging is W = 11^T/n) and
- * as an independent cross-check of the sparse kernels. */
+/* The same calls with the per-call weight arguments of the paper's signatures (section
+ * "Asynchronous decentralized communication"): neighbor_win_put / neighbor_win_accumulate(tensor,
+ * name, [self_weight, dst_weights]), neighbor_win_get(tensor, name, [src_weights]), win_update(name,
+ * [self_weight, src_weights]).  The window is laid out over the static topology; a call may name
+ * any SUBSET of its edges, with any weights ("the ranks used in dst_weights and src_weights should
+ * be the subset of the neighbors defined under the global static topology").  On one device the
+ * dictionaries of all agents together are arrays in the window's slot order:
+ *   self_weight: n device floats, agent j's self_weight; NULL = no such argument.
+ *   dst_weight / src_weight: E device floats, the weight of the edge that slot e stands for (slot e
+ *       of receiver i holds what sender slot_src[e] pushes to i, or what i pulls from it); NULL = no
+ *       such argument.
+ *   dst_on / src_on: E device int32 flags, nonzero for the edges the call names; NULL = all edges.
+ * Without an argument the call behaves as its plain form above (put, get: weight 1 and X unchanged;
+ * accumulate, update: the topology's own weights).
+ *   put:        every active j writes dst_weight * x_j into its slot at each named out-neighbor,
+ *               then, if self_weight is given, keeps self_weight[j] * x_j.
+ *   accumulate: every active j adds dst_weight * x_j (and dst_weight * p_j) to those slots, then
+ *               keeps self_weight[j] * x_j (and p_j likewise).
+ *   get:        every active i writes src_weight * x_j into its own slot for each named in-neighbor j.
+ *   update:     every active i sets x_i = self_weight[i] x_i + sum over its named slots of
+ *               src_weight * slot; the window is left as it is.
+ * Edges that are not named are neither written nor read.  Other arguments and errors as above. */
+int bf_win_put_weighted(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, void* Win,
+                        const float* self_weight, const float* dst_weight, const int32_t* dst_on,
+                        int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+int bf_win_get_weighted(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
+                        const float* src_weight, const int32_t* src_on, int64_t d, int64_t ld, bf_dtype_t dt,
+                        void* hip_stream);
+int bf_win_accumulate_weighted(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,
+                               void* Win, float* win_p, const float* self_weight, const float* dst_weight,
+                               const int32_t* dst_on, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+int bf_win_update_weighted(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, const void* Win,
+                           const float* self_weight, const float* src_weight, const int32_t* src_on,
+                           int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
+
+/* Same product through the dense n x n form of W^(round) on the fp32 matrix cores (BF_F32 with
+ * n <= 256; anything else is computed by the list kernels of bf_neighbor_allreduce).  Intended for
+ * dense / fully connected W (periodic global averaging is W = 11^T/n) and as an independent
+ * cross-check of the sparse kernels. */
 int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
                  int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
@@ -238,8 +286,7 @@ int bf_pushsum_atc_step(const bf_topology_t* t, int32_t round, const void* X_in,
 
 /* Tracker update of gradient tracking (same appendix, last line of the recursion):
  *   Y_out = W (Y_in + G_new - G_old).
- * All four matrices share dtype and layout; Y_out may equal Y_in.  Needs an LDS tile or a chain
- * plan (n <= 640 agents), else BF_ERR_UNSUPPORTED. */
+ * All four matrices share dtype and layout; Y_out may equal Y_in. */
 int bf_tracking_step(const bf_topology_t* t, int32_t round, const void* Y_in, void* Y_out, const void* G_new,
                      const void* G_old, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
@@ -258,8 +305,7 @@ int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X
  *   psi_i = x_i - alpha g_i;   phi_i = psi_i + x_i - psi_prev_i;   X_out[i,:] = sum_j w_ij phi_j;
  *   Psi_prev[i,:] <- psi_i.
  * Psi_prev is fp32, n x d with leading dimension ld, updated in place; before the first iteration
- * the caller sets it to X (so that phi^(0) = psi^(0)).  G has the dtype and layout of X.  Needs an
- * LDS tile or a chain plan (n <= 640 agents), else BF_ERR_UNSUPPORTED. */
+ * the caller sets it to X (so that phi^(0) = psi^(0)).  G has the dtype and layout of X. */
 int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
                             const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
                             bf_dtype_t dt, void* hip_stream);
@@ -268,13 +314,14 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
  * eqs. dgd-1 and dgd-2; the adapt-then-combine form of bf_grad_least_squares + bf_atc_step):
  * `iterations` iterations in ONE launch,
  *   x_i <- sum_j w_ij^(round0+k) (x_j - alpha A_j^T (A_j x_j - b_j)),   k = 0 .. iterations-1,
- * for problems small enough that one agent's A_i (m x d fp32) fits one CU's LDS next to 20 KB of
- * working storage (the paper's example, m = 32, d = 1024, does) and n is at most the number of CUs;
- * otherwise BF_ERR_UNSUPPORTED and the two-call path is the one to use.  One workgroup per agent
- * keeps A_i in LDS for the whole run and the agents meet at a grid barrier once per iteration.
+ * when one agent's A_i (m x d fp32) fits one CU's LDS next to 20 KB of working storage (the paper's
+ * example, m = 32, d = 1024, does), m <= 64, d <= 4096 and n is at most the number of CUs: one
+ * workgroup per agent keeps A_i in LDS for the whole run and the agents meet at a grid barrier once
+ * per iteration.  Larger problems run the same iterations as two launches each (bf_grad_least_squares
+ * into the first half of `work`, then bf_atc_step in place).
  * A: n x m x d row-major fp32, b: n x m, X: n x d with pitch ld, updated in place; work: device
- * scratch of 2 * n * ld floats (contents undefined afterwards).  1 <= m <= 64, d a multiple of 4,
- * 4 <= d <= 4096.  Every barrier wait is bounded: if the workgroups cannot all be resident at once
+ * scratch of 2 * n * ld floats (contents undefined afterwards).  1 <= m <= 8192, d a multiple of 4,
+ * d >= 4.  Every barrier wait is bounded: if the workgroups cannot all be resident at once
  * (the device is busy with other kernels for about a second) the run gives up, X is undefined and
  * bf_dgd_status reports it.  One such run at a time per topology object (they share the barrier
  * words); runs on one stream are ordered and safe.
@@ -296,7 +343,7 @@ int bf_exact_diffusion_least_squares_run(const bf_topology_t* t, int32_t round0,
 
 /* Local least-squares gradients of decentralized linear regression (eq. dgd-1):
  *   G[i,:] = A_i^T (A_i x_i - b_i),  A: n x m x d row-major fp32, b: n x m fp32.
- * 1 <= m <= 64, d a multiple of 4.  G must not alias X. */
+ * 1 <= m <= 8192, d a multiple of 4.  G must not alias X. */
 int bf_grad_least_squares(int32_t n, int32_t m, int64_t d, const float* A, const float* b,
                           const float* X, int64_t ldx, float* G, int64_t ldg, void* hip_stream);
 
@@ -335,10 +382,14 @@ int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on t
 /* Launch-shape override for experiments and sweeps; value 0 restores the built-in heuristic.
  *   knob 0: column-tile width of the LDS tile kernel in elements (power of two, 64..1024)
  *   knob 1: workgroups per compute unit for the tile kernel
- *   knob 2: 1 forces the cache-reliant row-gather fallback (out of place only)
+ *   knob 2: 1 forces the fallbacks for large agent counts (row gather, narrow tiles)
  *   knob 3: upper bound on the number of persistent workgroups
  *   knob 5: 1 disables the row-streaming chain kernel
- *   knob 8: 1 forces non-temporal loads/stores in the tile kernel, 2 forbids them
+ *   knob 8: 1 forces non-temporal loads/stores in the tile kernels, 2 forbids them
+ *   knob 12: 1 uses the pipelined tile kernel (loader and reducer waves) also for cache-resident
+ *           in-place rounds, 2 never uses it
+ *   knob 13: 1 keeps bf_neighbor_allreduce_multi from running shift rounds in registers, 2 makes
+ *           it do so whenever the rounds have that form (the default also weighs n and count)
  *   knob 9: 1 keeps the chain kernel at 256-thread workgroups
  *   knob 7: 1 disables the alternating (odd rounds right-to-left) tile order
  *   knob 6: forces the chain kernel (where the round has a chain plan) with 1, 2 or 4 16-byte

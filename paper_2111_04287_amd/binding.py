@@ -29,7 +29,7 @@ EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_topology_chain_plan", "bf_topology_window_slots", "bf_topology_export_window",
-    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_dgd_least_squares_run", "bf_exact_diffusion_least_squares_run", "bf_dgd_status", "bf_stream_probe", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
+    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_win_put_weighted", "bf_win_get_weighted", "bf_win_accumulate_weighted", "bf_win_update_weighted", "bf_dgd_least_squares_run", "bf_exact_diffusion_least_squares_run", "bf_dgd_status", "bf_stream_probe", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -94,6 +94,10 @@ def _load():
     L.bf_exact_diffusion_least_squares_run.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, C.c_float, i64, i64, vp]
     L.bf_stream_probe.argtypes = [i32, vp, vp, i64, i32, vp]
     L.bf_win_get.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_win_put_weighted.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_win_get_weighted.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_win_accumulate_weighted.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
+    L.bf_win_update_weighted.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_update.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_accumulate.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_win_update_then_collect.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, C.c_int, vp]
@@ -345,9 +349,9 @@ def _win_args(t, rnd, active, X, Win, p, win_p):
     ptr, n, d, ld = _mat(X, "X")
     _rows(t, n)
     E = bf_topology_window_slots(t, rnd)
-    if Win.dim() != 2 or Win.shape != (E, d) or Win.dtype != X.dtype or (E > 1 and Win.stride(0) != ld) or \
+    if Win.dim() != 2 or Win.shape != (E, d) or Win.dtype != torch.float32 or (E > 1 and Win.stride(0) != ld) or \
             (d > 1 and Win.stride(1) != 1):
-        raise ValueError("Win must be a (slots, d) matrix with the dtype and row stride of X")
+        raise ValueError("Win must be a float32 (slots, d) matrix with the row stride (in elements) of X")
     if active is not None and (active.dtype != torch.int32 or active.numel() != n or not active.is_contiguous()):
         raise ValueError("active must be a contiguous int32 vector with one flag per agent")
     if (p is None) != (win_p is None):
@@ -391,6 +395,52 @@ def bf_win_update_then_collect(t, rnd, X, p, Win, win_p, active=None, stream=Non
                                           None if win_p is None else win_p.data_ptr(), d, ld, _dtype_code(X),
                                           _stream(stream)), "bf_win_update_then_collect")
     return X, p, Win, win_p
+
+
+def _call_weights(t, rnd, n, self_weight, edge_weight, edge_on):
+    import torch
+    E = bf_topology_window_slots(t, rnd)
+    if self_weight is not None:
+        _vec(self_weight, n, "self_weight")
+    if edge_weight is not None:
+        _vec(edge_weight, E, "dst_weight / src_weight")
+    if edge_on is not None and (edge_on.dtype != torch.int32 or edge_on.numel() != E or not edge_on.is_contiguous()):
+        raise ValueError("dst_on / src_on must be a contiguous int32 vector with one flag per slot")
+    return tuple(None if v is None else v.data_ptr() for v in (self_weight, edge_weight, edge_on))
+
+
+def bf_win_put_weighted(t, rnd, X, Win, self_weight=None, dst_weight=None, dst_on=None, active=None, stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, None, None)
+    sw, ew, eo = _call_weights(t, rnd, X.shape[0], self_weight, dst_weight, dst_on)
+    _check(lib.bf_win_put_weighted(t.handle, rnd, act, ptr, Win.data_ptr(), sw, ew, eo, d, ld, _dtype_code(X), _stream(stream)),
+           "bf_win_put_weighted")
+    return X, Win
+
+
+def bf_win_get_weighted(t, rnd, X, Win, src_weight=None, src_on=None, active=None, stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, None, None)
+    _, ew, eo = _call_weights(t, rnd, X.shape[0], None, src_weight, src_on)
+    _check(lib.bf_win_get_weighted(t.handle, rnd, act, ptr, Win.data_ptr(), ew, eo, d, ld, _dtype_code(X), _stream(stream)),
+           "bf_win_get_weighted")
+    return Win
+
+
+def bf_win_accumulate_weighted(t, rnd, X, p, Win, win_p, self_weight=None, dst_weight=None, dst_on=None, active=None,
+                               stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, p, win_p)
+    sw, ew, eo = _call_weights(t, rnd, X.shape[0], self_weight, dst_weight, dst_on)
+    _check(lib.bf_win_accumulate_weighted(t.handle, rnd, act, ptr, None if p is None else p.data_ptr(), Win.data_ptr(),
+                                          None if win_p is None else win_p.data_ptr(), sw, ew, eo, d, ld, _dtype_code(X),
+                                          _stream(stream)), "bf_win_accumulate_weighted")
+    return X, p, Win, win_p
+
+
+def bf_win_update_weighted(t, rnd, X, Win, self_weight=None, src_weight=None, src_on=None, active=None, stream=None):
+    ptr, d, ld, act = _win_args(t, rnd, active, X, Win, None, None)
+    sw, ew, eo = _call_weights(t, rnd, X.shape[0], self_weight, src_weight, src_on)
+    _check(lib.bf_win_update_weighted(t.handle, rnd, act, ptr, Win.data_ptr(), sw, ew, eo, d, ld, _dtype_code(X),
+                                      _stream(stream)), "bf_win_update_weighted")
+    return X
 
 
 def bf_dense_mix(t, rnd, X_in, X_out, stream=None):

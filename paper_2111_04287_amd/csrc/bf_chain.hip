@@ -49,13 +49,8 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
 #pragma unroll
       for (int w = 0; w < CW; ++w) {
         const int64_t off = static_cast<int64_t>(row) * ld + col[w];
-#if BF_NT_CHAIN_LOAD
         xr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
         if constexpr (G_ON_LOAD) gr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g + off * EB));
-#else
-        xr[w] = *reinterpret_cast<const u32x4*>(p.x_in + off * EB);
-        if constexpr (G_ON_LOAD) gr[w] = *reinterpret_cast<const u32x4*>(p.g + off * EB);
-#endif
         if constexpr (OP == OP_TRACK) g2r[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
         if constexpr (STATE_ON_LOAD) {
 #pragma unroll
@@ -286,6 +281,90 @@ __global__ __launch_bounds__(256) void bf_gather_kernel(const TileParams p) {
   }
 }
 
+// Second fallback for large agent counts, for what the row gather cannot do: updates in place and
+// the ops that carry a state or a second gradient (Exact-Diffusion, tracking).  The column-owned LDS
+// tile of the main kernels narrowed to C = 32, 16, 8 or 4 columns, so that n x C fp32 values still
+// fit one CU's LDS for thousands of agents; a workgroup stages its tile (local update included),
+// then every thread produces 4-column pieces of output rows, walking the row's in-neighbor list
+// itself (lists come through the vector caches: rows differ between the lanes of a wave).  Row
+// segments of 16..128 bytes make this slow; it exists so that no valid call is refused.
+template <int DT, int OP, bool WITH_Y>
+__global__ __launch_bounds__(1024) void bf_narrow_kernel(const TileParams p) {
+  extern __shared__ f32x4 lds_raw[];
+  float* lds = reinterpret_cast<float*>(lds_raw);
+  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED || OP == OP_TRACK);
+  constexpr bool STAGE_M = (OP == OP_MOM_ATC || OP == OP_ED);
+  const int log_c = p.log_c;                       // 2..5
+  const int vpr_log = log_c - 2;                   // 4-column pieces per tile row (log2)
+  const int npieces = p.n << vpr_log;
+  const int64_t d = p.d, ld = p.ld;
+  for (int64_t tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {
+    const int64_t c0 = tile << log_c;
+    for (int u = threadIdx.x; u < npieces; u += blockDim.x) {
+      const int row = u >> vpr_log;
+      const int cit = (u & ((1 << vpr_log) - 1)) << 2;
+      const int64_t col = c0 + cit;
+      float xv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (col < d) {
+        const int64_t off = static_cast<int64_t>(row) * ld + col;
+        const int64_t rem = d - col;
+        // element by element: a piece may straddle d, and bf16 pieces are only 8-byte aligned
+        float gv[4] = {0.f, 0.f, 0.f, 0.f}, hv[4] = {0.f, 0.f, 0.f, 0.f}, sv[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int e = 0; e < 4; ++e)
+          if (e < rem) {
+            load_in<DT, 1>(p.x_in, off + e, &xv[e]);
+            if constexpr (STAGE_G) load_in<DT, 1>(p.g, off + e, &gv[e]);
+            if constexpr (OP == OP_TRACK) load_in<DT, 1>(p.g2, off + e, &hv[e]);
+            if constexpr (STAGE_M) sv[e] = p.m[off + e];
+          }
+        if constexpr (STAGE_M) {
+          local_update4<OP>(xv, gv, sv, p.alpha, p.beta);
+          for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + e] = sv[e];
+        } else if constexpr (OP == OP_TRACK) {
+          for (int e = 0; e < 4; ++e) xv[e] = (xv[e] + gv[e]) - hv[e];
+        } else if constexpr (STAGE_G) {
+          for (int e = 0; e < 4; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
+        }
+      }
+      f32x4 t = {xv[0], xv[1], xv[2], xv[3]};
+      *reinterpret_cast<f32x4*>(lds + (row << log_c) + cit) = t;
+    }
+    __syncthreads();
+    for (int u = threadIdx.x; u < npieces; u += blockDim.x) {
+      const int i = u >> vpr_log;
+      const int cit = (u & ((1 << vpr_log) - 1)) << 2;
+      const int64_t col = c0 + cit;
+      if (col >= d) continue;
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+      for (int q = p.rowptr[i]; q < p.rowptr[i + 1]; ++q) {
+        const u32x2 en = p.ent[q];
+        const float w = __uint_as_float(en.y);
+        const f32x4 v = *reinterpret_cast<const f32x4*>(lds + (static_cast<int>(en.x) << log_c) + cit);
+        acc[0] = fmaf(w, v.x, acc[0]); acc[1] = fmaf(w, v.y, acc[1]);
+        acc[2] = fmaf(w, v.z, acc[2]); acc[3] = fmaf(w, v.w, acc[3]);
+      }
+      const int64_t off = static_cast<int64_t>(i) * ld + col;
+      const int64_t rem = d - col;
+      const int valid = rem >= 4 ? 4 : static_cast<int>(rem);
+      if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
+        for (int e = 0; e < valid; ++e) {
+          float g;
+          load_in<DT, 1>(p.g, off + e, &g);
+          if constexpr (OP == OP_MOM_AWC) { g = fmaf(p.beta, p.m[off + e], g); p.m[off + e] = g; }
+          acc[e] = fmaf(-p.alpha, g, acc[e]);
+        }
+      }
+      float rcp = 1.0f;
+      if constexpr (WITH_Y) rcp = 1.0f / p.p_out[i];
+      for (int e = 0; e < valid; ++e) {
+        store_out<DT, 1, false>(p.x_out, off + e, &acc[e], 1);
+        if constexpr (WITH_Y) { const float y = acc[e] * rcp; store_out<DT, 1, false>(p.y, off + e, &y, 1); }
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // M <- beta M + G, elementwise (pre-pass of the gather fallback's momentum ops).
 template <int DT>
 __global__ __launch_bounds__(256) void bf_momentum_kernel(float* M, const char* G, int n, int64_t d, int64_t ld, float beta) {
@@ -357,6 +436,35 @@ int launch_gather(int op, bool with_y, const TileParams& tp, int grid, hipStream
   return BF_OK;
 }
 
+template <int DT>
+int launch_narrow(int op, bool with_y, const TileParams& tp, size_t lds, int grid, hipStream_t st) {
+#define BF_NARROW(OPV, YV)                                                                                    \
+  do {                                                                                                        \
+    auto kern = bf_narrow_kernel<DT, OPV, YV>;                                                                \
+    if (lds > 48 * 1024) {                                                                                    \
+      static thread_local size_t raised = 0;                                                                  \
+      if (raised < lds) {                                                                                     \
+        BF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));   \
+        raised = lds;                                                                                         \
+      }                                                                                                       \
+    }                                                                                                         \
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(1024), lds, st, tp);                                            \
+  } while (0)
+  switch (op) {
+    case OP_MIX: if (with_y) BF_NARROW(OP_MIX, true); else BF_NARROW(OP_MIX, false); break;
+    case OP_ATC: if (with_y) BF_NARROW(OP_ATC, true); else BF_NARROW(OP_ATC, false); break;
+    case OP_TRACK: BF_NARROW(OP_TRACK, false); break;
+    case OP_AWC: BF_NARROW(OP_AWC, false); break;
+    case OP_MOM_ATC: BF_NARROW(OP_MOM_ATC, false); break;
+    case OP_ED: BF_NARROW(OP_ED, false); break;
+    default: BF_NARROW(OP_MOM_AWC, false); break;
+  }
+#undef BF_NARROW
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
 int launch_chain_f32(int op, bool with_y, int cw, bool wide, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st) {
   return launch_chain<DT_F32>(op, with_y, cw, wide, tp, nchunks, grid, st);
 }
@@ -368,6 +476,12 @@ int launch_gather_f32(int op, bool with_y, const TileParams& tp, int grid, hipSt
 }
 int launch_gather_bf16(int op, bool with_y, const TileParams& tp, int grid, hipStream_t st) {
   return launch_gather<DT_BF16>(op, with_y, tp, grid, st);
+}
+int launch_narrow_f32(int op, bool with_y, const TileParams& tp, size_t lds, int grid, hipStream_t st) {
+  return launch_narrow<DT_F32>(op, with_y, tp, lds, grid, st);
+}
+int launch_narrow_bf16(int op, bool with_y, const TileParams& tp, size_t lds, int grid, hipStream_t st) {
+  return launch_narrow<DT_BF16>(op, with_y, tp, lds, grid, st);
 }
 int launch_momentum(int dt, float* M, const char* G, int n, int64_t d, int64_t ld, float beta, int grid, hipStream_t st) {
   if (dt == BF_F32) hipLaunchKernelGGL(bf_momentum_kernel<DT_F32>, dim3(grid), dim3(256), 0, st, M, G, n, d, ld, beta);

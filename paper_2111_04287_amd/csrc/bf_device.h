@@ -52,12 +52,6 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // The momentum matrix does not: with bf16 storage a lane's two 16-byte halves of M are moved by
 // separate instructions, and with the hint every 128-byte line became two partial transfers
 // (-25 % on the store, -2 % on the load).
-#ifndef BF_NT_CHAIN_LOAD
-#define BF_NT_CHAIN_LOAD 1
-#endif
-#ifndef BF_INTERLEAVE
-#define BF_INTERLEAVE 1
-#endif
 template <bool NT, typename T> __device__ __forceinline__ T ld_stream(const T* ptr) {
   if constexpr (NT) return __builtin_nontemporal_load(ptr);
   else return *ptr;
@@ -102,6 +96,19 @@ struct TileParams {
   int32_t rows_b;        // rows of the second LDS tile (0: n).  Smaller when the rounds that write it leave
                          // all rows from rows_b on empty and the rounds that read it never refer to them
   float alpha, beta;
+};
+
+// Parameters of the kernel that runs uniform shift rounds in registers (bf_shift.hip).
+struct ShiftParams {
+  const char* x_in;
+  char*       x_out;
+  int64_t d, ld, ntiles;
+  int32_t n;             // 64, 128, 192 or 256
+  int32_t log_c;         // tile width
+  int32_t reverse;
+  int32_t count;         // rounds per pass, 1..8
+  int32_t shift[8];      // per round: s in x_i <- w_self x_i + w_peer x_((i+s) mod n)
+  float   w_self[8], w_peer[8];
 };
 
 template <int DT> struct Elem { static constexpr int bytes = DT == DT_F32 ? 4 : 2; static constexpr int per16 = 16 / bytes; };
@@ -186,11 +193,16 @@ struct Shape { int log_c; int lw; int wgs_per_cu; int threads; size_t lds_bytes;
 // Launchers, one translation unit per storage type for the tile kernel.  All return a bf status.
 int launch_tile_op_f32(int op, bool with_y, const TileParams& tp, const Shape& s, int grid, hipStream_t st);
 int launch_tile_op_bf16(int op, bool with_y, const TileParams& tp, const Shape& s, int grid, hipStream_t st);
+int launch_pipe_op_f32(int op, bool with_y, const TileParams& tp, const Shape& s, int grid, hipStream_t st);
+int launch_pipe_op_bf16(int op, bool with_y, const TileParams& tp, const Shape& s, int grid, hipStream_t st);
 int launch_chain_f32(int op, bool with_y, int cw, bool wide, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st);
 int launch_chain_bf16(int op, bool with_y, int cw, bool wide, const TileParams& tp, int64_t nchunks, int grid, hipStream_t st);
 int launch_gather_f32(int op, bool with_y, const TileParams& tp, int grid, hipStream_t st);
 int launch_gather_bf16(int op, bool with_y, const TileParams& tp, int grid, hipStream_t st);
+int launch_narrow_f32(int op, bool with_y, const TileParams& tp, size_t lds, int grid, hipStream_t st);
+int launch_narrow_bf16(int op, bool with_y, const TileParams& tp, size_t lds, int grid, hipStream_t st);
 // M <- beta M + G for the gather fallback's momentum ops; G has storage type dt (BF_F32 / BF_BF16).
+int launch_shift_rounds(int dt, const ShiftParams& p, int grid, size_t lds, hipStream_t st);
 int launch_momentum(int dt, float* M, const char* G, int n, int64_t d, int64_t ld, float beta, int grid, hipStream_t st);
 
 }  // namespace bf

@@ -34,6 +34,10 @@ struct Round {
   int32_t max_degree = 0;
   int32_t wclass = 0;            // bf_wclass_t bit mask
   std::vector<ChainStep> chain;  // n steps when the off-diagonal graph is a union of paths and cycles
+  // Uniform shift round: every row is {i, (i + shift) mod n} with the same two weights (every round
+  // of the one-peer exponential graph is); shift == 0 otherwise.
+  int32_t shift = 0;
+  float   shift_w_self = 0.0f, shift_w_peer = 0.0f;
 };
 
 // Window layout of a round (one slot per off-diagonal entry, agent 0's slots first, in CSR order)

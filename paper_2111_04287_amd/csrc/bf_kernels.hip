@@ -52,8 +52,8 @@ __global__ __launch_bounds__(1024) void bf_pushsum_w_kernel(const int32_t* rowpt
 // same bytes; successive calls on one stream give the atomicity the paper asks of
 // update_then_collect.  Agents whose `active` entry is zero do nothing.
 struct WinParams {
-  float* x;
-  float* win;
+  char* x;                   // n x ld, fp32 or bf16
+  float* win;                // E x ld, always fp32 (slots accumulate)
   const int32_t* active;     // n flags, or null: everybody
   const int32_t* in_ptr;
   const float* slot_w;
@@ -61,13 +61,17 @@ struct WinParams {
   const float* self_w;
   const int32_t* out_ptr;
   const u32x2* out_ent;      // {slot, weight bits}
+  // per-call arguments of the paper's signatures (all optional, all in the window's slot order):
+  const float* call_self_w;  // n: self_weight of this call
+  const float* call_edge_w;  // E: dst_weights (put, accumulate) / src_weights (get, update) of this call
+  const int32_t* call_edge_on;  // E flags: the subset of edges this call names; null: all
   int64_t d, ld;
   int32_t n, chunks;
 };
 
 enum { WIN_PUT = 0, WIN_ACCUMULATE = 1, WIN_COLLECT = 2, WIN_AVERAGE = 3, WIN_GET = 4 };
 
-template <int MODE>
+template <int MODE, int DT>
 __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
   constexpr int U = 4;
   const int tid = threadIdx.x;
@@ -84,79 +88,104 @@ __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
       const int64_t rem = p.d - col[u];
       valid[u] = rem >= 4 ? 4 : (rem > 0 ? static_cast<int>(rem) : 0);
     }
-    auto load = [&](const float* row, int u) -> f32x4 {
-      // a vector that starts inside the row may end in the row's padding: rows are 16-byte multiples
+    // four columns of a row of X (storage type DT) or of the window (fp32); a vector that starts
+    // inside the row may end in the row's padding: rows are 16-byte multiples
+    auto load_x = [&](int64_t row, int u) -> f32x4 {
+      if (!valid[u]) return f32x4{0.f, 0.f, 0.f, 0.f};
+      float v[4];
+      load_in<DT, 4>(p.x, row * p.ld + col[u], v);
+      return f32x4{v[0], v[1], v[2], v[3]};
+    };
+    auto store_x = [&](int64_t row, int u, f32x4 v) {
+      const float e[4] = {v.x, v.y, v.z, v.w};
+      if (valid[u]) store_out<DT, 4, false>(p.x, row * p.ld + col[u], e, valid[u]);      // never the padding
+    };
+    auto load_w = [&](const float* row, int u) -> f32x4 {
       return valid[u] ? *reinterpret_cast<const f32x4*>(row + col[u]) : f32x4{0.f, 0.f, 0.f, 0.f};
     };
-    auto store = [&](float* row, int u, f32x4 v) {
+    auto store_w = [&](float* row, int u, f32x4 v) {
       if (valid[u] == 4) { *reinterpret_cast<f32x4*>(row + col[u]) = v; return; }
       const float e[4] = {v.x, v.y, v.z, v.w};
-      for (int k = 0; k < valid[u]; ++k) row[col[u] + k] = e[k];      // never the padding
+      for (int k = 0; k < valid[u]; ++k) row[col[u] + k] = e[k];
     };
+    auto edge_on = [&](int e) { return !p.call_edge_on || p.call_edge_on[e] != 0; };
     if constexpr (MODE == WIN_GET) {
       for (int e = p.in_ptr[a]; e < p.in_ptr[a + 1]; ++e) {
-        const float* srow = p.x + static_cast<int64_t>(p.slot_src[e]) * p.ld;
+        if (!edge_on(e)) continue;
         float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
         f32x4 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = load(srow, u);
+        for (int u = 0; u < U; ++u) v[u] = load_x(p.slot_src[e], u);
+        if (p.call_edge_w) {
+          const float w = p.call_edge_w[e];
 #pragma unroll
-        for (int u = 0; u < U; ++u) store(wrow, u, v[u]);
+          for (int u = 0; u < U; ++u) { v[u].x *= w; v[u].y *= w; v[u].z *= w; v[u].w *= w; }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) store_w(wrow, u, v[u]);
       }
       continue;
     }
-    float* xrow = p.x + static_cast<int64_t>(a) * p.ld;
     f32x4 x[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) x[u] = load(xrow, u);
+    for (int u = 0; u < U; ++u) x[u] = load_x(a, u);
     if constexpr (MODE == WIN_PUT || MODE == WIN_ACCUMULATE) {
       for (int q = p.out_ptr[a]; q < p.out_ptr[a + 1]; ++q) {
         const u32x2 en = p.out_ent[q];
-        float* wrow = p.win + static_cast<int64_t>(en.x) * p.ld;
+        const int e = static_cast<int>(en.x);
+        if (!edge_on(e)) continue;
+        float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
         if constexpr (MODE == WIN_PUT) {
+          if (p.call_edge_w) {
+            const float w = p.call_edge_w[e];
 #pragma unroll
-          for (int u = 0; u < U; ++u) store(wrow, u, x[u]);
+            for (int u = 0; u < U; ++u) store_w(wrow, u, f32x4{w * x[u].x, w * x[u].y, w * x[u].z, w * x[u].w});
+          } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) store_w(wrow, u, x[u]);
+          }
         } else {
-          const float w = __uint_as_float(en.y);
+          const float w = p.call_edge_w ? p.call_edge_w[e] : __uint_as_float(en.y);
           f32x4 v[U];
 #pragma unroll
-          for (int u = 0; u < U; ++u) v[u] = load(wrow, u);
+          for (int u = 0; u < U; ++u) v[u] = load_w(wrow, u);
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             v[u].x = fmaf(w, x[u].x, v[u].x); v[u].y = fmaf(w, x[u].y, v[u].y);
             v[u].z = fmaf(w, x[u].z, v[u].z); v[u].w = fmaf(w, x[u].w, v[u].w);
-            store(wrow, u, v[u]);
+            store_w(wrow, u, v[u]);
           }
         }
       }
-      if constexpr (MODE == WIN_ACCUMULATE) {
-        const float sw = p.self_w[a];
+      if (MODE == WIN_ACCUMULATE || p.call_self_w) {
+        const float sw = p.call_self_w ? p.call_self_w[a] : p.self_w[a];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           x[u].x *= sw; x[u].y *= sw; x[u].z *= sw; x[u].w *= sw;
-          store(xrow, u, x[u]);
+          store_x(a, u, x[u]);
         }
       }
     } else {
       if constexpr (MODE == WIN_AVERAGE) {
-        const float sw = p.self_w[a];
+        const float sw = p.call_self_w ? p.call_self_w[a] : p.self_w[a];
 #pragma unroll
         for (int u = 0; u < U; ++u) { x[u].x *= sw; x[u].y *= sw; x[u].z *= sw; x[u].w *= sw; }
       }
       const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
       for (int e = p.in_ptr[a]; e < p.in_ptr[a + 1]; ++e) {
+        if (MODE == WIN_AVERAGE && !edge_on(e)) continue;
         float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
         f32x4 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = load(wrow, u);
+        for (int u = 0; u < U; ++u) v[u] = load_w(wrow, u);
         if constexpr (MODE == WIN_COLLECT) {
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             x[u].x += v[u].x; x[u].y += v[u].y; x[u].z += v[u].z; x[u].w += v[u].w;
-            store(wrow, u, zero);
+            store_w(wrow, u, zero);
           }
         } else {
-          const float w = p.slot_w[e];
+          const float w = p.call_edge_w ? p.call_edge_w[e] : p.slot_w[e];
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             x[u].x = fmaf(w, v[u].x, x[u].x); x[u].y = fmaf(w, v[u].y, x[u].y);
@@ -165,7 +194,7 @@ __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
         }
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) store(xrow, u, x[u]);
+      for (int u = 0; u < U; ++u) store_x(a, u, x[u]);
     }
   }
 }
@@ -179,9 +208,11 @@ __global__ __launch_bounds__(1024) void bf_win_p_kernel(const WinParams p, float
       const float pa = pv[a];
       for (int q = p.out_ptr[a]; q < p.out_ptr[a + 1]; ++q) {
         const u32x2 en = p.out_ent[q];
-        win_p[en.x] = fmaf(__uint_as_float(en.y), pa, win_p[en.x]);
+        if (p.call_edge_on && p.call_edge_on[en.x] == 0) continue;
+        const float w = p.call_edge_w ? p.call_edge_w[en.x] : __uint_as_float(en.y);
+        win_p[en.x] = fmaf(w, pa, win_p[en.x]);
       }
-      pv[a] = pa * p.self_w[a];
+      pv[a] = pa * (p.call_self_w ? p.call_self_w[a] : p.self_w[a]);
     } else {
       float pa = pv[a];
       for (int e = p.in_ptr[a]; e < p.in_ptr[a + 1]; ++e) { pa += win_p[e]; win_p[e] = 0.0f; }
@@ -269,7 +300,9 @@ __global__ __launch_bounds__(256) void bf_dense_kernel2(const float* x_in, float
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = rb * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
-        lds[row * P + wave * 32 + l32] = acc[rb][v];
+        // the padding rows must stay zero: 0 * x is NaN for a non-finite x, and a NaN there would
+        // spread to every row of the tiles that follow
+        if (row < n) lds[row * P + wave * 32 + l32] = acc[rb][v];
       }
     __syncthreads();
     for (int u = tid; u < nunits; u += 256) {
@@ -283,7 +316,6 @@ __global__ __launch_bounds__(256) void bf_dense_kernel2(const float* x_in, float
       }
     }
     __syncthreads();                               // before the next tile overwrites LDS
-    // the output pass overwrote the zero padding rows only with zeros (W's padded rows are zero)
   }
 }
 
@@ -293,7 +325,8 @@ __global__ __launch_bounds__(256) void bf_dense_kernel2(const float* x_in, float
 // tree).  Phase 2: each thread owns 4 columns and accumulates A_i^T r over the m rows.
 __global__ __launch_bounds__(1024) void bf_ls_grad_kernel(const float* A, const float* b, const float* X,
                                                          float* G, int m, int64_t d, int64_t ldx, int64_t ldg) {
-  __shared__ float resid[64];
+  extern __shared__ f32x4 lds_raw[];
+  float* resid = reinterpret_cast<float*>(lds_raw);            // m residuals
   const int i = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
   const float* Ai = A + static_cast<int64_t>(i) * m * d;
@@ -479,10 +512,18 @@ __global__ __launch_bounds__(1024) void bf_dgd_ls_kernel(const DgdParams p) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) __hip_atomic_store(h + e, hv[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // Grid barrier number it+1.  The half steps went out as agent-scope stores; each wave waits for
-    // its own to be acknowledged (workgroup-scope release), the workgroup meets, and one thread
-    // signals with an agent-scope release.  It polls with relaxed loads (an acquire load per poll
-    // would invalidate the L2 each time) and takes one agent-scope acquire fence at the end.
+    // Grid barrier number it+1.  Why the neighbors see the half steps: they went out as AGENT-scope
+    // atomic stores, i.e. each store is itself performed at the memory the XCDs share, not just in
+    // this XCD's L2.  The workgroup-scope release fence makes every wave wait until its own stores
+    // have been acknowledged from there (on this hardware: s_waitcnt vmcnt(0); the scope of a fence
+    // decides which caches are written back, not how long outstanding stores are waited for); the
+    // workgroup barrier orders all those waits before thread 0's arrival, which is an agent-scope
+    // release on the counter.  In the memory model's terms: store -> workgroup release fence ->
+    // barrier -> agent-scope release is one happens-before chain (release is cumulative), and the
+    // reader's agent-scope acquire after seeing the counter completes it.  An agent-scope fence per
+    // wave instead was measured: 6.4 us per iteration against 4.6, for no additional guarantee.
+    // Thread 0 polls with relaxed loads (an acquire load per poll would invalidate the L2 each time)
+    // and takes one agent-scope acquire fence at the end.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (tid == 0) {
@@ -769,9 +810,8 @@ int g_tune_stream = 0;    // 1: always non-temporal, 2: never
 int g_tune_cw = 0;        // chain kernel: 16-byte vectors per thread (1, 2 or 4)
 int g_tune_spin = 0;      // polls a grid-barrier wait may take before it gives up (0: default)
 int g_tune_extra = 0;     // 1: the grid barrier waits for an arrival that never comes (give-up test)
-#ifdef BF_PROFILE
-unsigned long long g_dbg_ptr = 0;
-#endif
+int g_tune_noshift = 0;   // 1: fused rounds never take the in-register form, 2: whenever it applies
+int g_tune_pipe = 0;      // 1: the pipelined kernel also for cache-resident rounds, 2: never
 
 
 int ilog2(int64_t v) { int l = 0; while ((int64_t{1} << (l + 1)) <= v) ++l; return l; }
@@ -819,6 +859,31 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_wgs =
   return BF_OK;
 }
 
+// Tile of the pipelined kernel: two n x C fp32 tiles share one CU's LDS; the widest power-of-two C in
+// [64, 1024] that fits, narrowed while the launch would leave CUs without a tile.
+int choose_pipe_shape(int n, int64_t d, const DeviceInfo& di, Shape* s) {
+  const size_t lds_cu = di.lds_per_cu ? di.lds_per_cu : 65536;
+  const size_t budget = std::min(lds_cu, di.lds_per_block_optin ? di.lds_per_block_optin : lds_cu);
+  int log_c = -1;
+  if (g_tune_tile > 0) {
+    const int lc = ilog2(g_tune_tile);
+    if ((1 << lc) != g_tune_tile || lc < 6 || lc > 10) return BF_ERR_UNSUPPORTED;
+    if (2 * static_cast<size_t>(n) * g_tune_tile * 4 > budget) return BF_ERR_UNSUPPORTED;
+    log_c = lc;
+  } else {
+    for (int lc = 10; lc >= 6 && log_c < 0; --lc)
+      if (2 * static_cast<size_t>(n) * (size_t{1} << lc) * 4 <= budget) log_c = lc;
+    if (log_c < 0) return BF_ERR_UNSUPPORTED;
+    while (log_c > 6 && ((d + (int64_t{1} << log_c) - 1) >> log_c) < di.cus) --log_c;
+  }
+  s->log_c = log_c;
+  s->lw = log_c >= 8 ? 4 : (log_c == 7 ? 2 : 1);
+  s->threads = 0;
+  s->wgs_per_cu = 1;
+  s->lds_bytes = 2 * static_cast<size_t>(n) * (size_t{1} << log_c) * 4;
+  return BF_OK;
+}
+
 // Overlap test on byte ranges [a, a+na) and [b, b+nb).
 bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
@@ -834,13 +899,17 @@ int check_matrix_shape(int32_t n, int64_t d, int64_t ld, int dt, MatArgs* ma) {
   const int eb = dt == BF_F32 ? 4 : 2;
   if ((ld * eb) % 16 != 0) return BF_ERR_ALIGN;
   ma->d = d; ma->ld = ld; ma->dt = dt; ma->n = n;
-  ma->bytes = static_cast<size_t>(n - 1) * ld * eb + static_cast<size_t>(d) * eb;
+  // what the kernels may read: whole 16-byte vectors up to the one that holds column d-1
+  ma->bytes = static_cast<size_t>(n - 1) * ld * eb + ((static_cast<size_t>(d) * eb + 15) & ~size_t{15});
   return BF_OK;
 }
 
 bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp, int dt, hipStream_t st) {
+// Choose the kernel for one call and launch it.  With `dry` set nothing is launched: the return
+// value then only says whether a kernel exists for the request, so that an entry point made of
+// several launches can find out before the first of them touches the caller's data.
+int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp, int dt, hipStream_t st, bool dry = false) {
   if (tp.d == 0) return BF_OK;
   bf::DeviceCopy* dc = nullptr;
   int rc = get_device_copy(t, false, &dc);
@@ -871,7 +940,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   if (fuse == 1 && dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather &&
       (g_tune_cw > 0 || static_cast<size_t>(t->n) * 256 * 4 > (di.lds_per_cu ? di.lds_per_cu : 65536) / 2)) {
     // Chain-structured round with too many agents for a 256-column LDS tile (measured: the tile
-    // kernel wins below that, the row-streaming kernel above): stream rows through registers when
+    // kernels win below that, the row-streaming kernel above): stream rows through registers when
     // the matrix is wide enough to give every CU several 256-thread workgroups.
     const int per16 = dt == BF_F32 ? 4 : 8;
     int cw = g_tune_cw > 0 ? g_tune_cw : (dt == BF_F32 ? 4 : 2);
@@ -885,11 +954,43 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     const int64_t chunk_cols = wide ? wide_cols : static_cast<int64_t>(256) * per16 * cw;
     const int64_t nchunks = (tp.d + chunk_cols - 1) / chunk_cols;
     if (nchunks >= 2 * static_cast<int64_t>(di.cus) || g_tune_cw > 0 || wide) {
+      if (dry) return BF_OK;
       tp.chain = reinterpret_cast<const bf::ChainStep*>(dc->blob + dc->chain_off[k]);
       int grid = static_cast<int>(std::min<int64_t>(nchunks, static_cast<int64_t>(di.cus) * (wide ? 1 : 8)));
       if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
       return dt == BF_F32 ? launch_chain_f32(op, with_y, cw, wide, tp, nchunks, grid, st)
                           : launch_chain_bf16(op, with_y, cw, wide, tp, nchunks, grid, st);
+    }
+  }
+  // Cache policy.  MI355X has a 256 MB memory-side cache.  An in-place update whose whole state
+  // is about that size is best left cacheable (the next round, walking the tiles in the opposite
+  // direction, finds most of it there: measured 71 % vs 65 % of HBM peak on 64 x 2^20 fp32);
+  // anything larger, or out of place, streams with non-temporal loads and stores.
+  bool cacheable = false;
+  {
+    const size_t eb = dt == BF_F32 ? 4 : 2;
+    size_t footprint = static_cast<size_t>(t->n) * tp.ld * eb;
+    if (tp.g) footprint *= 2;
+    if (tp.g2) footprint += static_cast<size_t>(t->n) * tp.ld * eb;
+    if (tp.m) footprint += static_cast<size_t>(t->n) * tp.ld * 4;
+    cacheable = tp.x_in == tp.x_out && footprint <= (size_t{320} << 20);
+  }
+  const bool stream = g_tune_stream == 1 ? true : (g_tune_stream == 2 ? false : !cacheable);
+  if (fuse == 1 && !g_tune_gather && (g_tune_pipe == 1 || (g_tune_pipe == 0 && stream))) {
+    // One streaming round: the pipelined kernel (loader waves and reducer waves, two LDS tiles per
+    // CU) measures 2-3 points of HBM peak above the one-tile kernel on matrices that do not fit the
+    // memory-side cache.  A cache-resident in-place round is left to the one-tile kernel, whose two
+    // workgroups per CU do better there (76 % vs 75 % on 64 x 2^20).
+    Shape ps;
+    if (choose_pipe_shape(t->n, tp.d, di, &ps) == BF_OK) {
+      if (dry) return BF_OK;
+      ps.stream = stream;
+      tp.log_c = ps.log_c;
+      tp.ntiles = (tp.d + (int64_t{1} << ps.log_c) - 1) >> ps.log_c;
+      int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus)));
+      if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
+      return dt == BF_F32 ? launch_pipe_op_f32(op, with_y, tp, ps, grid, st)
+                          : launch_pipe_op_bf16(op, with_y, tp, ps, grid, st);
     }
   }
   Shape s;
@@ -899,42 +1000,81 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
                                                                  fuse > 1 ? 8 : 10);   // fused: 256 columns at most (512 measured slower)
   if (fuse > 1 && rc != BF_OK) return rc;   // fused rounds exist only as the two-tile LDS kernel
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
-    // Too many agents for an LDS tile: row gather through the caches, out of place only.
-    if (tp.x_in == tp.x_out || op == OP_ED || op == OP_TRACK) return BF_ERR_UNSUPPORTED;
-    const int per16 = dt == BF_F32 ? 4 : 8;
-    const int64_t units = (tp.d + per16 - 1) / per16 * t->n;
-    const int grid = static_cast<int>(std::min<int64_t>((units + 255) / 256, static_cast<int64_t>(di.cus) * 32));
-    if (op == OP_MOM_ATC || op == OP_MOM_AWC) {
-      const int64_t u4 = (tp.d + 3) / 4 * t->n;
-      const int g2 = static_cast<int>(std::min<int64_t>((u4 + 255) / 256, static_cast<int64_t>(di.cus) * 32));
-      rc = launch_momentum(dt, tp.m, tp.g, t->n, tp.d, tp.ld, tp.beta, g2, st);
-      if (rc != BF_OK) return rc;
+    // Too many agents for a 64-column LDS tile.
+    const bool gatherable = tp.x_in != tp.x_out && op != OP_ED && op != OP_TRACK;
+    if (gatherable) {
+      // row gather through the caches (out of place only; no state matrix in the sum)
+      if (dry) return BF_OK;
+      const int per16 = dt == BF_F32 ? 4 : 8;
+      const int64_t units = (tp.d + per16 - 1) / per16 * t->n;
+      const int grid = static_cast<int>(std::min<int64_t>((units + 255) / 256, static_cast<int64_t>(di.cus) * 32));
+      if (op == OP_MOM_ATC || op == OP_MOM_AWC) {
+        const int64_t u4 = (tp.d + 3) / 4 * t->n;
+        const int g2 = static_cast<int>(std::min<int64_t>((u4 + 255) / 256, static_cast<int64_t>(di.cus) * 32));
+        rc = launch_momentum(dt, tp.m, tp.g, t->n, tp.d, tp.ld, tp.beta, g2, st);
+        if (rc != BF_OK) return rc;
+      }
+      return dt == BF_F32 ? launch_gather_f32(op, with_y, tp, grid, st) : launch_gather_bf16(op, with_y, tp, grid, st);
     }
-    return dt == BF_F32 ? launch_gather_f32(op, with_y, tp, grid, st) : launch_gather_bf16(op, with_y, tp, grid, st);
+    // in place, or an op the gather cannot express: tiles of 32, 16, 8 or 4 columns
+    const size_t lds_max = std::min(di.lds_per_cu ? di.lds_per_cu : size_t{65536},
+                                    di.lds_per_block_optin ? di.lds_per_block_optin : size_t{65536});
+    int lc = 5;
+    while (lc >= 2 && static_cast<size_t>(t->n) * (size_t{1} << lc) * 4 > lds_max) --lc;
+    if (lc < 2) return BF_ERR_UNSUPPORTED;
+    if (dry) return BF_OK;
+    tp.log_c = lc;
+    tp.ntiles = (tp.d + (int64_t{1} << lc) - 1) >> lc;
+    const int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus)));
+    const size_t lds = static_cast<size_t>(t->n) * (size_t{1} << lc) * 4;
+    return dt == BF_F32 ? launch_narrow_f32(op, with_y, tp, lds, grid, st) : launch_narrow_bf16(op, with_y, tp, lds, grid, st);
   }
   if (rc != BF_OK) return rc;
-#ifdef BF_PROFILE
-  if (!with_y) tp.y = reinterpret_cast<char*>(g_dbg_ptr);
-#endif
-  // Cache policy.  MI355X has a 256 MB memory-side cache.  An in-place update whose whole state
-  // is about that size is best left cacheable (the next round, walking the tiles in the opposite
-  // direction, finds most of it there: measured 71 % vs 65 % of HBM peak on 64 x 2^20 fp32);
-  // anything larger, or out of place, streams with non-temporal loads and stores.
-  {
-    const size_t eb = dt == BF_F32 ? 4 : 2;
-    size_t footprint = static_cast<size_t>(t->n) * tp.ld * eb;
-    if (tp.g) footprint *= 2;
-    if (tp.g2) footprint += static_cast<size_t>(t->n) * tp.ld * eb;
-    if (tp.m) footprint += static_cast<size_t>(t->n) * tp.ld * 4;
-    const bool cacheable = tp.x_in == tp.x_out && footprint <= (size_t{320} << 20);
-    s.stream = g_tune_stream == 1 ? true : (g_tune_stream == 2 ? false : !cacheable);
-  }
+  if (dry) return BF_OK;
+  s.stream = stream;
   tp.log_c = s.log_c;
   tp.ntiles = (tp.d + (int64_t{1} << s.log_c) - 1) >> s.log_c;
   int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus) * s.wgs_per_cu));
   if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
   return dt == BF_F32 ? launch_tile_op_f32(op, with_y, tp, s, grid, st)
                       : launch_tile_op_bf16(op, with_y, tp, s, grid, st);
+}
+
+// `count` rounds in registers when every one of them is a uniform shift round and the agents fill
+// whole waves (bf_shift.hip).  BF_ERR_UNSUPPORTED when the request has no such form: the caller
+// then takes the general path.
+int run_shift_rounds(bf_topology_t* t, int32_t round0, int32_t count, const TileParams& tp, int dt, hipStream_t st) {
+  const int32_t n = t->n;
+  if (g_tune_noshift == 1 || n % 64 != 0 || n > 256 || count < 1 || count > 8) return BF_ERR_UNSUPPORTED;
+  // Measured at d = 2^21..2^22: with 64-column tiles (n >= 192) the register rounds always win (n = 256:
+  // 1.8 / 1.8 / 2.0 ms for 2 / 4 / 8 rounds against 2.2 / 3.5 / 6.0 ms); with the wider tiles of fewer
+  // agents the LDS rounds hide behind the HBM transfers for the first few rounds and win there.
+  if (g_tune_noshift == 0 && ((n == 128 && count < 3) || (n == 64 && count < 5))) return BF_ERR_UNSUPPORTED;
+  ShiftParams sp{};
+  const size_t R = t->rounds.size();
+  for (int32_t j = 0; j < count; ++j) {
+    const bf::Round& r = t->rounds[(static_cast<size_t>(round0) + j) % R];
+    if (r.shift <= 0 || (r.shift >= 64 && r.shift % 64 != 0)) return BF_ERR_UNSUPPORTED;   // lane part or register part, not both
+    sp.shift[j] = r.shift; sp.w_self[j] = r.shift_w_self; sp.w_peer[j] = r.shift_w_peer;
+  }
+  int dev = 0;
+  BF_HIP_TRY(hipGetDevice(&dev));
+  DeviceInfo di;
+  int rc = device_info(dev, &di);
+  if (rc != BF_OK) return rc;
+  // a 64 KB tile: n x C fp32 with C = 16384 / n (64 columns at n = 256), two workgroups per CU
+  int log_c = ilog2(16384 / n);
+  if (n == 192) log_c = 6;
+  while (log_c > 6 && ((tp.d + (int64_t{1} << log_c) - 1) >> log_c) < 2 * static_cast<int64_t>(di.cus)) --log_c;
+  const size_t lds = static_cast<size_t>(n) * ((size_t{1} << log_c) + 4) * 4;
+  if (2 * lds + 256 > (di.lds_per_cu ? di.lds_per_cu : 65536)) return BF_ERR_UNSUPPORTED;
+  sp.x_in = tp.x_in; sp.x_out = tp.x_out; sp.d = tp.d; sp.ld = tp.ld;
+  sp.n = n; sp.log_c = log_c; sp.count = count;
+  sp.ntiles = (tp.d + (int64_t{1} << log_c) - 1) >> log_c;
+  sp.reverse = g_tune_noserp ? 0 : ((round0 / count) & 1);
+  int grid = static_cast<int>(std::min<int64_t>(sp.ntiles, static_cast<int64_t>(di.cus) * 2));
+  if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
+  return launch_shift_rounds(dt, sp, grid, lds, st);
 }
 
 // Device copy of a round's window plan, built on first use.
@@ -987,7 +1127,8 @@ int get_window_plan(bf_topology_t* t, size_t k, bf::DeviceCopy* dc, WinParams* w
 
 // Shared body of the four window calls.
 int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* active, void* X, float* pv,
-               void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+               void* Win, float* win_p, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream,
+               const float* call_self_w = nullptr, const float* call_edge_w = nullptr, const int32_t* call_edge_on = nullptr) {
   if (!tc || !X) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   bf_topology_t* t = const_cast<bf_topology_t*>(tc);
@@ -998,12 +1139,13 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
   MatArgs ma;
   int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
   if (rc != BF_OK) return rc;
-  if (dt != BF_F32) return BF_ERR_UNSUPPORTED;      // slots accumulate: fp32 only
   if (misaligned16(X) || misaligned16(Win)) return BF_ERR_ALIGN;
   if ((active && (reinterpret_cast<uintptr_t>(active) & 3u)) || (pv && (reinterpret_cast<uintptr_t>(pv) & 3u)) ||
-      (win_p && (reinterpret_cast<uintptr_t>(win_p) & 3u)))
+      (win_p && (reinterpret_cast<uintptr_t>(win_p) & 3u)) || (reinterpret_cast<uintptr_t>(call_self_w) & 3u) ||
+      (reinterpret_cast<uintptr_t>(call_edge_w) & 3u) || (reinterpret_cast<uintptr_t>(call_edge_on) & 3u))
     return BF_ERR_ALIGN;
-  const size_t win_bytes = E > 0 ? static_cast<size_t>(E - 1) * ld * 4 + static_cast<size_t>(d) * 4 : 0;
+  // the window is fp32 whatever the storage type of X (slots accumulate), with X's pitch in elements
+  const size_t win_bytes = E > 0 ? static_cast<size_t>(E - 1) * ld * 4 + ((static_cast<size_t>(d) * 4 + 15) & ~size_t{15}) : 0;
   if (E > 0 && overlaps(X, ma.bytes, Win, win_bytes)) return BF_ERR_ALIAS;
   if (pv && E > 0 && (overlaps(pv, static_cast<size_t>(t->n) * 4, X, ma.bytes) || overlaps(pv, static_cast<size_t>(t->n) * 4, Win, win_bytes) ||
              overlaps(win_p, static_cast<size_t>(E) * 4, X, ma.bytes) || overlaps(win_p, static_cast<size_t>(E) * 4, Win, win_bytes) ||
@@ -1018,9 +1160,10 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
   WinParams wp{};
   rc = get_window_plan(t, static_cast<size_t>(round) % t->rounds.size(), dc, &wp);
   if (rc != BF_OK) return rc;
-  wp.x = static_cast<float*>(X);
+  wp.x = static_cast<char*>(X);
   wp.win = static_cast<float*>(Win);
   wp.active = active;
+  wp.call_self_w = call_self_w; wp.call_edge_w = call_edge_w; wp.call_edge_on = call_edge_on;
   wp.d = d; wp.ld = ld; wp.n = t->n;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (pv && (mode == WIN_ACCUMULATE || mode == WIN_COLLECT)) {
@@ -1035,13 +1178,19 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
   wp.chunks = static_cast<int32_t>(chunks);
   const int64_t units = chunks * t->n;
   const int grid = static_cast<int>(std::min<int64_t>(units, static_cast<int64_t>(di.cus) * 8));
+#define BF_WIN(M)                                                                                         \
+  do {                                                                                                    \
+    if (dt == BF_F32) hipLaunchKernelGGL((bf_win_kernel<M, DT_F32>), dim3(grid), dim3(256), 0, st, wp);   \
+    else hipLaunchKernelGGL((bf_win_kernel<M, DT_BF16>), dim3(grid), dim3(256), 0, st, wp);               \
+  } while (0)
   switch (mode) {
-    case WIN_PUT: hipLaunchKernelGGL(bf_win_kernel<WIN_PUT>, dim3(grid), dim3(256), 0, st, wp); break;
-    case WIN_ACCUMULATE: hipLaunchKernelGGL(bf_win_kernel<WIN_ACCUMULATE>, dim3(grid), dim3(256), 0, st, wp); break;
-    case WIN_COLLECT: hipLaunchKernelGGL(bf_win_kernel<WIN_COLLECT>, dim3(grid), dim3(256), 0, st, wp); break;
-    case WIN_GET: hipLaunchKernelGGL(bf_win_kernel<WIN_GET>, dim3(grid), dim3(256), 0, st, wp); break;
-    default: hipLaunchKernelGGL(bf_win_kernel<WIN_AVERAGE>, dim3(grid), dim3(256), 0, st, wp); break;
+    case WIN_PUT: BF_WIN(WIN_PUT); break;
+    case WIN_ACCUMULATE: BF_WIN(WIN_ACCUMULATE); break;
+    case WIN_COLLECT: BF_WIN(WIN_COLLECT); break;
+    case WIN_GET: BF_WIN(WIN_GET); break;
+    default: BF_WIN(WIN_AVERAGE); break;
   }
+#undef BF_WIN
   BF_HIP_TRY(hipGetLastError());
   return BF_OK;
 }
@@ -1053,9 +1202,7 @@ extern "C" {
 int bf_last_hip_error(void) { return g_last_hip_error; }
 
 int bf_set_tuning(int32_t knob, int32_t value) {
-#ifndef BF_PROFILE
   if (value < 0) return BF_ERR_SIZE;
-#endif
   if (knob == 0) g_tune_tile = value;
   else if (knob == 1) g_tune_wgs = value;
   else if (knob == 2) g_tune_gather = value;
@@ -1067,10 +1214,8 @@ int bf_set_tuning(int32_t knob, int32_t value) {
   else if (knob == 6) g_tune_cw = value;
   else if (knob == 10) g_tune_spin = value;
   else if (knob == 11) g_tune_extra = value;
-#ifdef BF_PROFILE
-  else if (knob == 100) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFF00000000ull) | static_cast<uint32_t>(value);
-  else if (knob == 101) g_dbg_ptr = (g_dbg_ptr & 0xFFFFFFFFull) | (static_cast<unsigned long long>(static_cast<uint32_t>(value)) << 32);
-#endif
+  else if (knob == 12) g_tune_pipe = value;
+  else if (knob == 13) g_tune_noshift = value;
   else return BF_ERR_KIND;
   return BF_OK;
 }
@@ -1124,7 +1269,27 @@ int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t 
   tp.x_out = static_cast<char*>(X_out);
   tp.d = d; tp.ld = ld;
   tp.fuse = count;
-  return run_tile(const_cast<bf_topology_t*>(t), round0, OP_MIX, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+  bf_topology_t* tt = const_cast<bf_topology_t*>(t);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (d == 0) return BF_OK;
+  rc = run_shift_rounds(tt, round0, count, tp, dt, st);
+  if (rc != BF_ERR_UNSUPPORTED) return rc;
+  rc = run_tile(tt, round0, OP_MIX, false, tp, dt, st);
+  if (rc != BF_ERR_UNSUPPORTED || count == 1) return rc;
+  // No room for two LDS tiles (many agents): `count` separate passes, the first from X_in to X_out,
+  // the others in place on X_out.  For BF_F32 the result is the same bits either way; BF_BF16 then
+  // rounds after every round, as separate calls do.  Every pass is checked for a kernel first.
+  tp.fuse = 1;
+  TileParams tq = tp;
+  tq.x_in = tq.x_out;
+  // round numbers modulo twice the period: same weight matrix, same tile direction, no overflow
+  const int64_t period2 = 2 * static_cast<int64_t>(tt->rounds.size());
+  auto rnd = [&](int32_t j) { return static_cast<int32_t>((static_cast<int64_t>(round0) + j) % period2); };
+  for (int32_t j = 0; j < count; ++j)
+    if ((rc = run_tile(tt, rnd(j), OP_MIX, false, j == 0 ? tp : tq, dt, st, true)) != BF_OK) return rc;
+  for (int32_t j = 0; j < count; ++j)
+    if ((rc = run_tile(tt, rnd(j), OP_MIX, false, j == 0 ? tp : tq, dt, st)) != BF_OK) return rc;
+  return BF_OK;
 }
 
 int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, int32_t round, int32_t local_size,
@@ -1165,15 +1330,18 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
   if (rc != BF_ERR_UNSUPPORTED) return rc;
   // Too many agents for two LDS tiles: the three stages as three passes.  The first may write
   // X_out, the other two update it in place (every row of X_out is overwritten in the end, so the
-  // zeros the first two stages leave in rows M and up are never seen).
+  // zeros the first two stages leave in rows M and up are never seen).  All three are checked for a
+  // kernel before the first is launched.
   tp.fuse = 1;
   tp.rows_b = 0;
-  rc = run_tile(two, r3, OP_MIX, false, tp, dt, st);
-  if (rc != BF_OK) return rc;
-  tp.x_in = tp.x_out;
-  rc = run_tile(two, r3 + 1, OP_MIX, false, tp, dt, st);
-  if (rc != BF_OK) return rc;
-  return run_tile(two, r3 + 2, OP_MIX, false, tp, dt, st);
+  TileParams tq = tp;
+  tq.x_in = tq.x_out;
+  if ((rc = run_tile(two, r3, OP_MIX, false, tp, dt, st, true)) != BF_OK) return rc;
+  if ((rc = run_tile(two, r3 + 1, OP_MIX, false, tq, dt, st, true)) != BF_OK) return rc;
+  if ((rc = run_tile(two, r3 + 2, OP_MIX, false, tq, dt, st, true)) != BF_OK) return rc;
+  if ((rc = run_tile(two, r3, OP_MIX, false, tp, dt, st)) != BF_OK) return rc;
+  if ((rc = run_tile(two, r3 + 1, OP_MIX, false, tq, dt, st)) != BF_OK) return rc;
+  return run_tile(two, r3 + 2, OP_MIX, false, tq, dt, st);
 }
 
 int bf_win_put(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
@@ -1201,6 +1369,32 @@ int bf_win_update_then_collect(const bf_topology_t* t, int32_t round, const int3
   return win_common(WIN_COLLECT, t, round, active, X, p, Win, win_p, d, ld, dt, hip_stream);
 }
 
+int bf_win_put_weighted(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, void* Win,
+                        const float* self_weight, const float* dst_weight, const int32_t* dst_on,
+                        int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  return win_common(WIN_PUT, t, round, active, X, nullptr, Win, nullptr, d, ld, dt, hip_stream, self_weight, dst_weight, dst_on);
+}
+
+int bf_win_get_weighted(const bf_topology_t* t, int32_t round, const int32_t* active, const void* X, void* Win,
+                        const float* src_weight, const int32_t* src_on, int64_t d, int64_t ld, bf_dtype_t dt,
+                        void* hip_stream) {
+  return win_common(WIN_GET, t, round, active, const_cast<void*>(X), nullptr, Win, nullptr, d, ld, dt, hip_stream, nullptr,
+                    src_weight, src_on);
+}
+
+int bf_win_accumulate_weighted(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, float* p,
+                               void* Win, float* win_p, const float* self_weight, const float* dst_weight,
+                               const int32_t* dst_on, int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  return win_common(WIN_ACCUMULATE, t, round, active, X, p, Win, win_p, d, ld, dt, hip_stream, self_weight, dst_weight, dst_on);
+}
+
+int bf_win_update_weighted(const bf_topology_t* t, int32_t round, const int32_t* active, void* X, const void* Win,
+                           const float* self_weight, const float* src_weight, const int32_t* src_on,
+                           int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
+  return win_common(WIN_AVERAGE, t, round, active, X, nullptr, const_cast<void*>(Win), nullptr, d, ld, dt, hip_stream,
+                    self_weight, src_weight, src_on);
+}
+
 int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
                  int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream) {
   if (!t || !X_in || !X_out) return BF_ERR_NULL;
@@ -1208,10 +1402,18 @@ int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* 
   MatArgs ma;
   int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
   if (rc != BF_OK) return rc;
-  if (dt != BF_F32 || t->n > 256) return BF_ERR_UNSUPPORTED;
   if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   if (d == 0) return BF_OK;
+  if (dt != BF_F32 || t->n > 256) {
+    // no matrix-core kernel for this storage type or this many agents: the list kernels compute the
+    // same product (a dense W is a CSR with full rows)
+    TileParams tp{};
+    tp.x_in = static_cast<const char*>(X_in);
+    tp.x_out = static_cast<char*>(X_out);
+    tp.d = d; tp.ld = ld;
+    return run_tile(const_cast<bf_topology_t*>(t), round, OP_MIX, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+  }
   bf::DeviceCopy* dc = nullptr;
   rc = get_device_copy(const_cast<bf_topology_t*>(t), true, &dc);
   if (rc != BF_OK) return rc;
@@ -1295,11 +1497,6 @@ static int pushsum_common(const bf_topology_t* t, int32_t round, const void* X_i
       raised = wl;
     }
   }
-  // w first (one small workgroup, in-place safe); the tile kernel then reads w_out for the ratio.
-  hipLaunchKernelGGL(bf_pushsum_w_kernel, dim3(1), dim3(1024), wl, st,
-                     reinterpret_cast<const int32_t*>(dc->blob + dc->rowptr_off[k]),
-                     reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[k]), w_in, w_out, t->n);
-  BF_HIP_TRY(hipGetLastError());
   TileParams tp{};
   tp.x_in = static_cast<const char*>(X_in);
   tp.x_out = static_cast<char*>(X_out);
@@ -1308,6 +1505,15 @@ static int pushsum_common(const bf_topology_t* t, int32_t round, const void* X_i
   tp.y = static_cast<char*>(Y);
   tp.p_out = w_out;
   tp.d = d; tp.ld = ld;
+  // is there a kernel for the matrix part?  Asked before w is advanced, so that an error leaves
+  // the caller's push-sum state as it was
+  rc = run_tile(tt, round, G ? OP_ATC : OP_MIX, Y != nullptr, tp, dt, st, true);
+  if (rc != BF_OK) return rc;
+  // w first (one small workgroup, in-place safe); the tile kernel then reads w_out for the ratio.
+  hipLaunchKernelGGL(bf_pushsum_w_kernel, dim3(1), dim3(1024), wl, st,
+                     reinterpret_cast<const int32_t*>(dc->blob + dc->rowptr_off[k]),
+                     reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[k]), w_in, w_out, t->n);
+  BF_HIP_TRY(hipGetLastError());
   return run_tile(tt, round, G ? OP_ATC : OP_MIX, Y != nullptr, tp, dt, st);
 }
 
@@ -1402,21 +1608,49 @@ static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t itera
   if (round0 < 0) return BF_ERR_ROUND;
   bf_topology_t* t = const_cast<bf_topology_t*>(tc);
   const int32_t n = t->n;
-  if (iterations < 0 || m < 1 || m > 64 || d < 4 || (d % 4) != 0 || ld < d || (ld % 4) != 0) return BF_ERR_SIZE;
+  if (iterations < 0 || m < 1 || m > 8192 || d < 4 || (d % 4) != 0 || ld < d || (ld % 4) != 0) return BF_ERR_SIZE;
   if (static_cast<uint64_t>(n) * static_cast<uint64_t>(iterations) >= (uint64_t{1} << 32)) return BF_ERR_SIZE;
   if (misaligned16(A) || misaligned16(X) || misaligned16(work) || (reinterpret_cast<uintptr_t>(b) & 3u)) return BF_ERR_ALIGN;
   const size_t xb = (static_cast<size_t>(n - 1) * ld + d) * 4, wb = (static_cast<size_t>(2 * n - 1) * ld + d) * 4;
   const size_t ab = static_cast<size_t>(n) * m * d * 4, bb = static_cast<size_t>(n) * m * 4;
-  if (overlaps(X, xb, work, wb) || overlaps(X, xb, A, ab) || overlaps(X, xb, b, bb) || overlaps(work, wb, A, ab) ||
-      overlaps(work, wb, b, bb))
-    return BF_ERR_ALIAS;
+  if (overlaps(X, xb, A, ab) || overlaps(X, xb, b, bb)) return BF_ERR_ALIAS;
+  if (overlaps(X, xb, work, wb) || overlaps(work, wb, A, ab) || overlaps(work, wb, b, bb)) return BF_ERR_ALIAS;
   if (Psi && (misaligned16(Psi))) return BF_ERR_ALIGN;
   if (Psi && (overlaps(Psi, xb, X, xb) || overlaps(Psi, xb, work, wb) || overlaps(Psi, xb, A, ab) || overlaps(Psi, xb, b, bb)))
     return BF_ERR_ALIAS;
-  if (d > 4096) return BF_ERR_UNSUPPORTED;
   if (iterations == 0) return BF_OK;
   bf::DeviceCopy* dc = nullptr;
-  int rc = get_device_copy(t, false, &dc);
+  int rc = BF_OK;
+  // Does the problem fit the one-launch kernel?  One workgroup per agent, all resident at once, A_i
+  // and 20 KB of working storage in one CU's LDS, rows of at most 4096 columns.
+  bool fits = d <= 4096 && m <= 64;
+  if (fits) {
+    int dev = 0;
+    BF_HIP_TRY(hipGetDevice(&dev));
+    DeviceInfo di0;
+    rc = device_info(dev, &di0);
+    if (rc != BF_OK) return rc;
+    const size_t need = static_cast<size_t>(m) * d * 4 + static_cast<size_t>(d) * 4 * (Psi ? 2 : 1) + 1024 * 16 + 128 * 4 + 64;
+    const size_t have = std::min(di0.lds_per_cu ? di0.lds_per_cu : size_t{65536},
+                                 di0.lds_per_block_optin ? di0.lds_per_block_optin : size_t{65536});
+    fits = need <= have && n <= di0.cus;
+  }
+  if (!fits) {
+    // Too large for that: the same iterations as two launches each (gradient, then the fused
+    // adapt-then-combine or Exact-Diffusion step in place), the first half of `work` holding the
+    // gradients.
+    const int64_t period2 = 2 * static_cast<int64_t>(t->rounds.size());
+    for (int32_t k = 0; k < iterations; ++k) {
+      const int32_t r = static_cast<int32_t>((static_cast<int64_t>(round0) + k) % period2);
+      rc = bf_grad_least_squares(n, m, d, A, b, X, ld, work, ld, hip_stream);
+      if (rc != BF_OK) return rc;
+      rc = Psi ? bf_exact_diffusion_step(t, r, X, X, work, Psi, alpha, d, ld, BF_F32, hip_stream)
+               : bf_atc_step(t, r, X, X, work, nullptr, alpha, 0.0f, BF_ATC, d, ld, BF_F32, hip_stream);
+      if (rc != BF_OK) return rc;
+    }
+    return BF_OK;
+  }
+  rc = get_device_copy(t, false, &dc);
   if (rc != BF_OK) return rc;
   DeviceInfo di;
   rc = device_info(dc->device, &di);
@@ -1425,11 +1659,12 @@ static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t itera
   const size_t lds = static_cast<size_t>(m) * d * 4 + static_cast<size_t>(d) * 4 * (Psi ? 2 : 1) + 1024 * 16 + 128 * 4;
   const size_t lds_max = std::min(di.lds_per_cu ? di.lds_per_cu : size_t{65536},
                                   di.lds_per_block_optin ? di.lds_per_block_optin : size_t{65536});
-  if (lds + 64 > lds_max || n > di.cus) return BF_ERR_UNSUPPORTED;   // 64: the kernel's static LDS
+  if (lds + 64 > lds_max || n > di.cus) return BF_ERR_UNSUPPORTED;   // (checked above; 64: the kernel's static LDS)
   {
     std::lock_guard<std::mutex> lk(t->mu);
     if (!dc->sync) BF_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&dc->sync), 256));
   }
+  unsigned int* const sync = dc->sync;
   if (lds > 48 * 1024) {
     static thread_local size_t raised = 0;
     if (raised < lds) {
@@ -1441,7 +1676,7 @@ static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t itera
   DgdParams p{};
   p.A = A; p.b = b; p.X = X; p.H = work; p.Psi = Psi;
   p.blob = dc->blob;
-  p.sync = dc->sync;
+  p.sync = sync;
   p.d = d; p.ld = ld; p.n = n; p.m = m; p.iters = iterations;
   p.round_k0 = static_cast<int32_t>(static_cast<size_t>(round0) % t->rounds.size());
   p.nrounds = static_cast<int32_t>(t->rounds.size());
@@ -1449,7 +1684,7 @@ static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t itera
   p.extra_arrivals = g_tune_extra ? 1u : 0u;
   p.spin_limit = g_tune_spin > 0 ? static_cast<uint32_t>(g_tune_spin) : (1u << 20);   // of the order of a second of polling
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL(bf_sync_clear_kernel, dim3(1), dim3(64), 0, st, dc->sync);
+  hipLaunchKernelGGL(bf_sync_clear_kernel, dim3(1), dim3(64), 0, st, sync);
   BF_HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(bf_dgd_ls_kernel, dim3(n), dim3(1024), lds, st, p);
   BF_HIP_TRY(hipGetLastError());
@@ -1475,10 +1710,11 @@ int bf_dgd_status(const bf_topology_t* tc, int32_t* timed_out, void* hip_stream)
   int rc = get_device_copy(t, false, &dc);
   if (rc != BF_OK) return rc;
   *timed_out = 0;
-  if (!dc->sync) return BF_OK;                       // never run on this device
+  unsigned int* const sync = dc->sync;
+  if (!sync) return BF_OK;                           // never run on this device
   unsigned int host[2] = {0u, 0u};
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  BF_HIP_TRY(hipMemcpyAsync(host, dc->sync, sizeof(host), hipMemcpyDeviceToHost, st));
+  BF_HIP_TRY(hipMemcpyAsync(host, sync, sizeof(host), hipMemcpyDeviceToHost, st));
   BF_HIP_TRY(hipStreamSynchronize(st));
   *timed_out = host[1] != 0u ? 1 : 0;
   return BF_OK;
@@ -1512,14 +1748,14 @@ int bf_stream_probe(int32_t mode, const void* src, void* dst, int64_t bytes, int
 int bf_grad_least_squares(int32_t n, int32_t m, int64_t d, const float* A, const float* b,
                           const float* X, int64_t ldx, float* G, int64_t ldg, void* hip_stream) {
   if (!A || !b || !X || !G) return BF_ERR_NULL;
-  if (n < 1 || m < 1 || m > 64 || d < 0 || (d % 4) != 0 || ldx < d || ldg < d) return BF_ERR_SIZE;
+  if (n < 1 || m < 1 || m > 8192 || d < 0 || (d % 4) != 0 || ldx < d || ldg < d) return BF_ERR_SIZE;
   if ((ldx % 4) != 0 || (ldg % 4) != 0) return BF_ERR_ALIGN;
   if (misaligned16(A) || misaligned16(X) || misaligned16(G) || (reinterpret_cast<uintptr_t>(b) & 3u)) return BF_ERR_ALIGN;
   const size_t xb = (static_cast<size_t>(n - 1) * ldx + d) * 4, gb = (static_cast<size_t>(n - 1) * ldg + d) * 4;
   const size_t ab = static_cast<size_t>(n) * m * d * 4, bb = static_cast<size_t>(n) * m * 4;
   if (overlaps(G, gb, X, xb) || overlaps(G, gb, A, ab) || overlaps(G, gb, b, bb)) return BF_ERR_ALIAS;
   if (d == 0) return BF_OK;
-  hipLaunchKernelGGL(bf_ls_grad_kernel, dim3(n), dim3(1024), 0, static_cast<hipStream_t>(hip_stream),
+  hipLaunchKernelGGL(bf_ls_grad_kernel, dim3(n), dim3(1024), static_cast<size_t>(m) * 4, static_cast<hipStream_t>(hip_stream),
                      A, b, X, G, m, d, ldx, ldg);
   BF_HIP_TRY(hipGetLastError());
   return BF_OK;

@@ -1,0 +1,288 @@
+// The pipelined column-tile kernel and its launchers (template code; included by bf_tile_f32.hip
+// and bf_tile_bf16.hip, which instantiate it for one storage type each).
+#ifndef BF_PIPE_INC_H_
+#define BF_PIPE_INC_H_
+
+#include "bf_device.h"
+
+namespace bf {
+
+template <int NB> struct RawVec;
+template <> struct RawVec<16> { typedef u32x4 type; };
+template <> struct RawVec<8> { typedef u32x2 type; };
+
+// Widen one staging unit of UC columns of storage type DT to fp32.
+template <int DT, int UC, typename R>
+__device__ __forceinline__ void widen_unit(const R& raw, float* out) {
+  if constexpr (DT == DT_F32) {
+    out[0] = __uint_as_float(raw.x); out[1] = __uint_as_float(raw.y);
+    out[2] = __uint_as_float(raw.z); out[3] = __uint_as_float(raw.w);
+  } else if constexpr (UC == 8) {
+    out[0] = bf16_lo(raw.x); out[1] = bf16_hi(raw.x); out[2] = bf16_lo(raw.y); out[3] = bf16_hi(raw.y);
+    out[4] = bf16_lo(raw.z); out[5] = bf16_hi(raw.z); out[6] = bf16_lo(raw.w); out[7] = bf16_hi(raw.w);
+  } else {
+    out[0] = bf16_lo(raw.x); out[1] = bf16_hi(raw.x); out[2] = bf16_lo(raw.y); out[3] = bf16_hi(raw.y);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// One persistent workgroup per CU owns two n x C fp32 tiles in LDS and splits its waves into two
+// roles.  The NL loader waves stream the next column tile from HBM, U 16-byte vectors per lane in
+// flight at a time, apply the local update (x - alpha g; momentum; Exact-Diffusion; tracking) and
+// put the values to be mixed into one LDS tile.  The NR reducer waves meanwhile produce the output
+// rows of the previous tile from the other LDS tile -- one wave per (row, 64*LW-column span), the
+// row's in-neighbor list read through the scalar cache, fp32 accumulation in list order -- and
+// store them.  The two roles meet at one workgroup barrier per tile.  A CU thus issues loads and
+// stores all the time, a few KB of each in flight, instead of a tile-sized burst of one kind
+// followed by a burst of the other.
+//
+// DT: storage type of X/G/Y.  OP: what is staged and what is subtracted.  WITH_Y: also write the
+// push-sum ratio.  LW: columns per lane in the reduce phase.
+template <int DT, int OP, bool WITH_Y, int LW, int NL, int NR, int U, bool STREAM>
+__global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParams p) {
+  extern __shared__ f32x4 lds_raw[];
+  float* lds = reinterpret_cast<float*>(lds_raw);
+
+  constexpr int EB = Elem<DT>::bytes;
+  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED || OP == OP_TRACK);
+  constexpr bool STAGE_G2 = (OP == OP_TRACK);
+  constexpr bool STAGE_M = (OP == OP_MOM_ATC || OP == OP_ED);
+  // A staging unit is 16 bytes of X, except next to an fp32 state matrix with bf16 storage: there
+  // it is four columns (8 bytes of X and G, 16 bytes of M), so that every wave-wide access of M is
+  // one contiguous kilobyte.
+  constexpr int UC = (DT == DT_BF16 && !STAGE_M) ? 8 : 4;
+  constexpr int UC_LOG = UC == 8 ? 3 : 2;
+  typedef typename RawVec<UC * EB>::type raw_t;
+  constexpr int LT = NL * 64;                       // loader threads
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int log_c = p.log_c;
+  const int upr_log = log_c - UC_LOG;               // staging units per tile row (log2)
+  const int upr_mask = (1 << upr_log) - 1;
+  const int nunits = p.n << upr_log;
+  const int64_t d = p.d, ld = p.ld;
+  // A unit past the tile's end re-reads the last unit, a column at or past d re-reads the row's
+  // last in-range vector: loads are unconditional, only the LDS write and the M store are predicated.
+  const int64_t last_vec = d > 0 ? ((d - 1) >> UC_LOG) << UC_LOG : 0;
+
+  auto load_tile = [&](int64_t tile, float* buf) {
+    const int64_t c0 = tile << log_c;
+    for (int base = 0; base < nunits; base += LT * U) {
+      raw_t xr[U];
+      raw_t gr[STAGE_G ? U : 1];
+      raw_t g2r[STAGE_G2 ? U : 1];
+      f32x4 mr[STAGE_M ? U : 1];
+#pragma unroll
+      for (int k = 0; k < U; ++k) {
+        const int u = min(base + k * LT + tid, nunits - 1);
+        const int row = u >> upr_log;
+        const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
+        const int64_t off = static_cast<int64_t>(row) * ld + col;
+        xr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.x_in + off * EB));
+        if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g + off * EB));
+        if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g2 + off * EB));
+        if constexpr (STAGE_M) mr[k] = ld_stream<STREAM>(reinterpret_cast<const f32x4*>(p.m + off));
+      }
+#pragma unroll
+      for (int k = 0; k < U; ++k) {
+        const int u = base + k * LT + tid;
+        const int row = u >> upr_log;
+        const int cit = (u & upr_mask) << UC_LOG;     // column inside the tile
+        const int64_t col = c0 + cit;
+        const bool live = u < nunits && col < d;
+        float xv[UC];
+        widen_unit<DT, UC>(xr[k], xv);
+        if constexpr (STAGE_G) {
+          float gv[UC];
+          widen_unit<DT, UC>(gr[k], gv);
+          if constexpr (STAGE_M) {
+            float sv[4] = {mr[k].x, mr[k].y, mr[k].z, mr[k].w};
+            local_update4<OP>(xv, gv, sv, p.alpha, p.beta);
+            if (live) {
+              float* mp = p.m + static_cast<int64_t>(row) * ld + col;
+              const int64_t rem = d - col;
+              if (rem >= 4) { f32x4 t = {sv[0], sv[1], sv[2], sv[3]}; st_stream<STREAM>(reinterpret_cast<f32x4*>(mp), t); }
+              else for (int e = 0; e < 4; ++e) if (e < rem) mp[e] = sv[e];
+            }
+          } else if constexpr (STAGE_G2) {
+            // gradient tracking: the mixed value is y + g_new - g_old
+            float hv[UC];
+            widen_unit<DT, UC>(g2r[k], hv);
+#pragma unroll
+            for (int e = 0; e < UC; ++e) xv[e] = (xv[e] + gv[e]) - hv[e];
+          } else {
+#pragma unroll
+            for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
+          }
+        }
+        if (live) {
+          float* dst = buf + (row << log_c) + cit;
+#pragma unroll
+          for (int q = 0; q < UC / 4; ++q) {
+            f32x4 t = {xv[4 * q], xv[4 * q + 1], xv[4 * q + 2], xv[4 * q + 3]};
+            *reinterpret_cast<f32x4*>(dst + 4 * q) = t;
+          }
+        }
+      }
+    }
+  };
+
+  constexpr int SPAN_LOG = (LW == 4 ? 8 : (LW == 2 ? 7 : 6));      // log2(64*LW)
+  const int spans_log = log_c - SPAN_LOG;
+  const int nops = p.n << spans_log;
+  const int tile_floats = p.n << log_c;
+
+  const csr_i32_ptr rowptr = (csr_i32_ptr)(uintptr_t)p.rowptr;
+  const csr_ent_ptr ent = (csr_ent_ptr)(uintptr_t)p.ent;
+
+  // Output rows of one tile: reducer wave w takes the (row, 64*LW-column span) pairs w, w+NR, ...
+  // Each is the weighted sum over the row's in-neighbor list, read from the LDS tile in list order
+  // with fp32 accumulation; the list comes through the scalar cache, and entries go in batches of
+  // four (then two, then one) so that a wave waits once per batch of LDS reads.
+  auto reduce_tile = [&](int64_t tile, const float* buf) {
+    const int64_t c0 = tile << log_c;
+    const bool full = c0 + (int64_t{1} << log_c) <= d;      // no ragged tail in this tile
+    for (int op = wave - NL; op < nops; op += NR) {
+      const int i = op >> spans_log;
+      const int cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
+      const int64_t col = c0 + cit;
+      const int beg = rowptr[i], end = rowptr[i + 1];
+      float acc[LW];
+#pragma unroll
+      for (int e = 0; e < LW; ++e) acc[e] = 0.0f;
+      const float* src = buf + cit;
+      auto batch = [&](int q, auto kc) {
+        constexpr int K = decltype(kc)::value;
+        u32x2 en[K];
+#pragma unroll
+        for (int u = 0; u < K; ++u) en[u] = ent[q + u];
+        float v[K][LW];
+#pragma unroll
+        for (int u = 0; u < K; ++u) {
+          const float* sp = src + (static_cast<int>(en[u].x) << log_c);
+          if constexpr (LW == 4) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(sp);
+            v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
+          } else if constexpr (LW == 2) {
+            const f32x2 t = *reinterpret_cast<const f32x2*>(sp);
+            v[u][0] = t.x; v[u][1] = t.y;
+          } else {
+            v[u][0] = sp[0];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < K; ++u) {
+          const float w = __uint_as_float(en[u].y);
+#pragma unroll
+          for (int e = 0; e < LW; ++e) acc[e] = fmaf(w, v[u][e], acc[e]);
+        }
+      };
+      int q = beg;
+      for (; q + 4 <= end; q += 4) batch(q, std::integral_constant<int, 4>{});
+      if (q + 2 <= end) { batch(q, std::integral_constant<int, 2>{}); q += 2; }
+      if (q < end) batch(q, std::integral_constant<int, 1>{});
+      if (full || col < d) {
+        const int64_t rem = d - col;
+        const int valid = (full || rem >= LW) ? LW : static_cast<int>(rem);
+        const int64_t off = static_cast<int64_t>(i) * ld + col;
+        if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
+          // Adapt-while-communicate: the receiver's own gradient is subtracted after the mix.
+          float gv[LW];
+          load_in<DT, LW>(p.g, off, gv);
+          if constexpr (OP == OP_MOM_AWC) {
+            float mv[LW];
+            load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), off, mv);
+#pragma unroll
+            for (int e = 0; e < LW; ++e) gv[e] = fmaf(p.beta, mv[e], gv[e]);
+            store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), off, gv, valid);
+          }
+#pragma unroll
+          for (int e = 0; e < LW; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);
+        }
+        store_out<DT, LW, STREAM>(p.x_out, off, acc, valid);
+        if constexpr (WITH_Y) {
+          const float rcp = 1.0f / p.p_out[i];
+          float yv[LW];
+#pragma unroll
+          for (int e = 0; e < LW; ++e) yv[e] = acc[e] * rcp;
+          store_out<DT, LW, STREAM>(p.y, off, yv, valid);
+        }
+      }
+    }
+  };
+
+  // Odd rounds walk the tiles backwards: the columns a round wrote last are the first ones the
+  // next round reads, so whatever the memory-side cache still holds of them is reused.
+  auto phys = [&](int64_t seq) { return p.reverse ? p.ntiles - 1 - seq : seq; };
+  const bool loader = wave < NL;
+  int64_t seq = blockIdx.x;
+  if (seq >= p.ntiles) return;
+  if (loader) load_tile(phys(seq), lds);
+  __syncthreads();
+  int cur = 0;
+  while (seq < p.ntiles) {
+    const int64_t next = seq + gridDim.x;
+    if (loader) {
+      if (next < p.ntiles) load_tile(phys(next), lds + (cur ^ 1) * tile_floats);
+    } else {
+      reduce_tile(phys(seq), lds + cur * tile_floats);
+    }
+    __syncthreads();
+    seq = next;
+    cur ^= 1;
+  }
+}
+
+template <int DT, int OP, bool WITH_Y, int LW, int NL, int NR, int U, bool STREAM>
+int launch_pipe_shape(const TileParams& tp, int grid, size_t lds, hipStream_t st) {
+  auto kern = bf_pipe_kernel<DT, OP, WITH_Y, LW, NL, NR, U, STREAM>;
+  if (lds > 48 * 1024) {
+    static thread_local size_t raised = 0;
+    if (raised < lds) {
+      BF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     static_cast<int>(lds)));
+      raised = lds;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3((NL + NR) * 64), lds, st, tp);
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
+// Four loader waves with eight vectors per lane in flight and twelve reducer waves: measured best of
+// the splits tried (4+8 and 8+8 waves leave the reducers short: with so few waves per SIMD nothing
+// hides the latency of a row's scalar list loads and LDS reads; two or three loader waves cannot
+// keep enough loads in flight).
+template <int DT, int OP, bool WITH_Y, int LW>
+int launch_pipe_lw(const TileParams& tp, int grid, size_t lds, bool stream, hipStream_t st) {
+  return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, true>(tp, grid, lds, st)
+                : launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, false>(tp, grid, lds, st);
+}
+
+template <int DT, int OP, bool WITH_Y>
+int launch_pipe(const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
+  switch (s.lw) {
+    case 4: return launch_pipe_lw<DT, OP, WITH_Y, 4>(tp, grid, s.lds_bytes, s.stream, st);
+    case 2: return launch_pipe_lw<DT, OP, WITH_Y, 2>(tp, grid, s.lds_bytes, s.stream, st);
+    default: return launch_pipe_lw<DT, OP, WITH_Y, 1>(tp, grid, s.lds_bytes, s.stream, st);
+  }
+}
+
+template <int DT>
+int launch_pipe_op(int op, bool with_y, const TileParams& tp, const Shape& s, int grid, hipStream_t st) {
+  switch (op) {
+    case OP_MIX: return with_y ? launch_pipe<DT, OP_MIX, true>(tp, s, grid, st) : launch_pipe<DT, OP_MIX, false>(tp, s, grid, st);
+    case OP_ATC: return with_y ? launch_pipe<DT, OP_ATC, true>(tp, s, grid, st) : launch_pipe<DT, OP_ATC, false>(tp, s, grid, st);
+    case OP_TRACK: return launch_pipe<DT, OP_TRACK, false>(tp, s, grid, st);
+    case OP_AWC: return launch_pipe<DT, OP_AWC, false>(tp, s, grid, st);
+    case OP_MOM_ATC: return launch_pipe<DT, OP_MOM_ATC, false>(tp, s, grid, st);
+    case OP_ED: return launch_pipe<DT, OP_ED, false>(tp, s, grid, st);
+    default: return launch_pipe<DT, OP_MOM_AWC, false>(tp, s, grid, st);
+  }
+}
+
+}  // namespace bf
+
+#endif  // BF_PIPE_INC_H_

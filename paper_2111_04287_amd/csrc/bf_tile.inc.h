@@ -137,9 +137,6 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   const int lane = tid & 63;
   const int spans_log = log_c - SPAN_LOG;
   const int nops = p.n << spans_log;
-  #ifndef BF_GATHER_ILP
-#define BF_GATHER_ILP 4
-#endif
   // Weighted sum of one output row-span over the row's in-neighbor list, read from an LDS tile.
   auto gather = [&](const float* tile_base, csr_i32_ptr rp, csr_ent_ptr en_list, int i, int cit, float* acc) {
     const int beg = rp[i], end = rp[i + 1];
@@ -179,7 +176,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
     // workgroups per CU only while they stay within 64 registers, which the batch of four would
     // cost them (unless they prefetch only half the tile, MAXPF == 2, the form used for long rows);
     // every other kernel is either well below or already above that line.
-    constexpr bool BATCHED = BF_GATHER_ILP >= 4 &&
+    constexpr bool BATCHED =
         !(DT == DT_F32 && LW == 4 && (OP == OP_MIX || OP == OP_AWC || OP == OP_MOM_AWC) && !MULTI && MAXPF == 4);
     int q = beg;
     if constexpr (BATCHED) {
@@ -231,27 +228,14 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   // first row-spans so that reads and writes alternate on the memory pipe.
   auto reduce_and_store = [&](int64_t tile, int64_t next, bool has_next) {
     int op = wave;
-#if BF_INTERLEAVE
 #pragma unroll
     for (int k = 0; k < MAXPF; ++k) {
       if (has_next) issue_one(next, k);
       if (op < nops) { row_op(tile, op); op += NW; }
     }
-#else
-    if (has_next) issue_loads(next);
-#endif
     for (; op < nops; op += NW) row_op(tile, op);
   };
 
-#ifdef BF_PROFILE
-  // Development-only phase timing (100 MHz wall clock), wave 0 and the last wave of each workgroup.
-  unsigned long long* dbg = reinterpret_cast<unsigned long long*>(p.y);
-  const bool rec = dbg && !WITH_Y && (tid == 0 || tid == THREADS - 64);
-  int it = 0;
-#define BF_MARK(k) if (rec && it < 16) dbg[((static_cast<size_t>(blockIdx.x) * 2 + (tid != 0)) * 16 + it) * 8 + (k)] = wall_clock64()
-#else
-#define BF_MARK(k)
-#endif
   // Odd rounds walk the tiles backwards: the columns a round wrote last are the first ones the
   // next round reads, so whatever the memory-side cache still holds of them is reused.
   auto phys = [&](int64_t seq) { return p.reverse ? p.ntiles - 1 - seq : seq; };
@@ -259,11 +243,8 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   if (seq < p.ntiles) issue_loads(phys(seq));
   while (seq < p.ntiles) {
     const int64_t tile = phys(seq);
-    BF_MARK(0);
     stage(tile);
-    BF_MARK(1);
     __syncthreads();
-    BF_MARK(2);
     if constexpr (MULTI) {
       // Only one such workgroup fits a CU (two tiles), so nothing else keeps the memory pipe busy
       // during the LDS rounds: the next tile's loads go out now, not during the last round.
@@ -388,15 +369,9 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       final_src = ((p.fuse - 1) & 1) ? tile_b : tile_a;
     }
     const int64_t next = seq + gridDim.x;
-    BF_MARK(3);
     reduce_and_store(tile, phys(next), !MULTI && next < p.ntiles);
-    BF_MARK(4);
     __syncthreads();
-    BF_MARK(5);
     seq = next;
-#ifdef BF_PROFILE
-    ++it;
-#endif
   }
 }
 

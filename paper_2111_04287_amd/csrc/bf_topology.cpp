@@ -199,6 +199,26 @@ int finalize_round(Round& r, int32_t n) {
   r.max_degree = maxdeg;
   r.wclass = (pull ? BF_W_PULL : 0) | (push ? BF_W_PUSH : 0);
   if (maxdeg <= 3) build_chain_plan(r, n);
+  // uniform shift round?  Two entries per row, the diagonal and (i + s) mod n, same s and the same
+  // two weights (bit for bit) in every row.
+  r.shift = 0;
+  if (n >= 2 && nnz == 2 * static_cast<int64_t>(n)) {
+    int32_t s = -1;
+    float ws = 0.0f, wp = 0.0f;
+    bool ok = true;
+    for (int32_t i = 0; i < n && ok; ++i) {
+      const int64_t b = r.rowptr[i];
+      if (r.rowptr[i + 1] - b != 2) { ok = false; break; }
+      const int q_self = r.col[b] == i ? 0 : (r.col[b + 1] == i ? 1 : -1);
+      if (q_self < 0) { ok = false; break; }
+      const int32_t j = r.col[b + 1 - q_self];
+      const int32_t si = ((j - i) % n + n) % n;
+      const float wsi = r.wgt[b + q_self], wpi = r.wgt[b + 1 - q_self];
+      if (i == 0) { s = si; ws = wsi; wp = wpi; }
+      else if (si != s || std::memcmp(&wsi, &ws, 4) != 0 || std::memcmp(&wpi, &wp, 4) != 0) ok = false;
+    }
+    if (ok && s > 0) { r.shift = s; r.shift_w_self = ws; r.shift_w_peer = wp; }
+  }
   return BF_OK;
 }
 

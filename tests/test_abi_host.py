@@ -246,10 +246,14 @@ def test_compute_calls_validate_before_touching_the_device():
     assert na(h, 0, A, A + 256, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS    # partial overlap
     assert na(h, 0, A, B, 0, 64, bf.BF_F32, None) == bf.BF_OK                  # empty: nothing to launch
     assert na(h, 0, A, A, 0, 64, bf.BF_F32, None) == bf.BF_OK
-    assert L.bf_dense_mix(h, 0, A, B, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_UNSUPPORTED
+    assert L.bf_dense_mix(h, 0, A, A + 256, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_ALIAS
     W1b, W2b = 0x60000000, 0x60001000
     wa = L.bf_win_accumulate
-    assert wa(h, 0, None, A, None, B, None, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_UNSUPPORTED
+    ww = L.bf_win_accumulate_weighted
+    assert ww(h, 0, None, A, None, B, None, W1b + 2, None, None, 64, 64, bf.BF_BF16, None) == bf.BF_ERR_ALIGN   # self_weight
+    assert ww(h, 0, None, A, None, B, None, None, None, W1b + 1, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIGN    # dst_on
+    assert ww(h, 0, None, None, None, B, None, None, None, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert L.bf_win_update_weighted(h, 0, None, A, A + 512, None, None, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     assert wa(h, 0, None, A, W1b, B, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_NULL        # p without win_p
     assert wa(h, 0, None, A, None, A + 512, None, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS  # Win inside X
     assert wa(h, 0, None, A, W1b, B, W1b + 8, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
@@ -265,12 +269,11 @@ def test_compute_calls_validate_before_touching_the_device():
     assert dg(h, -1, 5, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_ROUND
     assert dg(h, 0, -1, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_SIZE
     assert dg(h, 0, 5, 0, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_SIZE
-    assert dg(h, 0, 5, 65, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_SIZE
+    assert dg(h, 0, 5, 8193, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_SIZE
     assert dg(h, 0, 5, 32, A, B, G, WK, 1e-3, 1022, 1024, None) == bf.BF_ERR_SIZE      # d not a multiple of 4
     assert dg(h, 0, 5, 32, A, B, G, WK, 1e-3, 1024, 1000, None) == bf.BF_ERR_SIZE      # ld < d
     assert dg(h, 0, 5, 32, A, B, G + 4, WK, 1e-3, 1024, 1024, None) == bf.BF_ERR_ALIGN
     assert dg(h, 0, 5, 32, A, B, G, G + 4096, 1e-3, 1024, 1024, None) == bf.BF_ERR_ALIAS  # work inside X
-    assert dg(h, 0, 5, 32, A, B, G, WK, 1e-3, 8192, 8192, None) == bf.BF_ERR_UNSUPPORTED
     assert dg(h, 0, 0, 32, A, B, G, WK, 1e-3, 1024, 1024, None) == bf.BF_OK              # nothing to do
     assert L.bf_dgd_status(None, None, None) == bf.BF_ERR_NULL
     ed = L.bf_exact_diffusion_least_squares_run
@@ -315,7 +318,7 @@ def test_compute_calls_validate_before_touching_the_device():
     assert at(h, 0, A, B, G, M + 8, 0.1, 0.9, bf.BF_ATC, 64, 64, bf.BF_F32, None) == bf.BF_ERR_ALIGN
     ls = L.bf_grad_least_squares
     assert ls(4, 0, 64, A, B, G, 64, M, 64, None) == bf.BF_ERR_SIZE
-    assert ls(4, 65, 64, A, B, G, 64, M, 64, None) == bf.BF_ERR_SIZE
+    assert ls(4, 8193, 64, A, B, G, 64, M, 64, None) == bf.BF_ERR_SIZE
     assert ls(4, 8, 62, A, B, G, 64, M, 64, None) == bf.BF_ERR_SIZE
     assert ls(4, 8, 64, A, B, G, 64, G, 64, None) == bf.BF_ERR_ALIAS
     assert ls(4, 8, 64, A, None, G, 64, M, 64, None) == bf.BF_ERR_NULL
