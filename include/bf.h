@@ -332,6 +332,27 @@ int bf_dgd_least_squares_run(const bf_topology_t* t, int32_t round0, int32_t ite
                              int64_t d, int64_t ld, void* hip_stream);
 int bf_dgd_status(const bf_topology_t* t, int32_t* timed_out, void* hip_stream);
 
+/* bf_dgd_least_squares_run for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernel and
+ * bit-identical results; the only difference is where the scratch lives.  The half steps
+ * (2 * n * ld floats) and the two barrier words sit in a static device array of the library
+ * (2 MiB + 256 bytes per GPU, held until the process ends) instead of a caller workspace and a
+ * lazily allocated pair of words, and the call performs no hipMalloc / hipFree of any kind.
+ *   - 2 * n * ld * 4 bytes must not exceed 2 MiB (2,097,152), else BF_ERR_SIZE.
+ *   - Only the one-launch form exists here (m <= 64, d <= 4096, A_i in one CU's LDS, n <= CUs); a
+ *     larger problem is BF_ERR_UNSUPPORTED.
+ *   - The topology's device copy is never created here: if `t` has not been used by any compute call
+ *     on the current device yet (which is what uploads it), the call returns BF_ERR_UNSUPPORTED.
+ *   - Every call on a GPU shares that GPU's one array, whatever the topology: calls that overlap in
+ *     time on one GPU (different streams) race; calls on one stream are ordered and safe.  The
+ *     barrier words are cleared by a small kernel at the start of each call; the half steps need no
+ *     clearing (each is written before it is read).
+ * All other arguments, limits and error codes as for bf_dgd_least_squares_run; bf_dgd_status
+ * reports on whichever of the two variants ran last on the topology. */
+int bf_dgd_least_squares_run_static(const bf_topology_t* t, int32_t round0, int32_t iterations, int32_t m,
+                                    const float* A, const float* b, float* X, float alpha, int64_t d, int64_t ld,
+                                    void* hip_stream);
+
 /* Exact-Diffusion on the same problem in the same way (appendix "Application example:
  * Exact-Diffusion algorithm", eqs. ed-1, ed-2, ed-3 with the least-squares gradient):
  *   psi_i = x_i - alpha A_i^T (A_i x_i - b_i);  phi_i = psi_i + x_i - psi_prev_i;  x_i <- sum_j w_ij phi_j.

@@ -29,7 +29,7 @@ EXPORTS = [
     "bf_topology_create", "bf_topology_create_push_pull", "bf_topology_destroy", "bf_topology_n",
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_topology_chain_plan", "bf_topology_window_slots", "bf_topology_export_window",
-    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_win_put_weighted", "bf_win_get_weighted", "bf_win_accumulate_weighted", "bf_win_update_weighted", "bf_dgd_least_squares_run", "bf_exact_diffusion_least_squares_run", "bf_dgd_status", "bf_stream_probe", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
+    "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_win_put_weighted", "bf_win_get_weighted", "bf_win_accumulate_weighted", "bf_win_update_weighted", "bf_dgd_least_squares_run", "bf_dgd_least_squares_run_static", "bf_exact_diffusion_least_squares_run", "bf_dgd_status", "bf_stream_probe", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
 ]
@@ -91,6 +91,7 @@ def _load():
     L.bf_win_put.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_dgd_least_squares_run.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, C.c_float, i64, i64, vp]
     L.bf_dgd_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
+    L.bf_dgd_least_squares_run_static.argtypes = [vp, i32, i32, i32, vp, vp, vp, C.c_float, i64, i64, vp]
     L.bf_exact_diffusion_least_squares_run.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, C.c_float, i64, i64, vp]
     L.bf_stream_probe.argtypes = [i32, vp, vp, i64, i32, vp]
     L.bf_win_get.argtypes = [vp, i32, vp, vp, vp, i64, i64, C.c_int, vp]
@@ -531,6 +532,19 @@ def bf_dgd_least_squares_run(t, rnd0, iterations, A, b, X, work, alpha, stream=N
         raise ValueError("work must be a contiguous float32 tensor of at least 2 * n * ld elements")
     _check(lib.bf_dgd_least_squares_run(t.handle, rnd0, iterations, m, A.data_ptr(), b.data_ptr(), xp, work.data_ptr(),
                                         alpha, d, ldx, _stream(stream)), "bf_dgd_least_squares_run")
+    return X
+
+
+def bf_dgd_least_squares_run_static(t, rnd0, iterations, A, b, X, alpha, stream=None):
+    import torch
+    n, m, d = A.shape
+    xp, xn, xd, ldx = _mat(X, "X")
+    _rows(t, xn)
+    if not A.is_contiguous() or not b.is_contiguous() or (xn, xd) != (n, d) or tuple(b.shape) != (n, m) or \
+            A.dtype != torch.float32 or b.dtype != torch.float32 or X.dtype != torch.float32:
+        raise ValueError("shapes: A (n,m,d) contiguous, b (n,m) contiguous, X (n,d), all float32")
+    _check(lib.bf_dgd_least_squares_run_static(t.handle, rnd0, iterations, m, A.data_ptr(), b.data_ptr(), xp,
+                                               alpha, d, ldx, _stream(stream)), "bf_dgd_least_squares_run_static")
     return X
 
 

@@ -69,6 +69,8 @@ struct DeviceCopy {
   std::vector<size_t> win_off;           // 6 byte offsets per round
   std::vector<int32_t> win_slots;        // E per round
   unsigned int* sync = nullptr;          // arrival counter and error word of the grid-barrier kernel
+  unsigned int* last_sync = nullptr;     // the words the last grid-barrier run on this device used (sync, or the
+                                         // library's static scratch); not owned
 };
 
 }  // namespace bf

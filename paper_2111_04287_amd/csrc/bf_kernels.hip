@@ -581,6 +581,27 @@ __global__ void bf_sync_clear_kernel(unsigned int* sync) {
   if (threadIdx.x < 2) sync[threadIdx.x] = 0u;
 }
 
+// Scratch of the entry point that may not allocate (bf_dgd_least_squares_run_static): the double
+// buffered half steps, then the two barrier words.  One copy per device, held until the process
+// ends.  In host code the array's name is only a handle; the device address comes from
+// hipGetSymbolAddress, once per device, and is what kernels and copies are given.
+constexpr size_t kStaticHalfStepBytes = size_t{2} << 20;          // 2 * n * ld * 4 must fit
+constexpr size_t kStaticScratchBytes = kStaticHalfStepBytes + 256;
+static __device__ __align__(256) unsigned char bf_static_scratch[kStaticScratchBytes];
+
+int static_scratch_address(int dev, unsigned char** out) {
+  static std::mutex mu;
+  static std::vector<std::pair<int, unsigned char*>> known;       // device -> address of its copy
+  std::lock_guard<std::mutex> lk(mu);
+  for (auto& k : known)
+    if (k.first == dev) { *out = k.second; return BF_OK; }
+  void* ptr = nullptr;
+  BF_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(bf_static_scratch)));   // of the current device, which is dev
+  known.emplace_back(dev, static_cast<unsigned char*>(ptr));
+  *out = static_cast<unsigned char*>(ptr);
+  return BF_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Plain streaming kernels with 128-bit accesses: the practical ceilings (copy, read only, write
 // only) that the mixing kernels' bandwidth is compared with.  Persistent grid-stride loops, four
@@ -1601,26 +1622,30 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_ED, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
+// static_scratch: the half steps and barrier words live in the library's static device array and
+// nothing is allocated (the topology must already be resident on the device).
 static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t iterations, int32_t m,
                           const float* A, const float* b, float* X, float* Psi, bool want_psi, float* work,
-                          float alpha, int64_t d, int64_t ld, void* hip_stream) {
-  if (!tc || !A || !b || !X || !work || (want_psi && !Psi)) return BF_ERR_NULL;
+                          float alpha, int64_t d, int64_t ld, void* hip_stream, bool static_scratch = false) {
+  if (!tc || !A || !b || !X || (!work && !static_scratch) || (want_psi && !Psi)) return BF_ERR_NULL;
   if (round0 < 0) return BF_ERR_ROUND;
   bf_topology_t* t = const_cast<bf_topology_t*>(tc);
   const int32_t n = t->n;
   if (iterations < 0 || m < 1 || m > 8192 || d < 4 || (d % 4) != 0 || ld < d || (ld % 4) != 0) return BF_ERR_SIZE;
   if (static_cast<uint64_t>(n) * static_cast<uint64_t>(iterations) >= (uint64_t{1} << 32)) return BF_ERR_SIZE;
-  if (misaligned16(A) || misaligned16(X) || misaligned16(work) || (reinterpret_cast<uintptr_t>(b) & 3u)) return BF_ERR_ALIGN;
+  if (misaligned16(A) || misaligned16(X) || (work && misaligned16(work)) || (reinterpret_cast<uintptr_t>(b) & 3u)) return BF_ERR_ALIGN;
   const size_t xb = (static_cast<size_t>(n - 1) * ld + d) * 4, wb = (static_cast<size_t>(2 * n - 1) * ld + d) * 4;
   const size_t ab = static_cast<size_t>(n) * m * d * 4, bb = static_cast<size_t>(n) * m * 4;
+  if (static_scratch && static_cast<size_t>(2) * n * ld * 4 > kStaticHalfStepBytes) return BF_ERR_SIZE;
   if (overlaps(X, xb, A, ab) || overlaps(X, xb, b, bb)) return BF_ERR_ALIAS;
-  if (overlaps(X, xb, work, wb) || overlaps(work, wb, A, ab) || overlaps(work, wb, b, bb)) return BF_ERR_ALIAS;
+  if (work && (overlaps(X, xb, work, wb) || overlaps(work, wb, A, ab) || overlaps(work, wb, b, bb))) return BF_ERR_ALIAS;
   if (Psi && (misaligned16(Psi))) return BF_ERR_ALIGN;
-  if (Psi && (overlaps(Psi, xb, X, xb) || overlaps(Psi, xb, work, wb) || overlaps(Psi, xb, A, ab) || overlaps(Psi, xb, b, bb)))
+  if (Psi && (overlaps(Psi, xb, X, xb) || (work && overlaps(Psi, xb, work, wb)) || overlaps(Psi, xb, A, ab) || overlaps(Psi, xb, b, bb)))
     return BF_ERR_ALIAS;
   if (iterations == 0) return BF_OK;
   bf::DeviceCopy* dc = nullptr;
   int rc = BF_OK;
+  unsigned char* scratch = nullptr;
   // Does the problem fit the one-launch kernel?  One workgroup per agent, all resident at once, A_i
   // and 20 KB of working storage in one CU's LDS, rows of at most 4096 columns.
   bool fits = d <= 4096 && m <= 64;
@@ -1638,7 +1663,8 @@ static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t itera
   if (!fits) {
     // Too large for that: the same iterations as two launches each (gradient, then the fused
     // adapt-then-combine or Exact-Diffusion step in place), the first half of `work` holding the
-    // gradients.
+    // gradients.  The static-scratch variant has no room for this and refuses.
+    if (static_scratch) return BF_ERR_UNSUPPORTED;
     const int64_t period2 = 2 * static_cast<int64_t>(t->rounds.size());
     for (int32_t k = 0; k < iterations; ++k) {
       const int32_t r = static_cast<int32_t>((static_cast<int64_t>(round0) + k) % period2);
@@ -1650,7 +1676,22 @@ static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t itera
     }
     return BF_OK;
   }
-  rc = get_device_copy(t, false, &dc);
+  if (static_scratch) {
+    // never allocates: the topology's device copy must be there already
+    int dev = 0;
+    BF_HIP_TRY(hipGetDevice(&dev));
+    {
+      std::lock_guard<std::mutex> lk(t->mu);
+      for (auto& c : t->dev)
+        if (c.device == dev) dc = &c;
+    }
+    if (!dc) return BF_ERR_UNSUPPORTED;
+    rc = static_scratch_address(dev, &scratch);
+    if (rc != BF_OK) return rc;
+    work = reinterpret_cast<float*>(scratch);
+  } else {
+    rc = get_device_copy(t, false, &dc);
+  }
   if (rc != BF_OK) return rc;
   DeviceInfo di;
   rc = device_info(dc->device, &di);
@@ -1660,11 +1701,17 @@ static int dgd_run_common(const bf_topology_t* tc, int32_t round0, int32_t itera
   const size_t lds_max = std::min(di.lds_per_cu ? di.lds_per_cu : size_t{65536},
                                   di.lds_per_block_optin ? di.lds_per_block_optin : size_t{65536});
   if (lds + 64 > lds_max || n > di.cus) return BF_ERR_UNSUPPORTED;   // (checked above; 64: the kernel's static LDS)
+  unsigned int* sync = nullptr;
   {
     std::lock_guard<std::mutex> lk(t->mu);
-    if (!dc->sync) BF_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&dc->sync), 256));
+    if (static_scratch) {
+      sync = reinterpret_cast<unsigned int*>(scratch + kStaticHalfStepBytes);
+    } else {
+      if (!dc->sync) BF_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&dc->sync), 256));
+      sync = dc->sync;
+    }
+    dc->last_sync = sync;
   }
-  unsigned int* const sync = dc->sync;
   if (lds > 48 * 1024) {
     static thread_local size_t raised = 0;
     if (raised < lds) {
@@ -1703,6 +1750,12 @@ int bf_exact_diffusion_least_squares_run(const bf_topology_t* t, int32_t round0,
   return dgd_run_common(t, round0, iterations, m, A, b, X, Psi_prev, true, work, alpha, d, ld, hip_stream);
 }
 
+int bf_dgd_least_squares_run_static(const bf_topology_t* t, int32_t round0, int32_t iterations, int32_t m,
+                                    const float* A, const float* b, float* X, float alpha, int64_t d, int64_t ld,
+                                    void* hip_stream) {
+  return dgd_run_common(t, round0, iterations, m, A, b, X, nullptr, false, nullptr, alpha, d, ld, hip_stream, true);
+}
+
 int bf_dgd_status(const bf_topology_t* tc, int32_t* timed_out, void* hip_stream) {
   if (!tc || !timed_out) return BF_ERR_NULL;
   bf_topology_t* t = const_cast<bf_topology_t*>(tc);
@@ -1710,7 +1763,11 @@ int bf_dgd_status(const bf_topology_t* tc, int32_t* timed_out, void* hip_stream)
   int rc = get_device_copy(t, false, &dc);
   if (rc != BF_OK) return rc;
   *timed_out = 0;
-  unsigned int* const sync = dc->sync;
+  unsigned int* sync = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(t->mu);
+    sync = dc->last_sync;
+  }
   if (!sync) return BF_OK;                           // never run on this device
   unsigned int host[2] = {0u, 0u};
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
