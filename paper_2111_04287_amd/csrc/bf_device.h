@@ -61,6 +61,16 @@ template <bool NT, typename T> __device__ __forceinline__ void st_stream(T* ptr,
   else *ptr = v;
 }
 
+// Workgroup barrier for kernels whose waves hand data to each other through LDS only.
+// __syncthreads() also waits for every outstanding GLOBAL access of the wave (vmcnt(0)), which
+// drains a streaming kernel's store queue - and the loads it has prefetched - once per tile.  Here
+// only the LDS accesses are waited for; global loads and stores stay in flight across the barrier.
+// Safe where no wave reads global memory that another wave of the workgroup writes in the same
+// launch (every kernel here: a workgroup's tiles are disjoint column ranges).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Scalar-cache view of the topology: uniform addresses into these become s_load instructions.
 typedef const int32_t __attribute__((address_space(4)))* csr_i32_ptr;
 typedef const u32x2 __attribute__((address_space(4)))* csr_ent_ptr;

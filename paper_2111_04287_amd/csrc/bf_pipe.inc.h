@@ -220,7 +220,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   int64_t seq = blockIdx.x;
   if (seq >= p.ntiles) return;
   if (loader) load_tile(phys(seq), lds);
-  __syncthreads();
+  lds_barrier();
   int cur = 0;
   while (seq < p.ntiles) {
     const int64_t next = seq + gridDim.x;
@@ -229,7 +229,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
     } else {
       reduce_tile(phys(seq), lds + cur * tile_floats);
     }
-    __syncthreads();
+    lds_barrier();
     seq = next;
     cur ^= 1;
   }

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         *reinterpret_cast<f32x4*>(dst + 4 * q) = t;
       }
     }
-    __syncthreads();
+    lds_barrier();
     const int64_t next = seq + gridDim.x;
     if (next < p.ntiles) issue_loads(phys(next));     // in flight during the rounds
 
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         *reinterpret_cast<f32x4*>(lds + (64 * q + lane) * pitch + 4 * cg) = t;
       }
     }
-    __syncthreads();
+    lds_barrier();
     // store the tile, row-major and coalesced
     {
       const int64_t col = c0 + cit0;
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
           }
       }
     }
-    __syncthreads();
+    lds_barrier();
     seq = next;
   }
 }

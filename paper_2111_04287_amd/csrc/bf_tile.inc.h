@@ -244,7 +244,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
   while (seq < p.ntiles) {
     const int64_t tile = phys(seq);
     stage(tile);
-    __syncthreads();
+    lds_barrier();
     if constexpr (MULTI) {
       // Only one such workgroup fits a CU (two tiles), so nothing else keeps the memory pipe busy
       // during the LDS rounds: the next tile's loads go out now, not during the last round.
@@ -364,13 +364,13 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
             }
           }
         }
-        __syncthreads();
+        lds_barrier();
       }
       final_src = ((p.fuse - 1) & 1) ? tile_b : tile_a;
     }
     const int64_t next = seq + gridDim.x;
     reduce_and_store(tile, phys(next), !MULTI && next < p.ntiles);
-    __syncthreads();
+    lds_barrier();
     seq = next;
   }
 }
