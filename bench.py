@@ -8,6 +8,9 @@ momentum SGD in adapt-then-combine form on the static exponential graph, n = 32 
 d = 25,557,032 (a ResNet-50's parameter count), X and G stored as bf16, momentum fp32, all resident
 in HBM (11.4 GB moved per step, far beyond the 256 MB memory-side cache).  One step = one fused
 bf_atc_step: m <- beta m + g, x_i <- sum_j w_ij (x_j - alpha m_j), updating X and M in place.  The
+matrices live in the library's column-block layout (include/bf.h, BF_LD_BLOCKED; blocks of
+bf_recommended_block columns); the same step on agent-major rows is timed too and reported under
+per_config.config5_agent_major_rows.  The
 metric is the effective HBM bandwidth: compulsory bytes (every operand element read once, every
 result element written once: 2 + 2 + 4 read and 2 + 4 written = 14 bytes per element) divided by
 time.  The other four configurations are timed in the same run and reported under "per_config",
@@ -109,10 +112,22 @@ def main():
         return r
 
     # ------------------------------------------------------------------ headline: configuration 5
+    # in the library's column-block layout (blocks of bf_recommended_block columns); the same step on
+    # agent-major rows is timed right after it and reported under per_config
     n5, d5 = 32, workloads.RESNET50_PARAMS
     c5 = workloads.CONFIG5
     t5 = bf.bf_topology_create(bf.BF_EXP_STATIC, n5)
     ld5 = bf.bf_recommended_ld(d5, bf.BF_BF16)
+    B5 = bf.bf_recommended_block(n5, d5, bf.BF_BF16)
+    bytes5 = n5 * d5 * 14
+
+    def blocked(n, d, B, dtype, src=None):
+        data = torch.zeros(((d + B - 1) // B, n, B), dtype=dtype, device=dev)
+        m = bf.Blocked(data, d)
+        if src is not None:
+            bf.bf_blocked_pack(src, m)
+        return m
+
     X5 = workloads.alloc_rows(n5, d5, torch.bfloat16, dev, ld=ld5, fill=0)
     C5 = workloads.config5_centres(dev, n=n5, d=d5, ld=ld5)
     E5 = workloads.config5_noise(dev, 0, n=n5, d=d5, ld=ld5)
@@ -120,10 +135,12 @@ def main():
     M5 = workloads.alloc_rows(n5, d5, torch.float32, dev, ld=ld5, fill=0)
     bf.bf_grad_quadratic(X5, C5, E5, c5["lam"], c5["sigma"], G5)         # gradient generator: outside the timed region
     del C5, E5
-    bytes5 = n5 * d5 * 14
+    X5b = blocked(n5, d5, B5, torch.bfloat16, X5)                        # same state, converted once
+    G5b = blocked(n5, d5, B5, torch.bfloat16, G5)
+    M5b = blocked(n5, d5, B5, torch.float32, M5)
 
     def step5(k):
-        bf.bf_atc_step(t5, k, X5, X5, G5, M5, c5["alpha"], c5["beta"], bf.BF_ATC)
+        bf.bf_atc_step(t5, k, X5b, X5b, G5b, M5b, c5["alpha"], c5["beta"], bf.BF_ATC)
 
     wall, ev_ms = timed(step5, args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
@@ -143,16 +160,34 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[4] (the largest single-GPU configuration): momentum SGD, adapt-then-combine, static "
                                "exponential graph n=32 (10 nonzeros per row, weights 1/10), d=25,557,032, X and G bf16, "
-                               "M fp32, one fused in-place bf_atc_step per step, 14 bytes per element",
-                   "n": n5, "d": d5, "ld": ld5, "topology": "static_exp", "step": "bf_atc_step(momentum, ATC)"},
+                               "M fp32, one fused in-place bf_atc_step per step, 14 bytes per element; matrices resident "
+                               "in HBM in the library's column-block layout (blocks of %d columns); the same step on "
+                               "agent-major rows: per_config.config5_agent_major_rows" % B5,
+                   "n": n5, "d": d5, "layout": "column blocks", "block": B5, "topology": "static_exp",
+                   "step": "bf_atc_step(momentum, ATC)"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "agent_row_updates_per_s": round(n5 * args.steps / wall, 1),
-        "roofline": roofline("bf_pipe_kernel<bf16, momentum ATC>", bytes5, ev_ms, "config5_momentum_atc"),
+        "roofline": roofline("bf_pipe_kernel<bf16, momentum ATC>", bytes5, ev_ms, "config5_momentum_atc_column_blocks"),
     }
-    del X5, G5, M5
+    rows5 = None
+    if not args.no_extra:
+        # the agent-major leg goes on from the state the column-block leg reached
+        bf.bf_blocked_unpack(X5b, X5)
+        bf.bf_blocked_unpack(M5b, M5)
+        def step5_rows(k):
+            bf.bf_atc_step(t5, k, X5, X5, G5, M5, c5["alpha"], c5["beta"], bf.BF_ATC)
+
+        wall5r, ev5r = timed(step5_rows, min(args.steps, 100), args.warmup)
+        rows5 = {"ms_per_step": round(wall5r * 1e3 / min(args.steps, 100), 5), "steps": min(args.steps, 100), "ld": ld5,
+                 "effective_GBps": round(bytes5 * min(args.steps, 100) / wall5r / 1e9, 1),
+                 "pct_of_hbm_peak": round(100 * bytes5 * min(args.steps, 100) / wall5r / 1e9 / HBM_PEAK_GBPS, 2),
+                 "roofline": roofline("bf_pipe_kernel<bf16, momentum ATC>", bytes5, ev5r, "config5_momentum_atc",
+                                      note="agent-major rows (row i at i * ld): a column tile is 32 row segments in 32 distant "
+                                           "places of each of X, G and M")}
+    del X5, G5, M5, X5b, G5b, M5b
 
     if not args.no_extra:
-        per = {}
+        per = {"config5_agent_major_rows": rows5}
 
         def entry(name, kernel, bytes_per_step, n_agents, steps, wall, ev_ms, key, extra=None, note=None):
             e = {"ms_per_step": round(wall * 1e3 / steps, 5), "steps": steps,
@@ -179,7 +214,14 @@ def main():
         w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(topo, k, X2[k & 1], X2[1 - (k & 1)]), args.steps, args.warmup)
         entry("config2_static_exp_n64_d1048576_f32_out_of_place", "bf_pipe_kernel<f32, mix>", bytes2, n, args.steps, w_, e_,
               "config2_out_of_place", note="separate input and output buffers (512 MiB working set), streaming loads and stores")
-        del X2, X
+        del X2
+        B2 = bf.bf_recommended_block(n, d, bf.BF_F32)
+        X2b = [blocked(n, d, B2, torch.float32, X), blocked(n, d, B2, torch.float32)]
+        w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(topo, k, X2b[k & 1], X2b[1 - (k & 1)]), args.steps, args.warmup)
+        entry("config2_static_exp_n64_d1048576_f32_out_of_place_column_blocks", "bf_pipe_kernel<f32, mix>", bytes2, n, args.steps,
+              w_, e_, "config2_out_of_place_column_blocks", extra={"block": B2},
+              note="as above with the matrices in column blocks of %d" % B2)
+        del X2b, X
 
         # practical ceilings: a plain device-to-device copy of 1 GiB, and the library's own 128-bit
         # streaming kernels (best persistent-grid size of a small sweep)
@@ -228,7 +270,14 @@ def main():
         w_, e_ = timed(lambda k: bf.bf_pushsum_step(t4, k, X4, X4, w4, w4, None), 50, 5)
         entry("config4_pushsum_random_directed_n128_d2097152_f32", "bf_pushsum_w_kernel + bf_pipe_kernel<f32, mix>",
               2 * n4 * d4 * 4, n4, 50, w_, e_, "config4", note="launch_ms covers both kernels of a step (the n-scalar update and the mix)")
-        del X4
+        B4 = bf.bf_recommended_block(n4, d4, bf.BF_F32)
+        X4b = blocked(n4, d4, B4, torch.float32, X4)
+        w4.fill_(1.0)
+        w_, e_ = timed(lambda k: bf.bf_pushsum_step(t4, k, X4b, X4b, w4, w4, None), 50, 5)
+        entry("config4_pushsum_random_directed_n128_d2097152_f32_column_blocks", "bf_pushsum_w_kernel + bf_pipe_kernel<f32, mix>",
+              2 * n4 * d4 * 4, n4, 50, w_, e_, "config4_column_blocks", extra={"block": B4},
+              note="as above with X in column blocks of %d" % B4)
+        del X4, X4b
 
         # configuration 1: decentralized gradient descent on least squares (latency bound)
         d1 = workloads.config1_least_squares(dev)

@@ -32,6 +32,7 @@ EXPORTS = [
     "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_win_put_weighted", "bf_win_get_weighted", "bf_win_accumulate_weighted", "bf_win_update_weighted", "bf_dgd_least_squares_run", "bf_dgd_least_squares_run_static", "bf_exact_diffusion_least_squares_run", "bf_dgd_status", "bf_stream_probe", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
     "bf_atc_step", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
+    "bf_blocked_elems", "bf_recommended_block", "bf_blocked_pack", "bf_blocked_unpack",
 ]
 
 
@@ -119,6 +120,12 @@ def _load():
     L.bf_set_tuning.argtypes = [i32, i32]
     L.bf_recommended_ld.argtypes = [i64, C.c_int]
     L.bf_recommended_ld.restype = i64
+    L.bf_blocked_elems.argtypes = [i32, i64, i64]
+    L.bf_blocked_elems.restype = i64
+    L.bf_recommended_block.argtypes = [i32, i64, C.c_int]
+    L.bf_recommended_block.restype = i64
+    L.bf_blocked_pack.argtypes = [i32, i64, i64, vp, i64, vp, C.c_int, vp]
+    L.bf_blocked_unpack.argtypes = [i32, i64, i64, vp, i64, vp, C.c_int, vp]
     for name in EXPORTS:
         getattr(L, name)          # raises AttributeError if a declared symbol is missing
     return L
@@ -250,8 +257,38 @@ def _dtype_code(t):
     raise TypeError("libbf handles float32 and bfloat16 matrices, got %s" % t.dtype)
 
 
+class Blocked:
+    """A matrix in the column-block layout (``BF_LD_BLOCKED`` in bf.h): ``data`` is a contiguous
+    (ceil(d/B), n, B) tensor, ``d`` the number of columns that exist.  It stands where the calls
+    that accept the layout take a 2-D tensor; nothing is computed here."""
+
+    def __init__(self, data, d):
+        if data.dim() != 3 or not data.is_contiguous():
+            raise ValueError("a column-block matrix is a contiguous (blocks, n, B) tensor")
+        nb, n, blk = data.shape
+        if nb != (d + blk - 1) // blk:
+            raise ValueError("%d columns in blocks of %d need %d blocks, the tensor has %d" % (d, blk, (d + blk - 1) // blk, nb))
+        self.data, self.d = data, d
+        self.shape = (n, d)
+        self.dtype = data.dtype
+
+    def dim(self):
+        return 2
+
+    def stride(self, k):
+        return -self.data.shape[2] if k == 0 else 1     # what the C calls take as ld
+
+    def data_ptr(self):
+        return self.data.data_ptr()
+
+    def element_size(self):
+        return self.data.element_size()
+
+
 def _mat(t, name):
-    """(ptr, n, d, ld) of an agent-major 2-D tensor with unit column stride."""
+    """(ptr, n, d, ld) of an agent-major 2-D tensor with unit column stride, or of a Blocked."""
+    if isinstance(t, Blocked):
+        return t.data_ptr(), t.shape[0], t.d, t.stride(0)
     if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
         raise ValueError("%s must be 2-D with contiguous rows" % name)
     n, d = t.shape
@@ -294,6 +331,8 @@ def _vec(w, n, name):
 
 
 def _same_layout(ref, other, name):
+    if isinstance(ref, Blocked) != isinstance(other, Blocked):
+        raise ValueError("%s must have the layout of X_in" % name)
     if other.shape != ref.shape or (ref.shape[0] > 1 and other.stride(0) != ref.stride(0)) or other.dtype != ref.dtype:
         raise ValueError("%s must match the shape, row stride and dtype of X_in" % name)
 
@@ -611,6 +650,40 @@ def bf_consensus_stats(X, p=None, stats=None, mean_out=None, stream=None):
                                   stats.data_ptr(), None if mean_out is None else mean_out.data_ptr(),
                                   _stream(stream)), "bf_consensus_stats")
     return stats
+
+
+def bf_blocked_elems(n, d, block):
+    e = lib.bf_blocked_elems(n, d, block)
+    if e < 0:
+        raise BfError(int(e), "bf_blocked_elems")
+    return e
+
+
+def bf_recommended_block(n, d, dt):
+    b = lib.bf_recommended_block(n, d, dt)
+    if b < 0:
+        raise BfError(int(b), "bf_recommended_block")
+    return b
+
+
+def bf_blocked_pack(X, Xb, stream=None):
+    """X: agent-major 2-D tensor; Xb: Blocked of the same n, d and dtype (written)."""
+    ptr, n, d, ld = _mat(X, "X")
+    if not isinstance(Xb, Blocked) or Xb.shape != (n, d) or Xb.dtype != X.dtype:
+        raise ValueError("Xb must be a Blocked matrix with the shape and dtype of X")
+    _check(lib.bf_blocked_pack(n, d, ld, ptr, -Xb.stride(0), Xb.data_ptr(), _dtype_code(X), _stream(stream)),
+           "bf_blocked_pack")
+    return Xb
+
+
+def bf_blocked_unpack(Xb, X, stream=None):
+    """Xb: Blocked; X: agent-major 2-D tensor of the same n, d and dtype (written)."""
+    ptr, n, d, ld = _mat(X, "X")
+    if not isinstance(Xb, Blocked) or Xb.shape != (n, d) or Xb.dtype != X.dtype:
+        raise ValueError("Xb must be a Blocked matrix with the shape and dtype of X")
+    _check(lib.bf_blocked_unpack(n, d, -Xb.stride(0), Xb.data_ptr(), ld, ptr, _dtype_code(X), _stream(stream)),
+           "bf_blocked_unpack")
+    return X
 
 
 def bf_recommended_ld(d, dt):

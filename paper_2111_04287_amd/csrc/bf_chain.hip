@@ -306,7 +306,7 @@ __global__ __launch_bounds__(1024) void bf_narrow_kernel(const TileParams p) {
       const int64_t col = c0 + cit;
       float xv[4] = {0.f, 0.f, 0.f, 0.f};
       if (col < d) {
-        const int64_t off = static_cast<int64_t>(row) * ld + col;
+        const int64_t off = static_cast<int64_t>(row) * ld + col + tile_origin(p, c0);
         const int64_t rem = d - col;
         // element by element: a piece may straddle d, and bf16 pieces are only 8-byte aligned
         float gv[4] = {0.f, 0.f, 0.f, 0.f}, hv[4] = {0.f, 0.f, 0.f, 0.f}, sv[4] = {0.f, 0.f, 0.f, 0.f};
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(1024) void bf_narrow_kernel(const TileParams p) {
         acc[0] = fmaf(w, v.x, acc[0]); acc[1] = fmaf(w, v.y, acc[1]);
         acc[2] = fmaf(w, v.z, acc[2]); acc[3] = fmaf(w, v.w, acc[3]);
       }
-      const int64_t off = static_cast<int64_t>(i) * ld + col;
+      const int64_t off = static_cast<int64_t>(i) * ld + col + tile_origin(p, c0);
       const int64_t rem = d - col;
       const int valid = rem >= 4 ? 4 : static_cast<int>(rem);
       if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {

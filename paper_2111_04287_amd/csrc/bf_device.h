@@ -93,6 +93,9 @@ struct TileParams {
   int64_t ntiles;
   int32_t n;
   int32_t log_c;         // tile width C = 1 << log_c elements
+  int32_t block_log;     // 0: agent-major rows of pitch ld.  Else the column-block layout: blocks of
+                         // B = 1 << block_log columns, block k an n x B row-major matrix at element
+                         // k n B (ld = B; tiles never straddle a block: log_c <= block_log)
   int32_t reverse;       // walk the column tiles from the last to the first
   int32_t fuse;          // rounds applied per pass (1 = a single mix); >1 needs two LDS tiles
   // Fused rounds: the rounds before the last one (rowptr/ent hold the last) are found through the
@@ -107,6 +110,13 @@ struct TileParams {
                          // all rows from rows_b on empty and the rounds that read it never refer to them
   float alpha, beta;
 };
+
+// What to add to row * ld + column for the columns of the tile that starts at column c0: nothing
+// for agent-major rows; in the column-block layout block k = c0 / B starts (n - 1) B k elements
+// later than agent-major rows of pitch B would put it.
+__device__ __forceinline__ int64_t tile_origin(const TileParams& p, int64_t c0) {
+  return p.block_log ? ((c0 >> p.block_log) * (p.n - 1)) << p.block_log : int64_t{0};
+}
 
 // Parameters of the kernel that runs uniform shift rounds in registers (bf_shift.hip).
 struct ShiftParams {

@@ -849,7 +849,7 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_wgs =
     const int lc = ilog2(g_tune_tile);
     if ((1 << lc) != g_tune_tile || lc < 6 || lc > 10) return BF_ERR_UNSUPPORTED;
     const size_t bytes = static_cast<size_t>(n) * g_tune_tile * 4;
-    if (bytes > lds_blk || bytes > lds_cu) return BF_ERR_UNSUPPORTED;
+    if (bytes > lds_blk || bytes > lds_cu || lc > max_log_c) return BF_ERR_UNSUPPORTED;
     if (g_tune_wgs == 0) wgs = static_cast<int>(std::max<size_t>(1, lds_cu / bytes));
     if (bytes * wgs > lds_cu) return BF_ERR_UNSUPPORTED;
     log_c = lc;
@@ -882,17 +882,17 @@ int choose_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_wgs =
 
 // Tile of the pipelined kernel: two n x C fp32 tiles share one CU's LDS; the widest power-of-two C in
 // [64, 1024] that fits, narrowed while the launch would leave CUs without a tile.
-int choose_pipe_shape(int n, int64_t d, const DeviceInfo& di, Shape* s) {
+int choose_pipe_shape(int n, int64_t d, const DeviceInfo& di, Shape* s, int max_log_c = 10) {
   const size_t lds_cu = di.lds_per_cu ? di.lds_per_cu : 65536;
   const size_t budget = std::min(lds_cu, di.lds_per_block_optin ? di.lds_per_block_optin : lds_cu);
   int log_c = -1;
   if (g_tune_tile > 0) {
     const int lc = ilog2(g_tune_tile);
     if ((1 << lc) != g_tune_tile || lc < 6 || lc > 10) return BF_ERR_UNSUPPORTED;
-    if (2 * static_cast<size_t>(n) * g_tune_tile * 4 > budget) return BF_ERR_UNSUPPORTED;
+    if (2 * static_cast<size_t>(n) * g_tune_tile * 4 > budget || lc > max_log_c) return BF_ERR_UNSUPPORTED;
     log_c = lc;
   } else {
-    for (int lc = 10; lc >= 6 && log_c < 0; --lc)
+    for (int lc = max_log_c; lc >= 6 && log_c < 0; --lc)
       if (2 * static_cast<size_t>(n) * (size_t{1} << lc) * 4 <= budget) log_c = lc;
     if (log_c < 0) return BF_ERR_UNSUPPORTED;
     while (log_c > 6 && ((d + (int64_t{1} << log_c) - 1) >> log_c) < di.cus) --log_c;
@@ -911,17 +911,39 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   return pa < pb + nb && pb < pa + na;
 }
 
-struct MatArgs { int64_t d, ld; int dt; int n; size_t bytes; };
+struct MatArgs {
+  int64_t d, ld; int dt; int n;
+  size_t bytes;       // extent of a matrix of the call's element type
+  int block_log;      // 0: agent-major; else log2 of the block width of the column-block layout
+  // extent of a matrix of `eb`-byte elements in the same layout (momentum and the like are fp32)
+  size_t extent(int eb) const {
+    if (block_log) return static_cast<size_t>((d + ld - 1) / ld) * n * ld * eb;
+    return static_cast<size_t>(n - 1) * ld * eb + ((static_cast<size_t>(d) * eb + 15) & ~size_t{15});
+  }
+};
 
-// Common checks of an n x d matrix argument set.  Returns the extent in bytes through ma->bytes.
-int check_matrix_shape(int32_t n, int64_t d, int64_t ld, int dt, MatArgs* ma) {
+// Common checks of an n x d matrix argument set.  A negative ld = -B names the column-block layout
+// with blocks of B columns (a power of two in [64, 2^20]): accepted only where the caller says so,
+// else BF_ERR_UNSUPPORTED.  ma->ld is then B.  ma->bytes is what the kernels may touch: for
+// agent-major rows whole 16-byte vectors up to the one that holds column d-1, for column blocks
+// every block in full.
+int check_matrix_shape(int32_t n, int64_t d, int64_t ld, int dt, MatArgs* ma, bool blocked_ok = false) {
   if (dt != BF_F32 && dt != BF_BF16) return BF_ERR_KIND;
-  if (d < 0 || ld < d || ld < 1 || ld > (int64_t{1} << 40)) return BF_ERR_SIZE;
   const int eb = dt == BF_F32 ? 4 : 2;
+  ma->d = d; ma->dt = dt; ma->n = n; ma->block_log = 0;
+  if (ld < 0) {
+    const int64_t blk = -ld;
+    if (d < 0 || blk < 64 || blk > (int64_t{1} << 20) || (blk & (blk - 1)) != 0 || d > (int64_t{1} << 40)) return BF_ERR_SIZE;
+    if (!blocked_ok) return BF_ERR_UNSUPPORTED;
+    ma->ld = blk;
+    ma->block_log = ilog2(blk);
+    ma->bytes = ma->extent(eb);
+    return BF_OK;
+  }
+  if (d < 0 || ld < d || ld < 1 || ld > (int64_t{1} << 40)) return BF_ERR_SIZE;
   if ((ld * eb) % 16 != 0) return BF_ERR_ALIGN;
-  ma->d = d; ma->ld = ld; ma->dt = dt; ma->n = n;
-  // what the kernels may read: whole 16-byte vectors up to the one that holds column d-1
-  ma->bytes = static_cast<size_t>(n - 1) * ld * eb + ((static_cast<size_t>(d) * eb + 15) & ~size_t{15});
+  ma->ld = ld;
+  ma->bytes = ma->extent(eb);
   return BF_OK;
 }
 
@@ -958,7 +980,12 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     tp.ent = reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[kl]);
     tp.reverse = g_tune_noserp ? 0 : ((round / fuse) & 1);
   }
-  if (fuse == 1 && dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather &&
+  // Column-block layout: tiles stay inside a block, and the two kernels that walk whole rows (the
+  // chain kernel, the gather fallback) do not apply.
+  const bool blocked = tp.block_log > 0;
+  if (blocked && fuse > 1) return BF_ERR_UNSUPPORTED;
+  const int cap_log_c = blocked ? std::min(tp.block_log, 10) : 10;
+  if (fuse == 1 && !blocked && dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather &&
       (g_tune_cw > 0 || static_cast<size_t>(t->n) * 256 * 4 > (di.lds_per_cu ? di.lds_per_cu : 65536) / 2)) {
     // Chain-structured round with too many agents for a 256-column LDS tile (measured: the tile
     // kernels win below that, the row-streaming kernel above): stream rows through registers when
@@ -990,10 +1017,11 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   bool cacheable = false;
   {
     const size_t eb = dt == BF_F32 ? 4 : 2;
-    size_t footprint = static_cast<size_t>(t->n) * tp.ld * eb;
+    const size_t row_elems = blocked ? static_cast<size_t>((tp.d + tp.ld - 1) / tp.ld * tp.ld) : static_cast<size_t>(tp.ld);
+    size_t footprint = static_cast<size_t>(t->n) * row_elems * eb;
     if (tp.g) footprint *= 2;
-    if (tp.g2) footprint += static_cast<size_t>(t->n) * tp.ld * eb;
-    if (tp.m) footprint += static_cast<size_t>(t->n) * tp.ld * 4;
+    if (tp.g2) footprint += static_cast<size_t>(t->n) * row_elems * eb;
+    if (tp.m) footprint += static_cast<size_t>(t->n) * row_elems * 4;
     cacheable = tp.x_in == tp.x_out && footprint <= (size_t{320} << 20);
   }
   const bool stream = g_tune_stream == 1 ? true : (g_tune_stream == 2 ? false : !cacheable);
@@ -1003,7 +1031,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     // memory-side cache.  A cache-resident in-place round is left to the one-tile kernel, whose two
     // workgroups per CU do better there (76 % vs 75 % on 64 x 2^20).
     Shape ps;
-    if (choose_pipe_shape(t->n, tp.d, di, &ps) == BF_OK) {
+    if (choose_pipe_shape(t->n, tp.d, di, &ps, cap_log_c) == BF_OK) {
       if (dry) return BF_OK;
       ps.stream = stream;
       tp.log_c = ps.log_c;
@@ -1018,11 +1046,11 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   // (the fused kernel needs more than 64 registers, so one workgroup per CU is all that runs)
   const int rows_b = fuse > 1 ? (tp.rows_b > 0 && tp.rows_b < t->n ? tp.rows_b : t->n) : 0;
   rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(t->n + rows_b, tp.d, di, &s, fuse > 1 ? 1 : 2,
-                                                                 fuse > 1 ? 8 : 10);   // fused: 256 columns at most (512 measured slower)
+                                                                 fuse > 1 ? 8 : cap_log_c);   // fused: 256 columns at most (512 measured slower)
   if (fuse > 1 && rc != BF_OK) return rc;   // fused rounds exist only as the two-tile LDS kernel
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
     // Too many agents for a 64-column LDS tile.
-    const bool gatherable = tp.x_in != tp.x_out && op != OP_ED && op != OP_TRACK;
+    const bool gatherable = tp.x_in != tp.x_out && op != OP_ED && op != OP_TRACK && !blocked;
     if (gatherable) {
       // row gather through the caches (out of place only; no state matrix in the sum)
       if (dry) return BF_OK;
@@ -1216,6 +1244,72 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
   return BF_OK;
 }
 
+// Layout conversion between agent-major rows and column blocks: one thread per 16 bytes of the
+// block side (coalesced there; row segments of B elements on the agent-major side).  PACK also
+// zero-fills the columns at or past d of the last block, UNPACK never writes them.
+template <int EB, bool PACK>
+__global__ __launch_bounds__(256) void bf_layout_kernel(const char* src, char* dst, int n, int64_t d, int64_t ld,
+                                                        int block_log, int64_t nunits) {
+  constexpr int PER = 16 / EB;
+  const int upb_log = block_log - (EB == 4 ? 2 : 3);          // 16-byte units per block row (log2)
+  for (int64_t u = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; u < nunits;
+       u += static_cast<int64_t>(gridDim.x) * 256) {
+    const int64_t rowu = u >> upb_log;                          // block * n + row
+    const int64_t blk = rowu / n;
+    const int row = static_cast<int>(rowu - blk * n);
+    const int64_t col = (blk << block_log) + ((u & ((int64_t{1} << upb_log) - 1)) * PER);
+    const char* rowmajor = (PACK ? src : dst) + (static_cast<int64_t>(row) * ld + col) * EB;
+    const char* blocked = (PACK ? dst : src) + u * 16;
+    if (col + PER <= d) {
+      if (PACK) *reinterpret_cast<u32x4*>(const_cast<char*>(blocked)) = *reinterpret_cast<const u32x4*>(rowmajor);
+      else *reinterpret_cast<u32x4*>(const_cast<char*>(rowmajor)) = *reinterpret_cast<const u32x4*>(blocked);
+    } else {
+      // the unit that straddles d (element by element), and the padding behind it
+      for (int e = 0; e < PER; ++e) {
+        const bool in = col + e < d;
+        for (int b = 0; b < EB; ++b) {
+          if (PACK) const_cast<char*>(blocked)[e * EB + b] = in ? rowmajor[e * EB + b] : char{0};
+          else if (in) const_cast<char*>(rowmajor)[e * EB + b] = blocked[e * EB + b];
+        }
+      }
+    }
+  }
+}
+
+int layout_common(bool pack, int32_t n, int64_t d, int64_t ld, const void* src, int64_t block, void* dst,
+                         bf_dtype_t dt, void* hip_stream) {
+  if (!src || !dst) return BF_ERR_NULL;
+  if (n < 1) return BF_ERR_SIZE;
+  MatArgs rm, bl;
+  int rc = check_matrix_shape(n, d, ld, dt, &rm);
+  if (rc != BF_OK) return rc;
+  if (block < 1) return BF_ERR_SIZE;
+  rc = check_matrix_shape(n, d, -block, dt, &bl, true);
+  if (rc != BF_OK) return rc;
+  if (misaligned16(src) || misaligned16(dst)) return BF_ERR_ALIGN;
+  if (overlaps(src, pack ? rm.bytes : bl.bytes, dst, pack ? bl.bytes : rm.bytes)) return BF_ERR_ALIAS;
+  if (d == 0) return BF_OK;
+  int dev = 0;
+  BF_HIP_TRY(hipGetDevice(&dev));
+  DeviceInfo di;
+  rc = device_info(dev, &di);
+  if (rc != BF_OK) return rc;
+  const int64_t nunits = static_cast<int64_t>(bl.bytes / 16);
+  const int grid = static_cast<int>(std::min<int64_t>((nunits + 255) / 256, static_cast<int64_t>(di.cus) * 16));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const char* s8 = static_cast<const char*>(src);
+  char* d8 = static_cast<char*>(dst);
+  if (dt == BF_F32) {
+    if (pack) hipLaunchKernelGGL((bf_layout_kernel<4, true>), dim3(grid), dim3(256), 0, st, s8, d8, n, d, ld, bl.block_log, nunits);
+    else hipLaunchKernelGGL((bf_layout_kernel<4, false>), dim3(grid), dim3(256), 0, st, s8, d8, n, d, ld, bl.block_log, nunits);
+  } else {
+    if (pack) hipLaunchKernelGGL((bf_layout_kernel<2, true>), dim3(grid), dim3(256), 0, st, s8, d8, n, d, ld, bl.block_log, nunits);
+    else hipLaunchKernelGGL((bf_layout_kernel<2, false>), dim3(grid), dim3(256), 0, st, s8, d8, n, d, ld, bl.block_log, nunits);
+  }
+  BF_HIP_TRY(hipGetLastError());
+  return BF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1262,16 +1356,16 @@ int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_i
   if (!t || !X_in || !X_out) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   MatArgs ma;
-  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
-  if (t->kind == BF_DENSE_USER && dt == BF_F32 && t->n <= 256)
+  if (t->kind == BF_DENSE_USER && dt == BF_F32 && t->n <= 256 && !ma.block_log)
     return bf_dense_mix(t, round, X_in, X_out, d, ld, dt, hip_stream);
   TileParams tp{};
   tp.x_in = static_cast<const char*>(X_in);
   tp.x_out = static_cast<char*>(X_out);
-  tp.d = d; tp.ld = ld;
+  tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_MIX, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -1486,7 +1580,7 @@ static int pushsum_common(const bf_topology_t* t, int32_t round, const void* X_i
   if (!t || !X_in || !X_out || !w_in || !w_out) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   MatArgs ma;
-  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(X_in) || misaligned16(X_out) || (Y && misaligned16(Y)) || (G && misaligned16(G))) return BF_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(w_in) & 3u) || (reinterpret_cast<uintptr_t>(w_out) & 3u)) return BF_ERR_ALIGN;
@@ -1525,7 +1619,7 @@ static int pushsum_common(const bf_topology_t* t, int32_t round, const void* X_i
   tp.alpha = alpha;
   tp.y = static_cast<char*>(Y);
   tp.p_out = w_out;
-  tp.d = d; tp.ld = ld;
+  tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
   // is there a kernel for the matrix part?  Asked before w is advanced, so that an error leaves
   // the caller's push-sum state as it was
   rc = run_tile(tt, round, G ? OP_ATC : OP_MIX, Y != nullptr, tp, dt, st, true);
@@ -1556,7 +1650,7 @@ int bf_tracking_step(const bf_topology_t* t, int32_t round, const void* Y_in, vo
   if (!t || !Y_in || !Y_out || !G_new || !G_old) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   MatArgs ma;
-  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(Y_in) || misaligned16(Y_out) || misaligned16(G_new) || misaligned16(G_old)) return BF_ERR_ALIGN;
   if (Y_in != Y_out && overlaps(Y_in, ma.bytes, Y_out, ma.bytes)) return BF_ERR_ALIAS;
@@ -1566,7 +1660,7 @@ int bf_tracking_step(const bf_topology_t* t, int32_t round, const void* Y_in, vo
   tp.x_out = static_cast<char*>(Y_out);
   tp.g = static_cast<const char*>(G_new);
   tp.g2 = static_cast<const char*>(G_old);
-  tp.d = d; tp.ld = ld;
+  tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_TRACK, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -1577,11 +1671,11 @@ int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X
   if (round < 0) return BF_ERR_ROUND;
   if (mode != BF_ATC && mode != BF_AWC) return BF_ERR_KIND;
   MatArgs ma;
-  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
-  if ((ld * 4) % 16 != 0 && M) return BF_ERR_ALIGN;
+  if ((ma.ld * 4) % 16 != 0 && M) return BF_ERR_ALIGN;
   if (misaligned16(X_in) || misaligned16(X_out) || misaligned16(G) || (M && misaligned16(M))) return BF_ERR_ALIGN;
-  const size_t mb = static_cast<size_t>(t->n - 1) * ld * 4 + static_cast<size_t>(d) * 4;
+  const size_t mb = ma.extent(4);
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   if (overlaps(G, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   if (M && (overlaps(M, mb, X_out, ma.bytes) || overlaps(M, mb, X_in, ma.bytes) || overlaps(M, mb, G, ma.bytes)))
@@ -1592,7 +1686,7 @@ int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X
   tp.g = static_cast<const char*>(G);
   tp.m = M;
   tp.alpha = alpha; tp.beta = beta;
-  tp.d = d; tp.ld = ld;
+  tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
   const int op = M ? (mode == BF_ATC ? OP_MOM_ATC : OP_MOM_AWC) : (mode == BF_ATC ? OP_ATC : OP_AWC);
   return run_tile(const_cast<bf_topology_t*>(t), round, op, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
@@ -1603,11 +1697,11 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
   if (!t || !X_in || !X_out || !G || !Psi_prev) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   MatArgs ma;
-  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
-  if ((ld * 4) % 16 != 0) return BF_ERR_ALIGN;
+  if ((ma.ld * 4) % 16 != 0) return BF_ERR_ALIGN;
   if (misaligned16(X_in) || misaligned16(X_out) || misaligned16(G) || misaligned16(Psi_prev)) return BF_ERR_ALIGN;
-  const size_t pb = static_cast<size_t>(t->n - 1) * ld * 4 + static_cast<size_t>(d) * 4;
+  const size_t pb = ma.extent(4);
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   if (overlaps(G, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   if (overlaps(Psi_prev, pb, X_out, ma.bytes) || overlaps(Psi_prev, pb, X_in, ma.bytes) || overlaps(Psi_prev, pb, G, ma.bytes))
@@ -1618,7 +1712,7 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
   tp.g = static_cast<const char*>(G);
   tp.m = Psi_prev;
   tp.alpha = alpha;
-  tp.d = d; tp.ld = ld;
+  tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_ED, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -1775,6 +1869,16 @@ int bf_dgd_status(const bf_topology_t* tc, int32_t* timed_out, void* hip_stream)
   BF_HIP_TRY(hipStreamSynchronize(st));
   *timed_out = host[1] != 0u ? 1 : 0;
   return BF_OK;
+}
+
+int bf_blocked_pack(int32_t n, int64_t d, int64_t ld, const void* X, int64_t block, void* X_blocked,
+                    bf_dtype_t dt, void* hip_stream) {
+  return layout_common(true, n, d, ld, X, block, X_blocked, dt, hip_stream);
+}
+
+int bf_blocked_unpack(int32_t n, int64_t d, int64_t block, const void* X_blocked, int64_t ld, void* X,
+                      bf_dtype_t dt, void* hip_stream) {
+  return layout_common(false, n, d, ld, X_blocked, block, X, dt, hip_stream);
 }
 
 int bf_stream_probe(int32_t mode, const void* src, void* dst, int64_t bytes, int32_t workgroups_per_cu,

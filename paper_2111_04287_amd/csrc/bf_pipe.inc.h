@@ -69,6 +69,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
 
   auto load_tile = [&](int64_t tile, float* buf) {
     const int64_t c0 = tile << log_c;
+    const int64_t t0 = tile_origin(p, c0);
     for (int base = 0; base < nunits; base += LT * U) {
       raw_t xr[U];
       raw_t gr[STAGE_G ? U : 1];
@@ -79,7 +80,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
         const int u = min(base + k * LT + tid, nunits - 1);
         const int row = u >> upr_log;
         const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
-        const int64_t off = static_cast<int64_t>(row) * ld + col;
+        const int64_t off = static_cast<int64_t>(row) * ld + col + t0;
         xr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.x_in + off * EB));
         if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g + off * EB));
         if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g2 + off * EB));
@@ -101,7 +102,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
             float sv[4] = {mr[k].x, mr[k].y, mr[k].z, mr[k].w};
             local_update4<OP>(xv, gv, sv, p.alpha, p.beta);
             if (live) {
-              float* mp = p.m + static_cast<int64_t>(row) * ld + col;
+              float* mp = p.m + static_cast<int64_t>(row) * ld + col + t0;
               const int64_t rem = d - col;
               if (rem >= 4) { f32x4 t = {sv[0], sv[1], sv[2], sv[3]}; st_stream<STREAM>(reinterpret_cast<f32x4*>(mp), t); }
               else for (int e = 0; e < 4; ++e) if (e < rem) mp[e] = sv[e];
@@ -144,6 +145,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   auto reduce_tile = [&](int64_t tile, const float* buf) {
     const int64_t c0 = tile << log_c;
     const bool full = c0 + (int64_t{1} << log_c) <= d;      // no ragged tail in this tile
+    const int64_t t0 = tile_origin(p, c0);
     for (int op = wave - NL; op < nops; op += NR) {
       const int i = op >> spans_log;
       const int cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
@@ -186,7 +188,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
       if (full || col < d) {
         const int64_t rem = d - col;
         const int valid = (full || rem >= LW) ? LW : static_cast<int>(rem);
-        const int64_t off = static_cast<int64_t>(i) * ld + col;
+        const int64_t off = static_cast<int64_t>(i) * ld + col + t0;
         if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
           // Adapt-while-communicate: the receiver's own gradient is subtracted after the mix.
           float gv[LW];

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const int u = min(tid + k * THREADS, nunits - 1);
       const int row = u >> upr_log;
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
-      const int64_t off = static_cast<int64_t>(row) * ld + col;
+      const int64_t off = static_cast<int64_t>(row) * ld + col + tile_origin(p, c0);
       xr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
       if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
       if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       float gv[UC];
       widen<DT>(graw, gv);
       if constexpr (STAGE_M) {
-        const int64_t off = static_cast<int64_t>(row) * ld + col;
+        const int64_t off = static_cast<int64_t>(row) * ld + col + tile_origin(p, c0);
 #pragma unroll
         for (int q = 0; q < MV; ++q) {
           float sv[4] = {mraw[q].x, mraw[q].y, mraw[q].z, mraw[q].w};
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
     for (int u = tid + MAXPF * THREADS; u < nunits; u += THREADS) {
       const int row = u >> upr_log;
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
-      const int64_t off = static_cast<int64_t>(row) * ld + col;
+      const int64_t off = static_cast<int64_t>(row) * ld + col + tile_origin(p, c0);
       const u32x4 xraw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
       u32x4 graw = {0, 0, 0, 0}, g2raw = {0, 0, 0, 0};
       f32x4 mraw[MV];
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       if (col < d) {
         const int64_t rem = d - col;
         const int valid = rem >= LW ? LW : static_cast<int>(rem);
-        const int64_t off = static_cast<int64_t>(i) * ld + col;
+        const int64_t off = static_cast<int64_t>(i) * ld + col + tile_origin(p, c0);
         if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
           // Adapt-while-communicate: the receiver's own gradient is subtracted after the mix.
           float gv[LW];

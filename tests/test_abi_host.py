@@ -339,6 +339,55 @@ def test_compute_calls_validate_before_touching_the_device():
     assert L.bf_set_tuning(0, 0) == bf.BF_OK
 
 
+def test_column_block_layout_argument_checks():
+    t = bf.bf_topology_create(bf.BF_RING, 4)
+    h = t.handle
+    A, B = 0x10000000, 0x20000000
+    L = bf.lib
+    assert bf.bf_blocked_elems(4, 1000, 256) == 4 * 1024
+    assert bf.bf_blocked_elems(3, 0, 64) == 0
+    assert L.bf_blocked_elems(4, 1000, 100) == bf.BF_ERR_SIZE              # not a power of two
+    assert L.bf_blocked_elems(4, 1000, 32) == bf.BF_ERR_SIZE
+    assert L.bf_blocked_elems(4, 1000, 1 << 21) == bf.BF_ERR_SIZE
+    assert L.bf_blocked_elems(0, 1000, 64) == bf.BF_ERR_SIZE
+    assert bf.bf_recommended_block(32, 25557032, bf.BF_BF16) == 16384 and bf.bf_recommended_block(64, 1 << 20, bf.BF_F32) == 16384
+    assert bf.bf_recommended_block(128, 1 << 21, bf.BF_F32) == 8192 and bf.bf_recommended_block(256, 1 << 22, bf.BF_F32) == 4096
+    assert bf.bf_recommended_block(5000, 1 << 22, bf.BF_F32) == 2048 and bf.bf_recommended_block(5, 4096, bf.BF_F32) == 4096
+    assert bf.bf_recommended_block(5, 100, bf.BF_F32) == 128 and bf.bf_recommended_block(5, 3, bf.BF_F32) == 64
+    assert bf.bf_recommended_block(5, 0, bf.BF_F32) == 64
+    assert L.bf_recommended_block(0, 100, bf.BF_F32) == bf.BF_ERR_SIZE
+    assert L.bf_recommended_block(4, 100, 9) == bf.BF_ERR_KIND
+    na = L.bf_neighbor_allreduce
+    assert na(h, 0, A, B, 100, -100, bf.BF_F32, None) == bf.BF_ERR_SIZE       # block width not a power of two
+    assert na(h, 0, A, B, 100, -32, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert na(h, 0, A, B, 100, -(1 << 21), bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert na(h, 0, A, B, 0, -64, bf.BF_F32, None) == bf.BF_OK               # empty
+    assert na(h, 0, A, A + 1024, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS   # 2 blocks x 4 x 64 x 4 = 2048 bytes each
+    assert na(h, 0, A, A + 2048, 0, -64, bf.BF_F32, None) == bf.BF_OK
+    # calls that take agent-major matrices only
+    assert L.bf_neighbor_allreduce_multi(h, 0, 2, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
+    assert L.bf_hierarchical_neighbor_allreduce(h, 0, 2, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
+    assert L.bf_dense_mix(h, 0, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
+    assert L.bf_win_put(h, 0, None, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
+    assert L.bf_consensus_stats(4, 100, -64, A, None, bf.BF_F32, B, None, None) == bf.BF_ERR_UNSUPPORTED
+    # the state matrix of a momentum step has the layout of X: its extent follows the blocks
+    G, M = 0x40000000, 0x50000000
+    at = L.bf_atc_step
+    assert at(h, 0, A, A, G, A + 512, 0.1, 0.9, bf.BF_ATC, 100, -64, bf.BF_BF16, None) == bf.BF_ERR_ALIAS
+    assert at(h, 0, A, A, G, G + 1024, 0.1, 0.9, bf.BF_ATC, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS    # M inside G (2048 bytes)
+    pk, up = L.bf_blocked_pack, L.bf_blocked_unpack
+    assert pk(4, 100, 104, None, 64, B, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert pk(4, 100, 104, A, 100, B, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert pk(4, 100, 96, A, 64, B, bf.BF_F32, None) == bf.BF_ERR_SIZE       # ld < d
+    assert pk(4, 100, 102, A, 64, B, bf.BF_F32, None) == bf.BF_ERR_ALIGN
+    assert pk(4, 100, 104, A, 64, A + 1024, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert pk(0, 100, 104, A, 64, B, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert pk(4, 0, 104, A, 64, B, bf.BF_F32, None) == bf.BF_OK
+    assert up(4, 100, 64, A, 104, A + 1024, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert up(4, 100, 64, A, 104, B + 8, bf.BF_F32, None) == bf.BF_ERR_ALIGN
+    assert up(4, 0, 64, A, 104, B, bf.BF_F32, None) == bf.BF_OK
+
+
 def _walk_chain_plan(steps, X):
     """Replay a chain plan the way the streaming kernel does: three live rows, each row loaded once."""
     n = X.shape[0]

@@ -1,0 +1,237 @@
+"""GPU parity of the column-block layout: the conversion kernels against the layout's definition
+written out in numpy, every call that accepts the layout against the same call on agent-major
+matrices (bit for bit: same kernels' arithmetic, other addresses) and against the fp64 oracle, and
+the momentum step at the benchmark's full size in the launch configuration bench.py times."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2111_04287_amd as bf
+import workloads
+from oracle import iterations as O
+from oracle import topology as OT
+
+pytestmark = pytest.mark.gpu
+DEV = torch.device("cuda:0")
+TOL32 = 1e-5
+
+
+def lib_W(t, r=0):
+    rowptr, col, wgt, _ = bf.bf_topology_export_csr(t, r)
+    return OT.from_csr(rowptr, col, wgt)
+
+
+def host(x):
+    return x.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rows(n, d, seed, dtype=torch.float32):
+    ld = workloads.padded_ld(d, 2 if dtype == torch.bfloat16 else 4)
+    return workloads.normal_rows(n, d, seed, DEV, ld=ld, dtype=dtype)
+
+
+def empty_blocked(n, d, B, dtype, fill=float("nan")):
+    data = torch.full(((d + B - 1) // B, n, B), fill, dtype=dtype, device=DEV)
+    return bf.Blocked(data, d)
+
+
+def to_blocked(X, B):
+    n, d = X.shape
+    return bf.bf_blocked_pack(X, empty_blocked(n, d, B, X.dtype))
+
+
+def from_blocked(Xb, like):
+    out = torch.full((like.shape[0], like.stride(0)), 7.0, dtype=like.dtype, device=DEV)[:, :like.shape[1]]
+    return bf.bf_blocked_unpack(Xb, out)
+
+
+def blocked_by_definition(X, B):
+    """Column c of agent i is element (c // B, i, c % B); the columns past d of the last block are zero."""
+    n, d = X.shape
+    nb = (d + B - 1) // B
+    full = torch.zeros((n, nb * B), dtype=X.dtype, device=X.device)
+    full[:, :d] = X
+    return full.reshape(n, nb, B).permute(1, 0, 2).contiguous()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,d,B", [(1, 64, 64), (3, 5, 64), (7, 1000, 128), (32, 3 * 512 + 37, 512), (5, 4096 * 2 + 1, 4096),
+                                   (64, 256 * 9, 256), (130, 77, 1024)])
+def test_pack_and_unpack_follow_the_layout_definition(dtype, n, d, B):
+    X = rows(n, d, 10 + n, dtype=dtype)
+    Xb = to_blocked(X, B)
+    assert Xb.data.numel() == bf.bf_blocked_elems(n, d, B)
+    assert torch.equal(Xb.data.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                       blocked_by_definition(X, B).view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+    back = torch.full((n, X.stride(0)), 7.0, dtype=dtype, device=DEV)
+    bf.bf_blocked_unpack(Xb, back[:, :d])
+    assert torch.equal(back[:, :d], X)
+    assert bool((back[:, d:] == 7.0).all()), "columns past d of the agent-major rows are not written"
+
+
+CASES = [(5, 300, 64), (32, 3 * 512 + 37, 512), (64, 2 * 256 + 100, 256), (128, 1000, 1024), (32, 9000, 8192),
+         (16, 70000, 1 << 16), (300, 200, 64), (700, 150, 64)]
+
+
+def _knobs(setting):
+    for k, v in setting:
+        bf.bf_set_tuning(k, v)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,d,B", CASES)
+@pytest.mark.parametrize("setting", [(), ((12, 1),), ((12, 2),)], ids=["auto", "pipelined", "one-tile"])
+def test_every_accepting_call_gives_the_agent_major_bits(dtype, n, d, B, setting):
+    t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=min(10, n - 1), seed=77)
+    W = lib_W(t)
+    tol = TOL32 if dtype == torch.float32 else 2.0 ** -8
+    X, G, G2 = (rows(n, d, 40 + k, dtype=dtype) for k in range(3))
+    M0 = workloads.normal_rows(n, d, 49, DEV, ld=X.stride(0))
+    w0 = torch.rand(n, device=DEV) + 0.5
+    alpha, beta = 0.05, 0.9
+    a64, b64 = float(np.float32(alpha)), float(np.float32(beta))
+    Xb, Gb, G2b = (to_blocked(A, B) for A in (X, G, G2))
+
+    def fresh(A):
+        return torch.empty((n, A.stride(0)), dtype=A.dtype, device=DEV)[:, :d].copy_(A)
+
+    def both(call, in_place, state=None, ratio=False):
+        """Runs call(x_in, x_out, state, y) in both layouts; returns the agent-major results after
+        checking that the column-block ones hold the same bits and that block padding is untouched."""
+        xi = fresh(X)
+        xo = xi if in_place else torch.empty((n, X.stride(0)), dtype=dtype, device=DEV)[:, :d]
+        st = None if state is None else fresh(state)
+        y = torch.empty((n, X.stride(0)), dtype=dtype, device=DEV)[:, :d] if ratio else None
+        bxi = to_blocked(X, B)
+        bxo = bxi if in_place else empty_blocked(n, d, B, dtype, fill=3.0)
+        bst = None if state is None else to_blocked(state, B)
+        by = empty_blocked(n, d, B, dtype, fill=3.0) if ratio else None
+        try:
+            _knobs(setting)
+            call(xi, xo, st, y)
+            call(bxi, bxo, bst, by)
+        finally:
+            _knobs(tuple((k, 0) for k, _ in setting))
+        assert torch.equal(from_blocked(bxo, X), xo)
+        if st is not None:
+            assert torch.equal(from_blocked(bst, st), st)
+        if ratio:
+            assert torch.equal(from_blocked(by, X), y)
+        pad = bxo.data[-1, :, d - (bxo.data.shape[0] - 1) * B:]
+        if not in_place and pad.numel():
+            assert bool((pad == 3.0).all()), "the padding columns of the last block are never written"
+        return xo, st, y
+
+    for in_place in (False, True):
+        out, _, _ = both(lambda a, b, s, y: bf.bf_neighbor_allreduce(t, 1, a, b), in_place)
+        ref = O.mix(host(X), W)
+        assert np.abs(host(out) - ref).max() <= tol * np.abs(ref).max()
+        for mode, fn in ((bf.BF_ATC, O.atc_step), (bf.BF_AWC, O.awc_step)):
+            out, _, _ = both(lambda a, b, s, y: bf.bf_atc_step(t, 0, a, b, (Gb if isinstance(a, bf.Blocked) else G), None,
+                                                               alpha=alpha, mode=mode), in_place)
+            ref = fn(host(X), host(G), W, a64)
+            assert np.abs(host(out) - ref).max() <= tol * np.abs(ref).max()
+            out, Mn, _ = both(lambda a, b, s, y: bf.bf_atc_step(t, 0, a, b, (Gb if isinstance(a, bf.Blocked) else G), s,
+                                                                alpha=alpha, beta=beta, mode=mode), in_place, state=M0)
+            Mref = b64 * host(M0) + host(G)
+            ref = O.dmsgd_atc_step(host(X), host(M0), host(G), W, a64, b64)[0] if mode == bf.BF_ATC \
+                else O.mix(host(X), W) - a64 * Mref
+            assert np.abs(host(Mn) - Mref).max() <= 1e-6 * np.abs(Mref).max()
+            assert np.abs(host(out) - ref).max() <= tol * np.abs(ref).max()
+        # Exact-Diffusion (state: psi of the step before), tracking, push-sum with the ratio
+        out, Pn, _ = both(lambda a, b, s, y: bf.bf_exact_diffusion_step(t, 0, a, b, (Gb if isinstance(a, bf.Blocked) else G), s,
+                                                                        alpha), in_place, state=M0)
+        ref, Pref = O.exact_diffusion_step(host(X), host(M0), host(G), W, a64)
+        assert np.abs(host(out) - ref).max() <= tol * np.abs(ref).max()
+        assert np.abs(host(Pn) - Pref).max() <= 1e-6 * np.abs(Pref).max()
+        out, _, _ = both(lambda a, b, s, y: bf.bf_tracking_step(t, 0, a, b, *((Gb, G2b) if isinstance(a, bf.Blocked) else (G, G2))),
+                         in_place)
+        ref = O.mix(host(X) + host(G) - host(G2), W)
+        assert np.abs(host(out) - ref).max() <= tol * max(np.abs(ref).max(), 1.0)
+        for with_g in (False, True):
+            w1 = torch.empty_like(w0)
+
+            def ps(a, b, s, y):
+                if with_g:
+                    bf.bf_pushsum_atc_step(t, 0, a, b, (Gb if isinstance(a, bf.Blocked) else G), alpha, w0, w1, y)
+                else:
+                    bf.bf_pushsum_step(t, 0, a, b, w0, w1, y)
+            out, _, y = both(ps, in_place, ratio=True)
+            xin = host(X) - a64 * host(G) if with_g else host(X)
+            ref = O.mix(xin, W)
+            wref = O.mix(host(w0)[:, None], W)[:, 0]
+            assert np.abs(host(out) - ref).max() <= tol * np.abs(ref).max()
+            assert np.abs(host(w1) - wref).max() <= TOL32 * np.abs(wref).max()
+            yref = ref / wref[:, None]
+            assert np.abs(host(y) - yref).max() <= 2 * tol * np.abs(yref).max()
+
+
+def test_layout_mismatch_and_agent_major_only_calls_are_refused():
+    n, d, B = 8, 300, 64
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    X = rows(n, d, 1)
+    Xb = to_blocked(X, B)
+    with pytest.raises(ValueError):
+        bf.bf_neighbor_allreduce(t, 0, Xb, X)                      # mixed layouts
+    with pytest.raises(ValueError):
+        bf.bf_neighbor_allreduce(t, 0, Xb, to_blocked(X, 128))     # two block widths
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_neighbor_allreduce_multi(t, 0, 2, Xb, Xb)
+    assert e.value.code == bf.BF_ERR_UNSUPPORTED
+    with pytest.raises(bf.BfError) as e:
+        bf.bf_dense_mix(t, 0, Xb, empty_blocked(n, d, B, torch.float32))
+    assert e.value.code == bf.BF_ERR_UNSUPPORTED
+
+
+def sample_columns(d, seed):
+    rng = np.random.default_rng(seed)
+    cols = set(range(0, 300)) | set(range(d - 64, d))
+    for c in (256, 512, 1024):
+        for k in rng.integers(1, d // c, size=6):
+            cols |= set(range(k * c - 5, k * c + 5))
+    for s in rng.integers(0, d - 40, size=20):
+        cols |= set(range(int(s), int(s) + 33))
+    return torch.tensor(sorted(c for c in cols if 0 <= c < d), device=DEV)
+
+
+def test_config5_full_size_momentum_steps_in_column_blocks():
+    """The headline workload as bench.py times it: n = 32, d = 25,557,032, bf16 X and G, fp32 momentum,
+    in place, blocks of bf_recommended_block columns.  Oracle on sampled columns (the path is column
+    separable), which include the ragged tail inside the last block."""
+    n, d = 32, workloads.RESNET50_PARAMS
+    cfg = workloads.CONFIG5
+    B = bf.bf_recommended_block(n, d, bf.BF_BF16)
+    ld = bf.bf_recommended_ld(d, bf.BF_BF16)
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    W = lib_W(t)
+    cols = sample_columns(d, 5)
+    assert int(cols[-1]) == d - 1 and d % B == 14376     # the last block is ragged
+    scratch = workloads.alloc_rows(n, d, torch.bfloat16, DEV, ld=ld)          # agent-major staging for the recipe
+    scratch32 = workloads.alloc_rows(n, d, torch.float32, DEV, ld=ld)
+    Cc = workloads.config5_centres(DEV, n=n, d=d, ld=ld)
+    Ch = Cc[:, cols].float().cpu().numpy().astype(np.float64)
+    Cb = to_blocked(Cc, B)
+    del Cc
+    Xb = empty_blocked(n, d, B, torch.bfloat16, fill=0.0)
+    Gb = empty_blocked(n, d, B, torch.bfloat16, fill=0.0)
+    Eb = empty_blocked(n, d, B, torch.bfloat16, fill=0.0)
+    Mb = empty_blocked(n, d, B, torch.float32, fill=0.0)
+    a64, b64, s64 = (float(np.float32(cfg[k])) for k in ("alpha", "beta", "sigma"))
+    Xr, Mr = np.zeros((n, len(cols))), np.zeros((n, len(cols)))
+    flat = lambda b: b.data.view(-1, B)                                        # the gradient is elementwise
+    for k in range(6):
+        workloads.config5_noise(DEV, k, n=n, d=d, out=scratch)
+        Eh = scratch[:, cols].float().cpu().numpy().astype(np.float64)
+        bf.bf_blocked_pack(scratch, Eb)
+        bf.bf_grad_quadratic(flat(Xb), flat(Cb), flat(Eb), cfg["lam"], cfg["sigma"], flat(Gb))
+        bf.bf_atc_step(t, k, Xb, Xb, Gb, Mb, alpha=cfg["alpha"], beta=cfg["beta"], mode=bf.BF_ATC)
+        Xr, Mr = O.dmsgd_atc_step(Xr, Mr, O.quadratic_noise_grad(Xr, Ch, Eh, cfg["lam"], s64), W, a64, b64)
+        bf.bf_blocked_unpack(Xb, scratch)
+        got = scratch[:, cols].float().cpu().numpy().astype(np.float64)
+        assert np.abs(got - Xr).max() <= 2e-2 * np.abs(Xr).max(), "step %d" % k
+        bf.bf_blocked_unpack(Mb, scratch32)
+        gotm = scratch32[:, cols].cpu().numpy().astype(np.float64)
+        assert np.abs(gotm - Mr).max() <= 2e-2 * np.abs(Mr).max(), "momentum, step %d" % k
+    pad = Xb.data[-1, :, d - (Xb.data.shape[0] - 1) * B:]
+    assert bool((pad == 0).all()) and bool((Mb.data[-1, :, d - (Mb.data.shape[0] - 1) * B:] == 0).all())
