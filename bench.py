@@ -118,7 +118,7 @@ def main():
     c5 = workloads.CONFIG5
     t5 = bf.bf_topology_create(bf.BF_EXP_STATIC, n5)
     ld5 = bf.bf_recommended_ld(d5, bf.BF_BF16)
-    B5 = bf.bf_recommended_block(n5, d5, bf.BF_BF16)
+    B5 = bf.bf_recommended_block(t5, d5, bf.BF_BF16)
     bytes5 = n5 * d5 * 14
 
     def blocked(n, d, B, dtype, src=None):
@@ -215,7 +215,7 @@ def main():
         entry("config2_static_exp_n64_d1048576_f32_out_of_place", "bf_pipe_kernel<f32, mix>", bytes2, n, args.steps, w_, e_,
               "config2_out_of_place", note="separate input and output buffers (512 MiB working set), streaming loads and stores")
         del X2
-        B2 = bf.bf_recommended_block(n, d, bf.BF_F32)
+        B2 = bf.bf_recommended_block(topo, d, bf.BF_F32)
         X2b = [blocked(n, d, B2, torch.float32, X), blocked(n, d, B2, torch.float32)]
         w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(topo, k, X2b[k & 1], X2b[1 - (k & 1)]), args.steps, args.warmup)
         entry("config2_static_exp_n64_d1048576_f32_out_of_place_column_blocks", "bf_pipe_kernel<f32, mix>", bytes2, n, args.steps,
@@ -246,6 +246,12 @@ def main():
         X3 = workloads.config3_state(dev, n=n3, d=d3, ld=ld3)
         w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(t3, k, X3, X3), 24, 8)
         entry("config3_one_peer_exp2_n256_d4194304_f32", "bf_chain_kernel<f32, mix>", 2 * n3 * d3 * 4, n3, 24, w_, e_, "config3")
+        B3 = bf.bf_recommended_block(t3, d3, bf.BF_F32)
+        X3b = blocked(n3, d3, B3, torch.float32, X3)
+        w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce(t3, k, X3b, X3b), 24, 8)
+        entry("config3_one_peer_exp2_n256_d4194304_f32_column_blocks", "bf_chain_kernel<f32, mix>", 2 * n3 * d3 * 4, n3, 24, w_, e_,
+              "config3_column_blocks", extra={"block": B3}, note="as above with X in column blocks of %d" % B3)
+        del X3b
 
         # rows beyond the five configurations, part 1 (needs X3): several rounds per pass.  Reported
         # apart from the per-round figures: a fused pass moves each element through HBM once for
@@ -270,7 +276,7 @@ def main():
         w_, e_ = timed(lambda k: bf.bf_pushsum_step(t4, k, X4, X4, w4, w4, None), 50, 5)
         entry("config4_pushsum_random_directed_n128_d2097152_f32", "bf_pushsum_w_kernel + bf_pipe_kernel<f32, mix>",
               2 * n4 * d4 * 4, n4, 50, w_, e_, "config4", note="launch_ms covers both kernels of a step (the n-scalar update and the mix)")
-        B4 = bf.bf_recommended_block(n4, d4, bf.BF_F32)
+        B4 = bf.bf_recommended_block(t4, d4, bf.BF_F32)
         X4b = blocked(n4, d4, B4, torch.float32, X4)
         w4.fill_(1.0)
         w_, e_ = timed(lambda k: bf.bf_pushsum_step(t4, k, X4b, X4b, w4, w4, None), 50, 5)

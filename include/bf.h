@@ -174,9 +174,11 @@ int bf_topology_export_window(const bf_topology_t* t, int32_t round, int64_t* sl
  * of place) or 4..32-column LDS tiles (in place, n <= 10240); more agents than that in place is
  * BF_ERR_UNSUPPORTED.  The same holds for every call below that mixes a matrix.
  * ld may be BF_LD_BLOCKED(B): the matrices are then in column blocks of B columns, and the LDS tile
- * kernels run with tiles of at most B columns (same arithmetic, same bits).  bf_pushsum_step,
- * bf_pushsum_atc_step, bf_tracking_step, bf_atc_step and bf_exact_diffusion_step accept it too;
- * every other call takes agent-major matrices only. */
+ * kernels run with tiles of at most B columns and the row-streaming kernel with sweeps inside a
+ * block (same arithmetic, same bits).  bf_neighbor_allreduce_multi,
+ * bf_hierarchical_neighbor_allreduce, bf_pushsum_step, bf_pushsum_atc_step, bf_tracking_step,
+ * bf_atc_step and bf_exact_diffusion_step accept it too; every other call takes agent-major
+ * matrices only. */
 int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
                           int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 
@@ -405,10 +407,11 @@ int bf_consensus_stats(int32_t n, int64_t d, int64_t ld, const void* X, const fl
  * Negative (BF_ERR_SIZE) if block is not a power of two in [64, 2^20] or n, d are out of range. */
 int64_t bf_blocked_elems(int32_t n, int64_t d, int64_t block);
 
-/* Block width this library suggests for an n x d matrix: the power of two nearest to 2^20 / n within
- * [2048, 16384] (measured best on MI355X: 16384 columns at n <= 64, 8192 at n = 128), or the power of
- * two that covers d when d is smaller.  Negative on error. */
-int64_t bf_recommended_block(int32_t n, int64_t d, bf_dtype_t dt);
+/* Block width this library suggests for n x d matrices mixed over topology t (measured on MI355X):
+ * the power of two nearest to 2^20 / n within [2048, 16384] (16384 columns at n <= 64, 8192 at
+ * n = 128); 65536 when n > 160 and every round of t is a union of paths and cycles (those go to the
+ * row-streaming kernel); the power of two that covers d when d is smaller.  Negative on error. */
+int64_t bf_recommended_block(const bf_topology_t* t, int64_t d, bf_dtype_t dt);
 
 /* Layout conversion, device to device: X (agent-major, n x d, pitch ld) to X_blocked (column blocks
  * of `block` columns, bf_blocked_elems(n, d, block) elements; the padding columns of the last block

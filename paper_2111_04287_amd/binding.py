@@ -122,7 +122,7 @@ def _load():
     L.bf_recommended_ld.restype = i64
     L.bf_blocked_elems.argtypes = [i32, i64, i64]
     L.bf_blocked_elems.restype = i64
-    L.bf_recommended_block.argtypes = [i32, i64, C.c_int]
+    L.bf_recommended_block.argtypes = [vp, i64, C.c_int]
     L.bf_recommended_block.restype = i64
     L.bf_blocked_pack.argtypes = [i32, i64, i64, vp, i64, vp, C.c_int, vp]
     L.bf_blocked_unpack.argtypes = [i32, i64, i64, vp, i64, vp, C.c_int, vp]
@@ -659,8 +659,8 @@ def bf_blocked_elems(n, d, block):
     return e
 
 
-def bf_recommended_block(n, d, dt):
-    b = lib.bf_recommended_block(n, d, dt)
+def bf_recommended_block(t, d, dt):
+    b = lib.bf_recommended_block(t.handle, d, dt)
     if b < 0:
         raise BfError(int(b), "bf_recommended_block")
     return b

@@ -32,13 +32,14 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
 
   for (int64_t cseq = blockIdx.x; cseq < nchunks; cseq += gridDim.x) {
     const int64_t chunk = p.reverse ? nchunks - 1 - cseq : cseq;   // odd rounds run right to left
-    int64_t col[CW];
+    int64_t col[CW], acol[CW];     // the column, and where it lies within a row of pitch ld
     bool live[CW];
 #pragma unroll
     for (int w = 0; w < CW; ++w) {
       const int64_t c = ((chunk * CW + w) << CHUNK_LOG) + (static_cast<int64_t>(tid) << UC_LOG);
       live[w] = c < d;
       col[w] = min(c, last_vec);
+      acol[w] = col[w] + tile_origin(p, col[w]);
     }
     float prev[CW][UC], cur[CW][UC], nxt[CW][UC], first[CW][UC], last[CW][UC];
 
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
       f32x4 mr[CW][UC / 4];
 #pragma unroll
       for (int w = 0; w < CW; ++w) {
-        const int64_t off = static_cast<int64_t>(row) * ld + col[w];
+        const int64_t off = static_cast<int64_t>(row) * ld + acol[w];
         xr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
         if constexpr (G_ON_LOAD) gr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g + off * EB));
         if constexpr (OP == OP_TRACK) g2r[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
           float gv[UC];
           widen<DT>(gr[w], gv);
           if constexpr (STATE_ON_LOAD) {
-            const int64_t off = static_cast<int64_t>(row) * ld + col[w];
+            const int64_t off = static_cast<int64_t>(row) * ld + acol[w];
 #pragma unroll
             for (int q = 0; q < UC / 4; ++q) {
               float sv[4] = {mr[w][q].x, mr[w][q].y, mr[w][q].z, mr[w][q].w};
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
 #pragma unroll
       for (int w = 0; w < CW; ++w) {
         if (live[w]) {
-          const int64_t off = static_cast<int64_t>(st.row) * ld + col[w];
+          const int64_t off = static_cast<int64_t>(st.row) * ld + acol[w];
           const int64_t rem = d - col[w];
           if constexpr (G_ON_STORE) {
             float gv[UC];

@@ -125,6 +125,7 @@ struct ShiftParams {
   int64_t d, ld, ntiles;
   int32_t n;             // 64, 128, 192 or 256
   int32_t log_c;         // tile width
+  int32_t block_log;     // as in TileParams: 0 agent-major, else column blocks of 1 << block_log (ld = that)
   int32_t reverse;
   int32_t count;         // rounds per pass, 1..8
   int32_t shift[8];      // per round: s in x_i <- w_self x_i + w_peer x_((i+s) mod n)

@@ -980,13 +980,18 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     tp.ent = reinterpret_cast<const u32x2*>(dc->blob + dc->entry_off[kl]);
     tp.reverse = g_tune_noserp ? 0 : ((round / fuse) & 1);
   }
-  // Column-block layout: tiles stay inside a block, and the two kernels that walk whole rows (the
-  // chain kernel, the gather fallback) do not apply.
+  // Column-block layout: tiles stay inside a block (so do the chain kernel's sweeps of one 16-byte
+  // vector per thread), and the gather fallback, which walks whole rows, does not apply.
   const bool blocked = tp.block_log > 0;
-  if (blocked && fuse > 1) return BF_ERR_UNSUPPORTED;
+  const int64_t block_cols = blocked ? int64_t{1} << tp.block_log : INT64_MAX;
   const int cap_log_c = blocked ? std::min(tp.block_log, 10) : 10;
-  if (fuse == 1 && !blocked && dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather &&
-      (g_tune_cw > 0 || static_cast<size_t>(t->n) * 256 * 4 > (di.lds_per_cu ? di.lds_per_cu : 65536) / 2)) {
+  // (On column blocks the pipelined kernel keeps the lead up to 128-column tiles: n = 128 one-peer
+  // rounds on blocks of 8192 measure 6.2 TB/s there against 5.9 for the chain kernel at its best
+  // block width; on agent-major rows the chain kernel wins from 256-column tiles down.)
+  const size_t lds_cu_bytes = di.lds_per_cu ? di.lds_per_cu : 65536;
+  const bool chain_pays = blocked ? 2 * static_cast<size_t>(t->n) * 128 * 4 > lds_cu_bytes
+                                  : static_cast<size_t>(t->n) * 256 * 4 > lds_cu_bytes / 2;
+  if (fuse == 1 && dc->chain_off[k] != SIZE_MAX && !g_tune_nochain && !g_tune_gather && (g_tune_cw > 0 || chain_pays)) {
     // Chain-structured round with too many agents for a 256-column LDS tile (measured: the tile
     // kernels win below that, the row-streaming kernel above): stream rows through registers when
     // the matrix is wide enough to give every CU several 256-thread workgroups.
@@ -998,10 +1003,11 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     // peaks there: 5.55 TB/s vs 5.35 with 16 KB); needs at least one such chunk per CU.
     const int64_t wide_cols = static_cast<int64_t>(1024) * per16 * (dt == BF_F32 ? 4 : 2);
     const int64_t wide_chunks = (tp.d + wide_cols - 1) / wide_cols;
-    const bool wide = g_tune_cw == 0 && !g_tune_chain256 && wide_chunks >= di.cus && op != OP_MOM_ATC && op != OP_ED;
+    const bool wide = g_tune_cw == 0 && !g_tune_chain256 && wide_chunks >= di.cus && op != OP_MOM_ATC && op != OP_ED &&
+                      block_cols >= 1024 * per16;
     const int64_t chunk_cols = wide ? wide_cols : static_cast<int64_t>(256) * per16 * cw;
     const int64_t nchunks = (tp.d + chunk_cols - 1) / chunk_cols;
-    if (nchunks >= 2 * static_cast<int64_t>(di.cus) || g_tune_cw > 0 || wide) {
+    if ((nchunks >= 2 * static_cast<int64_t>(di.cus) || g_tune_cw > 0 || wide) && block_cols >= 256 * per16) {
       if (dry) return BF_OK;
       tp.chain = reinterpret_cast<const bf::ChainStep*>(dc->blob + dc->chain_off[k]);
       int grid = static_cast<int>(std::min<int64_t>(nchunks, static_cast<int64_t>(di.cus) * (wide ? 1 : 8)));
@@ -1046,7 +1052,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   // (the fused kernel needs more than 64 registers, so one workgroup per CU is all that runs)
   const int rows_b = fuse > 1 ? (tp.rows_b > 0 && tp.rows_b < t->n ? tp.rows_b : t->n) : 0;
   rc = g_tune_gather ? BF_ERR_UNSUPPORTED : choose_shape(t->n + rows_b, tp.d, di, &s, fuse > 1 ? 1 : 2,
-                                                                 fuse > 1 ? 8 : cap_log_c);   // fused: 256 columns at most (512 measured slower)
+                                                                 fuse > 1 ? std::min(8, cap_log_c) : cap_log_c);   // fused: 256 columns at most (512 measured slower)
   if (fuse > 1 && rc != BF_OK) return rc;   // fused rounds exist only as the two-tile LDS kernel
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
     // Too many agents for a 64-column LDS tile.
@@ -1114,11 +1120,12 @@ int run_shift_rounds(bf_topology_t* t, int32_t round0, int32_t count, const Tile
   // a 64 KB tile: n x C fp32 with C = 16384 / n (64 columns at n = 256), two workgroups per CU
   int log_c = ilog2(16384 / n);
   if (n == 192) log_c = 6;
+  if (tp.block_log) log_c = std::min(log_c, tp.block_log);
   while (log_c > 6 && ((tp.d + (int64_t{1} << log_c) - 1) >> log_c) < 2 * static_cast<int64_t>(di.cus)) --log_c;
   const size_t lds = static_cast<size_t>(n) * ((size_t{1} << log_c) + 4) * 4;
   if (2 * lds + 256 > (di.lds_per_cu ? di.lds_per_cu : 65536)) return BF_ERR_UNSUPPORTED;
   sp.x_in = tp.x_in; sp.x_out = tp.x_out; sp.d = tp.d; sp.ld = tp.ld;
-  sp.n = n; sp.log_c = log_c; sp.count = count;
+  sp.n = n; sp.log_c = log_c; sp.count = count; sp.block_log = tp.block_log;
   sp.ntiles = (tp.d + (int64_t{1} << log_c) - 1) >> log_c;
   sp.reverse = g_tune_noserp ? 0 : ((round0 / count) & 1);
   int grid = static_cast<int>(std::min<int64_t>(sp.ntiles, static_cast<int64_t>(di.cus) * 2));
@@ -1375,14 +1382,14 @@ int bf_neighbor_allreduce_multi(const bf_topology_t* t, int32_t round0, int32_t 
   if (round0 < 0) return BF_ERR_ROUND;
   if (count < 1 || count > 8) return BF_ERR_SIZE;
   MatArgs ma;
-  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   TileParams tp{};
   tp.x_in = static_cast<const char*>(X_in);
   tp.x_out = static_cast<char*>(X_out);
-  tp.d = d; tp.ld = ld;
+  tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
   tp.fuse = count;
   bf_topology_t* tt = const_cast<bf_topology_t*>(t);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -1415,7 +1422,7 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
   if (local_size < 1 || static_cast<int64_t>(machine_topology->n) * local_size > (1 << 20)) return BF_ERR_SIZE;
   const int32_t n = machine_topology->n * local_size;
   MatArgs ma;
-  int rc = check_matrix_shape(n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
@@ -1437,7 +1444,7 @@ int bf_hierarchical_neighbor_allreduce(const bf_topology_t* machine_topology, in
   TileParams tp{};
   tp.x_in = static_cast<const char*>(X_in);
   tp.x_out = static_cast<char*>(X_out);
-  tp.d = d; tp.ld = ld;
+  tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
   tp.fuse = 3;
   // stage A writes rows 0..M-1 of the second LDS tile and stage B reads only those: the tile needs M rows
   tp.rows_b = mt->n;

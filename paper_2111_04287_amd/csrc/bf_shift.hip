@@ -54,9 +54,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   const int64_t step_bytes = static_cast<int64_t>(rstep) * ld * EB;
   const int nsteps = nunits / THREADS;              // <= MAXPF: the host keeps N * C within 16384 elements
   u32x4 xr[MAXPF];
+  // column blocks: block k of the tile's columns starts (n - 1) B k elements later than rows of pitch B would put it
+  auto block_origin = [&](int64_t c0) {
+    return p.block_log ? ((c0 >> p.block_log) * (N - 1)) << p.block_log : int64_t{0};
+  };
   auto issue_loads = [&](int64_t tile) {
     const int64_t col = min((tile << log_c) + cit0, last_vec);
-    const char* src = p.x_in + (static_cast<int64_t>(row0) * ld + col) * EB;
+    const char* src = p.x_in + (static_cast<int64_t>(row0) * ld + col + block_origin(tile << log_c)) * EB;
 #pragma unroll
     for (int k = 0; k < MAXPF; ++k)
       if (k < nsteps) xr[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + k * step_bytes));
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     {
       const int64_t col = c0 + cit0;
       const int64_t rem = d - col;                   // columns of this thread's units that exist
-      char* dstp = p.x_out + (static_cast<int64_t>(row0) * ld + col) * EB;
+      char* dstp = p.x_out + (static_cast<int64_t>(row0) * ld + col + block_origin(c0)) * EB;
       if (rem >= UC) {
 #pragma unroll
         for (int k = 0; k < MAXPF; ++k) {

@@ -646,16 +646,28 @@ int64_t bf_blocked_elems(int32_t n, int64_t d, int64_t block) {
   return (d + block - 1) / block * block * n;
 }
 
-int64_t bf_recommended_block(int32_t n, int64_t d, bf_dtype_t dt) {
+int64_t bf_recommended_block(const bf_topology_t* t, int64_t d, bf_dtype_t dt) {
+  if (!t) return BF_ERR_NULL;
   if (dt != BF_F32 && dt != BF_BF16) return BF_ERR_KIND;
-  if (n < 1 || d < 0 || d > (int64_t{1} << 40)) return BF_ERR_SIZE;
+  if (d < 0 || d > (int64_t{1} << 40)) return BF_ERR_SIZE;
+  const int64_t n = t->n;
   // Measured on MI355X (block widths 128 .. 2^20; n = 32 bf16 with fp32 momentum, n = 64 and
   // n = 128 fp32): bandwidth peaks where a block of fp32 values is about 4 MB -- 16384 columns at
   // n = 64, 8192 at n = 128; n = 32 is flat between 8192 and 16384 -- and falls off on both sides
   // (narrower: fewer neighbouring tiles share a block row; wider: the rows of a block drift apart
-  // like agent-major rows).  A matrix narrower than that is one block.
+  // like agent-major rows).
   int64_t b = 16384;
   while (b > 2048 && b * n > (int64_t{1} << 20)) b >>= 1;
+  // More agents than give the pipelined kernel 128-column tiles (two n x 128 fp32 tiles in 160 KB
+  // of LDS): rounds that are unions of paths and cycles go to the row-streaming kernel, whose
+  // workgroups sweep 4096 to 16384 columns of a row at a time; it measures best on blocks of 65536
+  // (n = 256 fp32: 5.88 TB/s against 5.55 agent-major and 4.9 on blocks of 4096).
+  if (2 * n * 128 * 4 > 160 * 1024) {
+    bool chains = !t->rounds.empty();
+    for (const auto& r : t->rounds) chains = chains && !r.chain.empty();
+    if (chains) b = 65536;
+  }
+  // a matrix narrower than that is one block
   while (b > 64 && b / 2 >= d) b >>= 1;
   return b;
 }

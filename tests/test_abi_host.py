@@ -350,13 +350,16 @@ def test_column_block_layout_argument_checks():
     assert L.bf_blocked_elems(4, 1000, 32) == bf.BF_ERR_SIZE
     assert L.bf_blocked_elems(4, 1000, 1 << 21) == bf.BF_ERR_SIZE
     assert L.bf_blocked_elems(0, 1000, 64) == bf.BF_ERR_SIZE
-    assert bf.bf_recommended_block(32, 25557032, bf.BF_BF16) == 16384 and bf.bf_recommended_block(64, 1 << 20, bf.BF_F32) == 16384
-    assert bf.bf_recommended_block(128, 1 << 21, bf.BF_F32) == 8192 and bf.bf_recommended_block(256, 1 << 22, bf.BF_F32) == 4096
-    assert bf.bf_recommended_block(5000, 1 << 22, bf.BF_F32) == 2048 and bf.bf_recommended_block(5, 4096, bf.BF_F32) == 4096
-    assert bf.bf_recommended_block(5, 100, bf.BF_F32) == 128 and bf.bf_recommended_block(5, 3, bf.BF_F32) == 64
-    assert bf.bf_recommended_block(5, 0, bf.BF_F32) == 64
-    assert L.bf_recommended_block(0, 100, bf.BF_F32) == bf.BF_ERR_SIZE
-    assert L.bf_recommended_block(4, 100, 9) == bf.BF_ERR_KIND
+    rb = lambda kind, n, d, dt=bf.BF_F32: bf.bf_recommended_block(bf.bf_topology_create(kind, n), d, dt)
+    assert rb(bf.BF_EXP_STATIC, 32, 25557032, bf.BF_BF16) == 16384 and rb(bf.BF_EXP_STATIC, 64, 1 << 20) == 16384
+    assert rb(bf.BF_EXP_STATIC, 128, 1 << 21) == 8192 and rb(bf.BF_EXP_STATIC, 256, 1 << 22) == 4096
+    assert rb(bf.BF_EXP_STATIC, 3000, 1 << 22) == 2048 and rb(bf.BF_EXP_STATIC, 5, 4096) == 4096
+    assert rb(bf.BF_RING, 5, 100) == 128 and rb(bf.BF_RING, 5, 3) == 64 and rb(bf.BF_RING, 5, 0) == 64
+    # rounds that are unions of paths and cycles, more agents than 128-column tiles allow: the row-streaming kernel
+    assert rb(bf.BF_EXP2_ONE_PEER, 256, 1 << 22) == 65536 and rb(bf.BF_RING, 200, 1 << 22) == 65536
+    assert rb(bf.BF_EXP2_ONE_PEER, 128, 1 << 22) == 8192 and rb(bf.BF_EXP2_ONE_PEER, 256, 20000) == 32768
+    assert L.bf_recommended_block(None, 100, bf.BF_F32) == bf.BF_ERR_NULL
+    assert L.bf_recommended_block(h, 100, 9) == bf.BF_ERR_KIND and L.bf_recommended_block(h, -1, bf.BF_F32) == bf.BF_ERR_SIZE
     na = L.bf_neighbor_allreduce
     assert na(h, 0, A, B, 100, -100, bf.BF_F32, None) == bf.BF_ERR_SIZE       # block width not a power of two
     assert na(h, 0, A, B, 100, -32, bf.BF_F32, None) == bf.BF_ERR_SIZE
@@ -365,8 +368,9 @@ def test_column_block_layout_argument_checks():
     assert na(h, 0, A, A + 1024, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS   # 2 blocks x 4 x 64 x 4 = 2048 bytes each
     assert na(h, 0, A, A + 2048, 0, -64, bf.BF_F32, None) == bf.BF_OK
     # calls that take agent-major matrices only
-    assert L.bf_neighbor_allreduce_multi(h, 0, 2, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
-    assert L.bf_hierarchical_neighbor_allreduce(h, 0, 2, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
+    assert L.bf_neighbor_allreduce_multi(h, 0, 2, A, A + 1024, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
+    assert L.bf_hierarchical_neighbor_allreduce(h, 0, 2, A, A + 2048, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS   # 8 rows
+    assert L.bf_neighbor_allreduce_multi(h, 0, 2, A, B, 0, -64, bf.BF_F32, None) == bf.BF_OK
     assert L.bf_dense_mix(h, 0, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
     assert L.bf_win_put(h, 0, None, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
     assert L.bf_consensus_stats(4, 100, -64, A, None, bf.BF_F32, B, None, None) == bf.BF_ERR_UNSUPPORTED

@@ -177,9 +177,6 @@ def test_layout_mismatch_and_agent_major_only_calls_are_refused():
     with pytest.raises(ValueError):
         bf.bf_neighbor_allreduce(t, 0, Xb, to_blocked(X, 128))     # two block widths
     with pytest.raises(bf.BfError) as e:
-        bf.bf_neighbor_allreduce_multi(t, 0, 2, Xb, Xb)
-    assert e.value.code == bf.BF_ERR_UNSUPPORTED
-    with pytest.raises(bf.BfError) as e:
         bf.bf_dense_mix(t, 0, Xb, empty_blocked(n, d, B, torch.float32))
     assert e.value.code == bf.BF_ERR_UNSUPPORTED
 
@@ -201,9 +198,9 @@ def test_config5_full_size_momentum_steps_in_column_blocks():
     separable), which include the ragged tail inside the last block."""
     n, d = 32, workloads.RESNET50_PARAMS
     cfg = workloads.CONFIG5
-    B = bf.bf_recommended_block(n, d, bf.BF_BF16)
-    ld = bf.bf_recommended_ld(d, bf.BF_BF16)
     t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    B = bf.bf_recommended_block(t, d, bf.BF_BF16)
+    ld = bf.bf_recommended_ld(d, bf.BF_BF16)
     W = lib_W(t)
     cols = sample_columns(d, 5)
     assert int(cols[-1]) == d - 1 and d % B == 14376     # the last block is ragged
@@ -235,3 +232,122 @@ def test_config5_full_size_momentum_steps_in_column_blocks():
         assert np.abs(gotm - Mr).max() <= 2e-2 * np.abs(Mr).max(), "momentum, step %d" % k
     pad = Xb.data[-1, :, d - (Xb.data.shape[0] - 1) * B:]
     assert bool((pad == 0).all()) and bool((Mb.data[-1, :, d - (Mb.data.shape[0] - 1) * B:] == 0).all())
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("cw", [1, 2, 4])
+@pytest.mark.parametrize("kind,n", [(bf.BF_RING, 16), (bf.BF_EXP2_ONE_PEER, 100), (bf.BF_EXP2_ONE_PEER, 256)])
+@pytest.mark.parametrize("d,B", [(3 * 1024 + 77, 1024), (2 * 8192 + 4100, 8192), (5000, 2048)])
+def test_row_streaming_kernel_on_column_blocks(dtype, cw, kind, n, d, B):
+    """Rounds whose graph is a union of paths and cycles: the chain kernel's sweeps stay inside a
+    block (blocks narrower than a sweep go to the tile kernels); same bits as agent-major rows."""
+    t = bf.bf_topology_create(kind, n)
+    X, G, G2 = (rows(n, d, 70 + k, dtype=dtype) for k in range(3))
+    S = workloads.normal_rows(n, d, 79, DEV, ld=X.stride(0))
+    w0 = torch.rand(n, device=DEV) + 0.5
+    Xb, Gb, G2b = (to_blocked(A, B) for A in (X, G, G2))
+
+    def fresh(A):
+        return torch.empty((n, A.stride(0)), dtype=A.dtype, device=DEV)[:, :d].copy_(A)
+
+    bf.bf_set_tuning(6, cw)
+    try:
+        for rnd in (0, 3):
+            for in_place in (False, True):
+                # plain mix
+                xi = fresh(X); xo = xi if in_place else fresh(X)
+                bi = to_blocked(X, B); bo = bi if in_place else empty_blocked(n, d, B, dtype)
+                bf.bf_neighbor_allreduce(t, rnd, xi, xo)
+                bf.bf_neighbor_allreduce(t, rnd, bi, bo)
+                assert torch.equal(from_blocked(bo, X), xo)
+                ref = O.mix(host(X), lib_W(t, rnd))
+                assert np.abs(host(xo) - ref).max() <= (TOL32 if dtype == torch.float32 else 2.0 ** -8) * np.abs(ref).max()
+                # momentum ATC and AWC, Exact-Diffusion (fp32 state updated in place)
+                for call in (lambda a, b, g, s: bf.bf_atc_step(t, rnd, a, b, g, s, alpha=0.05, beta=0.9, mode=bf.BF_ATC),
+                             lambda a, b, g, s: bf.bf_atc_step(t, rnd, a, b, g, s, alpha=0.05, beta=0.9, mode=bf.BF_AWC),
+                             lambda a, b, g, s: bf.bf_exact_diffusion_step(t, rnd, a, b, g, s, 0.05)):
+                    xi = fresh(X); xo = xi if in_place else fresh(X); st = fresh(S)
+                    bi = to_blocked(X, B); bo = bi if in_place else empty_blocked(n, d, B, dtype); bs = to_blocked(S, B)
+                    call(xi, xo, G, st)
+                    call(bi, bo, Gb, bs)
+                    assert torch.equal(from_blocked(bo, X), xo) and torch.equal(from_blocked(bs, S), st)
+                # tracking, push-sum with the ratio
+                xi = fresh(X); xo = xi if in_place else fresh(X)
+                bi = to_blocked(X, B); bo = bi if in_place else empty_blocked(n, d, B, dtype)
+                bf.bf_tracking_step(t, rnd, xi, xo, G, G2)
+                bf.bf_tracking_step(t, rnd, bi, bo, Gb, G2b)
+                assert torch.equal(from_blocked(bo, X), xo)
+                xi = fresh(X); xo = xi if in_place else fresh(X); y = fresh(X)
+                bi = to_blocked(X, B); bo = bi if in_place else empty_blocked(n, d, B, dtype); by = empty_blocked(n, d, B, dtype)
+                w1, w2 = torch.empty_like(w0), torch.empty_like(w0)
+                bf.bf_pushsum_step(t, rnd, xi, xo, w0, w1, y)
+                bf.bf_pushsum_step(t, rnd, bi, bo, w0, w2, by)
+                assert torch.equal(from_blocked(bo, X), xo) and torch.equal(from_blocked(by, X), y) and torch.equal(w1, w2)
+    finally:
+        bf.bf_set_tuning(6, 0)
+
+
+def _shift_topology(n, shifts, weights):
+    rp, cols, wg = [], [], []
+    for s, (ws, wp) in zip(shifts, weights):
+        base = len(cols)
+        for i in range(n):
+            rp.append(len(cols))
+            for j, w in sorted(((i, ws), ((i + s) % n, wp))):
+                cols.append(j); wg.append(w)
+        rp.append(len(cols))
+    return bf.bf_topology_create(bf.BF_CSR_USER, n, rounds=len(shifts), rowptr=rp, col=cols, wgt=wg)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("case", ["onepeer64", "onepeer256", "shift128", "exp100", "push300", "ring700"])
+@pytest.mark.parametrize("B", [64, 256, 8192])
+def test_fused_rounds_on_column_blocks(dtype, case, B):
+    """Several rounds per pass: in registers (uniform shift rounds), LDS tile to LDS tile, and as
+    separate passes when two tiles do not fit; each gives the agent-major bits."""
+    if case == "onepeer64":
+        t, n = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, 64), 64
+    elif case == "onepeer256":
+        t, n = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, 256), 256
+    elif case == "shift128":
+        t, n = _shift_topology(128, [3, 64, 100 - 36, 127 - 64 - 1], [(0.5, 0.5), (0.25, 0.75), (0.7, 0.3), (0.5, 0.5)]), 128
+    elif case == "exp100":
+        t, n = bf.bf_topology_create(bf.BF_EXP_STATIC, 100), 100
+    elif case == "push300":
+        t, n = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, 300, out_degree=5, seed=3), 300
+    else:
+        t, n = bf.bf_topology_create(bf.BF_RING, 700), 700
+    d = 2 * B + 100 if B <= 256 else B + 1000
+    X = rows(n, d, 90, dtype=dtype)
+    for round0, count in ((0, 2), (1, 5), (3, 8)):
+        for in_place in (False, True):
+            xi = torch.empty((n, X.stride(0)), dtype=dtype, device=DEV)[:, :d].copy_(X)
+            xo = xi if in_place else torch.empty((n, X.stride(0)), dtype=dtype, device=DEV)[:, :d]
+            bi = to_blocked(X, B)
+            bo = bi if in_place else empty_blocked(n, d, B, dtype)
+            bf.bf_neighbor_allreduce_multi(t, round0, count, xi, xo)
+            bf.bf_neighbor_allreduce_multi(t, round0, count, bi, bo)
+            assert torch.equal(from_blocked(bo, X), xo), (case, B, round0, count, in_place)
+    ref = host(X)
+    for r in range(3, 11):
+        ref = O.mix(ref, lib_W(t, r))
+    tol = TOL32 if dtype == torch.float32 else 8 * 2.0 ** -8
+    assert np.abs(host(xo) - ref).max() <= tol * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,L,d,B", [(4, 4, 1000, 256), (8, 8, 8192 + 136, 8192), (5, 3, 130, 64), (40, 20, 300, 128)])
+def test_hierarchical_averaging_on_column_blocks(dtype, M, L, d, B):
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, M)
+    n = M * L
+    X = rows(n, d, 95, dtype=dtype)
+    xo = torch.empty((n, X.stride(0)), dtype=dtype, device=DEV)[:, :d]
+    bo = empty_blocked(n, d, B, dtype)
+    bf.bf_hierarchical_neighbor_allreduce(t, 1, L, X, xo)
+    bf.bf_hierarchical_neighbor_allreduce(t, 1, L, to_blocked(X, B), bo)
+    assert torch.equal(from_blocked(bo, X), xo)
+    ref = O.hierarchical_neighbor_allreduce(host(X), lib_W(t, 1), L)
+    assert np.abs(host(xo) - ref).max() <= (TOL32 if dtype == torch.float32 else 2.0 ** -7) * np.abs(ref).max()
+    bi = to_blocked(X, B)
+    bf.bf_hierarchical_neighbor_allreduce(t, 1, L, bi, bi)
+    assert torch.equal(from_blocked(bi, X), xo)
