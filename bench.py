@@ -386,7 +386,14 @@ def main():
             "ms_per_step": round(w_ * 1e3 / 30, 4), "effective_GBps": round(2 * nh * Lh * dh * 4 * 30 / w_ / 1e9, 1),
             "pct_of_hbm_peak": round(100 * 2 * nh * Lh * dh * 4 * 30 / w_ / 1e9 / HBM_PEAK_GBPS, 2),
             "note": "local average, machine-level round, copy back: three fused rounds, one pass over X"}
-        del Xh2
+        Bh = 16384
+        Xhb = blocked(nh * Lh, dh, Bh, torch.float32, Xh2)
+        w_, e_ = timed(lambda k: bf.bf_hierarchical_neighbor_allreduce(th, k, Lh, Xhb, Xhb), 30, 5)
+        nxt["hierarchical_8_machines_x_8_agents_d4194304_column_blocks"] = {
+            "ms_per_step": round(w_ * 1e3 / 30, 4), "effective_GBps": round(2 * nh * Lh * dh * 4 * 30 / w_ / 1e9, 1),
+            "pct_of_hbm_peak": round(100 * 2 * nh * Lh * dh * 4 * 30 / w_ / 1e9 / HBM_PEAK_GBPS, 2), "block": Bh,
+            "note": "the same pass with X in column blocks of %d" % Bh}
+        del Xh2, Xhb
         Ew = bf.bf_topology_window_slots(t4, 0)
         Xw = workloads.config4_state(dev, n=n4, d=d4, ld=ld4)
         Ww = workloads.alloc_rows(Ew, d4, torch.float32, dev, ld=ld4, fill=0)

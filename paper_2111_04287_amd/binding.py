@@ -389,6 +389,8 @@ def _win_args(t, rnd, active, X, Win, p, win_p):
     ptr, n, d, ld = _mat(X, "X")
     _rows(t, n)
     E = bf_topology_window_slots(t, rnd)
+    if isinstance(X, Blocked) != isinstance(Win, Blocked):
+        raise ValueError("Win must have the layout of X")
     if Win.dim() != 2 or Win.shape != (E, d) or Win.dtype != torch.float32 or (E > 1 and Win.stride(0) != ld) or \
             (d > 1 and Win.stride(1) != 1):
         raise ValueError("Win must be a float32 (slots, d) matrix with the row stride (in elements) of X")

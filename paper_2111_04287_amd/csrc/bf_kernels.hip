@@ -67,6 +67,8 @@ struct WinParams {
   const int32_t* call_edge_on;  // E flags: the subset of edges this call names; null: all
   int64_t d, ld;
   int32_t n, chunks;
+  int32_t block_log;         // 0: agent-major rows; else X (n rows) and the window (E rows) in column blocks of 1 << block_log
+  int32_t slots;             // E
 };
 
 enum { WIN_PUT = 0, WIN_ACCUMULATE = 1, WIN_COLLECT = 2, WIN_AVERAGE = 3, WIN_GET = 4 };
@@ -77,36 +79,42 @@ __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
   const int tid = threadIdx.x;
   const int64_t units = static_cast<int64_t>(p.n) * p.chunks;
   for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
+    // consecutive workgroups walk along an agent's row in either layout (measured on column blocks:
+    // walking down the agents of a chunk instead is 5 % slower)
     const int a = static_cast<int>(unit / p.chunks);
     const int c = static_cast<int>(unit - static_cast<int64_t>(a) * p.chunks);
     if (p.active && p.active[a] == 0) continue;
     int64_t col[U];
+    int64_t xcol[U], wcol[U];      // where the column lies within a row of pitch ld, in X and in the window
     int valid[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       col[u] = (static_cast<int64_t>(c) * U + u) * 1024 + tid * 4;
       const int64_t rem = p.d - col[u];
       valid[u] = rem >= 4 ? 4 : (rem > 0 ? static_cast<int>(rem) : 0);
+      const int64_t blk = p.block_log ? col[u] >> p.block_log : 0;
+      xcol[u] = col[u] + ((blk * (p.n - 1)) << p.block_log);
+      wcol[u] = col[u] + ((blk * (p.slots - 1)) << p.block_log);
     }
     // four columns of a row of X (storage type DT) or of the window (fp32); a vector that starts
     // inside the row may end in the row's padding: rows are 16-byte multiples
     auto load_x = [&](int64_t row, int u) -> f32x4 {
       if (!valid[u]) return f32x4{0.f, 0.f, 0.f, 0.f};
       float v[4];
-      load_in<DT, 4>(p.x, row * p.ld + col[u], v);
+      load_in<DT, 4>(p.x, row * p.ld + xcol[u], v);
       return f32x4{v[0], v[1], v[2], v[3]};
     };
     auto store_x = [&](int64_t row, int u, f32x4 v) {
       const float e[4] = {v.x, v.y, v.z, v.w};
-      if (valid[u]) store_out<DT, 4, false>(p.x, row * p.ld + col[u], e, valid[u]);      // never the padding
+      if (valid[u]) store_out<DT, 4, false>(p.x, row * p.ld + xcol[u], e, valid[u]);      // never the padding
     };
     auto load_w = [&](const float* row, int u) -> f32x4 {
-      return valid[u] ? *reinterpret_cast<const f32x4*>(row + col[u]) : f32x4{0.f, 0.f, 0.f, 0.f};
+      return valid[u] ? *reinterpret_cast<const f32x4*>(row + wcol[u]) : f32x4{0.f, 0.f, 0.f, 0.f};
     };
     auto store_w = [&](float* row, int u, f32x4 v) {
-      if (valid[u] == 4) { *reinterpret_cast<f32x4*>(row + col[u]) = v; return; }
+      if (valid[u] == 4) { *reinterpret_cast<f32x4*>(row + wcol[u]) = v; return; }
       const float e[4] = {v.x, v.y, v.z, v.w};
-      for (int k = 0; k < valid[u]; ++k) row[col[u] + k] = e[k];
+      for (int k = 0; k < valid[u]; ++k) row[wcol[u] + k] = e[k];
     };
     auto edge_on = [&](int e) { return !p.call_edge_on || p.call_edge_on[e] != 0; };
     if constexpr (MODE == WIN_GET) {
@@ -1193,7 +1201,7 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
   // a topology without edges has no slots: Win and win_p may then be NULL
   if (E > 0 && (!Win || (pv == nullptr) != (win_p == nullptr))) return BF_ERR_NULL;
   MatArgs ma;
-  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(X) || misaligned16(Win)) return BF_ERR_ALIGN;
   if ((active && (reinterpret_cast<uintptr_t>(active) & 3u)) || (pv && (reinterpret_cast<uintptr_t>(pv) & 3u)) ||
@@ -1201,7 +1209,9 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
       (reinterpret_cast<uintptr_t>(call_edge_w) & 3u) || (reinterpret_cast<uintptr_t>(call_edge_on) & 3u))
     return BF_ERR_ALIGN;
   // the window is fp32 whatever the storage type of X (slots accumulate), with X's pitch in elements
-  const size_t win_bytes = E > 0 ? static_cast<size_t>(E - 1) * ld * 4 + ((static_cast<size_t>(d) * 4 + 15) & ~size_t{15}) : 0;
+  MatArgs mw = ma;
+  mw.n = static_cast<int>(E);
+  const size_t win_bytes = E > 0 ? mw.extent(4) : 0;
   if (E > 0 && overlaps(X, ma.bytes, Win, win_bytes)) return BF_ERR_ALIAS;
   if (pv && E > 0 && (overlaps(pv, static_cast<size_t>(t->n) * 4, X, ma.bytes) || overlaps(pv, static_cast<size_t>(t->n) * 4, Win, win_bytes) ||
              overlaps(win_p, static_cast<size_t>(E) * 4, X, ma.bytes) || overlaps(win_p, static_cast<size_t>(E) * 4, Win, win_bytes) ||
@@ -1220,7 +1230,7 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
   wp.win = static_cast<float*>(Win);
   wp.active = active;
   wp.call_self_w = call_self_w; wp.call_edge_w = call_edge_w; wp.call_edge_on = call_edge_on;
-  wp.d = d; wp.ld = ld; wp.n = t->n;
+  wp.d = d; wp.ld = ma.ld; wp.n = t->n; wp.block_log = ma.block_log; wp.slots = static_cast<int32_t>(E);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (pv && (mode == WIN_ACCUMULATE || mode == WIN_COLLECT)) {
     if (mode == WIN_ACCUMULATE) hipLaunchKernelGGL(bf_win_p_kernel<WIN_ACCUMULATE>, dim3(1), dim3(1024), 0, st, wp, pv, win_p);

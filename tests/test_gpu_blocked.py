@@ -351,3 +351,37 @@ def test_hierarchical_averaging_on_column_blocks(dtype, M, L, d, B):
     bi = to_blocked(X, B)
     bf.bf_hierarchical_neighbor_allreduce(t, 1, L, bi, bi)
     assert torch.equal(from_blocked(bi, X), xo)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,d,B", [(12, 4096 + 136, 1024), (33, 130 + 3, 64), (16, 2 * 8192 + 5000, 8192)])
+def test_window_calls_on_column_blocks(dtype, n, d, B):
+    """One asynchronous push-sum round (accumulate, update_then_collect), put / get / update and a
+    weighted call: X and the window in column blocks give the agent-major bits."""
+    t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=3, seed=5)
+    E = bf.bf_topology_window_slots(t, 0)
+    X = rows(n, d, 110, dtype=dtype)
+    W0 = workloads.normal_rows(E, d, 111, DEV, ld=X.stride(0))
+    active = torch.tensor([1 if (i * 7) % 5 else 0 for i in range(n)], dtype=torch.int32, device=DEV)
+    self_w = torch.rand(n, device=DEV)
+    edge_w = torch.rand(E, device=DEV)
+
+    def run(call):
+        x = torch.empty((n, X.stride(0)), dtype=dtype, device=DEV)[:, :d].copy_(X)
+        w = torch.empty((E, X.stride(0)), device=DEV)[:, :d].copy_(W0)
+        p, wp = torch.ones(n, device=DEV), torch.full((E,), 0.25, device=DEV)
+        xb, wb = to_blocked(X, B), to_blocked(W0, B)
+        pb, wpb = torch.ones(n, device=DEV), torch.full((E,), 0.25, device=DEV)
+        call(x, w, p, wp)
+        call(xb, wb, pb, wpb)
+        assert torch.equal(from_blocked(xb, X), x) and torch.equal(from_blocked(wb, W0), w)
+        assert torch.equal(p, pb) and torch.equal(wp, wpb)
+
+    for act in (None, active):
+        run(lambda x, w, p, wp: bf.bf_win_put(t, 0, x, w, active=act))
+        run(lambda x, w, p, wp: bf.bf_win_get(t, 0, x, w, active=act))
+        run(lambda x, w, p, wp: bf.bf_win_update(t, 0, x, w, active=act))
+        run(lambda x, w, p, wp: (bf.bf_win_accumulate(t, 0, x, p, w, wp, active=act),
+                                 bf.bf_win_update_then_collect(t, 0, x, p, w, wp, active=act)))
+        run(lambda x, w, p, wp: bf.bf_win_accumulate_weighted(t, 0, x, p, w, wp, self_weight=self_w, dst_weight=edge_w, active=act))
+        run(lambda x, w, p, wp: bf.bf_win_update_weighted(t, 0, x, w, self_weight=self_w, src_weight=edge_w, active=act))
