@@ -364,11 +364,11 @@ def main():
             compute_bound = nd >= 128
             dn["dense_w_n%d_d1048576_f32" % nd] = {
                 "ms_per_step": round(w_ * 1e3 / 40, 5), "TFLOPs": round(tf, 2), "effective_GBps": round(gb, 1),
-                "roofline": ({"bound": "mfma", "kernel": "bf_dense_kernel2 (v_mfma_f32_32x32x2_f32)", "achieved": round(tf, 2),
+                "roofline": ({"bound": "mfma", "kernel": "bf_dense_kernel (v_mfma_f32_32x32x2_f32)", "achieved": round(tf, 2),
                               "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_F32_PEAK_TFLOPS, 4),
                               "traffic": None, "launch_ms": round(e_, 5), "flops_per_launch": flops}
                              if compute_bound else
-                             {"bound": "hbm", "kernel": "bf_dense_kernel2 (v_mfma_f32_32x32x2_f32)", "achieved": round(gb, 1),
+                             {"bound": "hbm", "kernel": "bf_dense_kernel (v_mfma_f32_32x32x2_f32)", "achieved": round(gb, 1),
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(gb / HBM_PEAK_GBPS, 4), "traffic": None,
                               "launch_ms": round(e_, 5), "algorithmic_bytes_per_launch": 2 * nd * dd * 4,
                               "note": "n/4 = 16 flop per byte: below the fp32 matrix-core ridge (about 20), HBM bound"})}

@@ -271,6 +271,7 @@ class Blocked:
         self.data, self.d = data, d
         self.shape = (n, d)
         self.dtype = data.dtype
+        self.device = data.device
 
     def dim(self):
         return 2

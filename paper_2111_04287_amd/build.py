@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libbf.so")
 
-HIP_SOURCES = ["bf_tile_f32.hip", "bf_tile_bf16.hip", "bf_pipe_f32.hip", "bf_pipe_bf16.hip", "bf_chain.hip", "bf_shift.hip", "bf_kernels.hip"]
+HIP_SOURCES = ["bf_tile_f32.hip", "bf_tile_bf16.hip", "bf_pipe_f32.hip", "bf_pipe_bf16.hip", "bf_chain.hip", "bf_shift.hip", "bf_dense.hip", "bf_kernels.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 # packed fp32 instructions are kept off for every HIP translation unit
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -223,6 +223,8 @@ int launch_gather_bf16(int op, bool with_y, const TileParams& tp, int grid, hipS
 int launch_narrow_f32(int op, bool with_y, const TileParams& tp, size_t lds, int grid, hipStream_t st);
 int launch_narrow_bf16(int op, bool with_y, const TileParams& tp, size_t lds, int grid, hipStream_t st);
 // M <- beta M + G for the gather fallback's momentum ops; G has storage type dt (BF_F32 / BF_BF16).
+int launch_dense(int rb, const float* xi, float* xo, const float* wt, int n, int64_t d, int64_t ld, int block_log,
+                 int cus, size_t lds_cu, hipStream_t st);
 int launch_shift_rounds(int dt, const ShiftParams& p, int grid, size_t lds, hipStream_t st);
 int launch_momentum(int dt, float* M, const char* G, int n, int64_t d, int64_t ld, float beta, int grid, hipStream_t st);
 

@@ -230,104 +230,6 @@ __global__ __launch_bounds__(1024) void bf_win_p_kernel(const WinParams p, float
 }
 
 // ---------------------------------------------------------------------------------------------
-// Dense W on the fp32 matrix cores: X_out tile (n_pad x 128) = W (n_pad x n_pad) * X tile.
-// v_mfma_f32_32x32x2_f32 operand layout (wave64): A lane l holds A[l%32][l/32], B lane l holds
-// B[l/32][l%32], D register v of lane l holds D[8*(v/4) + 4*(l/32) + v%4][l%32].
-// wt is W transposed and zero padded (wt[k*n_pad + i] = w_ik) so A operands load coalesced.
-// 128-column tiles, one wave per 32-column block for ALL row blocks, so the four waves of a
-// workgroup are busy for any n.  For n_pad <= 64 the wave keeps its A operands (the
-// whole of W, 16 KB) in registers for the lifetime of the persistent workgroup; for larger n they
-// are read from L1/L2 (W^T is laid out so that the 64 lanes read two 128-byte segments).  Results
-// go back through the LDS tile so that global stores are 16 bytes per lane.
-template <int RB, bool WREG>
-__global__ __launch_bounds__(256) void bf_dense_kernel2(const float* x_in, float* x_out, const float* wt,
-                                                       int n, int64_t d, int64_t ld, int64_t ntiles) {
-  constexpr int NP = RB * 32;          // n padded to the MFMA row-block size
-  constexpr int P = 132;               // LDS row pitch in floats (16-byte multiple, breaks bank aliasing)
-  extern __shared__ f32x4 lds_raw[];
-  float* lds = reinterpret_cast<float*>(lds_raw);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, lh = lane >> 5;
-  const int64_t last_vec = ((d - 1) >> 2) << 2;
-
-  float areg[WREG ? RB * (NP / 2) : 1];
-  if constexpr (WREG) {
-#pragma unroll
-    for (int k2 = 0; k2 < NP / 2; ++k2)
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) areg[k2 * RB + rb] = wt[static_cast<size_t>(2 * k2 + lh) * NP + rb * 32 + l32];
-  }
-  // padding rows stay zero for the whole kernel
-  for (int u = tid; u < (NP - n) * 32; u += 256) {
-    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-    *reinterpret_cast<f32x4*>(lds + (n + (u >> 5)) * P + (u & 31) * 4) = z;
-  }
-  const int nunits = n * 32;
-  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const int64_t c0 = tile * 128;
-    for (int u0 = tid; u0 < nunits; u0 += 4 * 256) {
-      f32x4 v[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int u = min(u0 + k * 256, nunits - 1);
-        const int64_t col = min(c0 + (u & 31) * 4, last_vec);
-        v[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x_in + static_cast<int64_t>(u >> 5) * ld + col));
-      }
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int u = u0 + k * 256;
-        if (u < nunits) *reinterpret_cast<f32x4*>(lds + (u >> 5) * P + (u & 31) * 4) = v[k];
-      }
-    }
-    __syncthreads();
-    f32x16 acc[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) acc[rb] = f32x16{0};
-    const float* bcol = lds + wave * 32 + l32;
-    if constexpr (WREG) {
-#pragma unroll
-      for (int k2 = 0; k2 < NP / 2; ++k2) {
-        const float b = bcol[(2 * k2 + lh) * P];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(areg[k2 * RB + rb], b, acc[rb], 0, 0, 0);
-      }
-    } else {
-      const float* wa = wt + static_cast<size_t>(lh) * NP + l32;
-#pragma unroll 4
-      for (int k2 = 0; k2 < NP / 2; ++k2) {
-        const float b = bcol[(2 * k2 + lh) * P];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[static_cast<size_t>(2 * k2) * NP + rb * 32], b, acc[rb], 0, 0, 0);
-      }
-    }
-    __syncthreads();                               // every wave is done reading the input tile
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = rb * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
-        // the padding rows must stay zero: 0 * x is NaN for a non-finite x, and a NaN there would
-        // spread to every row of the tiles that follow
-        if (row < n) lds[row * P + wave * 32 + l32] = acc[rb][v];
-      }
-    __syncthreads();
-    for (int u = tid; u < nunits; u += 256) {
-      const int row = u >> 5;
-      const int64_t col = c0 + (u & 31) * 4;
-      if (col < d) {
-        const f32x4 o = *reinterpret_cast<const f32x4*>(lds + row * P + (u & 31) * 4);
-        float* dst = x_out + static_cast<int64_t>(row) * ld + col;
-        if (col + 4 <= d) __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
-        else { const float ov[4] = {o.x, o.y, o.z, o.w}; for (int e = 0; e < 4; ++e) if (col + e < d) dst[e] = ov[e]; }
-      }
-    }
-    __syncthreads();                               // before the next tile overwrites LDS
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Least-squares gradient g_i = A_i^T (A_i x_i - b_i) (eq. dgd-1).  One workgroup per agent.
 // Phase 1: one wave per row of A_i forms the residual (fp32 products, per-lane partial sums, wave
 // tree).  Phase 2: each thread owns 4 columns and accumulates A_i^T r over the m rows.
@@ -1377,7 +1279,7 @@ int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_i
   if (rc != BF_OK) return rc;
   if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
-  if (t->kind == BF_DENSE_USER && dt == BF_F32 && t->n <= 256 && !ma.block_log)
+  if (t->kind == BF_DENSE_USER && dt == BF_F32 && t->n <= 256)
     return bf_dense_mix(t, round, X_in, X_out, d, ld, dt, hip_stream);
   TileParams tp{};
   tp.x_in = static_cast<const char*>(X_in);
@@ -1532,62 +1434,35 @@ int bf_dense_mix(const bf_topology_t* t, int32_t round, const void* X_in, void* 
   if (!t || !X_in || !X_out) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   MatArgs ma;
-  int rc = check_matrix_shape(t->n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(X_in) || misaligned16(X_out)) return BF_ERR_ALIGN;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   if (d == 0) return BF_OK;
-  if (dt != BF_F32 || t->n > 256) {
-    // no matrix-core kernel for this storage type or this many agents: the list kernels compute the
-    // same product (a dense W is a CSR with full rows)
-    TileParams tp{};
-    tp.x_in = static_cast<const char*>(X_in);
-    tp.x_out = static_cast<char*>(X_out);
-    tp.d = d; tp.ld = ld;
-    return run_tile(const_cast<bf_topology_t*>(t), round, OP_MIX, false, tp, dt, static_cast<hipStream_t>(hip_stream));
-  }
-  bf::DeviceCopy* dc = nullptr;
-  rc = get_device_copy(const_cast<bf_topology_t*>(t), true, &dc);
-  if (rc != BF_OK) return rc;
-  DeviceInfo di;
-  rc = device_info(dc->device, &di);
-  if (rc != BF_OK) return rc;
-  const int n_pad = dc->n_pad;
-  const size_t k = static_cast<size_t>(round) % t->rounds.size();
-  const float* wt = dc->dense_t + k * static_cast<size_t>(n_pad) * n_pad;
-  const size_t lds = static_cast<size_t>(n_pad) * 132 * 4;
-  const int64_t ntiles = (d + 127) / 128;
-  const int per_cu = std::max<int>(1, static_cast<int>(std::min<size_t>(8, (di.lds_per_cu ? di.lds_per_cu : 65536) / lds)));
-  const int grid = static_cast<int>(std::min<int64_t>(ntiles, static_cast<int64_t>(di.cus) * per_cu));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const float* xi = static_cast<const float*>(X_in);
-  float* xo = static_cast<float*>(X_out);
-#define BF_DENSE(RBV, WR)                                                                                   \
-  do {                                                                                                      \
-    auto kern = bf_dense_kernel2<RBV, WR>;                                                                  \
-    if (lds > 48 * 1024) {                                                                                  \
-      static thread_local size_t raised = 0;                                                                \
-      if (raised < lds) {                                                                                   \
-        BF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                 \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
-        raised = lds;                                                                                       \
-      }                                                                                                     \
-    }                                                                                                       \
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, xi, xo, wt, t->n, d, ld, ntiles);              \
-  } while (0)
-  switch (n_pad / 32) {
-    case 1: BF_DENSE(1, true); break;
-    case 2: BF_DENSE(2, true); break;
-    case 3: BF_DENSE(3, false); break;
-    case 4: BF_DENSE(4, false); break;
-    case 5: BF_DENSE(5, false); break;
-    case 6: BF_DENSE(6, false); break;
-    case 7: BF_DENSE(7, false); break;
-    default: BF_DENSE(8, false); break;
+  if (dt == BF_F32 && t->n <= 256) {
+    bf::DeviceCopy* dc = nullptr;
+    rc = get_device_copy(const_cast<bf_topology_t*>(t), true, &dc);
+    if (rc != BF_OK) return rc;
+    DeviceInfo di;
+    rc = device_info(dc->device, &di);
+    if (rc != BF_OK) return rc;
+    const int n_pad = dc->n_pad;
+    const size_t k = static_cast<size_t>(round) % t->rounds.size();
+    const float* wt = dc->dense_t + k * static_cast<size_t>(n_pad) * n_pad;
+    const size_t lds_cu = std::min(di.lds_per_cu ? di.lds_per_cu : size_t{65536},
+                                   di.lds_per_block_optin ? di.lds_per_block_optin : size_t{65536});
+    rc = launch_dense(n_pad / 32, static_cast<const float*>(X_in), static_cast<float*>(X_out), wt, t->n, d, ma.ld,
+                      ma.block_log, di.cus, lds_cu, st);
+    if (rc != BF_ERR_UNSUPPORTED) return rc;
   }
-#undef BF_DENSE
-  BF_HIP_TRY(hipGetLastError());
-  return BF_OK;
+  // no matrix-core kernel for this storage type, this many agents, this little LDS or blocks this
+  // narrow: the list kernels compute the same product (a dense W is a CSR with full rows)
+  TileParams tp{};
+  tp.x_in = static_cast<const char*>(X_in);
+  tp.x_out = static_cast<char*>(X_out);
+  tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
+  return run_tile(const_cast<bf_topology_t*>(t), round, OP_MIX, false, tp, dt, st);
 }
 
 // Shared body of the push-sum entry points: optional local update x - alpha g before the mix.

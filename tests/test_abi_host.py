@@ -371,7 +371,7 @@ def test_column_block_layout_argument_checks():
     assert L.bf_neighbor_allreduce_multi(h, 0, 2, A, A + 1024, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     assert L.bf_hierarchical_neighbor_allreduce(h, 0, 2, A, A + 2048, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS   # 8 rows
     assert L.bf_neighbor_allreduce_multi(h, 0, 2, A, B, 0, -64, bf.BF_F32, None) == bf.BF_OK
-    assert L.bf_dense_mix(h, 0, A, B, 100, -64, bf.BF_F32, None) == bf.BF_ERR_UNSUPPORTED
+    assert L.bf_dense_mix(h, 0, A, A + 1024, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     assert L.bf_win_put(h, 0, None, A, A + 1024, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     assert L.bf_dgd_least_squares_run(h, 0, 5, 32, A, B, 0x40000000, 0x70000000, 1e-3, 1024, -1024, None) == bf.BF_ERR_SIZE
     assert L.bf_consensus_stats(4, 100, -64, A, None, bf.BF_F32, B, None, None) == bf.BF_ERR_UNSUPPORTED

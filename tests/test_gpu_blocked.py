@@ -177,7 +177,7 @@ def test_layout_mismatch_and_agent_major_only_calls_are_refused():
     with pytest.raises(ValueError):
         bf.bf_neighbor_allreduce(t, 0, Xb, to_blocked(X, 128))     # two block widths
     with pytest.raises(bf.BfError) as e:
-        bf.bf_dense_mix(t, 0, Xb, empty_blocked(n, d, B, torch.float32))
+        bf.bf_consensus_stats(Xb)
     assert e.value.code == bf.BF_ERR_UNSUPPORTED
 
 
@@ -385,3 +385,26 @@ def test_window_calls_on_column_blocks(dtype, n, d, B):
                                  bf.bf_win_update_then_collect(t, 0, x, p, w, wp, active=act)))
         run(lambda x, w, p, wp: bf.bf_win_accumulate_weighted(t, 0, x, p, w, wp, self_weight=self_w, dst_weight=edge_w, active=act))
         run(lambda x, w, p, wp: bf.bf_win_update_weighted(t, 0, x, w, self_weight=self_w, src_weight=edge_w, active=act))
+
+
+@pytest.mark.parametrize("n,d,B", [(5, 300, 64), (64, 3 * 256 + 10, 256), (100, 1000, 128), (256, 2 * 1024 + 72, 1024), (200, 500, 64)])
+def test_dense_mix_on_column_blocks(n, d, B):
+    """Dense W on the matrix cores with the matrices in column blocks (blocks narrower than the
+    kernel's tile go to the list kernels): the agent-major bits or, from the list kernels, the
+    oracle's values."""
+    rng = np.random.default_rng(n)
+    D = rng.random((n, n)).astype(np.float32)
+    D /= D.sum(axis=1, keepdims=True)
+    t = bf.bf_topology_create(bf.BF_DENSE_USER, n, dense_w=D)
+    X = rows(n, d, 120)
+    out = torch.empty((n, X.stride(0)), device=DEV)[:, :d]
+    bf.bf_dense_mix(t, 0, X, out)
+    ob = empty_blocked(n, d, B, torch.float32)
+    bf.bf_dense_mix(t, 0, to_blocked(X, B), ob)
+    ref = O.mix(host(X), lib_W(t))
+    got = from_blocked(ob, X)
+    assert np.abs(host(got) - ref).max() <= TOL32 * np.abs(ref).max()
+    assert np.abs(host(out) - ref).max() <= TOL32 * np.abs(ref).max()
+    xb = to_blocked(X, B)
+    bf.bf_dense_mix(t, 0, xb, xb)                                  # in place
+    assert torch.equal(from_blocked(xb, X), got)
