@@ -172,16 +172,16 @@ __device__ __forceinline__ void store_out(char* base, int64_t off, const float* 
 }
 
 // Load LW consecutive values of dtype DT (all below ld, so in bounds) and widen.
-template <int DT, int LW>
+template <int DT, int LW, bool NT = false>
 __device__ __forceinline__ void load_in(const char* base, int64_t off, float* v) {
   if constexpr (DT == DT_F32) {
     const float* ptr = reinterpret_cast<const float*>(base) + off;
-    if constexpr (LW == 4) { f32x4 t = *reinterpret_cast<const f32x4*>(ptr); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
+    if constexpr (LW == 4) { f32x4 t = ld_stream<NT>(reinterpret_cast<const f32x4*>(ptr)); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
     else if constexpr (LW == 2) { f32x2 t = *reinterpret_cast<const f32x2*>(ptr); v[0] = t.x; v[1] = t.y; }
     else { v[0] = ptr[0]; }
   } else {
     const uint16_t* ptr = reinterpret_cast<const uint16_t*>(base) + off;
-    if constexpr (LW == 4) { u32x2 t = *reinterpret_cast<const u32x2*>(ptr); v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y); }
+    if constexpr (LW == 4) { u32x2 t = ld_stream<NT>(reinterpret_cast<const u32x2*>(ptr)); v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y); }
     else if constexpr (LW == 2) { uint32_t t = *reinterpret_cast<const uint32_t*>(ptr); v[0] = bf16_lo(t); v[1] = bf16_hi(t); }
     else { v[0] = __uint_as_float(static_cast<uint32_t>(ptr[0]) << 16); }
   }

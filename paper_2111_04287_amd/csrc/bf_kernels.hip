@@ -73,7 +73,7 @@ struct WinParams {
 
 enum { WIN_PUT = 0, WIN_ACCUMULATE = 1, WIN_COLLECT = 2, WIN_AVERAGE = 3, WIN_GET = 4 };
 
-template <int MODE, int DT>
+template <int MODE, int DT, bool STREAM>
 __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
   constexpr int U = 4;
   const int tid = threadIdx.x;
@@ -101,18 +101,18 @@ __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
     auto load_x = [&](int64_t row, int u) -> f32x4 {
       if (!valid[u]) return f32x4{0.f, 0.f, 0.f, 0.f};
       float v[4];
-      load_in<DT, 4>(p.x, row * p.ld + xcol[u], v);
+      load_in<DT, 4, STREAM>(p.x, row * p.ld + xcol[u], v);
       return f32x4{v[0], v[1], v[2], v[3]};
     };
     auto store_x = [&](int64_t row, int u, f32x4 v) {
       const float e[4] = {v.x, v.y, v.z, v.w};
-      if (valid[u]) store_out<DT, 4, false>(p.x, row * p.ld + xcol[u], e, valid[u]);      // never the padding
+      if (valid[u]) store_out<DT, 4, STREAM>(p.x, row * p.ld + xcol[u], e, valid[u]);      // never the padding
     };
     auto load_w = [&](const float* row, int u) -> f32x4 {
-      return valid[u] ? *reinterpret_cast<const f32x4*>(row + wcol[u]) : f32x4{0.f, 0.f, 0.f, 0.f};
+      return valid[u] ? ld_stream<STREAM>(reinterpret_cast<const f32x4*>(row + wcol[u])) : f32x4{0.f, 0.f, 0.f, 0.f};
     };
     auto store_w = [&](float* row, int u, f32x4 v) {
-      if (valid[u] == 4) { *reinterpret_cast<f32x4*>(row + wcol[u]) = v; return; }
+      if (valid[u] == 4) { st_stream<STREAM>(reinterpret_cast<f32x4*>(row + wcol[u]), v); return; }
       const float e[4] = {v.x, v.y, v.z, v.w};
       for (int k = 0; k < valid[u]; ++k) row[wcol[u] + k] = e[k];
     };
@@ -1145,11 +1145,21 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
   if (chunks > INT32_MAX) return BF_ERR_SIZE;
   wp.chunks = static_cast<int32_t>(chunks);
   const int64_t units = chunks * t->n;
-  const int grid = static_cast<int>(std::min<int64_t>(units, static_cast<int64_t>(di.cus) * 8));
-#define BF_WIN(M)                                                                                         \
-  do {                                                                                                    \
-    if (dt == BF_F32) hipLaunchKernelGGL((bf_win_kernel<M, DT_F32>), dim3(grid), dim3(256), 0, st, wp);   \
-    else hipLaunchKernelGGL((bf_win_kernel<M, DT_BF16>), dim3(grid), dim3(256), 0, st, wp);               \
+  int grid = static_cast<int>(std::min<int64_t>(units, static_cast<int64_t>(di.cus) * 8));
+  if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
+  // Cache policy as for the mixing kernels: state and window beyond what the memory-side cache can
+  // keep between two calls stream with non-temporal loads and stores.
+  const size_t eb = dt == BF_F32 ? 4 : 2;
+  const bool stream = g_tune_stream == 1 ? true : (g_tune_stream == 2 ? false : ma.extent(static_cast<int>(eb)) + win_bytes > (size_t{320} << 20));
+#define BF_WIN(M)                                                                                                \
+  do {                                                                                                           \
+    if (dt == BF_F32) {                                                                                          \
+      if (stream) hipLaunchKernelGGL((bf_win_kernel<M, DT_F32, true>), dim3(grid), dim3(256), 0, st, wp);        \
+      else hipLaunchKernelGGL((bf_win_kernel<M, DT_F32, false>), dim3(grid), dim3(256), 0, st, wp);              \
+    } else {                                                                                                     \
+      if (stream) hipLaunchKernelGGL((bf_win_kernel<M, DT_BF16, true>), dim3(grid), dim3(256), 0, st, wp);       \
+      else hipLaunchKernelGGL((bf_win_kernel<M, DT_BF16, false>), dim3(grid), dim3(256), 0, st, wp);             \
+    }                                                                                                            \
   } while (0)
   switch (mode) {
     case WIN_PUT: BF_WIN(WIN_PUT); break;
