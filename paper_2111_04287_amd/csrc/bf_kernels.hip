@@ -947,7 +947,10 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     // memory-side cache.  A cache-resident in-place round is left to the one-tile kernel, whose two
     // workgroups per CU do better there (76 % vs 75 % on 64 x 2^20).
     Shape ps;
-    if (choose_pipe_shape(t->n, tp.d, di, &ps, cap_log_c) == BF_OK) {
+    // (column blocks: tiles of 512 columns below 32 agents and 256 from there on measure best --
+    // n = 8: 512 columns 6.2 TB/s, 1024 6.0, 256 3.1; n = 32: 256 columns 6.04, 512 5.67)
+    const int pipe_cap = blocked ? std::min(cap_log_c, t->n < 32 ? 9 : 8) : cap_log_c;
+    if (choose_pipe_shape(t->n, tp.d, di, &ps, pipe_cap) == BF_OK) {
       if (dry) return BF_OK;
       ps.stream = stream;
       tp.log_c = ps.log_c;
