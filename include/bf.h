@@ -177,8 +177,10 @@ int bf_topology_export_window(const bf_topology_t* t, int32_t round, int64_t* sl
  * kernels run with tiles of at most B columns and the row-streaming kernel with sweeps inside a
  * block (same arithmetic, same bits).  bf_neighbor_allreduce_multi,
  * bf_hierarchical_neighbor_allreduce, bf_pushsum_step, bf_pushsum_atc_step, bf_tracking_step,
- * bf_atc_step, bf_exact_diffusion_step and the bf_win_* calls (X with n rows and the window with E
- * rows, both in blocks of B) accept it too; every other call takes agent-major matrices only. */
+ * bf_atc_step, bf_exact_diffusion_step, bf_dense_mix, the bf_win_* calls (X with n rows and the
+ * window with E rows, both in blocks of B), bf_grad_quadratic and bf_consensus_stats accept it too;
+ * the least-squares calls (bf_grad_least_squares, the bf_*_least_squares_run family), whose access
+ * is by whole rows of small matrices, take agent-major matrices only. */
 int bf_neighbor_allreduce(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
                           int64_t d, int64_t ld, bf_dtype_t dt, void* hip_stream);
 

@@ -271,7 +271,7 @@ __global__ __launch_bounds__(1024) void bf_ls_grad_kernel(const float* A, const 
 // Synthetic gradient G = lam (X - C) + sigma E, elementwise in fp32.
 template <int DT>
 __global__ __launch_bounds__(256) void bf_grad_quadratic_kernel(const char* X, const char* C, const char* E, char* G,
-                                                               int n, int64_t d, int64_t ld, float lam, float sigma) {
+                                                               int n, int64_t d, int64_t ld, int block_log, float lam, float sigma) {
   constexpr int UC = Elem<DT>::per16;
   constexpr int EB = Elem<DT>::bytes;
   const int64_t upr = (d + UC - 1) / UC;
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256) void bf_grad_quadratic_kernel(const char* X, c
   for (int64_t u = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; u < total;
        u += static_cast<int64_t>(gridDim.x) * blockDim.x) {
     const int64_t row = u / upr, col = (u % upr) * UC;
-    const int64_t off = row * ld + col;
+    const int64_t off = row * ld + col + (block_log ? ((col >> block_log) * (n - 1)) << block_log : int64_t{0});
     float xv[UC], cv[UC], ev[UC], gv[UC];
     widen<DT>(*reinterpret_cast<const u32x4*>(X + off * EB), xv);
     widen<DT>(*reinterpret_cast<const u32x4*>(C + off * EB), cv);
@@ -559,22 +559,24 @@ __device__ __forceinline__ void atomic_max_nonneg(double* addr, double v) {
 
 template <int DT>
 __global__ __launch_bounds__(256) void bf_stats_kernel(const char* X, const float* p, int n, int64_t d, int64_t ld,
-                                                      double* stats, float* mean_out) {
+                                                      int block_log, double* stats, float* mean_out) {
   __shared__ double red[3][4];
   double ss = 0.0, mdev = 0.0, mabs = 0.0;
   for (int64_t c = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; c < d;
        c += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    // column blocks: column c of agent i is at i * ld + c plus the start of its block (ld = block width)
+    const int64_t co = c + (block_log ? ((c >> block_log) * (n - 1)) << block_log : int64_t{0});
     double sum = 0.0;
     for (int i = 0; i < n; ++i) {
       float v;
-      load_in<DT, 1>(X, static_cast<int64_t>(i) * ld + c, &v);
+      load_in<DT, 1>(X, static_cast<int64_t>(i) * ld + co, &v);
       sum += p ? static_cast<double>(v) / static_cast<double>(p[i]) : static_cast<double>(v);
     }
     const double mean = sum / n;
     if (mean_out) mean_out[c] = static_cast<float>(mean);
     for (int i = 0; i < n; ++i) {
       float v;
-      load_in<DT, 1>(X, static_cast<int64_t>(i) * ld + c, &v);
+      load_in<DT, 1>(X, static_cast<int64_t>(i) * ld + co, &v);
       const double y = p ? static_cast<double>(v) / static_cast<double>(p[i]) : static_cast<double>(v);
       const double dev = fabs(y - mean);
       ss += dev * dev;
@@ -1832,7 +1834,7 @@ int bf_grad_quadratic(int32_t n, int64_t d, int64_t ld, const void* X, const voi
   if (!X || !C || !E || !G) return BF_ERR_NULL;
   if (n < 1) return BF_ERR_SIZE;
   MatArgs ma;
-  int rc = check_matrix_shape(n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(X) || misaligned16(C) || misaligned16(E) || misaligned16(G)) return BF_ERR_ALIGN;
   if (overlaps(G, ma.bytes, X, ma.bytes) || overlaps(G, ma.bytes, C, ma.bytes) || overlaps(G, ma.bytes, E, ma.bytes))
@@ -1844,10 +1846,10 @@ int bf_grad_quadratic(int32_t n, int64_t d, int64_t ld, const void* X, const voi
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (dt == BF_F32)
     hipLaunchKernelGGL(bf_grad_quadratic_kernel<DT_F32>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X),
-                       static_cast<const char*>(C), static_cast<const char*>(E), static_cast<char*>(G), n, d, ld, lam, sigma);
+                       static_cast<const char*>(C), static_cast<const char*>(E), static_cast<char*>(G), n, d, ma.ld, ma.block_log, lam, sigma);
   else
     hipLaunchKernelGGL(bf_grad_quadratic_kernel<DT_BF16>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X),
-                       static_cast<const char*>(C), static_cast<const char*>(E), static_cast<char*>(G), n, d, ld, lam, sigma);
+                       static_cast<const char*>(C), static_cast<const char*>(E), static_cast<char*>(G), n, d, ma.ld, ma.block_log, lam, sigma);
   BF_HIP_TRY(hipGetLastError());
   return BF_OK;
 }
@@ -1857,7 +1859,7 @@ int bf_consensus_stats(int32_t n, int64_t d, int64_t ld, const void* X, const fl
   if (!X || !stats) return BF_ERR_NULL;
   if (n < 1) return BF_ERR_SIZE;
   MatArgs ma;
-  int rc = check_matrix_shape(n, d, ld, dt, &ma);
+  int rc = check_matrix_shape(n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   if (misaligned16(X) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return BF_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -1866,9 +1868,9 @@ int bf_consensus_stats(int32_t n, int64_t d, int64_t ld, const void* X, const fl
   if (d == 0) return BF_OK;
   const int grid = static_cast<int>(std::min<int64_t>((d + 255) / 256, 256 * 16));
   if (dt == BF_F32)
-    hipLaunchKernelGGL(bf_stats_kernel<DT_F32>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X), p, n, d, ld, stats, mean_out);
+    hipLaunchKernelGGL(bf_stats_kernel<DT_F32>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X), p, n, d, ma.ld, ma.block_log, stats, mean_out);
   else
-    hipLaunchKernelGGL(bf_stats_kernel<DT_BF16>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X), p, n, d, ld, stats, mean_out);
+    hipLaunchKernelGGL(bf_stats_kernel<DT_BF16>, dim3(grid), dim3(256), 0, st, static_cast<const char*>(X), p, n, d, ma.ld, ma.block_log, stats, mean_out);
   BF_HIP_TRY(hipGetLastError());
   return BF_OK;
 }

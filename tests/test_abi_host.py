@@ -374,7 +374,8 @@ def test_column_block_layout_argument_checks():
     assert L.bf_dense_mix(h, 0, A, A + 1024, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     assert L.bf_win_put(h, 0, None, A, A + 1024, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     assert L.bf_dgd_least_squares_run(h, 0, 5, 32, A, B, 0x40000000, 0x70000000, 1e-3, 1024, -1024, None) == bf.BF_ERR_SIZE
-    assert L.bf_consensus_stats(4, 100, -64, A, None, bf.BF_F32, B, None, None) == bf.BF_ERR_UNSUPPORTED
+    assert L.bf_consensus_stats(4, 100, -100, A, None, bf.BF_F32, B, None, None) == bf.BF_ERR_SIZE
+    assert L.bf_grad_quadratic(4, 100, -64, A, B, 0x40000000, 1.0, 0.1, A + 1024, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     # the state matrix of a momentum step has the layout of X: its extent follows the blocks
     G, M = 0x40000000, 0x50000000
     at = L.bf_atc_step

@@ -176,9 +176,9 @@ def test_layout_mismatch_and_agent_major_only_calls_are_refused():
         bf.bf_neighbor_allreduce(t, 0, Xb, X)                      # mixed layouts
     with pytest.raises(ValueError):
         bf.bf_neighbor_allreduce(t, 0, Xb, to_blocked(X, 128))     # two block widths
-    with pytest.raises(bf.BfError) as e:
-        bf.bf_consensus_stats(Xb)
-    assert e.value.code == bf.BF_ERR_UNSUPPORTED
+    A = torch.zeros((n, 4, d - d % 4), device=DEV)
+    with pytest.raises((bf.BfError, ValueError, AttributeError)):
+        bf.bf_grad_least_squares(A, torch.zeros((n, 4), device=DEV), Xb, Xb)   # whole-row access: agent-major only
 
 
 def sample_columns(d, seed):
@@ -216,12 +216,11 @@ def test_config5_full_size_momentum_steps_in_column_blocks():
     Mb = empty_blocked(n, d, B, torch.float32, fill=0.0)
     a64, b64, s64 = (float(np.float32(cfg[k])) for k in ("alpha", "beta", "sigma"))
     Xr, Mr = np.zeros((n, len(cols))), np.zeros((n, len(cols)))
-    flat = lambda b: b.data.view(-1, B)                                        # the gradient is elementwise
     for k in range(6):
         workloads.config5_noise(DEV, k, n=n, d=d, out=scratch)
         Eh = scratch[:, cols].float().cpu().numpy().astype(np.float64)
         bf.bf_blocked_pack(scratch, Eb)
-        bf.bf_grad_quadratic(flat(Xb), flat(Cb), flat(Eb), cfg["lam"], cfg["sigma"], flat(Gb))
+        bf.bf_grad_quadratic(Xb, Cb, Eb, cfg["lam"], cfg["sigma"], Gb)
         bf.bf_atc_step(t, k, Xb, Xb, Gb, Mb, alpha=cfg["alpha"], beta=cfg["beta"], mode=bf.BF_ATC)
         Xr, Mr = O.dmsgd_atc_step(Xr, Mr, O.quadratic_noise_grad(Xr, Ch, Eh, cfg["lam"], s64), W, a64, b64)
         bf.bf_blocked_unpack(Xb, scratch)
@@ -408,3 +407,23 @@ def test_dense_mix_on_column_blocks(n, d, B):
     xb = to_blocked(X, B)
     bf.bf_dense_mix(t, 0, xb, xb)                                  # in place
     assert torch.equal(from_blocked(xb, X), got)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,d,B", [(5, 300, 64), (32, 3 * 512 + 37, 512), (16, 9000, 8192)])
+def test_gradient_generator_and_diagnostics_on_column_blocks(dtype, n, d, B):
+    X, Cc, E = (rows(n, d, 130 + k, dtype=dtype) for k in range(3))
+    G = torch.empty((n, X.stride(0)), dtype=dtype, device=DEV)[:, :d]
+    bf.bf_grad_quadratic(X, Cc, E, 0.7, 0.3, G)
+    Gb = empty_blocked(n, d, B, dtype, fill=3.0)
+    bf.bf_grad_quadratic(to_blocked(X, B), to_blocked(Cc, B), to_blocked(E, B), 0.7, 0.3, Gb)
+    assert torch.equal(from_blocked(Gb, X), G)
+    pad = Gb.data[-1, :, d - (Gb.data.shape[0] - 1) * B:]
+    assert bool((pad == 3.0).all()), "the padding columns of the last block are never written"
+    p = torch.rand(n, device=DEV) + 0.5
+    for pv in (None, p):
+        m1, m2 = torch.empty(d, device=DEV), torch.empty(d, device=DEV)
+        s1 = bf.bf_consensus_stats(X, pv, mean_out=m1).clone()
+        s2 = bf.bf_consensus_stats(to_blocked(X, B), pv, mean_out=m2).clone()
+        assert torch.equal(m1, m2)
+        assert torch.equal(s1[1:], s2[1:]) and abs(float(s1[0]) - float(s2[0])) <= 1e-12 * float(s1[0])   # sums: atomics, any order
