@@ -265,7 +265,14 @@ def main():
                 "separate_rounds_ms": round(cnt * per["config3_one_peer_exp2_n256_d4194304_f32"]["ms_per_step"], 4),
                 "pass_GBps": round(2 * n3 * d3 * 4 * 16 / w_ / 1e9, 1),
                 "pass_pct_of_hbm_peak": round(100 * 2 * n3 * d3 * 4 * 16 / w_ / 1e9 / HBM_PEAK_GBPS, 2)}
-        del X3
+        X3s = blocked(n3, d3, 64, torch.float32, X3)
+        w_, e_ = timed(lambda k: bf.bf_neighbor_allreduce_multi(t3, 0, 8, X3s, X3s), 16, 4)
+        nxt["fused_rounds_one_peer_n256_d4194304_x8_column_blocks"] = {
+            "rounds_per_pass": 8, "ms_per_pass": round(w_ * 1e3 / 16, 4), "block": 64,
+            "pass_GBps": round(2 * n3 * d3 * 4 * 16 / w_ / 1e9, 1),
+            "pass_pct_of_hbm_peak": round(100 * 2 * n3 * d3 * 4 * 16 / w_ / 1e9 / HBM_PEAK_GBPS, 2),
+            "note": "X in column blocks of 64 (the register-round kernel's tile)"}
+        del X3, X3s
 
         # configuration 4: push-sum on the random directed graph, n=128, d=2^21
         n4, d4 = 128, 1 << 21
