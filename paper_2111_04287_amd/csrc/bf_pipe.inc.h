@@ -253,12 +253,22 @@ int launch_pipe_shape(const TileParams& tp, int grid, size_t lds, hipStream_t st
   return BF_OK;
 }
 
-// Four loader waves with eight vectors per lane in flight and twelve reducer waves: measured best of
-// the splits tried (4+8 and 8+8 waves leave the reducers short: with so few waves per SIMD nothing
-// hides the latency of a row's scalar list loads and LDS reads; two or three loader waves cannot
-// keep enough loads in flight).
+// The wave split.  Plain mixing and the ops that stage X (and G) only: four loader waves with eight
+// vectors per lane in flight and twelve reducer waves, the measured best of the splits tried (4+8
+// and 8+8 waves leave the reducers short: with so few waves per SIMD nothing hides the latency of a
+// row's scalar list loads and LDS reads; two or three loader waves cannot keep enough loads in
+// flight).  The ops that also read and write an fp32 state matrix while staging (momentum,
+// Exact-Diffusion) do most of their work in the loaders: eight loader waves with four vectors in
+// flight and eight reducers measure 2-3 % above the 4+12 split there on column blocks (n = 32 bf16
+// momentum: 6.25 against 6.08 TB/s; with eight vectors in flight 5.75).
 template <int DT, int OP, bool WITH_Y, int LW>
 int launch_pipe_lw(const TileParams& tp, int grid, size_t lds, bool stream, hipStream_t st) {
+  if constexpr (OP == OP_MOM_ATC || OP == OP_ED) {
+    // (on agent-major rows the two splits are within 1 % of each other, 4+12 ahead)
+    if (tp.block_log)
+      return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 8, 8, 4, true>(tp, grid, lds, st)
+                    : launch_pipe_shape<DT, OP, WITH_Y, LW, 8, 8, 4, false>(tp, grid, lds, st);
+  }
   return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, true>(tp, grid, lds, st)
                 : launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, false>(tp, grid, lds, st);
 }
