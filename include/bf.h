@@ -411,7 +411,7 @@ int64_t bf_blocked_elems(int32_t n, int64_t d, int64_t block);
 
 /* Block width this library suggests for n x d matrices mixed over topology t (measured on MI355X):
  * the power of two nearest to 2^20 / n within [2048, 16384] (16384 columns at n <= 64, 8192 at
- * n = 128); 65536 when n > 160 and every round of t is a union of paths and cycles (those go to the
+ * n = 128; at most 8192 for BF_BF16, whose steps usually carry an fp32 state matrix as well); 65536 when n > 160 and every round of t is a union of paths and cycles (those go to the
  * row-streaming kernel); the power of two that covers d when d is smaller.  Negative on error. */
 int64_t bf_recommended_block(const bf_topology_t* t, int64_t d, bf_dtype_t dt);
 

@@ -351,7 +351,7 @@ def test_column_block_layout_argument_checks():
     assert L.bf_blocked_elems(4, 1000, 1 << 21) == bf.BF_ERR_SIZE
     assert L.bf_blocked_elems(0, 1000, 64) == bf.BF_ERR_SIZE
     rb = lambda kind, n, d, dt=bf.BF_F32: bf.bf_recommended_block(bf.bf_topology_create(kind, n), d, dt)
-    assert rb(bf.BF_EXP_STATIC, 32, 25557032, bf.BF_BF16) == 16384 and rb(bf.BF_EXP_STATIC, 64, 1 << 20) == 16384
+    assert rb(bf.BF_EXP_STATIC, 32, 25557032, bf.BF_BF16) == 8192 and rb(bf.BF_EXP_STATIC, 64, 1 << 20) == 16384
     assert rb(bf.BF_EXP_STATIC, 128, 1 << 21) == 8192 and rb(bf.BF_EXP_STATIC, 256, 1 << 22) == 4096
     assert rb(bf.BF_EXP_STATIC, 3000, 1 << 22) == 2048 and rb(bf.BF_EXP_STATIC, 5, 4096) == 4096
     assert rb(bf.BF_RING, 5, 100) == 128 and rb(bf.BF_RING, 5, 3) == 64 and rb(bf.BF_RING, 5, 0) == 64

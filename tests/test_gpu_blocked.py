@@ -203,7 +203,7 @@ def test_config5_full_size_momentum_steps_in_column_blocks():
     ld = bf.bf_recommended_ld(d, bf.BF_BF16)
     W = lib_W(t)
     cols = sample_columns(d, 5)
-    assert int(cols[-1]) == d - 1 and d % B == 14376     # the last block is ragged
+    assert int(cols[-1]) == d - 1 and d % B == 6184     # the last block is ragged
     scratch = workloads.alloc_rows(n, d, torch.bfloat16, DEV, ld=ld)          # agent-major staging for the recipe
     scratch32 = workloads.alloc_rows(n, d, torch.float32, DEV, ld=ld)
     Cc = workloads.config5_centres(DEV, n=n, d=d, ld=ld)
