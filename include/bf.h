@@ -25,7 +25,7 @@
  *     M, Y, ...) has the same layout.  Why it exists: a column tile of the agent-major layout is n
  *     row segments in n distant places of every matrix (n x 3 streams and as many memory pages per
  *     tile with gradient and momentum), a tile of this layout is one contiguous piece per matrix.
- *     Measured on the n = 32, d = 25.5 M momentum step with blocks of 8192 columns: 6.05 TB/s
+ *     Measured on the n = 32, d = 25.5 M momentum step with blocks of 8192 columns: 6.3 TB/s
  *     against 5.06 TB/s agent-major.  A call that does not accept the layout answers
  *     BF_ERR_UNSUPPORTED.
  *   - Pointers named X*, G, M, Y, A, b, C, E, w_in/w_out and stats are DEVICE pointers owned by the
