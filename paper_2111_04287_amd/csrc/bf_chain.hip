@@ -51,8 +51,8 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
       for (int w = 0; w < CW; ++w) {
         const int64_t off = static_cast<int64_t>(row) * ld + acol[w];
         xr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
-        if constexpr (G_ON_LOAD) gr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g + off * EB));
-        if constexpr (OP == OP_TRACK) g2r[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
+        if constexpr (G_ON_LOAD) gr[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g + g_offset(p, row, col[w]) * EB));
+        if constexpr (OP == OP_TRACK) g2r[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g2 + g_offset(p, row, col[w]) * EB));
         if constexpr (STATE_ON_LOAD) {
 #pragma unroll
           for (int q = 0; q < UC / 4; ++q) mr[w][q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
           const int64_t rem = d - col[w];
           if constexpr (G_ON_STORE) {
             float gv[UC];
-            widen<DT>(*reinterpret_cast<const u32x4*>(p.g + off * EB), gv);
+            widen<DT>(*reinterpret_cast<const u32x4*>(p.g + g_offset(p, st.row, col[w]) * EB), gv);
             if constexpr (MOM) {
 #pragma unroll
               for (int q = 0; q < UC / 4; ++q) {
@@ -314,8 +314,8 @@ __global__ __launch_bounds__(1024) void bf_narrow_kernel(const TileParams p) {
         for (int e = 0; e < 4; ++e)
           if (e < rem) {
             load_in<DT, 1>(p.x_in, off + e, &xv[e]);
-            if constexpr (STAGE_G) load_in<DT, 1>(p.g, off + e, &gv[e]);
-            if constexpr (OP == OP_TRACK) load_in<DT, 1>(p.g2, off + e, &hv[e]);
+            if constexpr (STAGE_G) load_in<DT, 1>(p.g, g_offset(p, row, col) + e, &gv[e]);
+            if constexpr (OP == OP_TRACK) load_in<DT, 1>(p.g2, g_offset(p, row, col) + e, &hv[e]);
             if constexpr (STAGE_M) sv[e] = p.m[off + e];
           }
         if constexpr (STAGE_M) {
@@ -350,7 +350,7 @@ __global__ __launch_bounds__(1024) void bf_narrow_kernel(const TileParams p) {
       if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
         for (int e = 0; e < valid; ++e) {
           float g;
-          load_in<DT, 1>(p.g, off + e, &g);
+          load_in<DT, 1>(p.g, g_offset(p, i, col) + e, &g);
           if constexpr (OP == OP_MOM_AWC) { g = fmaf(p.beta, p.m[off + e], g); p.m[off + e] = g; }
           acc[e] = fmaf(-p.alpha, g, acc[e]);
         }

@@ -894,6 +894,8 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   }
   // Column-block layout: tiles stay inside a block (so do the chain kernel's sweeps of one 16-byte
   // vector per thread), and the gather fallback, which walks whole rows, does not apply.
+  if (tp.g_ld == 0) { tp.g_ld = tp.ld; tp.g_block_log = tp.block_log; }     // gradients laid out like the state
+  const bool same_layout = tp.g_ld == tp.ld && tp.g_block_log == tp.block_log;
   const bool blocked = tp.block_log > 0;
   const int64_t block_cols = blocked ? int64_t{1} << tp.block_log : INT64_MAX;
   const int cap_log_c = blocked ? std::min(tp.block_log, 10) : 10;
@@ -971,7 +973,7 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   if (fuse > 1 && rc != BF_OK) return rc;   // fused rounds exist only as the two-tile LDS kernel
   if (rc == BF_ERR_UNSUPPORTED && g_tune_tile == 0) {
     // Too many agents for a 64-column LDS tile.
-    const bool gatherable = tp.x_in != tp.x_out && op != OP_ED && op != OP_TRACK && !blocked;
+    const bool gatherable = tp.x_in != tp.x_out && op != OP_ED && op != OP_TRACK && !blocked && same_layout;
     if (gatherable) {
       // row gather through the caches (out of place only; no state matrix in the sum)
       if (dry) return BF_OK;
@@ -1571,21 +1573,24 @@ int bf_tracking_step(const bf_topology_t* t, int32_t round, const void* Y_in, vo
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_TRACK, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
-int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
-                float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld,
-                bf_dtype_t dt, void* hip_stream) {
+// Shared body of bf_atc_step and bf_atc_step_g: ld names the layout of X_in, X_out and M, ld_g that of G.
+static int atc_common(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                      float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld, int64_t ld_g,
+                      bf_dtype_t dt, void* hip_stream) {
   if (!t || !X_in || !X_out || !G) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   if (mode != BF_ATC && mode != BF_AWC) return BF_ERR_KIND;
-  MatArgs ma;
+  MatArgs ma, mg;
   int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
+  if (rc != BF_OK) return rc;
+  rc = check_matrix_shape(t->n, d, ld_g, dt, &mg, true);
   if (rc != BF_OK) return rc;
   if ((ma.ld * 4) % 16 != 0 && M) return BF_ERR_ALIGN;
   if (misaligned16(X_in) || misaligned16(X_out) || misaligned16(G) || (M && misaligned16(M))) return BF_ERR_ALIGN;
   const size_t mb = ma.extent(4);
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
-  if (overlaps(G, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
-  if (M && (overlaps(M, mb, X_out, ma.bytes) || overlaps(M, mb, X_in, ma.bytes) || overlaps(M, mb, G, ma.bytes)))
+  if (overlaps(G, mg.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (M && (overlaps(M, mb, X_out, ma.bytes) || overlaps(M, mb, X_in, ma.bytes) || overlaps(M, mb, G, mg.bytes)))
     return BF_ERR_ALIAS;
   TileParams tp{};
   tp.x_in = static_cast<const char*>(X_in);
@@ -1594,8 +1599,21 @@ int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X
   tp.m = M;
   tp.alpha = alpha; tp.beta = beta;
   tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
+  tp.g_ld = mg.ld; tp.g_block_log = mg.block_log;
   const int op = M ? (mode == BF_ATC ? OP_MOM_ATC : OP_MOM_AWC) : (mode == BF_ATC ? OP_ATC : OP_AWC);
   return run_tile(const_cast<bf_topology_t*>(t), round, op, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld,
+                bf_dtype_t dt, void* hip_stream) {
+  return atc_common(t, round, X_in, X_out, G, M, alpha, beta, mode, d, ld, ld, dt, hip_stream);
+}
+
+int bf_atc_step_g(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                  float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld, int64_t ld_g,
+                  bf_dtype_t dt, void* hip_stream) {
+  return atc_common(t, round, X_in, X_out, G, M, alpha, beta, mode, d, ld, ld_g, dt, hip_stream);
 }
 
 int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,

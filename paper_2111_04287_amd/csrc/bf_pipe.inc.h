@@ -82,8 +82,8 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
         const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
         const int64_t off = static_cast<int64_t>(row) * ld + col + t0;
         xr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.x_in + off * EB));
-        if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g + off * EB));
-        if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g2 + off * EB));
+        if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g + g_offset(p, row, col) * EB));
+        if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g2 + g_offset(p, row, col) * EB));
         if constexpr (STAGE_M) mr[k] = ld_stream<STREAM>(reinterpret_cast<const f32x4*>(p.m + off));
       }
 #pragma unroll
@@ -192,7 +192,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
         if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
           // Adapt-while-communicate: the receiver's own gradient is subtracted after the mix.
           float gv[LW];
-          load_in<DT, LW>(p.g, off, gv);
+          load_in<DT, LW>(p.g, g_offset(p, i, col), gv);
           if constexpr (OP == OP_MOM_AWC) {
             float mv[LW];
             load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), off, mv);

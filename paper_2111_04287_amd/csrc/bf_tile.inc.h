@@ -48,8 +48,8 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
       const int64_t off = static_cast<int64_t>(row) * ld + col + tile_origin(p, c0);
       xr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
-      if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
-      if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
+      if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + g_offset(p, row, col) * EB));
+      if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + g_offset(p, row, col) * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
         for (int q = 0; q < MV; ++q) mr[k * MV + q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
@@ -118,8 +118,8 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       const u32x4 xraw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.x_in + off * EB));
       u32x4 graw = {0, 0, 0, 0}, g2raw = {0, 0, 0, 0};
       f32x4 mraw[MV];
-      if constexpr (STAGE_G) graw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + off * EB));
-      if constexpr (STAGE_G2) g2raw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + off * EB));
+      if constexpr (STAGE_G) graw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g + g_offset(p, row, col) * EB));
+      if constexpr (STAGE_G2) g2raw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + g_offset(p, row, col) * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
         for (int q = 0; q < MV; ++q) mraw[q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
         if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
           // Adapt-while-communicate: the receiver's own gradient is subtracted after the mix.
           float gv[LW];
-          load_in<DT, LW>(p.g, off, gv);
+          load_in<DT, LW>(p.g, g_offset(p, i, col), gv);
           if constexpr (OP == OP_MOM_AWC) {
             float mv[LW];
             load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), off, mv);

@@ -428,3 +428,42 @@ def test_gradient_generator_and_diagnostics_on_column_blocks(dtype, n, d, B):
         s2 = bf.bf_consensus_stats(to_blocked(X, B), pv, mean_out=m2).clone()
         assert torch.equal(m1, m2)
         assert torch.equal(s1[1:], s2[1:]) and abs(float(s1[0]) - float(s2[0])) <= 1e-12 * float(s1[0])   # sums: atomics, any order
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,d,B", [(5, 300, 64), (32, 3 * 512 + 37, 512), (64, 9000, 8192), (300, 200, 64), (700, 150, 64)])
+@pytest.mark.parametrize("kind", [bf.BF_EXP_STATIC, bf.BF_RING])
+def test_gradient_in_a_layout_of_its_own(dtype, n, d, B, kind):
+    """State in column blocks with the gradient on agent-major rows, and the other way round: the
+    bits of the all-agent-major call, for ATC, AWC and both momentum forms, in place and not."""
+    t = bf.bf_topology_create(kind, n)
+    X, G = rows(n, d, 140, dtype=dtype), rows(n, d, 141, dtype=dtype)
+    M0 = workloads.normal_rows(n, d, 142, DEV, ld=X.stride(0))
+    Gb = to_blocked(G, B)
+
+    def fresh(A):
+        return torch.empty((n, A.stride(0)), dtype=A.dtype, device=DEV)[:, :d].copy_(A)
+
+    for cw in (0, 2):                                            # 2: the row-streaming kernel where the round allows it
+        bf.bf_set_tuning(6, cw)
+        try:
+            for mode in (bf.BF_ATC, bf.BF_AWC):
+                for with_m in (False, True):
+                    for in_place in (False, True):
+                        xi = fresh(X); xo = xi if in_place else fresh(X); m = fresh(M0) if with_m else None
+                        bf.bf_atc_step(t, 1, xi, xo, G, m, alpha=0.05, beta=0.9, mode=mode)
+                        # state in blocks, G on rows
+                        bi = to_blocked(X, B); bo = bi if in_place else empty_blocked(n, d, B, dtype)
+                        bm = to_blocked(M0, B) if with_m else None
+                        bf.bf_atc_step_g(t, 1, bi, bo, G, bm, alpha=0.05, beta=0.9, mode=mode)
+                        assert torch.equal(from_blocked(bo, X), xo)
+                        if with_m:
+                            assert torch.equal(from_blocked(bm, M0), m)
+                        # state on rows, G in blocks
+                        yi = fresh(X); yo = yi if in_place else fresh(X); ym = fresh(M0) if with_m else None
+                        bf.bf_atc_step_g(t, 1, yi, yo, Gb, ym, alpha=0.05, beta=0.9, mode=mode)
+                        assert torch.equal(yo, xo)
+                        if with_m:
+                            assert torch.equal(ym, m)
+        finally:
+            bf.bf_set_tuning(6, 0)
