@@ -320,14 +320,17 @@ int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X
                 float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld,
                 bf_dtype_t dt, void* hip_stream);
 
-/* bf_atc_step with the gradient in a layout of its own: ld describes X_in, X_out and M, ld_g
- * describes G; either may be a row pitch or BF_LD_BLOCKED(B).  Meant for a state that lives in column
- * blocks while each agent's gradient arrives as one contiguous vector (agent-major rows): reading
- * G that way costs nothing (measured on the n = 32, d = 25.5 M momentum step: 6.3 TB/s either way),
- * it is the in-place state that needs the blocks.  Same arithmetic, same bits as bf_atc_step. */
-int bf_atc_step_g(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
-                  float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld, int64_t ld_g,
-                  bf_dtype_t dt, void* hip_stream);
+/* bf_atc_step with a layout per matrix: ld describes X_in and X_out, ld_g describes G, ld_m
+ * describes M (ignored when M is NULL); each is a row pitch or BF_LD_BLOCKED(B).  What the agent-major
+ * layout costs is the scattered in-place read-write of the state; scattered read-only streams cost
+ * nothing.  Measured on the n = 32, d = 25.5 M bf16 momentum step (TB/s): everything on agent-major
+ * rows 5.06; X and G on rows -- one contiguous parameter and gradient vector per agent, as a
+ * per-agent producer and consumer have them -- and only the momentum, which nobody else looks at,
+ * in column blocks 5.96; X and M in blocks with G on rows 6.3, as with everything in blocks.
+ * Same arithmetic, same bits as bf_atc_step. */
+int bf_atc_step_layouts(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                        float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld, int64_t ld_g,
+                        int64_t ld_m, bf_dtype_t dt, void* hip_stream);
 
 /* One Exact-Diffusion iteration (appendix "Application example: Exact-Diffusion algorithm",
  * eqs. ed-1, ed-2, ed-3), fused into one pass:

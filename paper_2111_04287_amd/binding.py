@@ -30,7 +30,7 @@ EXPORTS = [
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_topology_chain_plan", "bf_topology_window_slots", "bf_topology_export_window",
     "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_win_put_weighted", "bf_win_get_weighted", "bf_win_accumulate_weighted", "bf_win_update_weighted", "bf_dgd_least_squares_run", "bf_dgd_least_squares_run_static", "bf_exact_diffusion_least_squares_run", "bf_dgd_status", "bf_stream_probe", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
-    "bf_atc_step", "bf_atc_step_g", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
+    "bf_atc_step", "bf_atc_step_layouts", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
     "bf_blocked_elems", "bf_recommended_block", "bf_blocked_pack", "bf_blocked_unpack",
 ]
@@ -110,7 +110,7 @@ def _load():
     L.bf_pushsum_atc_step.argtypes = [vp, i32, vp, vp, vp, f32, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_tracking_step.argtypes = [vp, i32, vp, vp, vp, vp, i64, i64, C.c_int, vp]
     L.bf_atc_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, f32, C.c_int, i64, i64, C.c_int, vp]
-    L.bf_atc_step_g.argtypes = [vp, i32, vp, vp, vp, vp, f32, f32, C.c_int, i64, i64, i64, C.c_int, vp]
+    L.bf_atc_step_layouts.argtypes = [vp, i32, vp, vp, vp, vp, f32, f32, C.c_int, i64, i64, i64, i64, C.c_int, vp]
     L.bf_exact_diffusion_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, i64, i64, C.c_int, vp]
     L.bf_grad_least_squares.argtypes = [i32, i32, i64, vp, vp, vp, i64, vp, i64, vp]
     L.bf_grad_quadratic.argtypes = [i32, i64, i64, vp, vp, vp, f32, f32, vp, C.c_int, vp]
@@ -550,22 +550,23 @@ def bf_atc_step(t, rnd, X_in, X_out, G, M=None, alpha=0.0, beta=0.0, mode=BF_ATC
     return X_out
 
 
-def bf_atc_step_g(t, rnd, X_in, X_out, G, M=None, alpha=0.0, beta=0.0, mode=BF_ATC, stream=None):
-    """bf_atc_step with G in a layout of its own (agent-major rows next to a state in column blocks,
-    or the other way round)."""
+def bf_atc_step_layouts(t, rnd, X_in, X_out, G, M=None, alpha=0.0, beta=0.0, mode=BF_ATC, stream=None):
+    """bf_atc_step with a layout per matrix: X_in/X_out, G and M may each be an agent-major tensor or a
+    Blocked (e.g. parameters and gradients as per-agent vectors, the momentum in column blocks)."""
+    import torch
     ptr, n, d, ld = _mat(X_in, "X_in")
     _rows(t, n)
     _same_layout(X_in, X_out, "X_out")
     gptr, gn, gd, ld_g = _mat(G, "G")
     if (gn, gd) != (n, d) or G.dtype != X_in.dtype:
         raise ValueError("G must have the shape and dtype of X_in")
+    mptr, ld_m = None, ld
     if M is not None:
-        import torch
-        if M.dtype != torch.float32 or M.shape != X_in.shape or (n > 1 and M.stride(0) != ld) or \
-                isinstance(M, Blocked) != isinstance(X_in, Blocked):
-            raise ValueError("M must be float32 with the shape and layout of X_in")
-    _check(lib.bf_atc_step_g(t.handle, rnd, ptr, X_out.data_ptr(), gptr, None if M is None else M.data_ptr(),
-                             alpha, beta, mode, d, ld, ld_g, _dtype_code(X_in), _stream(stream)), "bf_atc_step_g")
+        mptr, mn, md, ld_m = _mat(M, "M")
+        if (mn, md) != (n, d) or M.dtype != torch.float32:
+            raise ValueError("M must be float32 with the shape of X_in")
+    _check(lib.bf_atc_step_layouts(t.handle, rnd, ptr, X_out.data_ptr(), gptr, mptr, alpha, beta, mode, d, ld, ld_g,
+                                   ld_m, _dtype_code(X_in), _stream(stream)), "bf_atc_step_layouts")
     return X_out
 
 

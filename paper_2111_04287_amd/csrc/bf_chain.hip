@@ -55,7 +55,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
         if constexpr (OP == OP_TRACK) g2r[w] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.g2 + g_offset(p, row, col[w]) * EB));
         if constexpr (STATE_ON_LOAD) {
 #pragma unroll
-          for (int q = 0; q < UC / 4; ++q) mr[w][q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+          for (int q = 0; q < UC / 4; ++q) mr[w][q] = *reinterpret_cast<const f32x4*>(p.m + m_offset(p, row, col[w]) + 4 * q);
         }
       }
 #pragma unroll
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
           float gv[UC];
           widen<DT>(gr[w], gv);
           if constexpr (STATE_ON_LOAD) {
-            const int64_t off = static_cast<int64_t>(row) * ld + acol[w];
+            const int64_t off = m_offset(p, row, col[w]);
 #pragma unroll
             for (int q = 0; q < UC / 4; ++q) {
               float sv[4] = {mr[w][q].x, mr[w][q].y, mr[w][q].z, mr[w][q].w};
@@ -157,13 +157,14 @@ __global__ __launch_bounds__(THR) void bf_chain_kernel(const TileParams p, const
 #pragma unroll
               for (int q = 0; q < UC / 4; ++q) {
                 float mv[4];
-                load_in<DT_F32, 4>(reinterpret_cast<const char*>(p.m), off + 4 * q, mv);
+                load_in<DT_F32, 4>(reinterpret_cast<const char*>(p.m), m_offset(p, st.row, col[w]) + 4 * q, mv);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { mv[e] = fmaf(p.beta, mv[e], gv[4 * q + e]); gv[4 * q + e] = mv[e]; }
                 const int64_t r4 = rem - 4 * q;
                 if (r4 > 0) {
-                  if (r4 >= 4) { f32x4 t = {mv[0], mv[1], mv[2], mv[3]}; *reinterpret_cast<f32x4*>(p.m + off + 4 * q) = t; }
-                  else for (int e = 0; e < 4; ++e) if (e < r4) p.m[off + 4 * q + e] = mv[e];
+                  float* mp = p.m + m_offset(p, st.row, col[w]) + 4 * q;
+                  if (r4 >= 4) { f32x4 t = {mv[0], mv[1], mv[2], mv[3]}; *reinterpret_cast<f32x4*>(mp) = t; }
+                  else for (int e = 0; e < 4; ++e) if (e < r4) mp[e] = mv[e];
                 }
               }
             }
@@ -316,11 +317,11 @@ __global__ __launch_bounds__(1024) void bf_narrow_kernel(const TileParams p) {
             load_in<DT, 1>(p.x_in, off + e, &xv[e]);
             if constexpr (STAGE_G) load_in<DT, 1>(p.g, g_offset(p, row, col) + e, &gv[e]);
             if constexpr (OP == OP_TRACK) load_in<DT, 1>(p.g2, g_offset(p, row, col) + e, &hv[e]);
-            if constexpr (STAGE_M) sv[e] = p.m[off + e];
+            if constexpr (STAGE_M) sv[e] = p.m[m_offset(p, row, col) + e];
           }
         if constexpr (STAGE_M) {
           local_update4<OP>(xv, gv, sv, p.alpha, p.beta);
-          for (int e = 0; e < 4; ++e) if (e < rem) p.m[off + e] = sv[e];
+          for (int e = 0; e < 4; ++e) if (e < rem) p.m[m_offset(p, row, col) + e] = sv[e];
         } else if constexpr (OP == OP_TRACK) {
           for (int e = 0; e < 4; ++e) xv[e] = (xv[e] + gv[e]) - hv[e];
         } else if constexpr (STAGE_G) {
@@ -351,7 +352,7 @@ __global__ __launch_bounds__(1024) void bf_narrow_kernel(const TileParams p) {
         for (int e = 0; e < valid; ++e) {
           float g;
           load_in<DT, 1>(p.g, g_offset(p, i, col) + e, &g);
-          if constexpr (OP == OP_MOM_AWC) { g = fmaf(p.beta, p.m[off + e], g); p.m[off + e] = g; }
+          if constexpr (OP == OP_MOM_AWC) { const int64_t mo = m_offset(p, i, col) + e; g = fmaf(p.beta, p.m[mo], g); p.m[mo] = g; }
           acc[e] = fmaf(-p.alpha, g, acc[e]);
         }
       }

@@ -93,8 +93,8 @@ struct TileParams {
   int64_t ntiles;
   int32_t n;
   int32_t log_c;         // tile width C = 1 << log_c elements
-  int64_t g_ld;          // layout of the gradient matrices (g, g2), which may differ from that of the
-  int32_t g_block_log;   // state (X, M, Y): pitch and block width as ld / block_log below
+  int64_t g_ld, m_ld;    // layouts of the gradient matrices (g, g2) and of the fp32 state matrix (m), which
+  int32_t g_block_log, m_block_log;   // may differ from that of X and Y: pitch and block width as ld / block_log below
   int32_t block_log;     // 0: agent-major rows of pitch ld.  Else the column-block layout: blocks of
                          // B = 1 << block_log columns, block k an n x B row-major matrix at element
                          // k n B (ld = B; tiles never straddle a block: log_c <= block_log)
@@ -123,6 +123,10 @@ __device__ __forceinline__ int64_t tile_origin(const TileParams& p, int64_t c0) 
 // Element offset of column `col` of agent `row` in the gradient matrices, whose layout is their own.
 __device__ __forceinline__ int64_t g_offset(const TileParams& p, int64_t row, int64_t col) {
   return row * p.g_ld + col + (p.g_block_log ? ((col >> p.g_block_log) * (p.n - 1)) << p.g_block_log : int64_t{0});
+}
+// The same for the fp32 state matrix (momentum, psi of Exact-Diffusion).
+__device__ __forceinline__ int64_t m_offset(const TileParams& p, int64_t row, int64_t col) {
+  return row * p.m_ld + col + (p.m_block_log ? ((col >> p.m_block_log) * (p.n - 1)) << p.m_block_log : int64_t{0});
 }
 
 // Parameters of the kernel that runs uniform shift rounds in registers (bf_shift.hip).

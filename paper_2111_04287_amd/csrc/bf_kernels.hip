@@ -894,8 +894,9 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
   }
   // Column-block layout: tiles stay inside a block (so do the chain kernel's sweeps of one 16-byte
   // vector per thread), and the gather fallback, which walks whole rows, does not apply.
-  if (tp.g_ld == 0) { tp.g_ld = tp.ld; tp.g_block_log = tp.block_log; }     // gradients laid out like the state
-  const bool same_layout = tp.g_ld == tp.ld && tp.g_block_log == tp.block_log;
+  if (tp.g_ld == 0) { tp.g_ld = tp.ld; tp.g_block_log = tp.block_log; }     // gradients and state matrix laid out like X
+  if (tp.m_ld == 0) { tp.m_ld = tp.ld; tp.m_block_log = tp.block_log; }
+  const bool same_layout = tp.g_ld == tp.ld && tp.g_block_log == tp.block_log && tp.m_ld == tp.ld && tp.m_block_log == tp.block_log;
   const bool blocked = tp.block_log > 0;
   const int64_t block_cols = blocked ? int64_t{1} << tp.block_log : INT64_MAX;
   const int cap_log_c = blocked ? std::min(tp.block_log, 10) : 10;
@@ -1573,21 +1574,26 @@ int bf_tracking_step(const bf_topology_t* t, int32_t round, const void* Y_in, vo
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_TRACK, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
 
-// Shared body of bf_atc_step and bf_atc_step_g: ld names the layout of X_in, X_out and M, ld_g that of G.
+// Shared body of bf_atc_step and bf_atc_step_layouts: ld names the layout of X_in and X_out, ld_g that
+// of G, ld_m that of M.
 static int atc_common(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
                       float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld, int64_t ld_g,
-                      bf_dtype_t dt, void* hip_stream) {
+                      int64_t ld_m, bf_dtype_t dt, void* hip_stream) {
   if (!t || !X_in || !X_out || !G) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
   if (mode != BF_ATC && mode != BF_AWC) return BF_ERR_KIND;
-  MatArgs ma, mg;
+  MatArgs ma, mg, mm;
   int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
   rc = check_matrix_shape(t->n, d, ld_g, dt, &mg, true);
   if (rc != BF_OK) return rc;
-  if ((ma.ld * 4) % 16 != 0 && M) return BF_ERR_ALIGN;
+  mm = ma;
+  if (M) {
+    rc = check_matrix_shape(t->n, d, ld_m, BF_F32, &mm, true);
+    if (rc != BF_OK) return rc;
+  }
   if (misaligned16(X_in) || misaligned16(X_out) || misaligned16(G) || (M && misaligned16(M))) return BF_ERR_ALIGN;
-  const size_t mb = ma.extent(4);
+  const size_t mb = M ? mm.bytes : 0;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   if (overlaps(G, mg.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
   if (M && (overlaps(M, mb, X_out, ma.bytes) || overlaps(M, mb, X_in, ma.bytes) || overlaps(M, mb, G, mg.bytes)))
@@ -1600,6 +1606,7 @@ static int atc_common(const bf_topology_t* t, int32_t round, const void* X_in, v
   tp.alpha = alpha; tp.beta = beta;
   tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
   tp.g_ld = mg.ld; tp.g_block_log = mg.block_log;
+  tp.m_ld = mm.ld; tp.m_block_log = mm.block_log;
   const int op = M ? (mode == BF_ATC ? OP_MOM_ATC : OP_MOM_AWC) : (mode == BF_ATC ? OP_ATC : OP_AWC);
   return run_tile(const_cast<bf_topology_t*>(t), round, op, false, tp, dt, static_cast<hipStream_t>(hip_stream));
 }
@@ -1607,13 +1614,13 @@ static int atc_common(const bf_topology_t* t, int32_t round, const void* X_in, v
 int bf_atc_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
                 float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld,
                 bf_dtype_t dt, void* hip_stream) {
-  return atc_common(t, round, X_in, X_out, G, M, alpha, beta, mode, d, ld, ld, dt, hip_stream);
+  return atc_common(t, round, X_in, X_out, G, M, alpha, beta, mode, d, ld, ld, ld, dt, hip_stream);
 }
 
-int bf_atc_step_g(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
-                  float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld, int64_t ld_g,
-                  bf_dtype_t dt, void* hip_stream) {
-  return atc_common(t, round, X_in, X_out, G, M, alpha, beta, mode, d, ld, ld_g, dt, hip_stream);
+int bf_atc_step_layouts(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                        float* M, float alpha, float beta, bf_mode_t mode, int64_t d, int64_t ld, int64_t ld_g,
+                        int64_t ld_m, bf_dtype_t dt, void* hip_stream) {
+  return atc_common(t, round, X_in, X_out, G, M, alpha, beta, mode, d, ld, ld_g, ld_m, dt, hip_stream);
 }
 
 int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,

@@ -84,7 +84,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
         xr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.x_in + off * EB));
         if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g + g_offset(p, row, col) * EB));
         if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g2 + g_offset(p, row, col) * EB));
-        if constexpr (STAGE_M) mr[k] = ld_stream<STREAM>(reinterpret_cast<const f32x4*>(p.m + off));
+        if constexpr (STAGE_M) mr[k] = ld_stream<STREAM>(reinterpret_cast<const f32x4*>(p.m + m_offset(p, row, col)));
       }
 #pragma unroll
       for (int k = 0; k < U; ++k) {
@@ -102,7 +102,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
             float sv[4] = {mr[k].x, mr[k].y, mr[k].z, mr[k].w};
             local_update4<OP>(xv, gv, sv, p.alpha, p.beta);
             if (live) {
-              float* mp = p.m + static_cast<int64_t>(row) * ld + col + t0;
+              float* mp = p.m + m_offset(p, row, col);
               const int64_t rem = d - col;
               if (rem >= 4) { f32x4 t = {sv[0], sv[1], sv[2], sv[3]}; st_stream<STREAM>(reinterpret_cast<f32x4*>(mp), t); }
               else for (int e = 0; e < 4; ++e) if (e < rem) mp[e] = sv[e];
@@ -195,10 +195,10 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
           load_in<DT, LW>(p.g, g_offset(p, i, col), gv);
           if constexpr (OP == OP_MOM_AWC) {
             float mv[LW];
-            load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), off, mv);
+            load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), m_offset(p, i, col), mv);
 #pragma unroll
             for (int e = 0; e < LW; ++e) gv[e] = fmaf(p.beta, mv[e], gv[e]);
-            store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), off, gv, valid);
+            store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), m_offset(p, i, col), gv, valid);
           }
 #pragma unroll
           for (int e = 0; e < LW; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);

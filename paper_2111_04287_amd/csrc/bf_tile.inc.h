@@ -52,7 +52,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + g_offset(p, row, col) * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
-        for (int q = 0; q < MV; ++q) mr[k * MV + q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+        for (int q = 0; q < MV; ++q) mr[k * MV + q] = *reinterpret_cast<const f32x4*>(p.m + m_offset(p, row, col) + 4 * q);
       }
     }
   };
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       float gv[UC];
       widen<DT>(graw, gv);
       if constexpr (STAGE_M) {
-        const int64_t off = static_cast<int64_t>(row) * ld + col + tile_origin(p, c0);
+        const int64_t off = m_offset(p, row, col);
 #pragma unroll
         for (int q = 0; q < MV; ++q) {
           float sv[4] = {mraw[q].x, mraw[q].y, mraw[q].z, mraw[q].w};
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
       if constexpr (STAGE_G2) g2raw = ld_stream<STREAM>(reinterpret_cast<const u32x4*>(p.g2 + g_offset(p, row, col) * EB));
       if constexpr (STAGE_M) {
 #pragma unroll
-        for (int q = 0; q < MV; ++q) mraw[q] = *reinterpret_cast<const f32x4*>(p.m + off + 4 * q);
+        for (int q = 0; q < MV; ++q) mraw[q] = *reinterpret_cast<const f32x4*>(p.m + m_offset(p, row, col) + 4 * q);
       }
       stage_unit(u, c0, xraw, graw, g2raw, mraw);
     }
@@ -205,10 +205,10 @@ __global__ __launch_bounds__(THREADS) void bf_tile_kernel(const TileParams p) {
           load_in<DT, LW>(p.g, g_offset(p, i, col), gv);
           if constexpr (OP == OP_MOM_AWC) {
             float mv[LW];
-            load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), off, mv);
+            load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), m_offset(p, i, col), mv);
 #pragma unroll
             for (int e = 0; e < LW; ++e) gv[e] = fmaf(p.beta, mv[e], gv[e]);
-            store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), off, gv, valid);
+            store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), m_offset(p, i, col), gv, valid);
           }
 #pragma unroll
           for (int e = 0; e < LW; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);

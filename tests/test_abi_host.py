@@ -381,12 +381,15 @@ def test_column_block_layout_argument_checks():
     at = L.bf_atc_step
     assert at(h, 0, A, A, G, A + 512, 0.1, 0.9, bf.BF_ATC, 100, -64, bf.BF_BF16, None) == bf.BF_ERR_ALIAS
     assert at(h, 0, A, A, G, G + 1024, 0.1, 0.9, bf.BF_ATC, 100, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS    # M inside G (2048 bytes)
-    ag = L.bf_atc_step_g
-    assert ag(h, 0, A, A, None, None, 0.1, 0.0, bf.BF_ATC, 100, -64, 104, bf.BF_F32, None) == bf.BF_ERR_NULL
-    assert ag(h, 0, A, A, G, None, 0.1, 0.0, bf.BF_ATC, 100, -64, 96, bf.BF_F32, None) == bf.BF_ERR_SIZE      # ld_g < d
-    assert ag(h, 0, A, A, G, None, 0.1, 0.0, bf.BF_ATC, 100, -64, -100, bf.BF_F32, None) == bf.BF_ERR_SIZE
-    assert ag(h, 0, A, A, A + 1024, None, 0.1, 0.0, bf.BF_ATC, 100, -64, 104, bf.BF_F32, None) == bf.BF_ERR_ALIAS   # G inside X_out
-    assert ag(h, 0, A, A, G, G + 256, 0.1, 0.9, bf.BF_ATC, 100, -64, 104, bf.BF_F32, None) == bf.BF_ERR_ALIAS       # M inside G's rows
+    ag = L.bf_atc_step_layouts
+    assert ag(h, 0, A, A, None, None, 0.1, 0.0, bf.BF_ATC, 100, -64, 104, 104, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert ag(h, 0, A, A, G, None, 0.1, 0.0, bf.BF_ATC, 100, -64, 96, 104, bf.BF_F32, None) == bf.BF_ERR_SIZE      # ld_g < d
+    assert ag(h, 0, A, A, G, None, 0.1, 0.0, bf.BF_ATC, 100, -64, -100, 104, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert ag(h, 0, A, A, G, M, 0.1, 0.9, bf.BF_ATC, 100, 104, 104, -100, bf.BF_F32, None) == bf.BF_ERR_SIZE        # ld_m
+    assert ag(h, 0, A, A, G, M, 0.1, 0.9, bf.BF_ATC, 100, 104, 104, 102, bf.BF_BF16, None) == bf.BF_ERR_ALIGN       # M is fp32: 408-byte rows
+    assert ag(h, 0, A, A, A + 1024, None, 0.1, 0.0, bf.BF_ATC, 100, -64, 104, 104, bf.BF_F32, None) == bf.BF_ERR_ALIAS   # G inside X_out
+    assert ag(h, 0, A, A, G, G + 256, 0.1, 0.9, bf.BF_ATC, 100, -64, 104, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS       # M inside G's rows
+    assert ag(h, 0, A, A, G, A + 1600, 0.1, 0.9, bf.BF_ATC, 100, 104, 104, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS      # M (blocks) inside X (rows)
     pk, up = L.bf_blocked_pack, L.bf_blocked_unpack
     assert pk(4, 100, 104, None, 64, B, bf.BF_F32, None) == bf.BF_ERR_NULL
     assert pk(4, 100, 104, A, 100, B, bf.BF_F32, None) == bf.BF_ERR_SIZE

@@ -433,9 +433,9 @@ def test_gradient_generator_and_diagnostics_on_column_blocks(dtype, n, d, B):
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("n,d,B", [(5, 300, 64), (32, 3 * 512 + 37, 512), (64, 9000, 8192), (300, 200, 64), (700, 150, 64)])
 @pytest.mark.parametrize("kind", [bf.BF_EXP_STATIC, bf.BF_RING])
-def test_gradient_in_a_layout_of_its_own(dtype, n, d, B, kind):
-    """State in column blocks with the gradient on agent-major rows, and the other way round: the
-    bits of the all-agent-major call, for ATC, AWC and both momentum forms, in place and not."""
+def test_a_layout_per_matrix(dtype, n, d, B, kind):
+    """Every mix of agent-major rows and column blocks for (X, G, M): the bits of the all-agent-major
+    call, for ATC, AWC and both momentum forms, in place and not."""
     t = bf.bf_topology_create(kind, n)
     X, G = rows(n, d, 140, dtype=dtype), rows(n, d, 141, dtype=dtype)
     M0 = workloads.normal_rows(n, d, 142, DEV, ld=X.stride(0))
@@ -452,18 +452,15 @@ def test_gradient_in_a_layout_of_its_own(dtype, n, d, B, kind):
                     for in_place in (False, True):
                         xi = fresh(X); xo = xi if in_place else fresh(X); m = fresh(M0) if with_m else None
                         bf.bf_atc_step(t, 1, xi, xo, G, m, alpha=0.05, beta=0.9, mode=mode)
-                        # state in blocks, G on rows
-                        bi = to_blocked(X, B); bo = bi if in_place else empty_blocked(n, d, B, dtype)
-                        bm = to_blocked(M0, B) if with_m else None
-                        bf.bf_atc_step_g(t, 1, bi, bo, G, bm, alpha=0.05, beta=0.9, mode=mode)
-                        assert torch.equal(from_blocked(bo, X), xo)
-                        if with_m:
-                            assert torch.equal(from_blocked(bm, M0), m)
-                        # state on rows, G in blocks
-                        yi = fresh(X); yo = yi if in_place else fresh(X); ym = fresh(M0) if with_m else None
-                        bf.bf_atc_step_g(t, 1, yi, yo, Gb, ym, alpha=0.05, beta=0.9, mode=mode)
-                        assert torch.equal(yo, xo)
-                        if with_m:
-                            assert torch.equal(ym, m)
+                        for xb, gb, mb in ((1, 0, 1), (0, 1, 0), (0, 0, 1), (1, 1, 0), (1, 0, 0), (0, 1, 1)):
+                            if not with_m and (xb, gb, mb) in ((0, 0, 1), (1, 1, 0), (0, 1, 1)):
+                                continue                          # the same call as another one without M
+                            yi = to_blocked(X, B) if xb else fresh(X)
+                            yo = yi if in_place else (empty_blocked(n, d, B, dtype) if xb else fresh(X))
+                            ym = None if not with_m else (to_blocked(M0, B) if mb else fresh(M0))
+                            bf.bf_atc_step_layouts(t, 1, yi, yo, Gb if gb else G, ym, alpha=0.05, beta=0.9, mode=mode)
+                            assert torch.equal(from_blocked(yo, X) if xb else yo, xo), (xb, gb, mb, mode, with_m, in_place)
+                            if with_m:
+                                assert torch.equal(from_blocked(ym, M0) if mb else ym, m), (xb, gb, mb, mode, in_place)
         finally:
             bf.bf_set_tuning(6, 0)
