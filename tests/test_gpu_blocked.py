@@ -464,3 +464,51 @@ def test_a_layout_per_matrix(dtype, n, d, B, kind):
                                 assert torch.equal(from_blocked(ym, M0) if mb else ym, m), (xb, gb, mb, mode, in_place)
         finally:
             bf.bf_set_tuning(6, 0)
+
+
+@pytest.mark.parametrize("config", ["c2", "c3", "c4", "hier"])
+def test_full_size_configs_in_column_blocks_give_the_agent_major_bits(config):
+    """Configs 2, 3 and 4 and the hierarchical pass at the benchmark's sizes and block widths (the
+    launch configurations bench.py times): three rounds in column blocks equal the same rounds on
+    agent-major rows bit for bit; tests/test_gpu_fullsize.py holds the latter against the oracle."""
+    if config == "c2":
+        n, d = 64, 1 << 20
+        t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+        step = lambda k, a, b: bf.bf_neighbor_allreduce(t, k, a, b)
+        in_place = False
+    elif config == "c3":
+        n, d = 256, 1 << 22
+        t = bf.bf_topology_create(bf.BF_EXP2_ONE_PEER, n)
+        step = lambda k, a, b: bf.bf_neighbor_allreduce(t, k, a, b)
+        in_place = True
+    elif config == "c4":
+        n, d = 128, 1 << 21
+        t = bf.bf_topology_create(bf.BF_RANDOM_DIRECTED, n, out_degree=4, seed=workloads.CONFIG4_GRAPH_SEED)
+        in_place = True
+    else:
+        n, d = 64, 1 << 22
+        t = bf.bf_topology_create(bf.BF_EXP_STATIC, 8)
+        step = lambda k, a, b: bf.bf_hierarchical_neighbor_allreduce(t, k, 8, a, b)
+        in_place = True
+    B = 16384 if config == "hier" else bf.bf_recommended_block(t, d, bf.BF_F32)
+    ld = bf.bf_recommended_ld(d, bf.BF_F32)
+    X = workloads.normal_rows(n, d, 150, DEV, ld=ld)
+    Xb = to_blocked(X, B)
+    Y = X if in_place else workloads.alloc_rows(n, d, torch.float32, DEV, ld=ld)
+    Yb = Xb if in_place else empty_blocked(n, d, B, torch.float32)
+    if config == "c4":
+        w1, w2 = torch.ones(n, device=DEV), torch.ones(n, device=DEV)
+    cur, curb, nxt, nxtb = X, Xb, Y, Yb
+    for k in range(3):
+        if config == "c4":
+            bf.bf_pushsum_step(t, k, cur, nxt, w1, w1, None)
+            bf.bf_pushsum_step(t, k, curb, nxtb, w2, w2, None)
+        else:
+            step(k, cur, nxt)
+            step(k, curb, nxtb)
+        cur, curb, nxt, nxtb = nxt, nxtb, cur, curb
+    back = workloads.alloc_rows(n, d, torch.float32, DEV, ld=ld)
+    bf.bf_blocked_unpack(curb, back)
+    assert torch.equal(back, cur)
+    if config == "c4":
+        assert torch.equal(w1, w2)
