@@ -173,6 +173,7 @@ def main():
     mixed5 = None
     mom5 = None
     if not args.no_extra:
+        bf.bf_blocked_pack(G5, G5b)        # (unchanged data: a marker between the legs in a kernel trace)
         # state in column blocks, each agent's gradient as it arrives from a per-agent producer: one
         # contiguous vector (agent-major rows)
         w5m, e5m = timed(lambda k: bf.bf_atc_step_layouts(t5, k, X5b, X5b, G5, M5b, c5["alpha"], c5["beta"], bf.BF_ATC),
@@ -180,8 +181,9 @@ def main():
         mixed5 = {"ms_per_step": round(w5m * 1e3 / min(args.steps, 100), 5), "steps": min(args.steps, 100), "block": B5, "ld_g": ld5,
                   "effective_GBps": round(bytes5 * min(args.steps, 100) / w5m / 1e9, 1),
                   "pct_of_hbm_peak": round(100 * bytes5 * min(args.steps, 100) / w5m / 1e9 / HBM_PEAK_GBPS, 2),
-                  "roofline": roofline("bf_pipe_kernel<bf16, momentum ATC>", bytes5, e5m, "config5_momentum_atc_column_blocks",
+                  "roofline": roofline("bf_pipe_kernel<bf16, momentum ATC>", bytes5, e5m, "config5_momentum_atc_state_blocks_gradient_rows",
                                        note="bf_atc_step_layouts: X and M in column blocks, G on agent-major rows")}
+        bf.bf_blocked_pack(G5, G5b)
         # parameters and gradients as per-agent vectors (agent-major rows), only the momentum, which no
         # one but the library reads, in column blocks
         w5o, e5o = timed(lambda k: bf.bf_atc_step_layouts(t5, k, X5, X5, G5, M5b, c5["alpha"], c5["beta"], bf.BF_ATC),
@@ -189,7 +191,7 @@ def main():
         mom5 = {"ms_per_step": round(w5o * 1e3 / min(args.steps, 100), 5), "steps": min(args.steps, 100), "block": B5, "ld": ld5,
                 "effective_GBps": round(bytes5 * min(args.steps, 100) / w5o / 1e9, 1),
                 "pct_of_hbm_peak": round(100 * bytes5 * min(args.steps, 100) / w5o / 1e9 / HBM_PEAK_GBPS, 2),
-                "roofline": roofline("bf_pipe_kernel<bf16, momentum ATC>", bytes5, e5o, "config5_momentum_atc",
+                "roofline": roofline("bf_pipe_kernel<bf16, momentum ATC>", bytes5, e5o, "config5_momentum_atc_momentum_blocks",
                                      note="bf_atc_step_layouts: X and G on agent-major rows, M in column blocks")}
         # the agent-major leg goes on from the state the column-block leg reached
         bf.bf_blocked_unpack(X5b, X5)
