@@ -213,3 +213,32 @@ def test_window_pushsum_round_full_size():
         assert np.abs(got_w - rw).max() <= 1e-5 * max(np.abs(rw).max(), np.abs(rx).max())
         np.testing.assert_allclose(p.cpu().numpy(), rp, rtol=1e-5)
     assert abs(float(p.double().sum() + win_p.double().sum()) - n) < 1e-4
+
+
+def test_more_than_two_to_the_31_columns():
+    """Column indices beyond 32 bits: two agents on a ring (weights 1/2, 1/2), d = 2^31 + 1000, fp32,
+    on agent-major rows and in column blocks; constant rows with three marked columns."""
+    n, d = 2, (1 << 31) + 1000
+    t = bf.bf_topology_create(bf.BF_RING, n)
+    ld = bf.bf_recommended_ld(d, bf.BF_F32)
+    X = torch.empty((n, ld), device=DEV)[:, :d]
+    X[0].fill_(1.0)
+    X[1].fill_(3.0)
+    marks = {d - 1: (5.0, 9.0), (1 << 31) + 7: (-1.0, 3.0), 1 << 31: (1.0, 3.0), 0: (1.0, 3.0), 12345678: (1.0, 3.0)}
+    for c, (a, b) in marks.items():
+        X[0, c] = a
+        X[1, c] = b
+    out = torch.empty((n, ld), device=DEV)[:, :d]
+    bf.bf_neighbor_allreduce(t, 0, X, out)
+    for c, (a, b) in marks.items():
+        assert float(out[0, c]) == (a + b) / 2 and float(out[1, c]) == (a + b) / 2, c
+    B = 16384
+    Xb = bf.Blocked(torch.empty(((d + B - 1) // B, n, B), device=DEV), d)
+    bf.bf_blocked_pack(X, Xb)
+    bf.bf_neighbor_allreduce(t, 0, Xb, Xb)
+    out.fill_(0.0)
+    bf.bf_blocked_unpack(Xb, out)
+    for c, (a, b) in marks.items():
+        assert float(out[0, c]) == (a + b) / 2 and float(out[1, c]) == (a + b) / 2, c
+    st = bf.bf_consensus_stats(out)
+    assert float(st[0]) == 0.0 and float(st[2]) == 7.0           # both rows equal everywhere; the largest value is (5 + 9) / 2
