@@ -342,6 +342,13 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
                             const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
                             bf_dtype_t dt, void* hip_stream);
 
+/* bf_exact_diffusion_step with a layout per matrix, as bf_atc_step_layouts: ld describes X_in and
+ * X_out, ld_g describes G, ld_p describes Psi_prev (the state only this call reads: the one to keep in
+ * column blocks next to per-agent parameter and gradient vectors). */
+int bf_exact_diffusion_step_layouts(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                                    const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
+                                    int64_t ld_g, int64_t ld_p, bf_dtype_t dt, void* hip_stream);
+
 /* Decentralized gradient descent on least squares (section "Decentralized linear regression",
  * eqs. dgd-1 and dgd-2; the adapt-then-combine form of bf_grad_least_squares + bf_atc_step):
  * `iterations` iterations in ONE launch,

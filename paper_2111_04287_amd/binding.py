@@ -30,7 +30,7 @@ EXPORTS = [
     "bf_topology_rounds", "bf_topology_nnz", "bf_topology_max_degree", "bf_topology_class",
     "bf_topology_export_csr", "bf_topology_chain_plan", "bf_topology_window_slots", "bf_topology_export_window",
     "bf_win_put", "bf_win_get", "bf_win_accumulate", "bf_win_put_weighted", "bf_win_get_weighted", "bf_win_accumulate_weighted", "bf_win_update_weighted", "bf_dgd_least_squares_run", "bf_dgd_least_squares_run_static", "bf_exact_diffusion_least_squares_run", "bf_dgd_status", "bf_stream_probe", "bf_win_update", "bf_win_update_then_collect", "bf_neighbor_allreduce", "bf_neighbor_allreduce_multi", "bf_hierarchical_neighbor_allreduce", "bf_dense_mix", "bf_pushsum_step", "bf_pushsum_atc_step", "bf_tracking_step",
-    "bf_atc_step", "bf_atc_step_layouts", "bf_exact_diffusion_step", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
+    "bf_atc_step", "bf_atc_step_layouts", "bf_exact_diffusion_step", "bf_exact_diffusion_step_layouts", "bf_grad_least_squares", "bf_grad_quadratic", "bf_consensus_stats",
     "bf_strerror", "bf_last_hip_error", "bf_set_tuning", "bf_recommended_ld",
     "bf_blocked_elems", "bf_recommended_block", "bf_blocked_pack", "bf_blocked_unpack",
 ]
@@ -112,6 +112,7 @@ def _load():
     L.bf_atc_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, f32, C.c_int, i64, i64, C.c_int, vp]
     L.bf_atc_step_layouts.argtypes = [vp, i32, vp, vp, vp, vp, f32, f32, C.c_int, i64, i64, i64, i64, C.c_int, vp]
     L.bf_exact_diffusion_step.argtypes = [vp, i32, vp, vp, vp, vp, f32, i64, i64, C.c_int, vp]
+    L.bf_exact_diffusion_step_layouts.argtypes = [vp, i32, vp, vp, vp, vp, f32, i64, i64, i64, i64, C.c_int, vp]
     L.bf_grad_least_squares.argtypes = [i32, i32, i64, vp, vp, vp, i64, vp, i64, vp]
     L.bf_grad_quadratic.argtypes = [i32, i64, i64, vp, vp, vp, f32, f32, vp, C.c_int, vp]
     L.bf_consensus_stats.argtypes = [i32, i64, i64, vp, vp, C.c_int, vp, vp, vp]
@@ -580,6 +581,21 @@ def bf_exact_diffusion_step(t, rnd, X_in, X_out, G, Psi_prev, alpha, stream=None
         raise ValueError("Psi_prev must be float32 with the shape and row stride of X_in")
     _check(lib.bf_exact_diffusion_step(t.handle, rnd, ptr, X_out.data_ptr(), G.data_ptr(), Psi_prev.data_ptr(),
                                        alpha, d, ld, _dtype_code(X_in), _stream(stream)), "bf_exact_diffusion_step")
+    return X_out
+
+
+def bf_exact_diffusion_step_layouts(t, rnd, X_in, X_out, G, Psi_prev, alpha, stream=None):
+    """bf_exact_diffusion_step with a layout per matrix (X_in/X_out, G, Psi_prev: tensor or Blocked each)."""
+    import torch
+    ptr, n, d, ld = _mat(X_in, "X_in")
+    _rows(t, n)
+    _same_layout(X_in, X_out, "X_out")
+    gptr, gn, gd, ld_g = _mat(G, "G")
+    pptr, pn, pd, ld_p = _mat(Psi_prev, "Psi_prev")
+    if (gn, gd) != (n, d) or G.dtype != X_in.dtype or (pn, pd) != (n, d) or Psi_prev.dtype != torch.float32:
+        raise ValueError("G must have the shape and dtype of X_in, Psi_prev its shape in float32")
+    _check(lib.bf_exact_diffusion_step_layouts(t.handle, rnd, ptr, X_out.data_ptr(), gptr, pptr, alpha, d, ld, ld_g, ld_p,
+                                               _dtype_code(X_in), _stream(stream)), "bf_exact_diffusion_step_layouts")
     return X_out
 
 

@@ -1623,20 +1623,25 @@ int bf_atc_step_layouts(const bf_topology_t* t, int32_t round, const void* X_in,
   return atc_common(t, round, X_in, X_out, G, M, alpha, beta, mode, d, ld, ld_g, ld_m, dt, hip_stream);
 }
 
-int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
-                            const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
-                            bf_dtype_t dt, void* hip_stream) {
+// Shared body of bf_exact_diffusion_step and its _layouts form: ld names the layout of X_in and X_out,
+// ld_g that of G, ld_p that of Psi_prev.
+static int ed_common(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out, const void* G,
+                     float* Psi_prev, float alpha, int64_t d, int64_t ld, int64_t ld_g, int64_t ld_p,
+                     bf_dtype_t dt, void* hip_stream) {
   if (!t || !X_in || !X_out || !G || !Psi_prev) return BF_ERR_NULL;
   if (round < 0) return BF_ERR_ROUND;
-  MatArgs ma;
+  MatArgs ma, mg, mp;
   int rc = check_matrix_shape(t->n, d, ld, dt, &ma, true);
   if (rc != BF_OK) return rc;
-  if ((ma.ld * 4) % 16 != 0) return BF_ERR_ALIGN;
+  rc = check_matrix_shape(t->n, d, ld_g, dt, &mg, true);
+  if (rc != BF_OK) return rc;
+  rc = check_matrix_shape(t->n, d, ld_p, BF_F32, &mp, true);
+  if (rc != BF_OK) return rc;
   if (misaligned16(X_in) || misaligned16(X_out) || misaligned16(G) || misaligned16(Psi_prev)) return BF_ERR_ALIGN;
-  const size_t pb = ma.extent(4);
+  const size_t pb = mp.bytes;
   if (X_in != X_out && overlaps(X_in, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
-  if (overlaps(G, ma.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
-  if (overlaps(Psi_prev, pb, X_out, ma.bytes) || overlaps(Psi_prev, pb, X_in, ma.bytes) || overlaps(Psi_prev, pb, G, ma.bytes))
+  if (overlaps(G, mg.bytes, X_out, ma.bytes)) return BF_ERR_ALIAS;
+  if (overlaps(Psi_prev, pb, X_out, ma.bytes) || overlaps(Psi_prev, pb, X_in, ma.bytes) || overlaps(Psi_prev, pb, G, mg.bytes))
     return BF_ERR_ALIAS;
   TileParams tp{};
   tp.x_in = static_cast<const char*>(X_in);
@@ -1645,7 +1650,21 @@ int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X
   tp.m = Psi_prev;
   tp.alpha = alpha;
   tp.d = d; tp.ld = ma.ld; tp.block_log = ma.block_log;
+  tp.g_ld = mg.ld; tp.g_block_log = mg.block_log;
+  tp.m_ld = mp.ld; tp.m_block_log = mp.block_log;
   return run_tile(const_cast<bf_topology_t*>(t), round, OP_ED, false, tp, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int bf_exact_diffusion_step(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                            const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
+                            bf_dtype_t dt, void* hip_stream) {
+  return ed_common(t, round, X_in, X_out, G, Psi_prev, alpha, d, ld, ld, ld, dt, hip_stream);
+}
+
+int bf_exact_diffusion_step_layouts(const bf_topology_t* t, int32_t round, const void* X_in, void* X_out,
+                                    const void* G, float* Psi_prev, float alpha, int64_t d, int64_t ld,
+                                    int64_t ld_g, int64_t ld_p, bf_dtype_t dt, void* hip_stream) {
+  return ed_common(t, round, X_in, X_out, G, Psi_prev, alpha, d, ld, ld_g, ld_p, dt, hip_stream);
 }
 
 // static_scratch: the half steps and barrier words live in the library's static device array and

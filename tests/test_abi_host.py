@@ -390,6 +390,10 @@ def test_column_block_layout_argument_checks():
     assert ag(h, 0, A, A, A + 1024, None, 0.1, 0.0, bf.BF_ATC, 100, -64, 104, 104, bf.BF_F32, None) == bf.BF_ERR_ALIAS   # G inside X_out
     assert ag(h, 0, A, A, G, G + 256, 0.1, 0.9, bf.BF_ATC, 100, -64, 104, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS       # M inside G's rows
     assert ag(h, 0, A, A, G, A + 1600, 0.1, 0.9, bf.BF_ATC, 100, 104, 104, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS      # M (blocks) inside X (rows)
+    el = L.bf_exact_diffusion_step_layouts
+    assert el(h, 0, A, A, G, None, 0.1, 100, 104, 104, -64, bf.BF_F32, None) == bf.BF_ERR_NULL
+    assert el(h, 0, A, A, G, M, 0.1, 100, 104, 104, -100, bf.BF_F32, None) == bf.BF_ERR_SIZE
+    assert el(h, 0, A, A, G, G + 1024, 0.1, 100, 104, -64, -64, bf.BF_F32, None) == bf.BF_ERR_ALIAS
     pk, up = L.bf_blocked_pack, L.bf_blocked_unpack
     assert pk(4, 100, 104, None, 64, B, bf.BF_F32, None) == bf.BF_ERR_NULL
     assert pk(4, 100, 104, A, 100, B, bf.BF_F32, None) == bf.BF_ERR_SIZE

@@ -462,6 +462,17 @@ def test_a_layout_per_matrix(dtype, n, d, B, kind):
                             assert torch.equal(from_blocked(yo, X) if xb else yo, xo), (xb, gb, mb, mode, with_m, in_place)
                             if with_m:
                                 assert torch.equal(from_blocked(ym, M0) if mb else ym, m), (xb, gb, mb, mode, in_place)
+            # Exact-Diffusion: psi of the step before is the state
+            for in_place in (False, True):
+                xi = fresh(X); xo = xi if in_place else fresh(X); ps = fresh(M0)
+                bf.bf_exact_diffusion_step(t, 1, xi, xo, G, ps, 0.05)
+                for xb, gb, pb in ((0, 0, 1), (1, 0, 1), (0, 1, 0), (1, 1, 0)):
+                    yi = to_blocked(X, B) if xb else fresh(X)
+                    yo = yi if in_place else (empty_blocked(n, d, B, dtype) if xb else fresh(X))
+                    yp = to_blocked(M0, B) if pb else fresh(M0)
+                    bf.bf_exact_diffusion_step_layouts(t, 1, yi, yo, Gb if gb else G, yp, 0.05)
+                    assert torch.equal(from_blocked(yo, X) if xb else yo, xo), (xb, gb, pb, in_place)
+                    assert torch.equal(from_blocked(yp, M0) if pb else yp, ps), (xb, gb, pb, in_place)
         finally:
             bf.bf_set_tuning(6, 0)
 
