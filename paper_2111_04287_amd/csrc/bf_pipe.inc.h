@@ -138,71 +138,98 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   const csr_i32_ptr rowptr = (csr_i32_ptr)(uintptr_t)p.rowptr;
   const csr_ent_ptr ent = (csr_ent_ptr)(uintptr_t)p.ent;
 
+  auto where = [&](int op, int* i, int* cit) {
+    *i = op >> spans_log;
+    *cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
+  };
+  // Adapt-while-communicate: the receiver's own gradient (and momentum) values, which the reducers
+  // read from HBM themselves.  A wave's memory operations complete in issue order, so waiting for a
+  // value just requested also waits for every store before it.  The values are therefore requested
+  // two ops ahead, across tile boundaries, into two register sets used in turn (ga/ma by a wave's
+  // even ops of a tile, gb/mb by its odd ones; every wave is given an even number of ops per tile,
+  // those past the tile's end being empty): a store then has two ops' time to complete before
+  // anything waits behind it.  Like the loaders' reads, a request is not predicated: a column at or
+  // past d re-reads the row's last vector.
+  constexpr bool AWC = (OP == OP_AWC || OP == OP_MOM_AWC);
+  const int nops_even = (nops + 2 * NR - 1) / (2 * NR) * (2 * NR);
+  const int64_t last_own = d > 0 ? (d - 1) / LW * LW : 0;
+  [[maybe_unused]] float ga[LW], gb[LW], ma[LW], mb[LW];
+  auto fetch_own = [&](int64_t tile, int op, float* gv, float* mv) {
+    // (an empty op still issues its request, so that the number of requests in flight at each wait is
+    // the same on every path and known to the compiler; all its lanes read one and the same vector)
+    int i, cit;
+    where(min(op, nops - 1), &i, &cit);
+    if (op >= nops) cit -= lane * LW;
+    const int64_t col = min((tile << log_c) + cit, last_own);
+    load_in<DT, LW>(p.g, g_offset(p, i, col), gv);
+    if constexpr (OP == OP_MOM_AWC) load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), m_offset(p, i, col), mv);
+  };
+
   // Output rows of one tile: reducer wave w takes the (row, 64*LW-column span) pairs w, w+NR, ...
   // Each is the weighted sum over the row's in-neighbor list, read from the LDS tile in list order
   // with fp32 accumulation; the list comes through the scalar cache, and entries go in batches of
   // four (then two, then one) so that a wave waits once per batch of LDS reads.
-  auto reduce_tile = [&](int64_t tile, const float* buf) {
+  // `next_tile`: the tile this workgroup reduces after this one (this one again if it is the last).
+  auto reduce_tile = [&](int64_t tile, int64_t next_tile, const float* buf) {
     const int64_t c0 = tile << log_c;
     const bool full = c0 + (int64_t{1} << log_c) <= d;      // no ragged tail in this tile
     const int64_t t0 = tile_origin(p, c0);
-    for (int op = wave - NL; op < nops; op += NR) {
-      const int i = op >> spans_log;
-      const int cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
-      const int64_t col = c0 + cit;
-      const int beg = rowptr[i], end = rowptr[i + 1];
-      float acc[LW];
+    // one batch of K list entries of one row: K LDS vectors, then K x LW FMAs in list order
+    auto batch = [&](const float* src, float* acc, int q, auto kc) {
+      constexpr int K = decltype(kc)::value;
+      u32x2 en[K];
+#pragma unroll
+      for (int u = 0; u < K; ++u) en[u] = ent[q + u];
+      float v[K][LW];
+#pragma unroll
+      for (int u = 0; u < K; ++u) {
+        const float* sp = src + (static_cast<int>(en[u].x) << log_c);
+        if constexpr (LW == 4) {
+          const f32x4 t = *reinterpret_cast<const f32x4*>(sp);
+          v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
+        } else if constexpr (LW == 2) {
+          const f32x2 t = *reinterpret_cast<const f32x2*>(sp);
+          v[u][0] = t.x; v[u][1] = t.y;
+        } else {
+          v[u][0] = sp[0];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < K; ++u) {
+        const float w = __uint_as_float(en[u].y);
+#pragma unroll
+        for (int e = 0; e < LW; ++e) acc[e] = fmaf(w, v[u][e], acc[e]);
+      }
+    };
+    auto rest = [&](const float* src, float* acc, int q, int end) {
+      for (; q + 4 <= end; q += 4) batch(src, acc, q, std::integral_constant<int, 4>{});
+      if (q + 2 <= end) { batch(src, acc, q, std::integral_constant<int, 2>{}); q += 2; }
+      if (q < end) batch(src, acc, q, std::integral_constant<int, 1>{});
+    };
+    // One output vector: the weighted sum, minus the own gradient step (AWC); mn is the new momentum.
+    auto reduce_one = [&](int op, const float* gv, const float* mv, float* acc, float* mn) {
+      int i, cit;
+      where(op, &i, &cit);
 #pragma unroll
       for (int e = 0; e < LW; ++e) acc[e] = 0.0f;
-      const float* src = buf + cit;
-      auto batch = [&](int q, auto kc) {
-        constexpr int K = decltype(kc)::value;
-        u32x2 en[K];
+      rest(buf + cit, acc, rowptr[i], rowptr[i + 1]);
+      if constexpr (AWC) {
 #pragma unroll
-        for (int u = 0; u < K; ++u) en[u] = ent[q + u];
-        float v[K][LW];
-#pragma unroll
-        for (int u = 0; u < K; ++u) {
-          const float* sp = src + (static_cast<int>(en[u].x) << log_c);
-          if constexpr (LW == 4) {
-            const f32x4 t = *reinterpret_cast<const f32x4*>(sp);
-            v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
-          } else if constexpr (LW == 2) {
-            const f32x2 t = *reinterpret_cast<const f32x2*>(sp);
-            v[u][0] = t.x; v[u][1] = t.y;
-          } else {
-            v[u][0] = sp[0];
-          }
+        for (int e = 0; e < LW; ++e) {
+          mn[e] = OP == OP_MOM_AWC ? fmaf(p.beta, mv[e], gv[e]) : gv[e];
+          acc[e] = fmaf(-p.alpha, mn[e], acc[e]);
         }
-#pragma unroll
-        for (int u = 0; u < K; ++u) {
-          const float w = __uint_as_float(en[u].y);
-#pragma unroll
-          for (int e = 0; e < LW; ++e) acc[e] = fmaf(w, v[u][e], acc[e]);
-        }
-      };
-      int q = beg;
-      for (; q + 4 <= end; q += 4) batch(q, std::integral_constant<int, 4>{});
-      if (q + 2 <= end) { batch(q, std::integral_constant<int, 2>{}); q += 2; }
-      if (q < end) batch(q, std::integral_constant<int, 1>{});
+      }
+    };
+    auto store_one = [&](int op, const float* acc, const float* mn) {
+      int i, cit;
+      where(op, &i, &cit);
+      const int64_t col = c0 + cit;
       if (full || col < d) {
         const int64_t rem = d - col;
         const int valid = (full || rem >= LW) ? LW : static_cast<int>(rem);
         const int64_t off = static_cast<int64_t>(i) * ld + col + t0;
-        if constexpr (OP == OP_AWC || OP == OP_MOM_AWC) {
-          // Adapt-while-communicate: the receiver's own gradient is subtracted after the mix.
-          float gv[LW];
-          load_in<DT, LW>(p.g, g_offset(p, i, col), gv);
-          if constexpr (OP == OP_MOM_AWC) {
-            float mv[LW];
-            load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), m_offset(p, i, col), mv);
-#pragma unroll
-            for (int e = 0; e < LW; ++e) gv[e] = fmaf(p.beta, mv[e], gv[e]);
-            store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), m_offset(p, i, col), gv, valid);
-          }
-#pragma unroll
-          for (int e = 0; e < LW; ++e) acc[e] = fmaf(-p.alpha, gv[e], acc[e]);
-        }
+        if constexpr (OP == OP_MOM_AWC) store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), m_offset(p, i, col), mn, valid);
         store_out<DT, LW, STREAM>(p.x_out, off, acc, valid);
         if constexpr (WITH_Y) {
           const float rcp = 1.0f / p.p_out[i];
@@ -212,28 +239,61 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
           store_out<DT, LW, STREAM>(p.y, off, yv, valid);
         }
       }
+    };
+    if constexpr (AWC) {
+      float acc[LW], mn[LW];
+      auto ahead = [&](int op, float* gv, float* mv) {      // the op two after `op` in this wave's sequence
+        const int nx = op + 2 * NR;
+        const bool here = nx < nops_even;
+        fetch_own(here ? tile : next_tile, here ? nx : nx - nops_even, gv, mv);
+      };
+      for (int op = wave - NL; op < nops_even; op += 2 * NR) {
+        const bool first = op < nops, second = op + NR < nops;
+        if (first) reduce_one(op, ga, ma, acc, mn);
+        ahead(op, ga, ma);
+        if (first) store_one(op, acc, mn);
+        if (second) reduce_one(op + NR, gb, mb, acc, mn);
+        ahead(op + NR, gb, mb);
+        if (second) store_one(op + NR, acc, mn);
+      }
+    } else {
+      for (int op = wave - NL; op < nops; op += NR) {
+        float acc[LW];
+        reduce_one(op, nullptr, nullptr, acc, nullptr);
+        store_one(op, acc, nullptr);
+      }
     }
   };
 
   // Odd rounds walk the tiles backwards: the columns a round wrote last are the first ones the
   // next round reads, so whatever the memory-side cache still holds of them is reused.
   auto phys = [&](int64_t seq) { return p.reverse ? p.ntiles - 1 - seq : seq; };
-  const bool loader = wave < NL;
+  // Each role runs a loop of its own (both meet at the same barriers, one per tile): in one loop
+  // shared by both, the compiler sees the loaders' outstanding loads at the loop head and makes
+  // every wave wait there for all its memory operations, which for a reducer means waiting for
+  // the write acknowledgements of the tile it has just stored.
   int64_t seq = blockIdx.x;
   if (seq >= p.ntiles) return;
-  if (loader) load_tile(phys(seq), lds);
-  lds_barrier();
   int cur = 0;
-  while (seq < p.ntiles) {
-    const int64_t next = seq + gridDim.x;
-    if (loader) {
+  if (wave < NL) {
+    load_tile(phys(seq), lds);
+    lds_barrier();
+    for (; seq < p.ntiles; seq += gridDim.x, cur ^= 1) {
+      const int64_t next = seq + gridDim.x;
       if (next < p.ntiles) load_tile(phys(next), lds + (cur ^ 1) * tile_floats);
-    } else {
-      reduce_tile(phys(seq), lds + cur * tile_floats);
+      lds_barrier();
+    }
+  } else {
+    if constexpr (AWC) {
+      fetch_own(phys(seq), wave - NL, ga, ma);
+      fetch_own(phys(seq), wave - NL + NR, gb, mb);
     }
     lds_barrier();
-    seq = next;
-    cur ^= 1;
+    for (; seq < p.ntiles; seq += gridDim.x, cur ^= 1) {
+      const int64_t next = seq + gridDim.x;
+      reduce_tile(phys(seq), phys(next < p.ntiles ? next : seq), lds + cur * tile_floats);
+      lds_barrier();
+    }
   }
 }
 
