@@ -73,137 +73,162 @@ struct WinParams {
 
 enum { WIN_PUT = 0, WIN_ACCUMULATE = 1, WIN_COLLECT = 2, WIN_AVERAGE = 3, WIN_GET = 4 };
 
+// Scalar-cache views of the window plan and of the per-call arrays (one value per agent or per
+// edge, the same for every lane): uniform addresses into these become s_load instructions, which
+// leaves the vector-memory counter to the row traffic.
+typedef const float __attribute__((address_space(4)))* win_f32_ptr;
+
+// One unit of work: agent a, columns [c * 4096, (c + 1) * 4096).  FULL: every one of the workgroup's
+// 16-byte vectors lies inside [0, d), so nothing is predicated per lane.
+template <int MODE, int DT, bool STREAM, bool FULL>
+__device__ __forceinline__ void win_unit(const WinParams& p, int a, int c, int tid) {
+  constexpr int U = 4;
+  const bf::csr_i32_ptr in_ptr = (bf::csr_i32_ptr)(uintptr_t)p.in_ptr;
+  const bf::csr_i32_ptr out_ptr = (bf::csr_i32_ptr)(uintptr_t)p.out_ptr;
+  const bf::csr_i32_ptr slot_src = (bf::csr_i32_ptr)(uintptr_t)p.slot_src;
+  const bf::csr_i32_ptr edge_flags = (bf::csr_i32_ptr)(uintptr_t)p.call_edge_on;
+  const bf::csr_ent_ptr out_ent = (bf::csr_ent_ptr)(uintptr_t)p.out_ent;
+  const win_f32_ptr slot_w = (win_f32_ptr)(uintptr_t)p.slot_w;
+  const win_f32_ptr self_w = (win_f32_ptr)(uintptr_t)p.self_w;
+  const win_f32_ptr call_self_w = (win_f32_ptr)(uintptr_t)p.call_self_w;
+  const win_f32_ptr call_edge_w = (win_f32_ptr)(uintptr_t)p.call_edge_w;
+  int64_t xcol[U], wcol[U];      // where the column lies within a row of pitch ld, in X and in the window
+  int valid[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int64_t col = (static_cast<int64_t>(c) * U + u) * 1024 + tid * 4;
+    const int64_t rem = p.d - col;
+    valid[u] = FULL ? 4 : (rem >= 4 ? 4 : (rem > 0 ? static_cast<int>(rem) : 0));
+    const int64_t blk = p.block_log ? col >> p.block_log : 0;
+    xcol[u] = col + ((blk * (p.n - 1)) << p.block_log);
+    wcol[u] = col + ((blk * (p.slots - 1)) << p.block_log);
+  }
+  // four columns of a row of X (storage type DT) or of the window (fp32); a vector that starts
+  // inside the row may end in the row's padding: rows are 16-byte multiples
+  auto load_x = [&](int64_t row, int u) -> f32x4 {
+    if (!FULL && !valid[u]) return f32x4{0.f, 0.f, 0.f, 0.f};
+    float v[4];
+    load_in<DT, 4, STREAM>(p.x, row * p.ld + xcol[u], v);
+    return f32x4{v[0], v[1], v[2], v[3]};
+  };
+  auto store_x = [&](int64_t row, int u, f32x4 v) {
+    const float e[4] = {v.x, v.y, v.z, v.w};
+    if (FULL || valid[u]) store_out<DT, 4, STREAM>(p.x, row * p.ld + xcol[u], e, FULL ? 4 : valid[u]);      // never the padding
+  };
+  auto load_w = [&](const float* row, int u) -> f32x4 {
+    return (FULL || valid[u]) ? ld_stream<STREAM>(reinterpret_cast<const f32x4*>(row + wcol[u])) : f32x4{0.f, 0.f, 0.f, 0.f};
+  };
+  auto store_w = [&](float* row, int u, f32x4 v) {
+    if (FULL || valid[u] == 4) { st_stream<STREAM>(reinterpret_cast<f32x4*>(row + wcol[u]), v); return; }
+    const float e[4] = {v.x, v.y, v.z, v.w};
+    for (int k = 0; k < valid[u]; ++k) row[wcol[u] + k] = e[k];
+  };
+  auto edge_on = [&](int e) { return !p.call_edge_on || edge_flags[e] != 0; };
+  if constexpr (MODE == WIN_GET) {
+    const int end = in_ptr[a + 1];
+    for (int e = in_ptr[a]; e < end; ++e) {
+      if (!edge_on(e)) continue;
+      float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
+      f32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) v[u] = load_x(slot_src[e], u);
+      if (p.call_edge_w) {
+        const float w = call_edge_w[e];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { v[u].x *= w; v[u].y *= w; v[u].z *= w; v[u].w *= w; }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) store_w(wrow, u, v[u]);
+    }
+    return;
+  }
+  f32x4 x[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) x[u] = load_x(a, u);
+  if constexpr (MODE == WIN_PUT || MODE == WIN_ACCUMULATE) {
+    const int end = out_ptr[a + 1];
+    for (int q = out_ptr[a]; q < end; ++q) {
+      const u32x2 en = out_ent[q];
+      const int e = static_cast<int>(en.x);
+      if (!edge_on(e)) continue;
+      float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
+      if constexpr (MODE == WIN_PUT) {
+        if (p.call_edge_w) {
+          const float w = call_edge_w[e];
+#pragma unroll
+          for (int u = 0; u < U; ++u) store_w(wrow, u, f32x4{w * x[u].x, w * x[u].y, w * x[u].z, w * x[u].w});
+        } else {
+#pragma unroll
+          for (int u = 0; u < U; ++u) store_w(wrow, u, x[u]);
+        }
+      } else {
+        const float w = p.call_edge_w ? call_edge_w[e] : __uint_as_float(en.y);
+        f32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = load_w(wrow, u);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          v[u].x = fmaf(w, x[u].x, v[u].x); v[u].y = fmaf(w, x[u].y, v[u].y);
+          v[u].z = fmaf(w, x[u].z, v[u].z); v[u].w = fmaf(w, x[u].w, v[u].w);
+          store_w(wrow, u, v[u]);
+        }
+      }
+    }
+    if (MODE == WIN_ACCUMULATE || p.call_self_w) {
+      const float sw = p.call_self_w ? call_self_w[a] : self_w[a];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        x[u].x *= sw; x[u].y *= sw; x[u].z *= sw; x[u].w *= sw;
+        store_x(a, u, x[u]);
+      }
+    }
+  } else {
+    if constexpr (MODE == WIN_AVERAGE) {
+      const float sw = p.call_self_w ? call_self_w[a] : self_w[a];
+#pragma unroll
+      for (int u = 0; u < U; ++u) { x[u].x *= sw; x[u].y *= sw; x[u].z *= sw; x[u].w *= sw; }
+    }
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const int end = in_ptr[a + 1];
+    for (int e = in_ptr[a]; e < end; ++e) {
+      if (MODE == WIN_AVERAGE && !edge_on(e)) continue;
+      float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
+      f32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) v[u] = load_w(wrow, u);
+      if constexpr (MODE == WIN_COLLECT) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          x[u].x += v[u].x; x[u].y += v[u].y; x[u].z += v[u].z; x[u].w += v[u].w;
+          store_w(wrow, u, zero);
+        }
+      } else {
+        const float w = p.call_edge_w ? call_edge_w[e] : slot_w[e];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          x[u].x = fmaf(w, v[u].x, x[u].x); x[u].y = fmaf(w, v[u].y, x[u].y);
+          x[u].z = fmaf(w, v[u].z, x[u].z); x[u].w = fmaf(w, v[u].w, x[u].w);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) store_x(a, u, x[u]);
+  }
+}
+
 template <int MODE, int DT, bool STREAM>
 __global__ __launch_bounds__(256) void bf_win_kernel(const WinParams p) {
-  constexpr int U = 4;
   const int tid = threadIdx.x;
+  const bf::csr_i32_ptr active = (bf::csr_i32_ptr)(uintptr_t)p.active;
   const int64_t units = static_cast<int64_t>(p.n) * p.chunks;
   for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
     // consecutive workgroups walk along an agent's row in either layout (measured on column blocks:
     // walking down the agents of a chunk instead is 5 % slower)
     const int a = static_cast<int>(unit / p.chunks);
     const int c = static_cast<int>(unit - static_cast<int64_t>(a) * p.chunks);
-    if (p.active && p.active[a] == 0) continue;
-    int64_t col[U];
-    int64_t xcol[U], wcol[U];      // where the column lies within a row of pitch ld, in X and in the window
-    int valid[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      col[u] = (static_cast<int64_t>(c) * U + u) * 1024 + tid * 4;
-      const int64_t rem = p.d - col[u];
-      valid[u] = rem >= 4 ? 4 : (rem > 0 ? static_cast<int>(rem) : 0);
-      const int64_t blk = p.block_log ? col[u] >> p.block_log : 0;
-      xcol[u] = col[u] + ((blk * (p.n - 1)) << p.block_log);
-      wcol[u] = col[u] + ((blk * (p.slots - 1)) << p.block_log);
-    }
-    // four columns of a row of X (storage type DT) or of the window (fp32); a vector that starts
-    // inside the row may end in the row's padding: rows are 16-byte multiples
-    auto load_x = [&](int64_t row, int u) -> f32x4 {
-      if (!valid[u]) return f32x4{0.f, 0.f, 0.f, 0.f};
-      float v[4];
-      load_in<DT, 4, STREAM>(p.x, row * p.ld + xcol[u], v);
-      return f32x4{v[0], v[1], v[2], v[3]};
-    };
-    auto store_x = [&](int64_t row, int u, f32x4 v) {
-      const float e[4] = {v.x, v.y, v.z, v.w};
-      if (valid[u]) store_out<DT, 4, STREAM>(p.x, row * p.ld + xcol[u], e, valid[u]);      // never the padding
-    };
-    auto load_w = [&](const float* row, int u) -> f32x4 {
-      return valid[u] ? ld_stream<STREAM>(reinterpret_cast<const f32x4*>(row + wcol[u])) : f32x4{0.f, 0.f, 0.f, 0.f};
-    };
-    auto store_w = [&](float* row, int u, f32x4 v) {
-      if (valid[u] == 4) { st_stream<STREAM>(reinterpret_cast<f32x4*>(row + wcol[u]), v); return; }
-      const float e[4] = {v.x, v.y, v.z, v.w};
-      for (int k = 0; k < valid[u]; ++k) row[wcol[u] + k] = e[k];
-    };
-    auto edge_on = [&](int e) { return !p.call_edge_on || p.call_edge_on[e] != 0; };
-    if constexpr (MODE == WIN_GET) {
-      for (int e = p.in_ptr[a]; e < p.in_ptr[a + 1]; ++e) {
-        if (!edge_on(e)) continue;
-        float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
-        f32x4 v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = load_x(p.slot_src[e], u);
-        if (p.call_edge_w) {
-          const float w = p.call_edge_w[e];
-#pragma unroll
-          for (int u = 0; u < U; ++u) { v[u].x *= w; v[u].y *= w; v[u].z *= w; v[u].w *= w; }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) store_w(wrow, u, v[u]);
-      }
-      continue;
-    }
-    f32x4 x[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) x[u] = load_x(a, u);
-    if constexpr (MODE == WIN_PUT || MODE == WIN_ACCUMULATE) {
-      for (int q = p.out_ptr[a]; q < p.out_ptr[a + 1]; ++q) {
-        const u32x2 en = p.out_ent[q];
-        const int e = static_cast<int>(en.x);
-        if (!edge_on(e)) continue;
-        float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
-        if constexpr (MODE == WIN_PUT) {
-          if (p.call_edge_w) {
-            const float w = p.call_edge_w[e];
-#pragma unroll
-            for (int u = 0; u < U; ++u) store_w(wrow, u, f32x4{w * x[u].x, w * x[u].y, w * x[u].z, w * x[u].w});
-          } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) store_w(wrow, u, x[u]);
-          }
-        } else {
-          const float w = p.call_edge_w ? p.call_edge_w[e] : __uint_as_float(en.y);
-          f32x4 v[U];
-#pragma unroll
-          for (int u = 0; u < U; ++u) v[u] = load_w(wrow, u);
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            v[u].x = fmaf(w, x[u].x, v[u].x); v[u].y = fmaf(w, x[u].y, v[u].y);
-            v[u].z = fmaf(w, x[u].z, v[u].z); v[u].w = fmaf(w, x[u].w, v[u].w);
-            store_w(wrow, u, v[u]);
-          }
-        }
-      }
-      if (MODE == WIN_ACCUMULATE || p.call_self_w) {
-        const float sw = p.call_self_w ? p.call_self_w[a] : p.self_w[a];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          x[u].x *= sw; x[u].y *= sw; x[u].z *= sw; x[u].w *= sw;
-          store_x(a, u, x[u]);
-        }
-      }
-    } else {
-      if constexpr (MODE == WIN_AVERAGE) {
-        const float sw = p.call_self_w ? p.call_self_w[a] : p.self_w[a];
-#pragma unroll
-        for (int u = 0; u < U; ++u) { x[u].x *= sw; x[u].y *= sw; x[u].z *= sw; x[u].w *= sw; }
-      }
-      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-      for (int e = p.in_ptr[a]; e < p.in_ptr[a + 1]; ++e) {
-        if (MODE == WIN_AVERAGE && !edge_on(e)) continue;
-        float* wrow = p.win + static_cast<int64_t>(e) * p.ld;
-        f32x4 v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = load_w(wrow, u);
-        if constexpr (MODE == WIN_COLLECT) {
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            x[u].x += v[u].x; x[u].y += v[u].y; x[u].z += v[u].z; x[u].w += v[u].w;
-            store_w(wrow, u, zero);
-          }
-        } else {
-          const float w = p.call_edge_w ? p.call_edge_w[e] : p.slot_w[e];
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            x[u].x = fmaf(w, v[u].x, x[u].x); x[u].y = fmaf(w, v[u].y, x[u].y);
-            x[u].z = fmaf(w, v[u].z, x[u].z); x[u].w = fmaf(w, v[u].w, x[u].w);
-          }
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) store_x(a, u, x[u]);
-    }
+    if (p.active && active[a] == 0) continue;
+    if ((static_cast<int64_t>(c) + 1) * 4096 <= p.d) win_unit<MODE, DT, STREAM, true>(p, a, c, tid);
+    else win_unit<MODE, DT, STREAM, false>(p, a, c, tid);
   }
 }
 
