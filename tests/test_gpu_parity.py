@@ -405,6 +405,46 @@ def test_atc_awc_step_matches_oracle(mode, n, d):
     assert torch.equal(Xi, out)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,d", [(16, 11 * 1024 + 44), (40, 9 * 256 + 4), (128, 13 * 128 + 2), (256, 7 * 64 + 1)])
+def test_awc_on_the_pipelined_kernel_with_several_tiles_per_workgroup(dtype, n, d):
+    """The reducers of the pipelined kernel read the receiver's own gradient (and momentum) two rows
+    ahead, across tile boundaries.  A grid capped at three workgroups gives each of them several
+    tiles (an odd number of them, the last one ragged) in every tile width the kernel has; rounds
+    0 and 1 walk the tiles in opposite directions.  Checked against the oracle and, bit for bit,
+    against the uncapped launch."""
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    tol = TOL32 if dtype == torch.float32 else 2.0 ** -8
+    X, G = rows(n, d, 71, dtype=dtype), rows(n, d, 72, dtype=dtype)
+    M0 = workloads.normal_rows(n, d, 73, DEV, ld=X.stride(0))
+    alpha, beta = 0.05, 0.9
+    a64, b64 = float(np.float32(alpha)), float(np.float32(beta))
+    for rnd in range(2):
+        W = lib_W(t, rnd)
+        mixed = O.mix(host(X), W)
+        for with_m in (False, True):
+            got = []
+            for grid in (0, 3):
+                bf.bf_set_tuning(3, grid)
+                try:
+                    out = empty_like_rows(X)
+                    out.fill_(float("nan"))
+                    M = empty_like_rows(M0).copy_(M0) if with_m else None
+                    bf.bf_atc_step(t, rnd, X, out, G, M, alpha=alpha, beta=beta if with_m else 0.0, mode=bf.BF_AWC)
+                finally:
+                    bf.bf_set_tuning(3, 0)
+                got.append((out, M))
+            (out, M), (out3, M3) = got
+            assert torch.equal(out, out3), "capped grid differs (n=%d rnd=%d momentum=%s)" % (n, rnd, with_m)
+            if with_m:
+                assert torch.equal(M, M3)
+                Mn = b64 * host(M0) + host(G)
+                assert_close(M3, Mn, 1e-6, "momentum")
+                assert_close(out3, mixed - a64 * Mn, tol, "x")
+            else:
+                assert_close(out3, O.awc_step(host(X), host(G), W, a64), tol, "x")
+
+
 def test_config1_dgd_least_squares_200_iterations():
     data = workloads.config1_least_squares(DEV)
     A, b, alpha = data["A"], data["b"], data["alpha"]
