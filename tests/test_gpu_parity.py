@@ -239,6 +239,67 @@ def test_mix_bf16_matches_oracle():
     assert (got == rounded).mean() > 0.98
 
 
+def test_bf16_output_rounding_is_nearest_even_bit_for_bit():
+    """x_0 <- (a + b) / 2 with bf16 a, b of nearby exponents is exact in fp32, so the stored bf16 value
+    is that number rounded once: to nearest, ties to even, denormals kept, infinities and NaN passed on.
+    Hand-made ties in both directions, denormal ties, signed zeros, the largest finite values and
+    random pairs, in every kernel that stores bf16 (out of place: pipelined kernel; in place: one-tile
+    kernel; forced chain kernel), checked bit for bit against the oracle's rounding."""
+    n = 2
+    t = bf.bf_topology_create(bf.BF_CSR_USER, n, rounds=1, rowptr=np.array([0, 2, 3]), col=np.array([0, 1, 1]),
+                              wgt=np.array([0.5, 0.5, 1.0], dtype=np.float32), require_strongly_connected=False)
+    e7, e6 = 2.0 ** -7, 2.0 ** -6
+    pairs = [(1.0, 1.0 + e7), (1.0 + e7, 1.0 + e6), (-1.0, -1.0 - e7), (-1.0 - e7, -1.0 - e6),     # ties: down to even, up to even
+             (1.0, 1.0 + e6), (3.0, 3.0 + 2 * e7),                                                    # exact, no rounding
+             (2.0 ** -133, 2.0 ** -132), (2.0 ** -132, 3 * 2.0 ** -133), (2.0 ** -126, 2.0 ** -126 + 2.0 ** -133),   # denormal ties
+             (0.0, -0.0), (0.0, 2.0 ** -133),       # (sums start from +0, so -0 + -0 gives +0: not a rounding matter)
+             (3.3895313892515355e38, 3.3895313892515355e38), (3.3895313892515355e38, 3.376e38),
+             (float("inf"), 1.0), (float("-inf"), 5.0), (float("inf"), float("-inf")), (float("nan"), 1.0)]
+    rng = np.random.default_rng(77)
+    d = 4096 + 24
+    a = rng.standard_normal(d).astype(np.float32) * np.float32(2.0) ** rng.integers(-20, 20, d).astype(np.float32)
+    b = a * (1 + rng.integers(-64, 64, d).astype(np.float32) * np.float32(e7))
+    a, b = O.round_to_bf16(a), O.round_to_bf16(b)
+    for k, (x, y) in enumerate(pairs):
+        a[k * 8:(k + 1) * 8], b[k * 8:(k + 1) * 8] = x, y
+    a, b = O.round_to_bf16(a), O.round_to_bf16(b)                # (3.376e38 and the like: the nearest bf16)
+    with np.errstate(invalid="ignore", over="ignore"):
+        exact = (0.5 * a.astype(np.float64) + 0.5 * b.astype(np.float64)).astype(np.float32)
+        assert np.array_equal(exact.astype(np.float64)[np.isfinite(exact)], (0.5 * a.astype(np.float64) + 0.5 * b.astype(np.float64))[np.isfinite(exact)])
+    want = O.round_to_bf16(exact)
+    X = workloads.alloc_rows(n, d, torch.bfloat16, DEV, ld=workloads.padded_ld(d, 2))
+    X.copy_(torch.from_numpy(np.stack([a, b])).to(DEV).to(torch.bfloat16))
+    assert np.array_equal(X.float().cpu().numpy().view(np.uint32)[~np.isnan(a[None, :]).repeat(2, 0)],
+                          np.stack([a, b]).view(np.uint32)[~np.isnan(a[None, :]).repeat(2, 0)])
+
+    def check(out, what):
+        got = out[0].float().cpu().numpy()
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(got), nan), what
+        bad = np.nonzero(got.view(np.uint32)[~nan] != want.view(np.uint32)[~nan])[0]
+        assert bad.size == 0, "%s: %d values differ, first at %d: got %r want %r" % (what, bad.size, bad[0], got[~nan][bad[0]], want[~nan][bad[0]])
+        assert torch.equal(out[1], X[1])
+
+    out = empty_like_rows(X)
+    bf.bf_neighbor_allreduce(t, 0, X, out)
+    check(out, "out of place")
+    Xi = empty_like_rows(X).copy_(X)
+    bf.bf_neighbor_allreduce(t, 0, Xi, Xi)
+    check(Xi, "in place")
+    bf.bf_set_tuning(6, 1)
+    try:
+        out = empty_like_rows(X)
+        bf.bf_neighbor_allreduce(t, 0, X, out)
+    finally:
+        bf.bf_set_tuning(6, 0)
+    check(out, "chain kernel")
+    G = workloads.alloc_rows(n, d, torch.bfloat16, DEV, ld=X.stride(0), fill=0)
+    for mode in (bf.BF_ATC, bf.BF_AWC):
+        out = empty_like_rows(X)
+        bf.bf_atc_step(t, 0, X, out, G, None, alpha=0.25, mode=mode)          # zero gradient: the same numbers
+        check(out, "fused step, mode %d" % mode)
+
+
 def test_dynamic_api_with_constant_weights_equals_static():
     n, d = 64, 3000
     ts = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
