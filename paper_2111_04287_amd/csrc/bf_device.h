@@ -43,8 +43,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;   // quiet NaN
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
+// Two results at once: gfx950's v_cvt_pk_bf16_f32 (round to nearest even, denormals kept, NaN made
+// quiet), one instruction where the integer form above takes about eight per value.  The stores of
+// the mixing kernels go through here; with bf16 storage and no fp32 state matrix those kernels are
+// bound by the number of vector instructions they issue, not by HBM.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Streaming accesses.  Every element of X, G and M is read once and written once per call, so
