@@ -138,10 +138,12 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   const csr_i32_ptr rowptr = (csr_i32_ptr)(uintptr_t)p.rowptr;
   const csr_ent_ptr ent = (csr_ent_ptr)(uintptr_t)p.ent;
 
-  auto where = [&](int op, int* i, int* cit) {
-    *i = op >> spans_log;
-    *cit = ((op & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;
-  };
+  // Reducer wave w takes the ops w, w + NR, w + 2 NR, ... of a tile, op = row * spans + span.  NR is a
+  // multiple of the number of spans per row (1, 2 or 4), so a wave stays in one span: the columns of
+  // its lanes are fixed, and what depends on them -- the LDS address, the global column offset, the
+  // tail predicate -- is worked out once per tile, not once per op.
+  static_assert(NR % 4 == 0, "a reducer wave keeps its span");
+  const int cit = (((wave - NL) & ((1 << spans_log) - 1)) << SPAN_LOG) + lane * LW;    // column inside the tile
   // Adapt-while-communicate: the receiver's own gradient (and momentum) values, which the reducers
   // read from HBM themselves.  A wave's memory operations complete in issue order, so waiting for a
   // value just requested also waits for every store before it.  The values are therefore requested
@@ -157,10 +159,8 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   auto fetch_own = [&](int64_t tile, int op, float* gv, float* mv) {
     // (an empty op still issues its request, so that the number of requests in flight at each wait is
     // the same on every path and known to the compiler; all its lanes read one and the same vector)
-    int i, cit;
-    where(min(op, nops - 1), &i, &cit);
-    if (op >= nops) cit -= lane * LW;
-    const int64_t col = min((tile << log_c) + cit, last_own);
+    const int i = min(op, nops - 1) >> spans_log;
+    const int64_t col = min((tile << log_c) + (op >= nops ? cit - lane * LW : cit), last_own);
     load_in<DT, LW>(p.g, g_offset(p, i, col), gv);
     if constexpr (OP == OP_MOM_AWC) load_in<DT_F32, LW>(reinterpret_cast<const char*>(p.m), m_offset(p, i, col), mv);
   };
@@ -174,6 +174,13 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
     const int64_t c0 = tile << log_c;
     const bool full = c0 + (int64_t{1} << log_c) <= d;      // no ragged tail in this tile
     const int64_t t0 = tile_origin(p, c0);
+    // this lane's columns in this tile
+    const float* src = buf + cit;
+    const int64_t col = c0 + cit;
+    const bool live = full || col < d;
+    const int valid = (full || d - col >= LW) ? LW : static_cast<int>(d - col);
+    const int64_t out_col = col + t0;
+    [[maybe_unused]] const int64_t m_col = OP == OP_MOM_AWC ? m_offset(p, 0, col) : 0;
     // one batch of K list entries of one row: K LDS vectors, then K x LW FMAs in list order
     auto batch = [&](const float* src, float* acc, int q, auto kc) {
       constexpr int K = decltype(kc)::value;
@@ -208,11 +215,10 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
     };
     // One output vector: the weighted sum, minus the own gradient step (AWC); mn is the new momentum.
     auto reduce_one = [&](int op, const float* gv, const float* mv, float* acc, float* mn) {
-      int i, cit;
-      where(op, &i, &cit);
+      const int i = op >> spans_log;
 #pragma unroll
       for (int e = 0; e < LW; ++e) acc[e] = 0.0f;
-      rest(buf + cit, acc, rowptr[i], rowptr[i + 1]);
+      rest(src, acc, rowptr[i], rowptr[i + 1]);
       if constexpr (AWC) {
 #pragma unroll
         for (int e = 0; e < LW; ++e) {
@@ -222,14 +228,10 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
       }
     };
     auto store_one = [&](int op, const float* acc, const float* mn) {
-      int i, cit;
-      where(op, &i, &cit);
-      const int64_t col = c0 + cit;
-      if (full || col < d) {
-        const int64_t rem = d - col;
-        const int valid = (full || rem >= LW) ? LW : static_cast<int>(rem);
-        const int64_t off = static_cast<int64_t>(i) * ld + col + t0;
-        if constexpr (OP == OP_MOM_AWC) store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), m_offset(p, i, col), mn, valid);
+      const int i = op >> spans_log;
+      if (live) {
+        const int64_t off = static_cast<int64_t>(i) * ld + out_col;
+        if constexpr (OP == OP_MOM_AWC) store_out<DT_F32, LW, false>(reinterpret_cast<char*>(p.m), static_cast<int64_t>(i) * p.m_ld + m_col, mn, valid);
         store_out<DT, LW, STREAM>(p.x_out, off, acc, valid);
         if constexpr (WITH_Y) {
           const float rcp = 1.0f / p.p_out[i];
