@@ -64,7 +64,8 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   const int nunits = p.n << upr_log;
   const int64_t d = p.d, ld = p.ld;
   // A unit past the tile's end re-reads the last unit, a column at or past d re-reads the row's
-  // last in-range vector: loads are unconditional, only the LDS write and the M store are predicated.
+  // last in-range vector: within a step the loads are not predicated per lane, only the LDS write
+  // and the M store are.
   const int64_t last_vec = d > 0 ? ((d - 1) >> UC_LOG) << UC_LOG : 0;
 
   auto load_tile = [&](int64_t tile, float* buf) {
@@ -75,8 +76,11 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
       raw_t gr[STAGE_G ? U : 1];
       raw_t g2r[STAGE_G2 ? U : 1];
       f32x4 mr[STAGE_M ? U : 1];
+      // a small tile ends before the U-th unit of a lane: those steps are skipped as a whole
+      const int steps = (nunits - base + LT - 1) / LT;
 #pragma unroll
       for (int k = 0; k < U; ++k) {
+        if (k >= steps) break;
         const int u = min(base + k * LT + tid, nunits - 1);
         const int row = u >> upr_log;
         const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
@@ -88,6 +92,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
       }
 #pragma unroll
       for (int k = 0; k < U; ++k) {
+        if (k >= steps) break;
         const int u = base + k * LT + tid;
         const int row = u >> upr_log;
         const int cit = (u & upr_mask) << UC_LOG;     // column inside the tile
