@@ -63,14 +63,30 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   const int upr_mask = (1 << upr_log) - 1;
   const int nunits = p.n << upr_log;
   const int64_t d = p.d, ld = p.ld;
-  // A unit past the tile's end re-reads the last unit, a column at or past d re-reads the row's
-  // last in-range vector: within a step the loads are not predicated per lane, only the LDS write
-  // and the M store are.
+  // A row of a tile is at most 256 staging units and LT is a multiple of 256: a loader lane keeps
+  // its column through all its units of a tile and moves down LT / (units per row) rows from one
+  // unit to the next, so an address is the previous one plus a wave-uniform step -- two additions
+  // where row x pitch would be a 64-bit product.  Within a step the loads are not predicated per
+  // lane, only the LDS write and the M store are: a unit past the tile's end reads row 0 of its
+  // column, a column at or past d the row's last in-range vector.
+  static_assert(LT % 256 == 0, "a lane's units of a tile share one column");
   const int64_t last_vec = d > 0 ? ((d - 1) >> UC_LOG) << UC_LOG : 0;
+  const int rows_step = LT >> upr_log;
+  const int lcit = (tid & upr_mask) << UC_LOG;      // column inside the tile
+  const int row0 = tid >> upr_log;
 
   auto load_tile = [&](int64_t tile, float* buf) {
     const int64_t c0 = tile << log_c;
     const int64_t t0 = tile_origin(p, c0);
+    const int64_t col = min(c0 + lcit, last_vec);
+    const bool col_live = c0 + lcit < d;
+    const int64_t x_row0 = col + t0;
+    int64_t xo = static_cast<int64_t>(row0) * ld + x_row0;
+    const int64_t xs = static_cast<int64_t>(rows_step) * ld;
+    [[maybe_unused]] int64_t g_row0 = 0, go = 0, gs = 0, m_row0 = 0, mo = 0, ms = 0;
+    if constexpr (STAGE_G) { g_row0 = g_offset(p, 0, col); go = g_offset(p, row0, col); gs = static_cast<int64_t>(rows_step) * p.g_ld; }
+    if constexpr (STAGE_M) { m_row0 = m_offset(p, 0, col); mo = m_offset(p, row0, col); ms = static_cast<int64_t>(rows_step) * p.m_ld; }
+    int row = row0;                                  // this lane's row in the step about to be requested
     for (int base = 0; base < nunits; base += LT * U) {
       raw_t xr[U];
       raw_t gr[STAGE_G ? U : 1];
@@ -78,26 +94,30 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
       f32x4 mr[STAGE_M ? U : 1];
       // a small tile ends before the U-th unit of a lane: those steps are skipped as a whole
       const int steps = (nunits - base + LT - 1) / LT;
+      const int row_b = row;
+      [[maybe_unused]] const int64_t mo_b = mo;
 #pragma unroll
       for (int k = 0; k < U; ++k) {
         if (k >= steps) break;
-        const int u = min(base + k * LT + tid, nunits - 1);
-        const int row = u >> upr_log;
-        const int64_t col = min(c0 + (static_cast<int64_t>(u & upr_mask) << UC_LOG), last_vec);
-        const int64_t off = static_cast<int64_t>(row) * ld + col + t0;
-        xr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.x_in + off * EB));
-        if constexpr (STAGE_G) gr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g + g_offset(p, row, col) * EB));
-        if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g2 + g_offset(p, row, col) * EB));
-        if constexpr (STAGE_M) mr[k] = ld_stream<STREAM>(reinterpret_cast<const f32x4*>(p.m + m_offset(p, row, col)));
+        const bool in = row < p.n;
+        xr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.x_in + (in ? xo : x_row0) * EB));
+        xo += xs;
+        if constexpr (STAGE_G) {
+          gr[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g + (in ? go : g_row0) * EB));
+          if constexpr (STAGE_G2) g2r[k] = ld_stream<STREAM>(reinterpret_cast<const raw_t*>(p.g2 + (in ? go : g_row0) * EB));
+          go += gs;
+        }
+        if constexpr (STAGE_M) {
+          mr[k] = ld_stream<STREAM>(reinterpret_cast<const f32x4*>(p.m + (in ? mo : m_row0)));
+          mo += ms;
+        }
+        row += rows_step;
       }
 #pragma unroll
       for (int k = 0; k < U; ++k) {
         if (k >= steps) break;
-        const int u = base + k * LT + tid;
-        const int row = u >> upr_log;
-        const int cit = (u & upr_mask) << UC_LOG;     // column inside the tile
-        const int64_t col = c0 + cit;
-        const bool live = u < nunits && col < d;
+        const int rk = row_b + k * rows_step;
+        const bool live = rk < p.n && col_live;
         float xv[UC];
         widen_unit<DT, UC>(xr[k], xv);
         if constexpr (STAGE_G) {
@@ -107,7 +127,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
             float sv[4] = {mr[k].x, mr[k].y, mr[k].z, mr[k].w};
             local_update4<OP>(xv, gv, sv, p.alpha, p.beta);
             if (live) {
-              float* mp = p.m + m_offset(p, row, col);
+              float* mp = p.m + (mo_b + k * ms);
               const int64_t rem = d - col;
               if (rem >= 4) { f32x4 t = {sv[0], sv[1], sv[2], sv[3]}; st_stream<STREAM>(reinterpret_cast<f32x4*>(mp), t); }
               else for (int e = 0; e < 4; ++e) if (e < rem) mp[e] = sv[e];
@@ -124,7 +144,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
           }
         }
         if (live) {
-          float* dst = buf + (row << log_c) + cit;
+          float* dst = buf + (rk << log_c) + lcit;
 #pragma unroll
           for (int q = 0; q < UC / 4; ++q) {
             f32x4 t = {xv[4 * q], xv[4 * q + 1], xv[4 * q + 2], xv[4 * q + 3]};
@@ -322,22 +342,21 @@ int launch_pipe_shape(const TileParams& tp, int grid, size_t lds, hipStream_t st
 
 // The wave split.  Plain mixing and the ops that stage X (and G) only: four loader waves with eight
 // vectors per lane in flight and twelve reducer waves, the measured best of the splits tried (4+8
-// and 8+8 waves leave the reducers short: with so few waves per SIMD nothing hides the latency of a
-// row's scalar list loads and LDS reads; two or three loader waves cannot keep enough loads in
+// and 8+8 waves leave the reducers short; two or three loader waves cannot keep enough loads in
 // flight).  The ops that also read and write an fp32 state matrix while staging (momentum,
 // Exact-Diffusion) do most of their work in the loaders: eight loader waves with four vectors in
 // flight and eight reducers measure 2-3 % above the 4+12 split there on column blocks (n = 32 bf16
-// momentum: 6.25 against 6.08 TB/s; with eight vectors in flight 5.75).
+// momentum: 6.25 against 6.08 TB/s; with eight vectors in flight 5.75) and within 1 % of it on
+// agent-major rows.
 template <int DT, int OP, bool WITH_Y, int LW>
 int launch_pipe_lw(const TileParams& tp, int grid, size_t lds, bool stream, hipStream_t st) {
   if constexpr (OP == OP_MOM_ATC || OP == OP_ED) {
-    // (on agent-major rows the two splits are within 1 % of each other, 4+12 ahead)
-    if (tp.block_log)
-      return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 8, 8, 4, true>(tp, grid, lds, st)
-                    : launch_pipe_shape<DT, OP, WITH_Y, LW, 8, 8, 4, false>(tp, grid, lds, st);
+    return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 8, 8, 4, true>(tp, grid, lds, st)
+                  : launch_pipe_shape<DT, OP, WITH_Y, LW, 8, 8, 4, false>(tp, grid, lds, st);
+  } else {
+    return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, true>(tp, grid, lds, st)
+                  : launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, false>(tp, grid, lds, st);
   }
-  return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, true>(tp, grid, lds, st)
-                : launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, false>(tp, grid, lds, st);
 }
 
 template <int DT, int OP, bool WITH_Y>
