@@ -195,15 +195,16 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   // with fp32 accumulation; the list comes through the scalar cache, and entries go in batches of
   // four (then two, then one) so that a wave waits once per batch of LDS reads.
   // `next_tile`: the tile this workgroup reduces after this one (this one again if it is the last).
-  auto reduce_tile = [&](int64_t tile, int64_t next_tile, const float* buf) {
+  // FULL: the tile has no ragged tail, so no store is predicated.
+  auto reduce_tile_as = [&](int64_t tile, int64_t next_tile, const float* buf, auto full_c) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_c)::value;
     const int64_t c0 = tile << log_c;
-    const bool full = c0 + (int64_t{1} << log_c) <= d;      // no ragged tail in this tile
     const int64_t t0 = tile_origin(p, c0);
     // this lane's columns in this tile
     const float* src = buf + cit;
     const int64_t col = c0 + cit;
-    const bool live = full || col < d;
-    const int valid = (full || d - col >= LW) ? LW : static_cast<int>(d - col);
+    const bool live = FULL || col < d;
+    const int valid = (FULL || d - col >= LW) ? LW : static_cast<int>(d - col);
     const int64_t out_col = col + t0;
     [[maybe_unused]] const int64_t m_col = OP == OP_MOM_AWC ? m_offset(p, 0, col) : 0;
     // one batch of K list entries of one row: K LDS vectors, then K x LW FMAs in list order
@@ -290,6 +291,11 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
         store_one(op, acc, nullptr);
       }
     }
+  };
+
+  auto reduce_tile = [&](int64_t tile, int64_t next_tile, const float* buf) __attribute__((always_inline)) {
+    if (((tile + 1) << log_c) <= d) reduce_tile_as(tile, next_tile, buf, std::true_type{});
+    else reduce_tile_as(tile, next_tile, buf, std::false_type{});
   };
 
   // Odd rounds walk the tiles backwards: the columns a round wrote last are the first ones the
