@@ -172,15 +172,19 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   // Adapt-while-communicate: the receiver's own gradient (and momentum) values, which the reducers
   // read from HBM themselves.  A wave's memory operations complete in issue order, so waiting for a
   // value just requested also waits for every store before it.  The values are therefore requested
-  // two ops ahead, across tile boundaries, into two register sets used in turn (ga/ma by a wave's
-  // even ops of a tile, gb/mb by its odd ones; every wave is given an even number of ops per tile,
-  // those past the tile's end being empty): a store then has two ops' time to complete before
-  // anything waits behind it.  Like the loaders' reads, a request is not predicated: a column at or
-  // past d re-reads the row's last vector.
+  // AHEAD ops ahead, across tile boundaries, into AHEAD register sets used in turn (the op loop is
+  // unrolled AHEAD times so that every set has a fixed name; every wave is given a multiple of AHEAD
+  // ops per tile, those past the tile's end being empty): a store then has that many ops' time to
+  // complete before anything waits behind it.  Like the loaders' reads, a request is not predicated:
+  // a column at or past d re-reads the row's last vector.  For the compiler to know how many
+  // operations were issued after the request it waits for, that number must be the same on every
+  // path into the op loop: in tiles without a ragged tail nothing in the loop is conditional, and
+  // the two other ways in (the start of the kernel, a tile with a ragged tail) drain the queue first.
   constexpr bool AWC = (OP == OP_AWC || OP == OP_MOM_AWC);
-  const int nops_even = (nops + 2 * NR - 1) / (2 * NR) * (2 * NR);
+  constexpr int AHEAD = 4;
+  const int nops_even = (nops + AHEAD * NR - 1) / (AHEAD * NR) * (AHEAD * NR);
   const int64_t last_own = d > 0 ? (d - 1) / LW * LW : 0;
-  [[maybe_unused]] float ga[LW], gb[LW], ma[LW], mb[LW];
+  [[maybe_unused]] float gq[AHEAD][LW], mq[AHEAD][LW];
   auto fetch_own = [&](int64_t tile, int op, float* gv, float* mv) {
     // (an empty op still issues its request, so that the number of requests in flight at each wait is
     // the same on every path and known to the compiler; all its lanes read one and the same vector)
@@ -270,20 +274,18 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
     };
     if constexpr (AWC) {
       float acc[LW], mn[LW];
-      auto ahead = [&](int op, float* gv, float* mv) {      // the op two after `op` in this wave's sequence
-        const int nx = op + 2 * NR;
-        const bool here = nx < nops_even;
-        fetch_own(here ? tile : next_tile, here ? nx : nx - nops_even, gv, mv);
-      };
-      for (int op = wave - NL; op < nops_even; op += 2 * NR) {
-        const bool first = op < nops, second = op + NR < nops;
-        if (first) reduce_one(op, ga, ma, acc, mn);
-        ahead(op, ga, ma);
-        if (first) store_one(op, acc, mn);
-        if (second) reduce_one(op + NR, gb, mb, acc, mn);
-        ahead(op + NR, gb, mb);
-        if (second) store_one(op + NR, acc, mn);
+      for (int op = wave - NL; op < nops_even; op += AHEAD * NR) {
+#pragma unroll
+        for (int j = 0; j < AHEAD; ++j) {
+          const int oj = op + j * NR;
+          if (oj < nops) reduce_one(oj, gq[j], mq[j], acc, mn);
+          const int nx = oj + AHEAD * NR;              // the op that uses this register set next
+          const bool here = nx < nops_even;
+          fetch_own(here ? tile : next_tile, here ? nx : nx - nops_even, gq[j], mq[j]);
+          if (oj < nops) store_one(oj, acc, mn);
+        }
       }
+      if constexpr (!FULL) __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): see above
     } else {
       for (int op = wave - NL; op < nops; op += NR) {
         float acc[LW];
@@ -318,8 +320,9 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
     }
   } else {
     if constexpr (AWC) {
-      fetch_own(phys(seq), wave - NL, ga, ma);
-      fetch_own(phys(seq), wave - NL + NR, gb, mb);
+#pragma unroll
+      for (int j = 0; j < AHEAD; ++j) fetch_own(phys(seq), wave - NL + j * NR, gq[j], mq[j]);
+      __builtin_amdgcn_s_waitcnt(0x0F70);                           // vmcnt(0)
     }
     lds_barrier();
     for (; seq < p.ntiles; seq += gridDim.x, cur ^= 1) {
