@@ -441,6 +441,26 @@ def main():
             "note": "win_accumulate + win_update_then_collect, everybody active; bytes = x read and written "
                     "and every slot read and written, in each of the two calls"}
         del Xw, Ww
+        # the fused steps without a state matrix, and a graph with many entries per row: the cases the
+        # pipelined kernel runs at the rate of its issued instructions rather than at the HBM rate
+        # (column blocks, out of place; bytes = every operand read once, every result written once)
+        for tag, nn, dd, dtype, bdt in (("bf16_n32_d25557032", 32, workloads.RESNET50_PARAMS, torch.bfloat16, bf.BF_BF16),
+                                         ("f32_n128_d4194304", 128, 1 << 22, torch.float32, bf.BF_F32)):
+            tt = bf.bf_topology_create(bf.BF_EXP_STATIC, nn)
+            Bt = bf.bf_recommended_block(tt, dd, bdt)
+            eb = 2 if dtype == torch.bfloat16 else 4
+            Xs, Ys, Gs = (blocked(nn, dd, Bt, dtype) for _ in range(3))
+            Xs.data.normal_()
+            Gs.data.normal_()
+            for what, fn, nb in (("mix", lambda k: bf.bf_neighbor_allreduce(tt, 0, Xs, Ys), 2 * nn * dd * eb),
+                                 ("atc", lambda k: bf.bf_atc_step(tt, 0, Xs, Ys, Gs, None, 0.01, 0.0, bf.BF_ATC), 3 * nn * dd * eb),
+                                 ("awc", lambda k: bf.bf_atc_step(tt, 0, Xs, Ys, Gs, None, 0.01, 0.0, bf.BF_AWC), 3 * nn * dd * eb)):
+                w_, e_ = timed(fn, 30, 5)
+                nxt["static_exp_%s_%s_column_blocks" % (tag, what)] = {
+                    "ms_per_step": round(e_, 4), "effective_GBps": round(nb / (e_ * 1e-3) / 1e9, 1),
+                    "pct_of_hbm_peak": round(100 * nb / (e_ * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2), "block": Bt,
+                    "note": "bound by issued vector and scalar instructions, not by HBM"}
+            del Xs, Ys, Gs
         out["next_rows"] = nxt
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
