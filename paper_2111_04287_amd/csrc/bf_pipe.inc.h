@@ -197,7 +197,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   // Output rows of one tile: reducer wave w takes the (row, 64*LW-column span) pairs w, w+NR, ...
   // Each is the weighted sum over the row's in-neighbor list, read from the LDS tile in list order
   // with fp32 accumulation; the list comes through the scalar cache, and entries go in batches of
-  // four (then two, then one) so that a wave waits once per batch of LDS reads.
+  // eight (then four, two, one) so that a wave waits once per batch of LDS reads.
   // `next_tile`: the tile this workgroup reduces after this one (this one again if it is the last).
   // FULL: the tile has no ragged tail, so no store is predicated.
   auto reduce_tile_as = [&](int64_t tile, int64_t next_tile, const float* buf, auto full_c) __attribute__((always_inline)) {
@@ -239,7 +239,8 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
       }
     };
     auto rest = [&](const float* src, float* acc, int q, int end) {
-      for (; q + 4 <= end; q += 4) batch(src, acc, q, std::integral_constant<int, 4>{});
+      for (; q + 8 <= end; q += 8) batch(src, acc, q, std::integral_constant<int, 8>{});
+      if (q + 4 <= end) { batch(src, acc, q, std::integral_constant<int, 4>{}); q += 4; }
       if (q + 2 <= end) { batch(src, acc, q, std::integral_constant<int, 2>{}); q += 2; }
       if (q < end) batch(src, acc, q, std::integral_constant<int, 1>{});
     };
