@@ -449,7 +449,7 @@ def test_least_squares_gradient_shapes(n, m, d):
 
 
 @pytest.mark.parametrize("mode", [bf.BF_ATC, bf.BF_AWC])
-@pytest.mark.parametrize("n,d", [(16, 1024), (64, 2000), (256, 520), (5, 68)])
+@pytest.mark.parametrize("n,d", [(16, 1024), (64, 2000), (256, 520), (5, 68), (1, 300), (2, 64), (3, 1)])
 def test_atc_awc_step_matches_oracle(mode, n, d):
     t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
     W = lib_W(t)
