@@ -474,6 +474,9 @@ int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on t
  *           in-place rounds, 2 never uses it
  *   knob 13: 1 keeps bf_neighbor_allreduce_multi from running shift rounds in registers, 2 makes
  *           it do so whenever the rounds have that form (the default also weighs n and count)
+ *   knob 14: 1 makes the pipelined kernel's AWC step with bf16 storage fetch the receiver's own
+ *           gradient from HBM in the reducer waves, as with fp32 storage, instead of staging the
+ *           gradients in LDS
  *   knob 9: 1 keeps the chain kernel at 256-thread workgroups
  *   knob 7: 1 disables the alternating (odd rounds right-to-left) tile order
  *   knob 6: forces the chain kernel (where the round has a chain plan) with 1, 2 or 4 16-byte

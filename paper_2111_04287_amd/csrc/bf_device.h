@@ -82,6 +82,8 @@ typedef const int32_t __attribute__((address_space(4)))* csr_i32_ptr;
 typedef const u32x2 __attribute__((address_space(4)))* csr_ent_ptr;
 
 enum { OP_MIX = 0, OP_ATC = 1, OP_AWC = 2, OP_MOM_ATC = 3, OP_MOM_AWC = 4, OP_ED = 5, OP_TRACK = 6 };
+// (pipelined kernel only) AWC with the gradient tile staged in LDS beside the X tile
+enum { OP_AWC_LDS = 7 };
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
 struct TileParams {

@@ -803,6 +803,7 @@ int g_tune_spin = 0;      // polls a grid-barrier wait may take before it gives 
 int g_tune_extra = 0;     // 1: the grid barrier waits for an arrival that never comes (give-up test)
 int g_tune_noshift = 0;   // 1: fused rounds never take the in-register form, 2: whenever it applies
 int g_tune_pipe = 0;      // 1: the pipelined kernel also for cache-resident rounds, 2: never
+int g_tune_awc = 0;       // 1: AWC on the pipelined kernel always fetches its own gradient from HBM
 
 
 int ilog2(int64_t v) { int l = 0; while ((int64_t{1} << (l + 1)) <= v) ++l; return l; }
@@ -1015,6 +1016,18 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     const int pipe_cap = blocked ? std::min(cap_log_c, t->n < 32 ? 9 : 8) : cap_log_c;
     if (choose_pipe_shape(t->n, tp.d, di, &ps, pipe_cap) == BF_OK) {
       if (dry) return BF_OK;
+      // AWC with bf16 storage: the reducers are short of issue slots, and fetching their own gradient
+      // from HBM between their stores costs them a third of their rate.  Where n more fp32 rows fit
+      // each LDS tile at 256 columns or more (or without narrowing it), the loaders stage the gradients there instead (n = 32,
+      // static exponential graph: 4.2 -> 5.6 TB/s on column blocks, 4.1 -> 5.2 on agent-major rows,
+      // where the tile narrows from 512 to 256 columns).  With fp32 storage the reducers have the
+      // slots and the loaders the bytes: the fetch from HBM measures the same or better (n = 32: 6.36
+      // against 6.17 TB/s), so it stays.
+      int pipe_op = op;
+      if (op == OP_AWC && dt == BF_BF16 && !g_tune_awc) {
+        Shape ps2;
+        if (choose_pipe_shape(2 * t->n, tp.d, di, &ps2, pipe_cap) == BF_OK && (ps2.log_c >= 8 || ps2.log_c == ps.log_c)) { ps = ps2; pipe_op = OP_AWC_LDS; }
+      }
       ps.stream = stream;
       tp.log_c = ps.log_c;
       tp.ntiles = (tp.d + (int64_t{1} << ps.log_c) - 1) >> ps.log_c;
@@ -1026,8 +1039,8 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
       const int per_cu = (op == OP_MIX && g_tune_wgs != 1 && 2 * ps.lds_bytes <= lds_cu_pipe) ? 2 : 1;
       int grid = static_cast<int>(std::min<int64_t>(tp.ntiles, static_cast<int64_t>(di.cus) * per_cu));
       if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
-      return dt == BF_F32 ? launch_pipe_op_f32(op, with_y, tp, ps, grid, st)
-                          : launch_pipe_op_bf16(op, with_y, tp, ps, grid, st);
+      return dt == BF_F32 ? launch_pipe_op_f32(pipe_op, with_y, tp, ps, grid, st)
+                          : launch_pipe_op_bf16(pipe_op, with_y, tp, ps, grid, st);
     }
   }
   Shape s;
@@ -1332,6 +1345,7 @@ int bf_set_tuning(int32_t knob, int32_t value) {
   else if (knob == 11) g_tune_extra = value;
   else if (knob == 12) g_tune_pipe = value;
   else if (knob == 13) g_tune_noshift = value;
+  else if (knob == 14) g_tune_awc = value;
   else return BF_ERR_KIND;
   return BF_OK;
 }

@@ -44,7 +44,11 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   float* lds = reinterpret_cast<float*>(lds_raw);
 
   constexpr int EB = Elem<DT>::bytes;
-  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED || OP == OP_TRACK);
+  // OP_AWC_LDS: adapt-while-communicate with the gradients staged, as fp32, in n more rows of each
+  // LDS tile (row n + i holds agent i's): the reducer then takes its own gradient as one more LDS
+  // read behind the row's list instead of fetching it from HBM between its stores.
+  constexpr bool G_LDS = (OP == OP_AWC_LDS);
+  constexpr bool STAGE_G = (OP == OP_ATC || OP == OP_MOM_ATC || OP == OP_ED || OP == OP_TRACK || G_LDS);
   constexpr bool STAGE_G2 = (OP == OP_TRACK);
   constexpr bool STAGE_M = (OP == OP_MOM_ATC || OP == OP_ED);
   // A staging unit is 16 bytes of X, except next to an fp32 state matrix with bf16 storage: there
@@ -119,9 +123,9 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
         const int rk = row_b + k * rows_step;
         const bool live = rk < p.n && col_live;
         float xv[UC];
+        [[maybe_unused]] float gv[UC];
         widen_unit<DT, UC>(xr[k], xv);
         if constexpr (STAGE_G) {
-          float gv[UC];
           widen_unit<DT, UC>(gr[k], gv);
           if constexpr (STAGE_M) {
             float sv[4] = {mr[k].x, mr[k].y, mr[k].z, mr[k].w};
@@ -138,7 +142,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
             widen_unit<DT, UC>(g2r[k], hv);
 #pragma unroll
             for (int e = 0; e < UC; ++e) xv[e] = (xv[e] + gv[e]) - hv[e];
-          } else {
+          } else if constexpr (!G_LDS) {
 #pragma unroll
             for (int e = 0; e < UC; ++e) xv[e] = fmaf(-p.alpha, gv[e], xv[e]);
           }
@@ -150,6 +154,14 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
             f32x4 t = {xv[4 * q], xv[4 * q + 1], xv[4 * q + 2], xv[4 * q + 3]};
             *reinterpret_cast<f32x4*>(dst + 4 * q) = t;
           }
+          if constexpr (G_LDS) {
+            float* gdst = dst + (p.n << log_c);
+#pragma unroll
+            for (int q = 0; q < UC / 4; ++q) {
+              f32x4 t = {gv[4 * q], gv[4 * q + 1], gv[4 * q + 2], gv[4 * q + 3]};
+              *reinterpret_cast<f32x4*>(gdst + 4 * q) = t;
+            }
+          }
         }
       }
     }
@@ -158,7 +170,7 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
   constexpr int SPAN_LOG = (LW == 4 ? 8 : (LW == 2 ? 7 : 6));      // log2(64*LW)
   const int spans_log = log_c - SPAN_LOG;
   const int nops = p.n << spans_log;
-  const int tile_floats = p.n << log_c;
+  const int tile_floats = (G_LDS ? 2 * p.n : p.n) << log_c;
 
   const csr_i32_ptr rowptr = (csr_i32_ptr)(uintptr_t)p.rowptr;
   const csr_ent_ptr ent = (csr_ent_ptr)(uintptr_t)p.ent;
@@ -249,7 +261,17 @@ __global__ __launch_bounds__((NL + NR) * 64) void bf_pipe_kernel(const TileParam
       const int i = op >> spans_log;
 #pragma unroll
       for (int e = 0; e < LW; ++e) acc[e] = 0.0f;
+      [[maybe_unused]] float own[LW];
+      if constexpr (G_LDS) {
+        const float* gp = src + ((p.n + i) << log_c);
+#pragma unroll
+        for (int e = 0; e < LW; ++e) own[e] = gp[e];
+      }
       rest(src, acc, rowptr[i], rowptr[i + 1]);
+      if constexpr (G_LDS) {
+#pragma unroll
+        for (int e = 0; e < LW; ++e) acc[e] = fmaf(-p.alpha, own[e], acc[e]);
+      }
       if constexpr (AWC) {
 #pragma unroll
         for (int e = 0; e < LW; ++e) {
@@ -388,6 +410,9 @@ int launch_pipe_op(int op, bool with_y, const TileParams& tp, const Shape& s, in
     case OP_ATC: return with_y ? launch_pipe<DT, OP_ATC, true>(tp, s, grid, st) : launch_pipe<DT, OP_ATC, false>(tp, s, grid, st);
     case OP_TRACK: return launch_pipe<DT, OP_TRACK, false>(tp, s, grid, st);
     case OP_AWC: return launch_pipe<DT, OP_AWC, false>(tp, s, grid, st);
+    case OP_AWC_LDS:
+      if constexpr (DT == DT_BF16) return launch_pipe<DT, OP_AWC_LDS, false>(tp, s, grid, st);
+      else return BF_ERR_UNSUPPORTED;                  // (the dispatcher takes this form with bf16 storage only)
     case OP_MOM_ATC: return launch_pipe<DT, OP_MOM_ATC, false>(tp, s, grid, st);
     case OP_ED: return launch_pipe<DT, OP_ED, false>(tp, s, grid, st);
     default: return launch_pipe<DT, OP_MOM_AWC, false>(tp, s, grid, st);

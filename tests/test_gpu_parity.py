@@ -467,13 +467,18 @@ def test_atc_awc_step_matches_oracle(mode, n, d):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("n,d", [(16, 11 * 1024 + 44), (40, 9 * 256 + 4), (128, 13 * 128 + 2), (256, 7 * 64 + 1)])
-def test_awc_on_the_pipelined_kernel_with_several_tiles_per_workgroup(dtype, n, d):
-    """The reducers of the pipelined kernel read the receiver's own gradient (and momentum) two rows
-    ahead, across tile boundaries.  A grid capped at three workgroups gives each of them several
-    tiles (an odd number of them, the last one ragged) in every tile width the kernel has; rounds
-    0 and 1 walk the tiles in opposite directions.  Checked against the oracle and, bit for bit,
-    against the uncapped launch."""
+@pytest.mark.parametrize("n,d,tile", [(16, 11 * 1024 + 44, 1024), (16, 11 * 512 + 44, 512), (40, 9 * 256 + 4, 256),
+                                      (128, 13 * 128 + 2, 128), (64, 13 * 128 + 2, 128), (256, 7 * 64 + 1, 64),
+                                      (128, 7 * 64 + 1, 64), (16, 11 * 1024 + 44, 0)])
+def test_awc_on_the_pipelined_kernel_with_several_tiles_per_workgroup(dtype, n, d, tile):
+    """The reducers of the pipelined kernel take the receiver's own gradient (and momentum) either
+    from HBM, several rows ahead and across tile boundaries, or -- bf16 storage, no momentum, where
+    n more rows fit the LDS tile -- from a gradient tile the loaders stage (tuning knob 14 keeps
+    them from it).  A grid capped at three workgroups gives each of them several tiles (an odd
+    number of them, the last one ragged) in every tile width the kernel has (knob 0; the shapes
+    include one where the gradient rows fill LDS to the last byte and ones where they do not fit);
+    rounds 0 and 1 walk the tiles in opposite directions.  Checked against the oracle and, bit for
+    bit, between the capped and the uncapped launch and between the two forms."""
     t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
     tol = TOL32 if dtype == torch.float32 else 2.0 ** -8
     X, G = rows(n, d, 71, dtype=dtype), rows(n, d, 72, dtype=dtype)
@@ -485,8 +490,10 @@ def test_awc_on_the_pipelined_kernel_with_several_tiles_per_workgroup(dtype, n, 
         mixed = O.mix(host(X), W)
         for with_m in (False, True):
             got = []
-            for grid in (0, 3):
+            for grid, from_hbm in ((0, 0), (3, 0), (3, 1)):
                 bf.bf_set_tuning(3, grid)
+                bf.bf_set_tuning(0, tile)
+                bf.bf_set_tuning(14, from_hbm)
                 try:
                     out = empty_like_rows(X)
                     out.fill_(float("nan"))
@@ -494,11 +501,14 @@ def test_awc_on_the_pipelined_kernel_with_several_tiles_per_workgroup(dtype, n, 
                     bf.bf_atc_step(t, rnd, X, out, G, M, alpha=alpha, beta=beta if with_m else 0.0, mode=bf.BF_AWC)
                 finally:
                     bf.bf_set_tuning(3, 0)
+                    bf.bf_set_tuning(0, 0)
+                    bf.bf_set_tuning(14, 0)
                 got.append((out, M))
-            (out, M), (out3, M3) = got
+            (out, M), (out3, M3), (outh, Mh) = got
             assert torch.equal(out, out3), "capped grid differs (n=%d rnd=%d momentum=%s)" % (n, rnd, with_m)
+            assert torch.equal(out3, outh), "gradient from LDS and from HBM differ (n=%d rnd=%d momentum=%s)" % (n, rnd, with_m)
             if with_m:
-                assert torch.equal(M, M3)
+                assert torch.equal(M, M3) and torch.equal(M, Mh)
                 Mn = b64 * host(M0) + host(G)
                 assert_close(M3, Mn, 1e-6, "momentum")
                 assert_close(out3, mixed - a64 * Mn, tol, "x")
