@@ -234,6 +234,40 @@ def test_config5_full_size_momentum_steps_in_column_blocks():
     assert bool((pad == 0).all()) and bool((Mb.data[-1, :, d - (Mb.data.shape[0] - 1) * B:] == 0).all())
 
 
+@pytest.mark.parametrize("dtype,n,d", [(torch.bfloat16, 32, workloads.RESNET50_PARAMS), (torch.float32, 128, 1 << 22)])
+def test_steps_without_a_state_matrix_full_size_in_column_blocks(dtype, n, d):
+    """The plain mix and the ATC and AWC steps on the static exponential graph, out of place, at the
+    sizes and block width bench.py times them at beside the five configurations (bf16 with 32 agents
+    and ResNet-50's parameter count -- where AWC takes its gradients from the LDS tile --, fp32 with
+    128 agents and fourteen entries per row).  Oracle on sampled columns, ragged tail included."""
+    t = bf.bf_topology_create(bf.BF_EXP_STATIC, n)
+    code = bf.BF_BF16 if dtype == torch.bfloat16 else bf.BF_F32
+    B = bf.bf_recommended_block(t, d, code)
+    ld = bf.bf_recommended_ld(d, code)
+    W = lib_W(t)
+    tol = 2.0 ** -8 if dtype == torch.bfloat16 else TOL32
+    cols = sample_columns(d, 11)
+    assert int(cols[-1]) == d - 1
+    X = workloads.normal_rows(n, d, 160, DEV, ld=ld, dtype=dtype)
+    G = workloads.normal_rows(n, d, 161, DEV, ld=ld, dtype=dtype)
+    Xh, Gh = host(X[:, cols]), host(G[:, cols])
+    Xb, Gb = to_blocked(X, B), to_blocked(G, B)
+    Yb = empty_blocked(n, d, B, dtype)
+    alpha = 0.05
+    a64 = float(np.float32(alpha))
+    for what, run, ref in (
+            ("mix", lambda: bf.bf_neighbor_allreduce(t, 0, Xb, Yb), lambda: O.mix(Xh, W)),
+            ("ATC", lambda: bf.bf_atc_step(t, 0, Xb, Yb, Gb, None, alpha=alpha, mode=bf.BF_ATC), lambda: O.atc_step(Xh, Gh, W, a64)),
+            ("AWC", lambda: bf.bf_atc_step(t, 0, Xb, Yb, Gb, None, alpha=alpha, mode=bf.BF_AWC), lambda: O.awc_step(Xh, Gh, W, a64))):
+        Yb.data.fill_(float("nan"))
+        run()
+        bf.bf_blocked_unpack(Yb, X)                      # X is free by now: Xb holds the input
+        got, want = host(X[:, cols]), ref()
+        assert np.abs(got - want).max() <= tol * np.abs(want).max(), what
+        assert bool((Yb.data[-1, :, d - (Yb.data.shape[0] - 1) * B:] != Yb.data[-1, :, d - (Yb.data.shape[0] - 1) * B:]).all()), \
+            what + ": the padding of the last block was written"
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("cw", [1, 2, 4])
 @pytest.mark.parametrize("kind,n", [(bf.BF_RING, 16), (bf.BF_EXP2_ONE_PEER, 100), (bf.BF_EXP2_ONE_PEER, 256)])
