@@ -1230,8 +1230,16 @@ int win_common(int mode, const bf_topology_t* tc, int32_t round, const int32_t* 
   if (chunks > INT32_MAX) return BF_ERR_SIZE;
   wp.chunks = static_cast<int32_t>(chunks);
   const int64_t units = chunks * t->n;
-  int grid = static_cast<int>(std::min<int64_t>(units, static_cast<int64_t>(di.cus) * 8));
-  if (g_tune_grid > 0) grid = std::min(grid, g_tune_grid);
+  // One 256-thread workgroup per CU, as for a plain copy: these kernels only move data, and with more
+  // workgroups per CU the memory system serves the same streams more slowly (n = 128, 512 slots,
+  // d = 2^21: accumulate 5.14 -> 5.4 TB/s, update_then_collect 5.18 -> 5.5, put 5.1 -> 5.3, update
+  // 5.65 -> 6.0 against eight per CU; two per CU already lose the gain).
+  // (win_get with bf16 storage is the exception: it reads every X row once per out-edge in 8-byte
+  // pieces and lives on cache hits, which more resident workgroups raise: n = 32, 288 slots,
+  // d = 12.8 M: 4.3 ms with eight per CU, 6.1 ms with one.)
+  const int per_cu = (mode == WIN_GET && dt != BF_F32) ? 8 : 1;
+  int grid = static_cast<int>(std::min<int64_t>(units, static_cast<int64_t>(di.cus) * per_cu));
+  if (g_tune_grid > 0) grid = static_cast<int>(std::min<int64_t>(units, g_tune_grid));     // (the knob may also raise it)
   // Cache policy as for the mixing kernels: state and window beyond what the memory-side cache can
   // keep between two calls stream with non-temporal loads and stores.
   const size_t eb = dt == BF_F32 ? 4 : 2;
