@@ -373,7 +373,7 @@ int launch_pipe_shape(const TileParams& tp, int grid, size_t lds, hipStream_t st
 }
 
 // The wave split.  Plain mixing and the ops that stage X (and G) only: four loader waves with eight
-// vectors per lane in flight and twelve reducer waves, the measured best of the splits tried (4+8
+// (narrow tiles: four) vectors per lane in flight and twelve reducer waves, the measured best of the splits tried (4+8
 // and 8+8 waves leave the reducers short; two or three loader waves cannot keep enough loads in
 // flight).  The ops that also read and write an fp32 state matrix while staging (momentum,
 // Exact-Diffusion) do most of their work in the loaders: eight loader waves with four vectors in
@@ -389,8 +389,12 @@ int launch_pipe_lw(const TileParams& tp, int grid, size_t lds, bool stream, hipS
     return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 8, 8, UU, true>(tp, grid, lds, st)
                   : launch_pipe_shape<DT, OP, WITH_Y, LW, 8, 8, UU, false>(tp, grid, lds, st);
   } else {
-    return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, true>(tp, grid, lds, st)
-                  : launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, 8, false>(tp, grid, lds, st);
+    // (tiles narrower than 256 columns -- more than 80 agents -- do better with four vectors in flight
+    // than with eight: config 4 in place on column blocks 6.18 -> 6.35 TB/s, n = 160 5.89 -> 6.20;
+    // at 256 columns and more eight stay ahead by a percent)
+    constexpr int UU = LW == 4 ? 8 : 4;
+    return stream ? launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, UU, true>(tp, grid, lds, st)
+                  : launch_pipe_shape<DT, OP, WITH_Y, LW, 4, 12, UU, false>(tp, grid, lds, st);
   }
 }
 
