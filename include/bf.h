@@ -467,7 +467,8 @@ int         bf_last_hip_error(void);   /* hipError_t of the last BF_ERR_HIP on t
  *   knob 0: column-tile width of the LDS tile kernel in elements (power of two, 64..1024)
  *   knob 1: workgroups per compute unit for the tile kernel
  *   knob 2: 1 forces the fallbacks for large agent counts (row gather, narrow tiles)
- *   knob 3: upper bound on the number of persistent workgroups
+ *   knob 3: upper bound on the number of persistent workgroups (for the window calls: their number,
+ *           which may also exceed the default of one per compute unit)
  *   knob 5: 1 disables the row-streaming chain kernel
  *   knob 8: 1 forces non-temporal loads/stores in the tile kernels, 2 forbids them
  *   knob 12: 1 uses the pipelined tile kernel (loader and reducer waves) also for cache-resident
