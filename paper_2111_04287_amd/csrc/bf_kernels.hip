@@ -1014,7 +1014,16 @@ int run_tile(bf_topology_t* t, int32_t round, int op, bool with_y, TileParams tp
     // (column blocks: tiles of 512 columns below 32 agents and 256 from there on measure best --
     // n = 8: 512 columns 6.2 TB/s, 1024 6.0, 256 3.1; n = 32: 256 columns 6.04, 512 5.67)
     const int pipe_cap = blocked ? std::min(cap_log_c, t->n < 32 ? 9 : 8) : cap_log_c;
-    if (choose_pipe_shape(t->n, tp.d, di, &ps, pipe_cap) == BF_OK) {
+    bool pipe_fits = choose_pipe_shape(t->n, tp.d, di, &ps, pipe_cap) == BF_OK;
+    if (pipe_fits && ps.log_c < 7 && g_tune_pipe != 1) {
+      // More than 160 agents leave the two tiles 64 columns each (256-byte row pieces, one column per
+      // lane in the reduce phase).  The one-tile kernel gets 128 columns there and measures 10-60 %
+      // faster (n = 256, static exponential graph, bf16 momentum step: 4.0 against 3.2 TB/s; fp32
+      // ATC 4.9 against 4.3), so it takes those sizes.
+      Shape ts;
+      if (choose_shape(t->n, tp.d, di, &ts, 2, cap_log_c) == BF_OK && ts.log_c > ps.log_c) pipe_fits = false;
+    }
+    if (pipe_fits) {
       if (dry) return BF_OK;
       // AWC with bf16 storage: the reducers are short of issue slots, and fetching their own gradient
       // from HBM between their stores costs them a third of their rate.  Where n more fp32 rows fit
